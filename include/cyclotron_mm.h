@@ -1,0 +1,95 @@
+/* cyclotron_mm.h -- C ABI of the MI355X (gfx950) weight-stationary recurrence matmul.
+ *
+ * The operation is the weight-stationary program of the Cyclotron paper
+ * (section "Space-time Mappings of Dataflow Recurrences"; per-cell programs in
+ * the per-PE figure): a grid of cells (i,k) latches [i,k]_W <- A_ik once; for
+ * every time step j the north boundary injects B_kj, B moves down the i axis
+ * unchanged, and each cell computes
+ *        [i,k]_C <- [i,k-1]_C + [i,k]_W * [i,k]_B ,   [i,-1]_C = 0,
+ * handing the partial sum east along k until the last column emits
+ *        C_ij <- [i,k_end]_C .
+ * The value that leaves the grid is C_ij = sum_k A_ik B_kj (the paper's
+ * matrix-multiply recurrence, "Explicit Reduction Dimensions" form).
+ *
+ * All pointers are DEVICE pointers owned by the caller.  The library allocates
+ * nothing, keeps no reference after return and has no mutable global state.
+ * Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
+ * default stream); no call synchronises the device or the stream.  Functions
+ * return a cyc_status and never throw or abort; when the status is not CYC_OK
+ * nothing has been enqueued.
+ *
+ * Layout: A is M x K, B is K x N, C is M x N, dense row-major with the row
+ * length as leading dimension: A_ik = A[i*K+k], B_kj = B[k*N+j],
+ * C_ij = C[i*N+j].  C is overwritten (the chain starts from 0); C must not
+ * overlap A or B.
+ *
+ * Element types (cyc_dtype):
+ *   CYC_BF16_F32  A,B bfloat16; products exact, partial sums fp32; C fp32.
+ *                 The summation order over k is fixed per shape (bit-identical
+ *                 results run to run) but is not the strictly sequential order
+ *                 of the cell chain; it agrees with it to within fp32 rounding
+ *                 of a K-term sum.
+ *   CYC_I8_I32    A,B int8; partial sums int32, wrapping modulo 2^32; C int32.
+ *                 Bit-exact for any summation order.
+ *
+ * Degenerate extents: M == 0, N == 0 or batch == 0 do nothing and return
+ * CYC_OK; K == 0 fills C with zeros (the initial value of every chain).
+ * Any M, K, N >= 1 is accepted; shapes that are multiples of the kernel tiles
+ * with 16-byte aligned pointers take the fast paths.
+ */
+#ifndef CYCLOTRON_MM_H
+#define CYCLOTRON_MM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CYC_BF16_F32 = 0,
+    CYC_I8_I32 = 1
+} cyc_dtype;
+
+typedef enum {
+    CYC_OK = 0,
+    CYC_ERR_NULL = 1,    /* a required pointer is NULL while its extent is not empty */
+    CYC_ERR_SHAPE = 2,   /* negative extent, negative stride, or element count overflow */
+    CYC_ERR_DTYPE = 3,   /* dtype is not a cyc_dtype */
+    CYC_ERR_ALIAS = 4,   /* C overlaps A or B */
+    CYC_ERR_LAUNCH = 5   /* the HIP runtime refused the launch */
+} cyc_status;
+
+/* One grid: C (M x N) <- A (M x K) streamed against B (K x N).
+ * A, B: device, read only.  C: device, written.  stream: hipStream_t or NULL. */
+int cyc_recurrence_matmul(const void *A, const void *B, void *C,
+                          int64_t M, int64_t K, int64_t N,
+                          int dtype, void *stream);
+
+/* `batch` independent grids, each with its own stationary A (not part of the
+ * paper; the narrow-stream workload has one weight matrix per batch element).
+ * Element b uses A + b*strideA, B + b*strideB, C + b*strideC, strides counted
+ * in elements of the respective type.  strideA or strideB may be 0 (operand
+ * shared by all grids); strideC must be >= M*N when batch > 1. */
+int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
+                                  int64_t batch, int64_t M, int64_t K, int64_t N,
+                                  int64_t strideA, int64_t strideB, int64_t strideC,
+                                  int dtype, void *stream);
+
+/* Human-readable name of a cyc_status (static storage, never NULL). */
+const char *cyc_status_string(int status);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int cyc_version(void);
+
+/* Name of the kernel family the dispatcher would pick for this problem
+ * ("mfma256", "mfma128", "narrow", "generic", "zero", "none"); static storage.
+ * Host only; enqueues nothing.  Pointers are only inspected for alignment. */
+const char *cyc_kernel_name(const void *A, const void *B, const void *C,
+                            int64_t batch, int64_t M, int64_t K, int64_t N,
+                            int64_t strideA, int64_t strideB, int64_t strideC, int dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CYCLOTRON_MM_H */

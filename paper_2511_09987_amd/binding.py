@@ -1,0 +1,115 @@
+"""ctypes binding of libcyclotron_mm.so.  Same names as the C ABI (include/cyclotron_mm.h).
+
+PyTorch appears here only as the owner of device memory and streams.  There is no
+fallback: if the shared library is missing, the first call raises ImportError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+CYC_BF16_F32 = 0
+CYC_I8_I32 = 1
+CYC_OK = 0
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcyclotron_mm.so")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is not built; run `python -m paper_2511_09987_amd.build` "
+                          "(needs hipcc, cross-compiles for gfx950)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, ptr, cint = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.cyc_recurrence_matmul.argtypes = [ptr, ptr, ptr, i64, i64, i64, cint, ptr]
+    lib.cyc_recurrence_matmul.restype = cint
+    lib.cyc_recurrence_matmul_batched.argtypes = [ptr, ptr, ptr, i64, i64, i64, i64, i64, i64, i64, cint, ptr]
+    lib.cyc_recurrence_matmul_batched.restype = cint
+    lib.cyc_status_string.argtypes = [cint]
+    lib.cyc_status_string.restype = ctypes.c_char_p
+    lib.cyc_version.argtypes = []
+    lib.cyc_version.restype = cint
+    lib.cyc_kernel_name.argtypes = [ptr, ptr, ptr, i64, i64, i64, i64, i64, i64, i64, cint]
+    lib.cyc_kernel_name.restype = ctypes.c_char_p
+    return lib
+
+
+_cached = None
+
+
+def _lib() -> ctypes.CDLL:
+    """The loaded library; loading is deferred to first use so that the build module can be
+    imported before the library exists.  Raises ImportError if it is not built."""
+    global _cached
+    if _cached is None:
+        _cached = _load()
+    return _cached
+
+
+class CycError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(cyc_status_string(status))
+
+
+def cyc_status_string(status: int) -> str:
+    return _lib().cyc_status_string(int(status)).decode()
+
+
+def cyc_version() -> int:
+    return int(_lib().cyc_version())
+
+
+def cyc_recurrence_matmul(A: int, B: int, C: int, M: int, K: int, N: int, dtype: int, stream: int = 0) -> int:
+    """Raw call: device addresses as ints, returns the cyc_status."""
+    return int(_lib().cyc_recurrence_matmul(A, B, C, M, K, N, dtype, stream))
+
+
+def cyc_recurrence_matmul_batched(A: int, B: int, C: int, batch: int, M: int, K: int, N: int,
+                                  strideA: int, strideB: int, strideC: int, dtype: int, stream: int = 0) -> int:
+    return int(_lib().cyc_recurrence_matmul_batched(A, B, C, batch, M, K, N, strideA, strideB, strideC,
+                                                  dtype, stream))
+
+
+def cyc_kernel_name(A: int, B: int, C: int, batch: int, M: int, K: int, N: int,
+                    strideA: int, strideB: int, strideC: int, dtype: int) -> str:
+    return _lib().cyc_kernel_name(A, B, C, batch, M, K, N, strideA, strideB, strideC, dtype).decode()
+
+
+def recurrence_matmul(A, B, out=None, stream=None):
+    """Tensor-level convenience: C = weight-stationary recurrence of A against B.
+
+    A: (M,K) or (batch,M,K); B: (K,N) or (batch,K,N); contiguous CUDA tensors, both
+    torch.bfloat16 (C float32) or both torch.int8 (C int32).  Only allocates C and
+    forwards pointers to the C ABI on the current (or given) stream.
+    """
+    import torch
+    if not (A.is_cuda and B.is_cuda):
+        raise ValueError("A and B must be device tensors; there is no CPU path")
+    if A.dtype != B.dtype or A.dtype not in (torch.bfloat16, torch.int8):
+        raise ValueError("A and B must both be bfloat16 or both int8")
+    if A.dim() != B.dim() or A.dim() not in (2, 3) or not (A.is_contiguous() and B.is_contiguous()):
+        raise ValueError("A and B must be contiguous and both 2-D or both 3-D")
+    dtype = CYC_BF16_F32 if A.dtype == torch.bfloat16 else CYC_I8_I32
+    batch = A.shape[0] if A.dim() == 3 else 1
+    M, K = A.shape[-2:]
+    K2, N = B.shape[-2:]
+    if K != K2 or (A.dim() == 3 and B.shape[0] != batch):
+        raise ValueError(f"shape mismatch: A {tuple(A.shape)}, B {tuple(B.shape)}")
+    cshape = (batch, M, N) if A.dim() == 3 else (M, N)
+    cdtype = torch.float32 if dtype == CYC_BF16_F32 else torch.int32
+    if out is None:
+        out = torch.empty(cshape, dtype=cdtype, device=A.device)
+    elif tuple(out.shape) != cshape or out.dtype != cdtype or not out.is_contiguous() or out.device != A.device:
+        raise ValueError("out has the wrong shape, dtype, layout or device")
+    s = (stream if stream is not None else torch.cuda.current_stream(A.device)).cuda_stream
+    st = cyc_recurrence_matmul_batched(A.data_ptr(), B.data_ptr(), out.data_ptr(), batch, M, K, N,
+                                       M * K, K * N, M * N, dtype, s)
+    if st != CYC_OK:
+        raise CycError(st)
+    return out

@@ -1,0 +1,155 @@
+// cyc_api.hip -- the C ABI declared in include/cyclotron_mm.h: argument checks and
+// the choice of kernel.  No device work happens here except the launches.
+#include "../../include/cyclotron_mm.h"
+#include "cyc_internal.h"
+
+#include <cstdlib>
+#include <cstring>
+
+namespace {
+
+constexpr int64_t kMaxElems = (int64_t)1 << 46;   // keeps every byte offset far inside int64
+
+bool mul_ok(int64_t a, int64_t b, int64_t *out)
+{
+    if (a == 0 || b == 0) { *out = 0; return true; }
+    if (a > kMaxElems / b) return false;
+    *out = a * b;
+    return true;
+}
+
+bool overlaps(const void *p, int64_t pbytes, const void *q, int64_t qbytes)
+{
+    if (!p || !q || pbytes <= 0 || qbytes <= 0) return false;
+    uintptr_t a = (uintptr_t)p, b = (uintptr_t)q;
+    return a < b + (uintptr_t)qbytes && b < a + (uintptr_t)pbytes;
+}
+
+enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_NARROW };
+
+const char *kernel_label(Kernel k)
+{
+    switch (k) {
+        case K_NONE: return "none";
+        case K_ZERO: return "zero";
+        case K_GENERIC: return "generic";
+        case K_MFMA256: return "mfma256";
+        case K_MFMA128: return "mfma128";
+        case K_NARROW: return "narrow";
+    }
+    return "none";
+}
+
+// Validates and fills `p`.  Returns CYC_OK with *k == K_NONE when there is nothing to do.
+int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, int64_t K, int64_t N,
+         int64_t strideA, int64_t strideB, int64_t strideC, int dtype, cyc::Problem *p, Kernel *k)
+{
+    *k = K_NONE;
+    if (dtype != CYC_BF16_F32 && dtype != CYC_I8_I32) return CYC_ERR_DTYPE;
+    if (batch < 0 || M < 0 || K < 0 || N < 0 || strideA < 0 || strideB < 0 || strideC < 0) return CYC_ERR_SHAPE;
+    int64_t mk, kn, mn;
+    if (!mul_ok(M, K, &mk) || !mul_ok(K, N, &kn) || !mul_ok(M, N, &mn)) return CYC_ERR_SHAPE;
+    if (batch > 1) {
+        int64_t t;
+        if (strideC < mn) return CYC_ERR_SHAPE;
+        if (!mul_ok(batch, strideA > mk ? strideA : mk, &t) || !mul_ok(batch, strideB > kn ? strideB : kn, &t) ||
+            !mul_ok(batch, strideC, &t))
+            return CYC_ERR_SHAPE;
+        if ((strideA != 0 && strideA < mk) || (strideB != 0 && strideB < kn)) return CYC_ERR_SHAPE;
+    }
+    if (batch == 0 || M == 0 || N == 0) return CYC_OK;
+    if (!C) return CYC_ERR_NULL;
+    if (K > 0 && (!A || !B)) return CYC_ERR_NULL;
+
+    const bool i8 = dtype == CYC_I8_I32;
+    const int64_t es = i8 ? 1 : 2;
+    const int64_t spanA = ((batch - 1) * strideA + mk) * es, spanB = ((batch - 1) * strideB + kn) * es;
+    const int64_t spanC = ((batch - 1) * strideC + mn) * 4;
+    if (K > 0 && (overlaps(C, spanC, A, spanA) || overlaps(C, spanC, B, spanB))) return CYC_ERR_ALIAS;
+
+    p->A = A; p->B = B; p->C = const_cast<void *>(C);
+    p->batch = batch; p->M = M; p->K = K; p->N = N;
+    p->strideA = strideA; p->strideB = strideB; p->strideC = strideC;
+    p->i8 = i8;
+
+    if (K == 0) { *k = K_ZERO; return CYC_OK; }
+
+    // CYC_FORCE_KERNEL=generic|mfma256|mfma128|narrow overrides the heuristic when the named
+    // kernel supports the problem (testing and benchmarking aid).
+    const char *force = std::getenv("CYC_FORCE_KERNEL");
+    if (force && *force) {
+        if (!std::strcmp(force, "generic")) { *k = K_GENERIC; return CYC_OK; }
+        if (!std::strcmp(force, "mfma256") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256; return CYC_OK; }
+        if (!std::strcmp(force, "mfma128") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128; return CYC_OK; }
+        if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
+    }
+    if (cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
+    // 256x256 tiles once they can fill the chip; 128x128 tiles for mid-size problems
+    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256) * batch;
+    if (cyc::supports_mfma(*p, 256) && tiles256 >= 256) { *k = K_MFMA256; return CYC_OK; }
+    if (cyc::supports_mfma(*p, 128)) { *k = K_MFMA128; return CYC_OK; }
+    if (cyc::supports_mfma(*p, 256)) { *k = K_MFMA256; return CYC_OK; }
+    *k = K_GENERIC;
+    return CYC_OK;
+}
+
+int run(const cyc::Problem &p, Kernel k, hipStream_t s)
+{
+    hipError_t e = hipSuccess;
+    switch (k) {
+        case K_NONE: return CYC_OK;
+        case K_ZERO: e = cyc::launch_zero(p, s); break;
+        case K_GENERIC: e = cyc::launch_generic(p, s); break;
+        case K_MFMA256: e = cyc::launch_mfma(p, 256, s); break;
+        case K_MFMA128: e = cyc::launch_mfma(p, 128, s); break;
+        case K_NARROW: e = cyc::launch_narrow(p, s); break;
+    }
+    return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C, int64_t batch, int64_t M, int64_t K,
+                                  int64_t N, int64_t strideA, int64_t strideB, int64_t strideC, int dtype,
+                                  void *stream)
+{
+    cyc::Problem p;
+    Kernel k;
+    int st = plan(A, B, C, batch, M, K, N, strideA, strideB, strideC, dtype, &p, &k);
+    if (st != CYC_OK) return st;
+    return run(p, k, (hipStream_t)stream);
+}
+
+int cyc_recurrence_matmul(const void *A, const void *B, void *C, int64_t M, int64_t K, int64_t N, int dtype,
+                          void *stream)
+{
+    return cyc_recurrence_matmul_batched(A, B, C, 1, M, K, N, 0, 0, 0, dtype, stream);
+}
+
+const char *cyc_kernel_name(const void *A, const void *B, const void *C, int64_t batch, int64_t M, int64_t K,
+                            int64_t N, int64_t strideA, int64_t strideB, int64_t strideC, int dtype)
+{
+    cyc::Problem p;
+    Kernel k;
+    if (plan(A, B, C, batch, M, K, N, strideA, strideB, strideC, dtype, &p, &k) != CYC_OK) return "none";
+    return kernel_label(k);
+}
+
+const char *cyc_status_string(int status)
+{
+    switch (status) {
+        case CYC_OK: return "CYC_OK";
+        case CYC_ERR_NULL: return "CYC_ERR_NULL: required pointer is NULL";
+        case CYC_ERR_SHAPE: return "CYC_ERR_SHAPE: negative or overflowing extent or stride";
+        case CYC_ERR_DTYPE: return "CYC_ERR_DTYPE: unknown element type";
+        case CYC_ERR_ALIAS: return "CYC_ERR_ALIAS: C overlaps an input";
+        case CYC_ERR_LAUNCH: return "CYC_ERR_LAUNCH: HIP launch failed";
+    }
+    return "unknown cyc_status";
+}
+
+int cyc_version(void) { return 100; }
+
+}  // extern "C"

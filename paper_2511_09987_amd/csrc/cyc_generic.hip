@@ -1,0 +1,108 @@
+// cyc_generic.hip -- shape-agnostic kernel of the weight-stationary recurrence
+// (paper, "Space-time Mappings of Dataflow Recurrences"): every C_ij is the chain
+// acc <- acc + A_ik * B_kj run in ascending k from 0, exactly as the cell row
+// (i,0..K-1) produces it for time step j.  Used for ragged extents, unaligned
+// pointers and tiny problems; the fast paths live in cyc_mfma.hip / cyc_narrow.hip.
+#include "cyc_internal.h"
+
+namespace cyc {
+namespace {
+
+constexpr int GT = 64;   // C tile edge per workgroup
+constexpr int GK = 16;   // k slab staged in LDS
+
+__device__ inline float widen(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ inline int widen(int8_t v) { return (int)v; }
+
+// 256 threads; thread (ty,tx) owns rows ty*4..+3 and columns tx*4..+3 of the tile.
+template <typename In, typename Acc>
+__global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ A, const In *__restrict__ B,
+                                                         Acc *__restrict__ C, int64_t M, int64_t K, int64_t N,
+                                                         int64_t sA, int64_t sB, int64_t sC)
+{
+    __shared__ Acc As[GK][GT + 1];   // [k][i]
+    __shared__ Acc Bs[GK][GT + 1];   // [k][j]
+    const int t = threadIdx.x, tx = t & 15, ty = t >> 4;
+    const int64_t i0 = (int64_t)blockIdx.y * GT, j0 = (int64_t)blockIdx.x * GT;
+    A += (int64_t)blockIdx.z * sA;
+    B += (int64_t)blockIdx.z * sB;
+    C += (int64_t)blockIdx.z * sC;
+
+    Acc acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0;
+
+    for (int64_t k0 = 0; k0 < K; k0 += GK) {
+        // stage A[i0..+63][k0..+15] and B[k0..+15][j0..+63], zero outside the matrices
+#pragma unroll
+        for (int x = t; x < GT * GK; x += 256) {
+            int ai = x / GK, ak = x % GK;
+            int64_t gi = i0 + ai, gk = k0 + ak;
+            As[ak][ai] = (gi < M && gk < K) ? (Acc)widen(A[gi * K + gk]) : (Acc)0;
+            int bk = x / GT, bj = x % GT;
+            int64_t gj = j0 + bj;
+            gk = k0 + bk;
+            Bs[bk][bj] = (gk < K && gj < N) ? (Acc)widen(B[gk * N + gj]) : (Acc)0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            Acc a[4], b[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) { a[x] = As[k][ty * 4 + x]; b[x] = Bs[k][tx * 4 + x]; }
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) acc[x][y] += a[x] * b[y];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            int64_t gi = i0 + ty * 4 + x, gj = j0 + tx * 4 + y;
+            if (gi < M && gj < N) C[gi * N + gj] = acc[x][y];
+        }
+}
+
+template <typename Acc>
+__global__ __launch_bounds__(256) void ws_zero_kernel(Acc *__restrict__ C, int64_t count, int64_t sC)
+{
+    Acc *c = C + (int64_t)blockIdx.y * sC;
+    for (int64_t x = (int64_t)blockIdx.x * 256 + threadIdx.x; x < count; x += (int64_t)gridDim.x * 256) c[x] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_generic(const Problem &p, hipStream_t s)
+{
+    // gridDim.y and .z are limited to 65535
+    if ((p.M + GT - 1) / GT > 65535 || p.batch > 65535) return hipErrorInvalidValue;
+    dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.batch);
+    if (p.i8)
+        hipLaunchKernelGGL((ws_generic_kernel<int8_t, int>), grid, dim3(256), 0, s, (const int8_t *)p.A,
+                           (const int8_t *)p.B, (int *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC);
+    else
+        hipLaunchKernelGGL((ws_generic_kernel<uint16_t, float>), grid, dim3(256), 0, s, (const uint16_t *)p.A,
+                           (const uint16_t *)p.B, (float *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC);
+    return hipGetLastError();
+}
+
+hipError_t launch_zero(const Problem &p, hipStream_t s)
+{
+    if (p.batch > 65535) return hipErrorInvalidValue;
+    int64_t count = p.M * p.N;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    dim3 grid((unsigned)blocks, (unsigned)p.batch);
+    if (p.i8)
+        hipLaunchKernelGGL((ws_zero_kernel<int>), grid, dim3(256), 0, s, (int *)p.C, count, p.strideC);
+    else
+        hipLaunchKernelGGL((ws_zero_kernel<float>), grid, dim3(256), 0, s, (float *)p.C, count, p.strideC);
+    return hipGetLastError();
+}
+
+}  // namespace cyc

@@ -1,0 +1,273 @@
+// cyc_mfma.hip -- MFMA kernels of the weight-stationary recurrence for gfx950.
+//
+// Mapping of the paper's weight-stationary program ("Space-time Mappings of Dataflow
+// Recurrences") onto one compute unit: a workgroup owns a BM x BN block of C.  Its
+// share of the stationary operand A (BM rows) is staged through LDS once per 128
+// bytes of k and then held in registers while the whole BN-wide slice of the j stream
+// passes over it; the B values that the paper moves cell to cell down the i axis are
+// one LDS read that every row of the block shares; the partial sums that the paper
+// hands east along k never move: they are the MFMA accumulators, and only the value
+// leaving the last column, C_ij <- [i,k_end]_C, is written to memory.
+//
+// Both element types share one byte geometry: a k-tile is 128 bytes of a row of A
+// (64 bf16 or 128 int8 values), cut into eight 16-byte chunks.
+#include "cyc_internal.h"
+
+namespace cyc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
+#define CYC_LDS __attribute__((address_space(3)))
+#define CYC_GLB __attribute__((address_space(1)))
+
+// accumulator type and MFMA instruction per element type; operands travel as 4 dwords
+template <bool I8> struct Acc;
+template <> struct Acc<false> {
+    typedef float elem;
+    typedef f32x16 type;   // bf16 x bf16 -> fp32, 32x32 tile, 16 k per instruction
+    static __device__ __forceinline__ type mfma(i32x4 a, i32x4 b, type c)
+    { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0); }
+};
+template <> struct Acc<true> {
+    typedef int elem;
+    typedef i32x16 type;   // int8 x int8 -> int32, 32x32 tile, 32 k per instruction
+    static __device__ __forceinline__ type mfma(i32x4 a, i32x4 b, type c)
+    { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+};
+
+template <bool I8, int BM_, int BN_, int WM_, int WN_>
+struct Cfg {
+    static constexpr bool I8v = I8;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int NW = WM * WN, NT = NW * 64;
+    static constexpr int ES = I8 ? 1 : 2;          // bytes per input element
+    static constexpr int BKE = 128 / ES;           // k elements per tile
+    static constexpr int KSTEP = 32 / ES;          // k elements per MFMA (32 bytes of k)
+    static constexpr int A_BYTES = BM * 128;
+    static constexpr int RB = BN * ES;             // bytes per row of the B tile
+    static constexpr int B_BYTES = BKE * RB;
+    static constexpr int STAGE = A_BYTES + B_BYTES;
+    static constexpr int CPR = RB / 16;            // 16-byte chunks per B row
+    static constexpr int RPI = 64 / CPR;           // B rows covered by one wave-wide 1 KiB load
+    static constexpr int AI = BM / 8 / NW;         // 1 KiB A loads per wave per k-tile
+    static constexpr int BI = B_BYTES / 1024 / NW; // 1 KiB B loads per wave per k-tile
+    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
+    static_assert(BM % (8 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "loads must divide evenly over waves");
+    static_assert(CPR <= 64 && 2 * STAGE <= 160 * 1024, "tile does not fit");
+};
+
+// LDS placement.  A tile: row r (128 bytes) at r*128, its chunk c stored in slot c ^ swzA(r).
+// B tile: row k (RB bytes) at k*RB, its chunk c stored in slot c ^ swzB(k).  The XORs spread
+// the rows that one fragment read touches over distinct banks.
+__device__ __forceinline__ int swzA(int r) { return (r >> 1) & 7; }
+template <class C>
+__device__ __forceinline__ int swzB(int k)
+{
+    if (!C::I8v) return ((k & 3) << 2) | (C::CPR >= 32 ? ((k >> 3) & 1) << 4 : 0);
+    return C::CPR >= 16 ? (k & 7) << 1 : ((k >> 1) & 3) << 1;
+}
+
+// 64 lanes x 16 bytes go from global memory straight into LDS at lds_addr + lane*16
+// (lds_addr wave-uniform).  Written as asm so that the compiler does not make every later
+// LDS read wait for these copies; completion is awaited explicitly with tile_fence().
+__device__ __forceinline__ void async_copy16(const char *g, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(g)
+                 : "memory", "m0");
+}
+// all of this wave's copies and LDS reads are done; then meet the other waves
+__device__ __forceinline__ void tile_fence()
+{
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
+                                                        char *__restrict__ Cout, int M, int K, int N, int64_t sA,
+                                                        int64_t sB, int64_t sC, int tiles_m, int tiles_n)
+{
+    constexpr int ES = C::ES, RB = C::RB, TM = C::TM, TN = C::TN;
+    __shared__ __attribute__((aligned(1024))) char lds_raw[2 * C::STAGE];
+    CYC_LDS char *lds = (CYC_LDS char *)lds_raw;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+
+    const int l = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = w / C::WN, wn = w % C::WN;
+
+    // ---- which C block: workgroups are dealt round-robin to the 8 XCDs, so ids congruent
+    // mod 8 share an L2.  Give each XCD a contiguous run of blocks, ordered so that the
+    // 32 blocks resident at a time form 4 block-rows x 8 block-columns: the 4 row panels
+    // of A (the stationary operand) stay in that XCD's L2 while the columns stream by.
+    int bid = blockIdx.x;
+    const int nblk = tiles_m * tiles_n;
+    if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int group = bid / per_group, in_group = bid % per_group;
+    const int rows_here = (tiles_m - group * GM) < GM ? (tiles_m - group * GM) : GM;
+    const int tm_blk = group * GM + in_group % rows_here, tn_blk = in_group / rows_here;
+    const int m0 = tm_blk * C::BM, n0 = tn_blk * C::BN;
+
+    A += (int64_t)blockIdx.y * sA * ES;
+    B += (int64_t)blockIdx.y * sB * ES;
+    Cout += (int64_t)blockIdx.y * sC * 4;
+
+    // ---- global source of each 16-byte chunk this lane copies per k-tile
+    const char *gA[C::AI];
+    const char *gB[C::BI];
+#pragma unroll
+    for (int t = 0; t < C::AI; ++t) {
+        int r = (w * C::AI + t) * 8 + (l >> 3);
+        int c = (l & 7) ^ swzA(r);
+        gA[t] = A + ((int64_t)(m0 + r) * K) * ES + c * 16;
+    }
+#pragma unroll
+    for (int t = 0; t < C::BI; ++t) {
+        int kr = (w * C::BI + t) * C::RPI + l / C::CPR;
+        int c = (l % C::CPR) ^ swzB<C>(kr);
+        gB[t] = B + ((int64_t)kr * N + n0) * ES + c * 16;
+    }
+    const int64_t stepB = (int64_t)C::BKE * N * ES;
+
+    auto issue = [&](int stage) {
+        const uint32_t base = lds_base + stage * C::STAGE;
+#pragma unroll
+        for (int t = 0; t < C::AI; ++t) {
+            async_copy16(gA[t], base + (w * C::AI + t) * 1024);
+            gA[t] += 128;
+        }
+#pragma unroll
+        for (int t = 0; t < C::BI; ++t) {
+            async_copy16(gB[t], base + C::A_BYTES + (w * C::BI + t) * 1024);
+            gB[t] += stepB;
+        }
+    };
+
+    // ---- LDS read offsets of this lane's fragments
+    // A fragment (32 rows x 32 bytes of k): lane holds row l%32, chunk 2*ks + l/32.
+    int offA[4];
+    {
+        int r = wm * (TM * 32) + (l & 31);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) offA[ks] = r * 128 + (((ks * 2 + (l >> 5)) ^ swzA(r)) << 4);
+    }
+    // B fragment through the LDS transpose read.  In every 16-lane group the lanes point
+    // at a (4 k x 16 n) bf16 or (8 k x 16 n) int8 patch and receive, per lane, consecutive
+    // k of one column: lane l ends up with column l%32 and k group l/32 of the MFMA operand.
+    int offB[TN];
+    {
+        const int lq = l & 15, colhalf = (l >> 4) & 1, kg = l >> 5;
+        const int krow = C::I8v ? 16 * kg + (lq >> 1) : 8 * kg + (lq >> 2);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            int ncol = wn * (TN * 32) + tn * 32 + colhalf * 16 + (C::I8v ? 8 * (lq & 1) : 4 * (lq & 3));
+            int byte = ncol * ES;
+            offB[tn] = C::A_BYTES + krow * RB + ((((byte >> 4)) ^ swzB<C>(krow)) << 4) + (byte & 15);
+        }
+    }
+
+    typename Acc<C::I8v>::type acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    const int nkt = K / C::BKE;
+    issue(0);
+    tile_fence();
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nkt) issue(cur ^ 1);
+        const int sb = cur * C::STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            i32x4 fa[TM];
+            i32x4 fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = *(CYC_LDS i32x4 *)(lds + sb + offA[ks] + i * 32 * 128);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                i32x2 lo, hi;
+                if (C::I8v) {
+                    lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[j] + (ks * 32) * RB));
+                    hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[j] + (ks * 32 + 8) * RB));
+                } else {
+                    bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16) * RB));
+                    bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16 + 4) * RB));
+                    lo = __builtin_bit_cast(i32x2, a);
+                    hi = __builtin_bit_cast(i32x2, b);
+                }
+                fb[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = Acc<C::I8v>::mfma(fa[i], fb[j], acc[i][j]);
+        }
+        tile_fence();
+    }
+
+    // ---- C_ij <- [i,k_end]_C.  Accumulator register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
+    // column l%32 of its 32x32 tile: for fixed r, 32 lanes write 128 contiguous bytes.
+    typedef typename Acc<C::I8v>::elem elem;
+    elem *Cw = (elem *)Cout;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * (TN * 32) + j * 32 + (l & 31);
+            const int row0 = m0 + wm * (TM * 32) + i * 32 + (l >> 5) * 4;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int row = row0 + (r >> 2) * 8 + (r & 3);
+                const elem v = acc[i][j][r];
+                Cw[(int64_t)row * N + col] = v;
+            }
+        }
+}
+
+template <class C>
+hipError_t launch_cfg(const Problem &p, hipStream_t s)
+{
+    const int tiles_m = (int)(p.M / C::BM), tiles_n = (int)(p.N / C::BN);
+    dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)p.batch);
+    hipLaunchKernelGGL((ws_mfma_kernel<C>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+                       (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool supports_mfma(const Problem &p, int tile)
+{
+    if (tile != 256 && tile != 128) return false;
+    const int es = p.i8 ? 1 : 2, bke = 128 / es;
+    if (p.K <= 0 || p.M % tile || p.N % tile || p.K % bke) return false;
+    if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
+    if ((p.M / tile) * (p.N / tile) > (1 << 30)) return false;
+    if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C) & 15) return false;
+    if (p.batch > 1 && (((p.strideA * es) | (p.strideB * es) | (p.strideC * 4)) & 15)) return false;
+    return true;
+}
+
+hipError_t launch_mfma(const Problem &p, int tile, hipStream_t s)
+{
+    if (!supports_mfma(p, tile)) return hipErrorInvalidValue;
+    if (tile == 256)
+        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 4>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 4>>(p, s);
+    return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2>>(p, s);
+}
+
+}  // namespace cyc

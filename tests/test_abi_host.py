@@ -1,0 +1,78 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "cyclotron_mm.h")
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import paper_2511_09987_amd as p
+    if not os.path.exists(p.lib_path()):
+        from paper_2511_09987_amd import build
+        build.build()
+    return p
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cyc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_documented_entry_points():
+    names = declared_functions()
+    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_status_string", "cyc_version"):
+        assert need in names
+
+
+def test_library_exports_every_declared_symbol(pkg):
+    lib = ctypes.CDLL(pkg.lib_path())
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+
+
+def test_status_strings_and_version(pkg):
+    assert pkg.cyc_version() >= 100
+    assert pkg.cyc_status_string(0) == "CYC_OK"
+    for st in range(1, 6):
+        assert pkg.cyc_status_string(st).startswith("CYC_ERR_")
+    assert "unknown" in pkg.cyc_status_string(99)
+
+
+def test_argument_validation_happens_on_the_host(pkg):
+    """Every call here returns an error (or has nothing to do) before any device work."""
+    f, fb = pkg.cyc_recurrence_matmul, pkg.cyc_recurrence_matmul_batched
+    a, b, c = 0x10000, 0x20000, 0x30000
+    assert f(a, b, c, 4, 4, 4, 9) == 3                       # unknown dtype
+    assert f(a, b, c, -1, 4, 4, 0) == 2                      # negative extent
+    assert f(a, b, c, 1 << 40, 1 << 40, 4, 0) == 2           # element count overflow
+    assert f(0, b, c, 4, 4, 4, 0) == 1                       # NULL A
+    assert f(a, b, 0, 4, 4, 4, 1) == 1                       # NULL C
+    assert f(a, b, a, 4, 4, 4, 1) == 4                       # C aliases A
+    assert f(a, b, b + 8, 4, 4, 4, 0) == 4                   # C overlaps B
+    assert f(0, 0, 0, 0, 4, 4, 0) == 0                       # M == 0: nothing to do
+    assert f(0, 0, 0, 4, 4, 0, 1) == 0                       # N == 0: nothing to do
+    assert fb(a, b, c, 0, 4, 4, 4, 16, 16, 16, 0) == 0       # batch == 0
+    assert fb(a, b, c, 2, 4, 4, 4, 16, 16, 8, 0) == 2        # strideC < M*N
+    assert fb(a, b, c, 2, 4, 4, 4, 8, 16, 16, 0) == 2        # 0 < strideA < M*K
+    assert fb(a, b, c, 2, 4, 4, 4, -16, 16, 16, 0) == 2      # negative stride
+
+
+def test_dispatch_table(pkg):
+    """Which kernel family serves which problem (host-only query)."""
+    k = pkg.cyc_kernel_name
+    A, B, C = 1 << 32, 2 << 32, 3 << 32
+    assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 0) == "mfma256"
+    assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 1) == "mfma256"
+    assert k(A, B, C, 1, 512, 512, 512, 0, 0, 0, 0) == "mfma128"
+    assert k(A, B, C, 1, 64, 64, 64, 0, 0, 0, 1) == "generic"
+    assert k(A, B, C, 1, 17, 33, 5, 0, 0, 0, 0) == "generic"
+    assert k(A + 2, B, C, 1, 512, 512, 512, 0, 0, 0, 0) == "generic"      # unaligned A
+    assert k(A, B, C, 1, 512, 0, 512, 0, 0, 0, 0) == "zero"
+    assert k(A, B, C, 1, 0, 8, 512, 0, 0, 0, 0) == "none"

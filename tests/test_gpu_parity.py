@@ -1,0 +1,256 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+int8 results must be bit-exact.  bf16 results must satisfy
+    max_ij |C_ij - Cref_ij| / sum_k |A_ik||B_kj|  <=  2e-2
+(the bound the benchmark definition states), and must be bit-exact whenever the data are
+small integers, because then every partial sum is an integer below 2^24 and all summation
+orders give the same fp32 value.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from datagen import ws_inputs
+from helpers import BF16_TOL, bits_to_f64, rel_err, torch_bf16_to_bits
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2511_09987_amd as pkg
+    assert os.path.exists(pkg.lib_path()), "libcyclotron_mm.so must be built in-tree"
+    return pkg
+
+
+def gen(mode, shape_a, shape_b, seed, kind="default"):
+    """Inputs on the GPU plus their host copies in the oracle's format."""
+    if mode == "i8":
+        r = 8 if kind == "small" else 127
+        A = ws_inputs.uniform_int(shape_a, r, seed, 0, DEV)
+        B = ws_inputs.uniform_int(shape_b, r, seed, 1, DEV)
+        return A, B, A.cpu().numpy(), B.cpu().numpy()
+    if kind == "small":
+        A = ws_inputs.small_int_bf16(shape_a, 8, seed, 0, DEV)
+        B = ws_inputs.small_int_bf16(shape_b, 8, seed, 1, DEV)
+    else:
+        A = ws_inputs.normal_bf16(shape_a, 1.0, seed, 0, DEV)
+        B = ws_inputs.normal_bf16(shape_b, 1.0, seed, 1, DEV)
+    return A, B, torch_bf16_to_bits(A), torch_bf16_to_bits(B)
+
+
+def check(mode, C, Cref, Ah, Bh, exact):
+    C = C.cpu().numpy()
+    assert C.shape == Cref.shape and C.dtype == Cref.dtype
+    if mode == "i8" or exact:
+        assert np.array_equal(C, Cref), f"{int((C != Cref).sum())} of {C.size} elements differ"
+    else:
+        err = rel_err(C, Cref, bits_to_f64(Ah), bits_to_f64(Bh))
+        assert err <= BF16_TOL, f"relative error {err:.3e} above {BF16_TOL}"
+        # a correct fp32 accumulation of K terms stays below K * 2^-23 on this metric
+        assert err <= Ah.shape[-1] * 2.0 ** -23, f"relative error {err:.3e} is suspicious for K={Ah.shape[-1]}"
+
+
+def run_case(lib, oracle, mode, M, K, N, seed, kind="default", force=None, expect_kernel=None):
+    A, B, Ah, Bh = gen(mode, (M, K), (K, N), seed, kind)
+    old = os.environ.pop("CYC_FORCE_KERNEL", None)
+    if force:
+        os.environ["CYC_FORCE_KERNEL"] = force
+    try:
+        if expect_kernel:
+            C0 = torch.empty((M, N), dtype=torch.int32 if mode == "i8" else torch.float32, device=DEV)
+            name = lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C0.data_ptr(), 1, M, K, N, 0, 0, 0,
+                                       lib.CYC_I8_I32 if mode == "i8" else lib.CYC_BF16_F32)
+            assert name == expect_kernel, f"dispatcher chose {name}, test is written for {expect_kernel}"
+        C = lib.recurrence_matmul(A, B)
+        torch.cuda.synchronize()
+    finally:
+        os.environ.pop("CYC_FORCE_KERNEL", None)
+        if old is not None:
+            os.environ["CYC_FORCE_KERNEL"] = old
+    Cref = oracle.ws_rowchain(Ah, Bh, mode)
+    check(mode, C, Cref, Ah, Bh, exact=(kind == "small"))
+    return C
+
+
+# ---------------------------------------------------------------- config 1 and 2, in full
+def test_config1_int8_64_against_literal_cell_grid(lib, oracle):
+    w = ws_inputs.WORKLOADS["c1_i8_64"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C = lib.recurrence_matmul(A, B)
+    Cref = oracle.ws_cells(A.cpu().numpy(), B.cpu().numpy(), "i8")
+    assert np.array_equal(C.cpu().numpy(), Cref)
+
+
+def test_config2_bf16_512(lib, oracle):
+    w = ws_inputs.WORKLOADS["c2_bf16_512"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C = lib.recurrence_matmul(A, B)
+    Ah, Bh = torch_bf16_to_bits(A), torch_bf16_to_bits(B)
+    Cref = oracle.ws_rowchain(Ah, Bh, "bf16")
+    check("bf16", C, Cref, Ah, Bh, exact=False)
+
+
+# ------------------------------------------------ ragged and tiny shapes (generic kernel)
+RAGGED = [(1, 1, 1), (1, 37, 1), (17, 33, 5), (5, 1, 7), (63, 64, 65), (65, 15, 63), (255, 129, 257),
+          (130, 300, 70), (3, 1000, 2), (64, 64, 64), (100, 8, 100)]
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_ragged_shapes(lib, oracle, mode):
+    for n, (M, K, N) in enumerate(RAGGED):
+        run_case(lib, oracle, mode, M, K, N, seed=1000 + n)
+        run_case(lib, oracle, mode, M, K, N, seed=2000 + n, kind="small")
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_generic_kernel_on_tile_multiple_shapes(lib, oracle, mode):
+    run_case(lib, oracle, mode, 256, 256, 256, seed=31, force="generic", expect_kernel="generic")
+
+
+# ----------------------------------------------------------------------- MFMA kernels
+MFMA128 = [(128, 128, 128), (128, 256, 128), (256, 128, 384), (384, 640, 128), (512, 512, 512)]
+MFMA256 = [(256, 128, 256), (256, 256, 256), (512, 384, 256), (256, 1024, 768), (768, 256, 512), (1280, 128, 1024)]
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+@pytest.mark.parametrize("tile,shapes", (("mfma128", MFMA128), ("mfma256", MFMA256)))
+def test_mfma_tiles(lib, oracle, mode, tile, shapes):
+    for n, (M, K, N) in enumerate(shapes):
+        run_case(lib, oracle, mode, M, K, N, seed=3000 + n, force=tile, expect_kernel=tile)
+        run_case(lib, oracle, mode, M, K, N, seed=4000 + n, kind="small", force=tile, expect_kernel=tile)
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+@pytest.mark.parametrize("tile", ("mfma128", "mfma256"))
+def test_mfma_one_hot_probes(lib, tile, mode):
+    """A = a e_p e_q^T, B = b e_q e_r^T  =>  C = ab e_p e_r^T, with p, q, r on and around
+    lane, fragment, wave, k-tile and block boundaries."""
+    M, K, N = 512, 512, 512
+    tdt = torch.int8 if mode == "i8" else torch.bfloat16
+    spots = [0, 1, 3, 4, 7, 8, 15, 16, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 383, 384, 511]
+    os.environ["CYC_FORCE_KERNEL"] = tile
+    try:
+        rng = np.random.default_rng(5)
+        for trial in range(40):
+            p, q, r = (int(rng.choice(spots)) for _ in range(3))
+            A = torch.zeros((M, K), dtype=tdt, device=DEV)
+            B = torch.zeros((K, N), dtype=tdt, device=DEV)
+            A[p, q] = 3
+            B[q, r] = -5
+            B[(q + 1) % K, r] = 7          # must not contribute: A has nothing in column q+1
+            C = lib.recurrence_matmul(A, B)
+            nz = torch.nonzero(C).cpu().tolist()
+            assert nz == [[p, r]], (p, q, r, nz[:5])
+            assert float(C[p, r]) == -15.0
+    finally:
+        os.environ.pop("CYC_FORCE_KERNEL", None)
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_closed_forms_on_gpu(lib, mode):
+    """All-ones gives K everywhere (a dropped or doubled k slice is invisible to the bf16
+    tolerance but not to this); identity weights pass B through unchanged."""
+    tdt = torch.int8 if mode == "i8" else torch.bfloat16
+    for M, K, N in ((512, 1024, 512), (256, 8192, 256), (70, 999, 33)):
+        A = torch.ones((M, K), dtype=tdt, device=DEV)
+        B = torch.ones((K, N), dtype=tdt, device=DEV)
+        C = lib.recurrence_matmul(A, B)
+        assert bool((C == K).all()), (M, K, N)
+    for K, N in ((512, 256), (1024, 1024), (77, 19)):
+        A = torch.eye(K, dtype=torch.float32, device=DEV).to(tdt)
+        _, B, _, _ = gen(mode, (K, K), (K, N), seed=77)
+        C = lib.recurrence_matmul(A, B)
+        assert torch.equal(C.double(), B.double()), (K, N)
+
+
+# ------------------------------------------------------------ determinism and batching
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_run_to_run_bit_identical(lib, mode):
+    for M, K, N in ((512, 512, 512), (1024, 2048, 1024), (130, 300, 70)):
+        A, B, _, _ = gen(mode, (M, K), (K, N), seed=55)
+        C1 = lib.recurrence_matmul(A, B)
+        C2 = lib.recurrence_matmul(A, B)
+        assert torch.equal(C1.view(torch.int32), C2.view(torch.int32))
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_batched_equals_loop_of_single_calls(lib, mode):
+    for batch, M, K, N in ((3, 256, 256, 256), (2, 128, 384, 128), (4, 33, 65, 17), (2, 512, 1024, 16)):
+        A, B, _, _ = gen(mode, (batch, M, K), (batch, K, N), seed=66)
+        C = lib.recurrence_matmul(A, B)
+        for b in range(batch):
+            Cb = lib.recurrence_matmul(A[b], B[b])
+            assert torch.equal(C[b].view(torch.int32), Cb.view(torch.int32)), (batch, M, K, N, b)
+
+
+def test_batched_shared_operands(lib):
+    """strideA = 0 or strideB = 0 share one operand across the batch."""
+    batch, M, K, N = 3, 128, 256, 128
+    A, B, _, _ = gen("i8", (batch, M, K), (batch, K, N), seed=67)
+    C = torch.empty((batch, M, N), dtype=torch.int32, device=DEV)
+    s = torch.cuda.current_stream().cuda_stream
+    st = lib.cyc_recurrence_matmul_batched(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, K, N,
+                                           0, K * N, M * N, lib.CYC_I8_I32, s)
+    assert st == 0
+    for b in range(batch):
+        assert torch.equal(C[b], lib.recurrence_matmul(A[0], B[b]))
+    st = lib.cyc_recurrence_matmul_batched(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, K, N,
+                                           M * K, 0, M * N, lib.CYC_I8_I32, s)
+    assert st == 0
+    for b in range(batch):
+        assert torch.equal(C[b], lib.recurrence_matmul(A[b], B[0]))
+
+
+# -------------------------------------------------------------- boundary behaviour
+def test_degenerate_extents_and_errors(lib):
+    s = torch.cuda.current_stream().cuda_stream
+    A = torch.ones((4, 4), dtype=torch.int8, device=DEV)
+    C = torch.full((4, 4), 9, dtype=torch.int32, device=DEV)
+    f = lib.cyc_recurrence_matmul
+    assert f(A.data_ptr(), A.data_ptr(), C.data_ptr(), 0, 4, 4, lib.CYC_I8_I32, s) == 0     # M == 0: no-op
+    assert f(A.data_ptr(), A.data_ptr(), C.data_ptr(), 4, 4, 0, lib.CYC_I8_I32, s) == 0     # N == 0: no-op
+    torch.cuda.synchronize()
+    assert bool((C == 9).all())
+    assert f(0, 0, C.data_ptr(), 4, 0, 4, lib.CYC_I8_I32, s) == 0                           # K == 0: zeros
+    torch.cuda.synchronize()
+    assert bool((C == 0).all())
+    assert f(0, A.data_ptr(), C.data_ptr(), 4, 4, 4, lib.CYC_I8_I32, s) == 1                # NULL
+    assert f(A.data_ptr(), A.data_ptr(), 0, 4, 4, 4, lib.CYC_I8_I32, s) == 1
+    assert f(A.data_ptr(), A.data_ptr(), C.data_ptr(), -1, 4, 4, lib.CYC_I8_I32, s) == 2    # shape
+    assert f(A.data_ptr(), A.data_ptr(), C.data_ptr(), 4, 4, 4, 7, s) == 3                  # dtype
+    assert f(C.data_ptr(), A.data_ptr(), C.data_ptr(), 4, 4, 4, lib.CYC_I8_I32, s) == 4     # alias
+    with pytest.raises(ValueError):
+        lib.recurrence_matmul(A.cpu(), A.cpu())          # no CPU path
+    with pytest.raises(ValueError):
+        lib.recurrence_matmul(A, A.view(2, 8))           # K mismatch
+
+
+def test_unaligned_pointers_fall_back(lib, oracle):
+    """Tile-multiple shapes at odd addresses must not take the 16-byte-aligned fast path."""
+    M = K = N = 256
+    buf = ws_inputs.uniform_int((M * K + K * N + 8,), 127, 91, 0, DEV)
+    A = buf[1:1 + M * K].view(M, K)
+    B = buf[3 + M * K:3 + M * K + K * N].view(K, N)
+    C = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    name = lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), 1, M, K, N, 0, 0, 0, lib.CYC_I8_I32)
+    assert name == "generic"
+    st = lib.cyc_recurrence_matmul(A.data_ptr(), B.data_ptr(), C.data_ptr(), M, K, N, lib.CYC_I8_I32,
+                                   torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    Cref = oracle.ws_rowchain(A.cpu().numpy(), B.cpu().numpy(), "i8")
+    assert np.array_equal(C.cpu().numpy(), Cref)
+
+
+def test_side_stream(lib, oracle):
+    A, B, Ah, Bh = gen("i8", (256, 256), (256, 256), seed=12)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        C = lib.recurrence_matmul(A, B)
+    s.synchronize()
+    assert np.array_equal(C.cpu().numpy(), oracle.ws_rowchain(Ah, Bh, "i8"))

@@ -83,7 +83,7 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
         if (!std::strcmp(force, "mfma128") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128; return CYC_OK; }
         if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
     }
-    if (cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
+    if (cyc::prefers_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
     // 256x256 tiles once they can fill the chip; 128x128 tiles for mid-size problems
     const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256) * batch;
     if (cyc::supports_mfma(*p, 256) && tiles256 >= 256) { *k = K_MFMA256; return CYC_OK; }

@@ -23,6 +23,7 @@ bool supports_mfma(const Problem &p, int tile);
 hipError_t launch_mfma(const Problem &p, int tile, hipStream_t s);
 // HBM-bound streaming kernel for N <= 16; requires supports_narrow(p)
 bool supports_narrow(const Problem &p);
+bool prefers_narrow(const Problem &p);   // supported and expected to beat the GEMM kernels
 hipError_t launch_narrow(const Problem &p, hipStream_t s);
 
 }  // namespace cyc

@@ -1,6 +1,220 @@
-// placeholder until the streaming kernel lands
+// cyc_narrow.hip -- HBM-bound kernel of the weight-stationary recurrence for a narrow j
+// stream (N <= 16), gfx950.
+//
+// This is the regime the paper gives as the reason for the weight-stationary mapping
+// ("Space-time Mappings of Dataflow Recurrences"): A, the weights, is far larger than B
+// and C, so A must cross the memory interface exactly once.  Here the roles on chip are
+// therefore inverted relative to the paper's cell grid: the whole B (K x N, a few hundred
+// KiB) is what stays resident -- each wave keeps its k-slice of B in registers for the
+// life of the workgroup -- and A streams past it at HBM speed, 16 rows at a time, straight
+// from global memory into MFMA operand registers.  The k chain [i,k]_C <- [i,k-1]_C + W*B
+// is cut into 8 contiguous k-slices, one per wave; each slice is accumulated in k order in
+// an MFMA accumulator, and the 8 partial sums of a row block are added in slice order by
+// one wave through LDS (fixed order: results are bit-identical run to run, no atomics).
 #include "cyc_internal.h"
+
+#include <type_traits>
+
 namespace cyc {
-bool supports_narrow(const Problem &) { return false; }
-hipError_t launch_narrow(const Problem &, hipStream_t) { return hipErrorInvalidValue; }
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
+#define CYC_LDS __attribute__((address_space(3)))
+
+constexpr int NWAVES = 8;     // k-slices per workgroup
+constexpr int DEPTH = 8;      // 16-byte loads in flight per lane
+constexpr int RB = 16;        // rows of A per MFMA (one row block)
+
+template <bool I8> struct Mac;
+template <> struct Mac<false> {   // 16x16 tile, 32 k per instruction
+    typedef f32x4 acc_t;
+    typedef float elem;
+    static __device__ __forceinline__ acc_t mfma(i32x4 a, i32x4 b, acc_t c)
+    { return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0); }
+};
+template <> struct Mac<true> {    // 16x16 tile, 64 k per instruction
+    typedef i32x4 acc_t;
+    typedef int elem;
+    static __device__ __forceinline__ acc_t mfma(i32x4 a, i32x4 b, acc_t c)
+    { return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
+};
+
+// wait for this wave's LDS traffic only (loads of A stay in flight), then meet the other waves
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// S: MFMA steps per wave per row block; a step is 64 bytes of k per row.  The workgroup covers
+// k < 8*S*64/ES.  FULL: K is exactly that, so no lane ever needs masking.
+template <bool I8, int S, bool FULL>
+__global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__restrict__ A, const char *__restrict__ B,
+                                                                char *__restrict__ Cout, int M, int K, int N,
+                                                                int64_t sA, int64_t sB, int64_t sC, int rows_per_wg)
+{
+    constexpr int ES = I8 ? 1 : 2;
+    constexpr int KS = 64 / ES;          // k values per step
+    constexpr int CH = 16 / ES;          // k values per 16-byte chunk
+    constexpr int HALF = S / 2;          // B is staged through LDS in two halves
+    typedef typename Mac<I8>::acc_t acc_t;
+    typedef typename Mac<I8>::elem elem;
+
+    __shared__ __attribute__((aligned(16))) char ldsB[NWAVES][HALF * KS * 16 * ES];
+    __shared__ __attribute__((aligned(16))) acc_t red[2][NWAVES][64];
+
+    const int l = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lq = l & 15, g = l >> 4;
+
+    A += (int64_t)blockIdx.y * sA * ES;
+    B += (int64_t)blockIdx.y * sB * ES;
+    elem *C = (elem *)Cout + (int64_t)blockIdx.y * sC;
+
+    const int kw0 = w * S * KS;          // first k of this wave's slice
+
+    // ---- this wave's slice of B -> MFMA operand registers, once.  Rows of B are copied into a
+    // wave-private LDS patch ([k][16 columns], zero beyond N and K) and read back through the
+    // LDS transpose read, which hands every lane consecutive k of one column.
+    i32x4 Bf[S];
+    {
+        typedef typename std::conditional<I8, int8_t, uint16_t>::type in_t;
+        const in_t *Bg = (const in_t *)B;
+        CYC_LDS in_t *patch = (CYC_LDS in_t *)ldsB[w];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int kh0 = kw0 + h * HALF * KS;
+            for (int x = l; x < HALF * KS * 16; x += 64) {
+                const int kk = kh0 + (x >> 4), j = x & 15;
+                patch[x] = (kk < K && j < N) ? Bg[(int64_t)kk * N + j] : (in_t)0;
+            }
+#pragma unroll
+            for (int s = 0; s < HALF; ++s) {
+                i32x2 lo, hi;
+                if (I8) {
+                    CYC_LDS char *p = (CYC_LDS char *)patch + (s * 64 + 16 * g + (lq >> 1)) * 16 + 8 * (lq & 1);
+                    lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)p);
+                    hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(p + 8 * 16));
+                } else {
+                    CYC_LDS char *p = (CYC_LDS char *)patch + (s * 32 + 8 * g + (lq >> 2)) * 32 + 8 * (lq & 3);
+                    lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                    hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 32)));
+                }
+                Bf[h * HALF + s] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+            }
+            // the patch is rewritten by the next half: reads above must have completed
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    }
+
+    // ---- stream A.  Lane l feeds row l%16 of the row block and the 16-byte chunk l/16 of each
+    // 64-byte step; rows past M re-read row M-1 (their results are never stored).
+    const int row_begin = blockIdx.x * rows_per_wg;
+    const int row_end = (row_begin + rows_per_wg) < M ? (row_begin + rows_per_wg) : M;
+    const int nrb = (row_end - row_begin + RB - 1) / RB;
+    const int64_t row_bytes = (int64_t)K * ES;
+    const int lane_off = kw0 * ES + g * 16;
+    auto row_ptr = [&](int rb) -> const char * {
+        int r = row_begin + rb * RB + lq;
+        r = r < M ? r : M - 1;
+        return A + (int64_t)r * row_bytes + lane_off;
+    };
+    auto fetch = [&](const char *p, int s) -> i32x4 {
+        if (FULL) return *(const i32x4 *)(p + s * 64);
+        i32x4 v = {0, 0, 0, 0};
+        if (kw0 + s * KS + g * CH < K) v = *(const i32x4 *)(p + s * 64);
+        return v;
+    };
+
+    i32x4 ring[DEPTH];
+    const char *p_cur = row_ptr(0);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(p_cur, d);
+
+    for (int rb = 0; rb < nrb; ++rb) {
+        const char *p_next = row_ptr(rb + 1 < nrb ? rb + 1 : rb);
+        acc_t acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const i32x4 a = ring[s % DEPTH];
+            ring[s % DEPTH] = (s + DEPTH < S) ? fetch(p_cur, s + DEPTH) : fetch(p_next, s + DEPTH - S);
+            if (s & 1) acc1 = Mac<I8>::mfma(a, Bf[s], acc1);
+            else acc0 = Mac<I8>::mfma(a, Bf[s], acc0);
+        }
+        p_cur = p_next;
+
+        // ---- join the 8 k-slices in slice order; wave rb%8 does it and emits C_ij
+        red[rb & 1][w][l] = acc0 + acc1;
+        lds_barrier();
+        if (w == (rb & 7)) {
+            acc_t sum = red[rb & 1][0][l];
+#pragma unroll
+            for (int v = 1; v < NWAVES; ++v) sum += red[rb & 1][v][l];
+            // accumulator register r of lane l is row 4*(l/16) + r, column l%16 of the 16x16 tile
+            if (lq < N) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = row_begin + rb * RB + 4 * g + r;
+                    const elem v = sum[r];
+                    if (row < row_end) C[(int64_t)row * N + lq] = v;
+                }
+            }
+        }
+    }
 }
+
+template <bool I8, int S, bool FULL>
+hipError_t launch_one(const Problem &p, int rows_per_wg, hipStream_t s)
+{
+    dim3 grid((unsigned)((p.M + rows_per_wg - 1) / rows_per_wg), (unsigned)p.batch);
+    hipLaunchKernelGGL((ws_narrow_kernel<I8, S, FULL>), grid, dim3(NWAVES * 64), 0, s, (const char *)p.A,
+                       (const char *)p.B, (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC,
+                       rows_per_wg);
+    return hipGetLastError();
+}
+
+template <bool I8>
+hipError_t launch_dtype(const Problem &p, int rows_per_wg, hipStream_t s)
+{
+    const int64_t per_step = (int64_t)NWAVES * (I8 ? 64 : 32);   // k covered by one step of all waves
+    const int steps = (int)((p.K + per_step - 1) / per_step);
+    const bool full = (p.K % per_step) == 0;
+    if (steps <= 8) return full && steps == 8 ? launch_one<I8, 8, true>(p, rows_per_wg, s) : launch_one<I8, 8, false>(p, rows_per_wg, s);
+    if (steps <= 16) return full && steps == 16 ? launch_one<I8, 16, true>(p, rows_per_wg, s) : launch_one<I8, 16, false>(p, rows_per_wg, s);
+    if (steps <= 24) return full && steps == 24 ? launch_one<I8, 24, true>(p, rows_per_wg, s) : launch_one<I8, 24, false>(p, rows_per_wg, s);
+    return full && steps == 32 ? launch_one<I8, 32, true>(p, rows_per_wg, s) : launch_one<I8, 32, false>(p, rows_per_wg, s);
+}
+
+}  // namespace
+
+bool supports_narrow(const Problem &p)
+{
+    const int es = p.i8 ? 1 : 2;
+    const int64_t kmax = (int64_t)NWAVES * 32 * (p.i8 ? 64 : 32);   // 8192 bf16, 16384 int8
+    if (p.N < 1 || p.N > 16 || p.K < 1 || p.K > kmax || p.M < 1) return false;
+    if ((p.K * es) % 16) return false;                    // rows of A must stay 16-byte aligned
+    if (p.M > (1 << 30) || p.batch > 65535) return false;
+    if ((uintptr_t)p.A & 15) return false;
+    if (p.batch > 1 && ((p.strideA * es) & 15)) return false;
+    return true;
+}
+
+bool prefers_narrow(const Problem &p)
+{
+    // worth it only when A dominates: enough rows to amortise loading B into registers
+    return supports_narrow(p) && p.M * p.batch >= 4096 && p.K >= 1024;
+}
+
+hipError_t launch_narrow(const Problem &p, hipStream_t s)
+{
+    if (!supports_narrow(p)) return hipErrorInvalidValue;
+    // one workgroup per compute unit when the problem allows: rows_per_wg ~ total rows / 256
+    int64_t rows = (p.M * p.batch + 255) / 256;
+    rows = (rows + RB - 1) / RB * RB;
+    if (rows < 64) rows = 64;
+    if (rows > p.M) rows = (p.M + RB - 1) / RB * RB;
+    return p.i8 ? launch_dtype<true>(p, (int)rows, s) : launch_dtype<false>(p, (int)rows, s);
+}
+
+}  // namespace cyc

@@ -168,6 +168,49 @@ def test_closed_forms_on_gpu(lib, mode):
         assert torch.equal(C.double(), B.double()), (K, N)
 
 
+# ------------------------------------------------------------- narrow-stream kernel
+NARROW = [  # (batch, M, K, N)
+    (1, 64, 8192, 16), (2, 512, 8192, 16), (1, 256, 2048, 16), (1, 100, 4096, 16), (3, 33, 6144, 16),
+    (1, 128, 1280, 16), (1, 48, 8, 16), (1, 64, 8192, 15), (1, 64, 4096, 1), (2, 40, 1032, 7),
+    (1, 16, 8184, 16), (1, 300, 3072, 9)]
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_narrow_kernel(lib, oracle, mode):
+    os.environ["CYC_FORCE_KERNEL"] = "narrow"
+    try:
+        for n, (batch, M, K, N) in enumerate(NARROW):
+            if mode == "i8":
+                K = K * 2 if K % 16 else K          # int8 rows must stay 16-byte aligned
+            for kind in ("default", "small"):
+                A, B, Ah, Bh = gen(mode, (batch, M, K), (batch, K, N), seed=5000 + n, kind=kind)
+                C0 = torch.empty((batch, M, N), dtype=torch.int32 if mode == "i8" else torch.float32, device=DEV)
+                name = lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C0.data_ptr(), batch, M, K, N, M * K, K * N,
+                                           M * N, lib.CYC_I8_I32 if mode == "i8" else lib.CYC_BF16_F32)
+                assert name == "narrow", (batch, M, K, N, name)
+                C = lib.recurrence_matmul(A, B)
+                for b in range(batch):
+                    Cref = oracle.ws_rowchain(Ah[b], Bh[b], mode)
+                    check(mode, C[b], Cref, Ah[b], Bh[b], exact=(kind == "small"))
+    finally:
+        os.environ.pop("CYC_FORCE_KERNEL", None)
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_narrow_all_ones_and_dispatch(lib, mode):
+    """The batched narrow workload picks the streaming kernel by itself; all-ones gives K."""
+    tdt = torch.int8 if mode == "i8" else torch.bfloat16
+    batch, M, K, N = 2, 4096, 8192, 16
+    A = torch.ones((batch, M, K), dtype=tdt, device=DEV)
+    B = torch.ones((batch, K, N), dtype=tdt, device=DEV)
+    C = torch.empty((batch, M, N), dtype=torch.int32 if mode == "i8" else torch.float32, device=DEV)
+    name = lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, K, N, M * K, K * N, M * N,
+                               lib.CYC_I8_I32 if mode == "i8" else lib.CYC_BF16_F32)
+    assert name == "narrow"
+    lib.recurrence_matmul(A, B, out=C)
+    assert bool((C == K).all())
+
+
 # ------------------------------------------------------------ determinism and batching
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
 def test_run_to_run_bit_identical(lib, mode):

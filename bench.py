@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the weight-stationary recurrence matmul on one MI355X.
+
+A step is one pass of the whole hot path (load the stationary A, stream B, run the k chains,
+emit C) over one synthetic workload, i.e. one call of the C ABI.  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu] [--no-extra]
+                  [--copy-calibration]
+
+The headline workload is the 8192^3 bf16 case (compute bound, MFMA roofline); the int8 8192^3
+and the batched narrow-stream cases are measured after it and reported under "workloads".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# published MI355X peaks used for the roofline fractions
+PEAK = {"bf16": (2500.0, "TFLOP/s"), "i8": (5000.0, "TOP/s")}
+HBM_PEAK_GBS = 8000.0
+ROTATE = 3     # distinct (A, B, C) sets cycled through, so operands are not served from cache
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3_bf16_8192")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-extra", action="store_true", help="measure only the headline workload")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one 1 GiB device copy (reference point for HBM traffic counters)")
+    return ap.parse_args()
+
+
+def measure(lib, torch, w, steps, warmup, sets):
+    """Time `steps` launches; returns (wall ms per step, mean kernel ms by events, kernel name)."""
+    from datagen import ws_inputs
+    dev = "cuda:0"
+    data = []
+    for r in range(sets):
+        wr = ws_inputs.Workload(w.name, w.dtype, w.batch, w.M, w.K, w.N, w.dist, w.param, w.seed + 1000 * r)
+        A, B = ws_inputs.make_inputs(wr, dev)
+        cshape = (w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N)
+        C = torch.empty(cshape, dtype=torch.int32 if w.dtype == "i8" else torch.float32, device=dev)
+        data.append((A, B, C))
+    A, B, C = data[0]
+    dt = lib.CYC_I8_I32 if w.dtype == "i8" else lib.CYC_BF16_F32
+    kname = lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), w.batch, w.M, w.K, w.N,
+                                w.M * w.K, w.K * w.N, w.M * w.N, dt)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        a, b, c = data[i % sets]
+        st = lib.cyc_recurrence_matmul_batched(a.data_ptr(), b.data_ptr(), c.data_ptr(), w.batch, w.M, w.K, w.N,
+                                               w.M * w.K, w.K * w.N, w.M * w.N, dt, stream.cuda_stream)
+        if st != 0:
+            raise RuntimeError(lib.cyc_status_string(st))
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    # the library is launched on torch's current stream, so torch events bracket its kernels
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    kern_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+    del data
+    torch.cuda.empty_cache()
+    return wall_ms, kern_ms, kname
+
+
+def roofline(w, kern_ms):
+    if w.N <= 16:   # HBM bound: algorithmic bytes = A and B read once, C written once
+        ach = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
+        return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+    peak, unit = PEAK[w.dtype]
+    ach = w.ops / (kern_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": round(ach, 1), "peak": peak, "unit": unit,
+            "frac": round(ach / peak, 4), "traffic": None}
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The oracle's row-chain form, as it stands, on a bounded block of the same workload."""
+    import numpy as np
+    import torch
+    from datagen import ws_inputs
+    from oracle import ws_oracle
+    mode = "i8" if w.dtype == "i8" else "bf16"
+
+    def block(rows, cols):
+        wr = ws_inputs.Workload(w.name, w.dtype, 1, rows, w.K, cols, w.dist, w.param, w.seed)
+        A, B = ws_inputs.make_inputs(wr, "cpu")
+        if mode == "bf16":
+            return ws_oracle.bf16_bits(A), ws_oracle.bf16_bits(B)
+        return A.numpy(), B.numpy()
+
+    cols = min(w.N, 1024)
+    A, B = block(64, cols)
+    t0 = time.perf_counter()
+    ws_oracle.ws_rowchain(A, B, mode)
+    rate = 64 * w.K * cols / max(time.perf_counter() - t0, 1e-6)        # cell-steps per second
+    rows = int(min(max(64, rate * budget_s / (w.K * cols)), 8192)) // 16 * 16
+    A, B = block(rows, cols)
+    t0 = time.perf_counter()
+    ws_oracle.ws_rowchain(A, B, mode)
+    dt = time.perf_counter() - t0
+    unit = "TOP/s" if mode == "i8" else "TFLOP/s"
+    return {"value": round(2.0 * rows * w.K * cols / dt / 1e12, 6), "unit": unit, "cores": ws_oracle.threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"row-chain oracle on a {rows} x {w.K} x {cols} block (first rows of A, first columns of B) "
+                      f"of {w.name}, same seed and distribution"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on exactly one GPU (no collectives, no sharding); got --gpus {args.gpus}",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2511_09987_amd as lib
+    from datagen import ws_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    if args.workload not in ws_inputs.WORKLOADS:
+        print(f"bench.py: unknown workload {args.workload}; choose from {sorted(ws_inputs.WORKLOADS)}", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    w = ws_inputs.WORKLOADS[args.workload]
+    torch.cuda.synchronize()
+    wall_ms, kern_ms, kname = measure(lib, torch, w, args.steps, args.warmup, ROTATE)
+    unit = "GB/s" if w.N <= 16 else PEAK[w.dtype][1]
+    value = (w.algorithmic_bytes / 1e9 if w.N <= 16 else w.ops / 1e12) / (wall_ms * 1e-3)
+
+    out = {
+        "metric": "recurrence matmul TFLOP/s (TOP/s int8) and % of MI355X MFMA/HBM roofline",
+        "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "int8", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "M": w.M, "K": w.K, "N": w.N, "kernel": kname,
+                   "accumulate": "fp32" if w.dtype == "bf16" else "int32", "seed": w.seed,
+                   "operand_sets_rotated": ROTATE},
+        "roofline": dict(roofline(w, kern_ms), kernel=kname, kernel_ms=round(kern_ms, 5)),
+    }
+
+    if not args.no_extra:
+        extra = {}
+        for name in ("c3_bf16_8192", "c4_i8_8192", "c5_bf16_narrow", "c2_bf16_512", "c1_i8_64"):
+            if name == w.name:
+                continue
+            wx = ws_inputs.WORKLOADS[name]
+            sets = ROTATE if wx.algorithmic_bytes * ROTATE < 40e9 else 1
+            wms, kms, kn = measure(lib, torch, wx, args.steps, args.warmup, sets)
+            rf = roofline(wx, kms)
+            extra[name] = {"kernel": kn, "ms_per_step": round(wms, 5), "kernel_ms": round(kms, 5),
+                           "achieved": rf["achieved"], "unit": rf["unit"], "bound": rf["bound"], "frac": rf["frac"]}
+        out["workloads"] = extra
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration_bytes"] = {"read": src.numel() * 4, "written": src.numel() * 4}
+        del src, dst
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot produce a whole 8192^3 product in test time, so each workload is checked
+ (a) element by element on sampled blocks of C that the row-chain oracle computes from the
+     matching rows of A and columns of B (fixed corner blocks plus seeded origins that are not
+     multiples of any kernel tile, so the blocks straddle tile, wave and fragment boundaries);
+ (b) as a whole through identities that hold at any size: the sum identity
+     sum_ij C_ij = sum_k (sum_i A_ik)(sum_j B_kj) and Freivalds' check C x = A (B x) for seeded
+     +-1 vectors x.  For int8 both are exact (all quantities are integers below 2^53 and are
+     evaluated in fp64 on integers); for bf16 they are gross-error detectors with a bound.
+"""
+import numpy as np
+import pytest
+import torch
+
+from datagen import ws_inputs
+from helpers import BF16_TOL, bits_to_f64, rel_err, torch_bf16_to_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2511_09987_amd as pkg
+    return pkg
+
+
+def host(t, mode):
+    return t.cpu().numpy() if mode == "i8" else torch_bf16_to_bits(t)
+
+
+def block_origins(M, N, size, seed, extra=3):
+    rng = np.random.default_rng(seed)
+    org = [(0, 0), (M - size, N - size)]
+    for _ in range(extra):
+        org.append((int(rng.integers(1, M - size)) | 1, int(rng.integers(1, N - size)) | 1))   # odd: never tile aligned
+    return org
+
+
+def check_blocks(oracle, mode, A, B, C, size, seed, exact):
+    M, N = C.shape
+    worst = 0.0
+    for (i0, j0) in block_origins(M, N, size, seed):
+        Ah = host(A[i0:i0 + size, :], mode)
+        Bh = host(B[:, j0:j0 + size].contiguous(), mode)
+        Cref = oracle.ws_rowchain(Ah, Bh, mode)
+        Cg = C[i0:i0 + size, j0:j0 + size].cpu().numpy()
+        if exact:
+            assert np.array_equal(Cg, Cref), f"block at ({i0},{j0}): {int((Cg != Cref).sum())} elements differ"
+        else:
+            err = rel_err(Cg, Cref, bits_to_f64(Ah), bits_to_f64(Bh))
+            worst = max(worst, err)
+            assert err <= BF16_TOL, f"block at ({i0},{j0}): relative error {err:.3e}"
+            assert err <= A.shape[1] * 2.0 ** -23, f"block at ({i0},{j0}): error {err:.3e} suspicious for fp32 chains"
+    return worst
+
+
+def test_config4_int8_8192_blocks_and_checksums(lib, oracle):
+    w = ws_inputs.WORKLOADS["c4_i8_8192"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C = lib.recurrence_matmul(A, B)
+    assert lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), 1, w.M, w.K, w.N, 0, 0, 0,
+                               lib.CYC_I8_I32) == "mfma256"
+    check_blocks(oracle, "i8", A, B, C, 256, seed=44, exact=True)
+    # sum identity, exact: |sum| <= 8192^3 * 127^2 < 2^53
+    Ad, Bd, Cd = A.double(), B.double(), C.double()
+    lhs = Cd.sum().item()
+    rhs = (Ad.sum(dim=0) * Bd.sum(dim=1)).sum().item()
+    assert lhs == rhs
+    # Freivalds with +-1 vectors: every entry of C x and A (B x) is an integer below 2^53
+    g = torch.Generator(device="cpu").manual_seed(4)
+    for _ in range(8):
+        x = (torch.randint(0, 2, (w.N, 1), generator=g, dtype=torch.int64) * 2 - 1).double().to(DEV)
+        assert torch.equal(Cd @ x, Ad @ (Bd @ x))
+    # and from the left, which catches a wrong row as the right-hand check catches a wrong column
+    for _ in range(4):
+        y = (torch.randint(0, 2, (1, w.M), generator=g, dtype=torch.int64) * 2 - 1).double().to(DEV)
+        assert torch.equal(y @ Cd, (y @ Ad) @ Bd)
+
+
+def test_config3_bf16_8192_blocks_and_checksums(lib, oracle):
+    w = ws_inputs.WORKLOADS["c3_bf16_8192"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C = lib.recurrence_matmul(A, B)
+    assert lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), 1, w.M, w.K, w.N, 0, 0, 0,
+                               lib.CYC_BF16_F32) == "mfma256"
+    worst = check_blocks(oracle, "bf16", A, B, C, 256, seed=33, exact=False)
+    print(f"config 3 worst sampled relative error {worst:.3e}")
+    # Freivalds in fp64 as a whole-matrix gross-error detector: |C x - A (B x)|_i <= tol * (|A| (|B| |x|))_i
+    Ad, Bd, Cd = A.double(), B.double(), C.double()
+    g = torch.Generator(device="cpu").manual_seed(3)
+    for _ in range(4):
+        x = (torch.randint(0, 2, (w.N, 1), generator=g, dtype=torch.int64) * 2 - 1).double().to(DEV)
+        lhs, rhs = Cd @ x, Ad @ (Bd @ x)
+        bound = Ad.abs() @ (Bd.abs() @ x.abs())
+        assert bool(((lhs - rhs).abs() <= 1e-3 * bound).all())
+
+
+def test_bf16_8192_small_integer_data_is_bit_exact(lib, oracle):
+    """Integer-valued bf16 inputs of magnitude <= 8: all partial sums are integers below 2^24, so
+    the MFMA kernel must agree with the oracle bit for bit whatever its summation order, and the
+    whole product can be compared exactly with an fp64 matmul."""
+    M = K = N = 8192
+    A = ws_inputs.small_int_bf16((M, K), 8, 303, 0, DEV)
+    B = ws_inputs.small_int_bf16((K, N), 8, 303, 1, DEV)
+    C = lib.recurrence_matmul(A, B)
+    check_blocks(oracle, "bf16", A, B, C, 256, seed=34, exact=True)
+    ref = A.double() @ B.double()          # exact: integers below 2^53
+    assert torch.equal(C.double(), ref)
+
+
+def test_config5_narrow_batch_rows_and_checksum(lib, oracle):
+    w = ws_inputs.WORKLOADS["c5_bf16_narrow"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C = lib.recurrence_matmul(A, B)
+    assert lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), w.batch, w.M, w.K, w.N, w.M * w.K,
+                               w.K * w.N, w.M * w.N, lib.CYC_BF16_F32) == "narrow"
+    rng = np.random.default_rng(55)
+    worst = 0.0
+    for b in (0, 13, 31):
+        Bh = torch_bf16_to_bits(B[b])
+        for i0 in (0, w.M - 192, int(rng.integers(1, w.M - 192)) | 1):
+            Ah = torch_bf16_to_bits(A[b, i0:i0 + 192, :])
+            Cref = oracle.ws_rowchain(Ah, Bh, "bf16")
+            err = rel_err(C[b, i0:i0 + 192].cpu().numpy(), Cref, bits_to_f64(Ah), bits_to_f64(Bh))
+            worst = max(worst, err)
+            assert err <= BF16_TOL and err <= w.K * 2.0 ** -23, (b, i0, err)
+    print(f"config 5 worst sampled relative error {worst:.3e}")
+    # every batch element against an fp64 product (gross errors anywhere in the 32 grids)
+    for b in range(w.batch):
+        ref = A[b].double() @ B[b].double()
+        den = A[b].double().abs() @ B[b].double().abs()
+        assert bool(((C[b].double() - ref).abs() <= 1e-3 * den).all()), b
+
+
+def test_config5_small_integer_data_is_bit_exact(lib):
+    w = ws_inputs.WORKLOADS["c5_bf16_narrow"]
+    A = ws_inputs.small_int_bf16((w.batch, w.M, w.K), 8, 505, 0, DEV)
+    B = ws_inputs.small_int_bf16((w.batch, w.K, w.N), 8, 505, 1, DEV)
+    C = lib.recurrence_matmul(A, B)
+    for b in range(w.batch):
+        assert torch.equal(C[b].double(), A[b].double() @ B[b].double()), b

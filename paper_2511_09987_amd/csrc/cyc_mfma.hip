@@ -183,20 +183,23 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    const int nkt = K / C::BKE;
-    issue(0);
-    tile_fence();
-
-    for (int kt = 0; kt < nkt; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nkt) issue(cur ^ 1);
-        const int sb = cur * C::STAGE;
+    // ---- main loop.  A k-tile (4 MFMA k-steps) is consumed in two halves.  The fragments of one
+    // half (2 k-steps: 2*TM A fragments, 2*TN B fragments) sit in one of two register sets; while the
+    // MFMAs of a half run from one set, the LDS reads of the following half fill the other, so the
+    // matrix pipe has queued work across the workgroup barrier.  Per k-tile kt:
+    //   half 0 of kt from set 0   | read half 1 of kt   -> set 1
+    //   fence: tile kt+1 has landed, every wave is done reading tile kt
+    //   start copying tile kt+2 into the stage tile kt occupied
+    //   half 1 of kt from set 1   | read half 0 of kt+1 -> set 0
+    i32x4 fa[2][2][TM];
+    i32x4 fb[2][2][TN];
+    auto read_half = [&](int set, int stage, int h) {
+        const int sb = stage * C::STAGE;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            i32x4 fa[TM];
-            i32x4 fb[TN];
+        for (int q = 0; q < 2; ++q) {
+            const int ks = h * 2 + q;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *(CYC_LDS i32x4 *)(lds + sb + offA[ks] + i * 32 * 128);
+            for (int i = 0; i < TM; ++i) fa[set][q][i] = *(CYC_LDS i32x4 *)(lds + sb + offA[ks] + i * 32 * 128);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 i32x2 lo, hi;
@@ -204,19 +207,46 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
                     lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[j] + (ks * 32) * RB));
                     hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[j] + (ks * 32 + 8) * RB));
                 } else {
-                    bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16) * RB));
-                    bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16 + 4) * RB));
-                    lo = __builtin_bit_cast(i32x2, a);
-                    hi = __builtin_bit_cast(i32x2, b);
+                    lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16) * RB)));
+                    hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16 + 4) * RB)));
                 }
-                fb[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+                fb[set][q][j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
             }
+        }
+    };
+    auto mma_half = [&](int set) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Acc<C::I8v>::mfma(fa[i], fb[j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
+    };
+    // ask the scheduler to alternate matrix instructions and LDS reads within the current region
+    auto interleave = [&]() {
+#pragma unroll
+        for (int x = 0; x < 2 * TM * TN; ++x) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
         }
-        tile_fence();
+    };
+
+    const int nkt = K / C::BKE;
+    issue(0);
+    tile_fence();                  // tile 0 in LDS
+    if (nkt > 1) issue(1);
+    read_half(0, 0, 0);
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int cur = kt & 1;
+        read_half(1, cur, 1);
+        mma_half(0);
+        interleave();
+        tile_fence();              // own copies of tile kt+1 and own reads of tile kt done; all waves meet
+        if (kt + 2 < nkt) issue(cur);
+        read_half(0, cur ^ 1, 0);   // after the last tile this reads stale LDS that nobody uses
+        mma_half(1);
+        interleave();
     }
 
     // ---- C_ij <- [i,k_end]_C.  Accumulator register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,

@@ -73,14 +73,14 @@ __device__ __forceinline__ int swzB(int k)
     return C::CPR >= 16 ? (k & 7) << 1 : ((k >> 1) & 3) << 1;
 }
 
-// 64 lanes x 16 bytes go from global memory straight into LDS at lds_addr + lane*16
-// (lds_addr wave-uniform).  Written as asm so that the compiler does not make every later
-// LDS read wait for these copies; completion is awaited explicitly with tile_fence().
-__device__ __forceinline__ void async_copy16(const char *g, uint32_t lds_addr)
+// 64 lanes x 16 bytes go from global memory (wave-uniform base + per-lane 32-bit offset) straight
+// into LDS at lds_addr + lane*16 (lds_addr wave-uniform).  Written as asm so that the compiler does
+// not make every later LDS read wait for these copies; completion is awaited with tile_fence().
+__device__ __forceinline__ void async_copy16(const char *base, uint32_t lane_off, uint32_t lds_addr)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr), "v"(g)
+                 : "s"(lds_addr), "v"(lane_off), "s"(base)
                  : "memory", "m0");
 }
 // all of this wave's copies and LDS reads are done; then meet the other waves
@@ -121,35 +121,33 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     B += (int64_t)blockIdx.y * sB * ES;
     Cout += (int64_t)blockIdx.y * sC * 4;
 
-    // ---- global source of each 16-byte chunk this lane copies per k-tile
-    const char *gA[C::AI];
-    const char *gB[C::BI];
+    // ---- global source of each 16-byte chunk this lane copies per k-tile: a wave-uniform base
+    // that advances with the k-tile, plus a fixed per-lane byte offset (below 2^32, see supports_mfma)
+    const char *baseA = A + ((int64_t)m0 * K) * ES;
+    const char *baseB = B + (int64_t)n0 * ES;
+    const int64_t stepB = (int64_t)C::BKE * N * ES;
+    uint32_t voffA[C::AI], voffB[C::BI];
 #pragma unroll
     for (int t = 0; t < C::AI; ++t) {
         int r = (w * C::AI + t) * 8 + (l >> 3);
         int c = (l & 7) ^ swzA(r);
-        gA[t] = A + ((int64_t)(m0 + r) * K) * ES + c * 16;
+        voffA[t] = (uint32_t)r * (uint32_t)(K * ES) + c * 16;
     }
 #pragma unroll
     for (int t = 0; t < C::BI; ++t) {
         int kr = (w * C::BI + t) * C::RPI + l / C::CPR;
         int c = (l % C::CPR) ^ swzB<C>(kr);
-        gB[t] = B + ((int64_t)kr * N + n0) * ES + c * 16;
+        voffB[t] = (uint32_t)kr * (uint32_t)(N * ES) + c * 16;
     }
-    const int64_t stepB = (int64_t)C::BKE * N * ES;
-
-    auto issue = [&](int stage) {
+    // copy number x (0 .. AI+BI-1) of this wave for k-tile `ktile` into LDS stage `stage`
+    auto issue_one = [&](int x, int stage, int ktile) {
         const uint32_t base = lds_base + stage * C::STAGE;
+        if (x < C::AI) async_copy16(baseA + (int64_t)ktile * 128, voffA[x], base + (w * C::AI + x) * 1024);
+        else async_copy16(baseB + (int64_t)ktile * stepB, voffB[x - C::AI], base + C::A_BYTES + (w * C::BI + x - C::AI) * 1024);
+    };
+    auto issue = [&](int stage, int ktile) {
 #pragma unroll
-        for (int t = 0; t < C::AI; ++t) {
-            async_copy16(gA[t], base + (w * C::AI + t) * 1024);
-            gA[t] += 128;
-        }
-#pragma unroll
-        for (int t = 0; t < C::BI; ++t) {
-            async_copy16(gB[t], base + C::A_BYTES + (w * C::BI + t) * 1024);
-            gB[t] += stepB;
-        }
+        for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, stage, ktile);
     };
 
     // ---- LDS read offsets of this lane's fragments
@@ -189,65 +187,69 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // matrix pipe has queued work across the workgroup barrier.  Per k-tile kt:
     //   half 0 of kt from set 0   | read half 1 of kt   -> set 1
     //   fence: tile kt+1 has landed, every wave is done reading tile kt
-    //   start copying tile kt+2 into the stage tile kt occupied
-    //   half 1 of kt from set 1   | read half 0 of kt+1 -> set 0
+    //   half 1 of kt from set 1   | read half 0 of kt+1 -> set 0 | copy tile kt+2 into kt's stage
+    // The copies are issued one at a time between groups of MFMAs: eight waves issuing all their
+    // copies at once would queue behind one another in the address unit and hold their MFMAs back.
     i32x4 fa[2][2][TM];
     i32x4 fb[2][2][TN];
-    auto read_half = [&](int set, int stage, int h) {
+    constexpr int NREAD = 2 * (TM + TN);   // fragment reads per half
+    constexpr int NMMA = 2 * TM * TN;      // MFMAs per half
+    constexpr int NG = C::AI + C::BI;      // groups per half = copies per wave per k-tile
+    // fragment read number r of a half: k-step q = r / (TM+TN); B fragments first, then A
+    auto read_one = [&](int r, int set, int stage, int h) {
         const int sb = stage * C::STAGE;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int ks = h * 2 + q;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[set][q][i] = *(CYC_LDS i32x4 *)(lds + sb + offA[ks] + i * 32 * 128);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                i32x2 lo, hi;
-                if (C::I8v) {
-                    lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[j] + (ks * 32) * RB));
-                    hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[j] + (ks * 32 + 8) * RB));
-                } else {
-                    lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16) * RB)));
-                    hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[j] + (ks * 16 + 4) * RB)));
-                }
-                fb[set][q][j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+        const int q = r / (TM + TN), e = r % (TM + TN), ks = h * 2 + q;
+        if (e < TN) {
+            i32x2 lo, hi;
+            if (C::I8v) {
+                lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[e] + (ks * 32) * RB));
+                hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[e] + (ks * 32 + 8) * RB));
+            } else {
+                lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[e] + (ks * 16) * RB)));
+                hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[e] + (ks * 16 + 4) * RB)));
             }
+            fb[set][q][e] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+        } else {
+            fa[set][q][e - TN] = *(CYC_LDS i32x4 *)(lds + sb + offA[ks] + (e - TN) * 32 * 128);
         }
     };
-    auto mma_half = [&](int set) {
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
+    // MFMA number m of a half
+    auto mma_one = [&](int m, int set) {
+        const int q = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
+        acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
     };
-    // ask the scheduler to alternate matrix instructions and LDS reads within the current region
-    auto interleave = [&]() {
+    // One half: NG groups; group g holds its share of the MFMAs of `set`, of the reads that fill
+    // the other set (front-loaded: all reads are issued in the first groups), and at most one copy.
+    auto half = [&](int set, int rd_stage, int rd_half, bool copies, int cp_stage, int cp_tile) {
+        constexpr int RPG = (NREAD + NG - 3) / (NG - 2);     // reads per group, none in the last two groups
 #pragma unroll
-        for (int x = 0; x < 2 * TM * TN; ++x) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+        for (int g = 0; g < NG; ++g) {
+            if (copies) issue_one(g, cp_stage, cp_tile);
+#pragma unroll
+            for (int r = g * RPG; r < (g + 1) * RPG && r < NREAD; ++r) read_one(r, set ^ 1, rd_stage, rd_half);
+#pragma unroll
+            for (int m = g * NMMA / NG; m < (g + 1) * NMMA / NG; ++m) mma_one(m, set);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     const int nkt = K / C::BKE;
-    issue(0);
+    issue(0, 0);
     tile_fence();                  // tile 0 in LDS
-    if (nkt > 1) issue(1);
-    read_half(0, 0, 0);
+    if (nkt > 1) issue(1, 1);
+#pragma unroll
+    for (int r = 0; r < NREAD; ++r) read_one(r, 0, 0, 0);
 
     for (int kt = 0; kt < nkt; ++kt) {
         const int cur = kt & 1;
-        read_half(1, cur, 1);
-        mma_half(0);
-        interleave();
+        half(0, cur, 1, false, 0, 0);
         tile_fence();              // own copies of tile kt+1 and own reads of tile kt done; all waves meet
-        if (kt + 2 < nkt) issue(cur);
-        read_half(0, cur ^ 1, 0);   // after the last tile this reads stale LDS that nobody uses
-        mma_half(1);
-        interleave();
+        // after the last tiles there is nothing left to fetch: re-copy the final tile into the free
+        // stage (never read) and read a stale half (never used) rather than branch around them
+        const int nxt = kt + 2 < nkt ? kt + 2 : nkt - 1;
+        half(1, cur ^ 1, 0, true, cur, nxt);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- C_ij <- [i,k_end]_C.  Accumulator register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
     // column l%32 of its 32x32 tile: for fixed r, 32 lanes write 128 contiguous bytes.
@@ -287,6 +289,8 @@ bool supports_mfma(const Problem &p, int tile)
     if (p.K <= 0 || p.M % tile || p.N % tile || p.K % bke) return false;
     if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
     if ((p.M / tile) * (p.N / tile) > (1 << 30)) return false;
+    // per-lane byte offsets inside a tile's rows are kept in 32 bits
+    if (p.K * es * 256 + 128 >= ((int64_t)1 << 32) || p.N * es * 128 + 512 >= ((int64_t)1 << 32)) return false;
     if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C) & 15) return false;
     if (p.batch > 1 && (((p.strideA * es) | (p.strideB * es) | (p.strideC * 4)) & 15)) return false;
     return true;

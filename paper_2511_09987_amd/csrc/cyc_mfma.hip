@@ -52,14 +52,15 @@ struct Cfg {
     static constexpr int A_BYTES = BM * 128;
     static constexpr int RB = BN * ES;             // bytes per row of the B tile
     static constexpr int B_BYTES = BKE * RB;
-    static constexpr int STAGE = A_BYTES + B_BYTES;
+    static constexpr int NSA = 2, NSB = 3;         // LDS stages: A is double, B triple buffered
+    static constexpr int LDS_BYTES = NSA * A_BYTES + NSB * B_BYTES;
     static constexpr int CPR = RB / 16;            // 16-byte chunks per B row
     static constexpr int RPI = 64 / CPR;           // B rows covered by one wave-wide 1 KiB load
     static constexpr int AI = BM / 8 / NW;         // 1 KiB A loads per wave per k-tile
     static constexpr int BI = B_BYTES / 1024 / NW; // 1 KiB B loads per wave per k-tile
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
     static_assert(BM % (8 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "loads must divide evenly over waves");
-    static_assert(CPR <= 64 && 2 * STAGE <= 160 * 1024, "tile does not fit");
+    static_assert(CPR <= 64 && LDS_BYTES <= 160 * 1024, "tile does not fit");
 };
 
 // LDS placement.  A tile: row r (128 bytes) at r*128, its chunk c stored in slot c ^ swzA(r).
@@ -83,10 +84,12 @@ __device__ __forceinline__ void async_copy16(const char *base, uint32_t lane_off
                  : "s"(lds_addr), "v"(lane_off), "s"(base)
                  : "memory", "m0");
 }
-// all of this wave's copies and LDS reads are done; then meet the other waves
+// This wave's LDS reads are done and all but its newest `keep` copies have landed (copies retire in
+// issue order); then meet the other waves.
+template <int KEEP>
 __device__ __forceinline__ void tile_fence()
 {
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(KEEP) : "memory");
 }
 
 template <class C>
@@ -95,7 +98,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
                                                         int64_t sB, int64_t sC, int tiles_m, int tiles_n)
 {
     constexpr int ES = C::ES, RB = C::RB, TM = C::TM, TN = C::TN;
-    __shared__ __attribute__((aligned(1024))) char lds_raw[2 * C::STAGE];
+    __shared__ __attribute__((aligned(1024))) char lds_raw[C::LDS_BYTES];
     CYC_LDS char *lds = (CYC_LDS char *)lds_raw;
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
@@ -139,15 +142,13 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         int c = (l % C::CPR) ^ swzB<C>(kr);
         voffB[t] = (uint32_t)kr * (uint32_t)(N * ES) + c * 16;
     }
-    // copy number x (0 .. AI+BI-1) of this wave for k-tile `ktile` into LDS stage `stage`
-    auto issue_one = [&](int x, int stage, int ktile) {
-        const uint32_t base = lds_base + stage * C::STAGE;
-        if (x < C::AI) async_copy16(baseA + (int64_t)ktile * 128, voffA[x], base + (w * C::AI + x) * 1024);
-        else async_copy16(baseB + (int64_t)ktile * stepB, voffB[x - C::AI], base + C::A_BYTES + (w * C::BI + x - C::AI) * 1024);
-    };
-    auto issue = [&](int stage, int ktile) {
-#pragma unroll
-        for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, stage, ktile);
+    // LDS map: NSA stages of the A tile, then NSB stages of the B tile
+    constexpr int LDS_B0 = C::NSA * C::A_BYTES;
+    // copy number x of this wave's share of k-tile `ktile`: x < AI is a piece of the A tile (into A
+    // stage sa), otherwise a piece of the B tile (into B stage sb)
+    auto issue_one = [&](int x, int sa, int sb, int ktile) {
+        if (x < C::AI) async_copy16(baseA + (int64_t)ktile * 128, voffA[x], lds_base + sa * C::A_BYTES + (w * C::AI + x) * 1024);
+        else async_copy16(baseB + (int64_t)ktile * stepB, voffB[x - C::AI], lds_base + LDS_B0 + sb * C::B_BYTES + (w * C::BI + x - C::AI) * 1024);
     };
 
     // ---- LDS read offsets of this lane's fragments
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         for (int tn = 0; tn < TN; ++tn) {
             int ncol = wn * (TN * 32) + tn * 32 + colhalf * 16 + (C::I8v ? 8 * (lq & 1) : 4 * (lq & 3));
             int byte = ncol * ES;
-            offB[tn] = C::A_BYTES + krow * RB + ((((byte >> 4)) ^ swzB<C>(krow)) << 4) + (byte & 15);
+            offB[tn] = LDS_B0 + krow * RB + ((((byte >> 4)) ^ swzB<C>(krow)) << 4) + (byte & 15);
         }
     }
 
@@ -185,32 +186,35 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // half (2 k-steps: 2*TM A fragments, 2*TN B fragments) sit in one of two register sets; while the
     // MFMAs of a half run from one set, the LDS reads of the following half fill the other, so the
     // matrix pipe has queued work across the workgroup barrier.  Per k-tile kt:
-    //   half 0 of kt from set 0   | read half 1 of kt   -> set 1
+    //   half 0 of kt from set 0 | read half 1 of kt   -> set 1 | copy B of tile kt+2
     //   fence: tile kt+1 has landed, every wave is done reading tile kt
-    //   half 1 of kt from set 1   | read half 0 of kt+1 -> set 0 | copy tile kt+2 into kt's stage
-    // The copies are issued one at a time between groups of MFMAs: eight waves issuing all their
-    // copies at once would queue behind one another in the address unit and hold their MFMAs back.
+    //   half 1 of kt from set 1 | read half 0 of kt+1 -> set 0 | copy A of tile kt+2
+    // The address unit needs 16 cycles per wave-wide copy, which over all waves is half the MFMA time
+    // of a k-tile, and a wave that cannot issue its copy cannot issue its MFMAs either.  Hence the
+    // copies are spread over both halves, one per group of MFMAs.  B can be fetched before the fence
+    // because it has a third stage: tile kt+2 goes where tile kt-1 was, which nobody reads any more.
     i32x4 fa[2][2][TM];
     i32x4 fb[2][2][TN];
     constexpr int NREAD = 2 * (TM + TN);   // fragment reads per half
     constexpr int NMMA = 2 * TM * TN;      // MFMAs per half
-    constexpr int NG = C::AI + C::BI;      // groups per half = copies per wave per k-tile
+    constexpr int NG = 8;                  // groups per half
+    static_assert(C::AI <= NG && C::BI <= NG, "one copy per group");
     // fragment read number r of a half: k-step q = r / (TM+TN); B fragments first, then A
-    auto read_one = [&](int r, int set, int stage, int h) {
-        const int sb = stage * C::STAGE;
+    auto read_one = [&](int r, int set, int sa, int sb, int h) {
         const int q = r / (TM + TN), e = r % (TM + TN), ks = h * 2 + q;
         if (e < TN) {
+            const int o = sb * C::B_BYTES + offB[e];
             i32x2 lo, hi;
             if (C::I8v) {
-                lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[e] + (ks * 32) * RB));
-                hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + sb + offB[e] + (ks * 32 + 8) * RB));
+                lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + o + (ks * 32) * RB));
+                hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + o + (ks * 32 + 8) * RB));
             } else {
-                lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[e] + (ks * 16) * RB)));
-                hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + sb + offB[e] + (ks * 16 + 4) * RB)));
+                lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + o + (ks * 16) * RB)));
+                hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + o + (ks * 16 + 4) * RB)));
             }
             fb[set][q][e] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
         } else {
-            fa[set][q][e - TN] = *(CYC_LDS i32x4 *)(lds + sb + offA[ks] + (e - TN) * 32 * 128);
+            fa[set][q][e - TN] = *(CYC_LDS i32x4 *)(lds + sa * C::A_BYTES + offA[ks] + (e - TN) * 32 * 128);
         }
     };
     // MFMA number m of a half
@@ -218,36 +222,43 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         const int q = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
         acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
     };
-    // One half: NG groups; group g holds its share of the MFMAs of `set`, of the reads that fill
-    // the other set (front-loaded: all reads are issued in the first groups), and at most one copy.
-    auto half = [&](int set, int rd_stage, int rd_half, bool copies, int cp_stage, int cp_tile) {
-        constexpr int RPG = (NREAD + NG - 3) / (NG - 2);     // reads per group, none in the last two groups
+    // One half: NG groups; group g holds its share of the MFMAs of `set`, of the reads that fill the
+    // other set (front-loaded: none in the last two groups), and at most one copy.
+    auto half = [&](int set, int rd_sa, int rd_sb, int rd_half, int cp_first, int cp_count, int cp_sa, int cp_sb, int cp_tile) {
+        constexpr int RPG = (NREAD + NG - 3) / (NG - 2);
 #pragma unroll
         for (int g = 0; g < NG; ++g) {
-            if (copies) issue_one(g, cp_stage, cp_tile);
+            if (g < cp_count) issue_one(cp_first + g, cp_sa, cp_sb, cp_tile);
 #pragma unroll
-            for (int r = g * RPG; r < (g + 1) * RPG && r < NREAD; ++r) read_one(r, set ^ 1, rd_stage, rd_half);
+            for (int r = g * RPG; r < (g + 1) * RPG && r < NREAD; ++r) read_one(r, set ^ 1, rd_sa, rd_sb, rd_half);
 #pragma unroll
             for (int m = g * NMMA / NG; m < (g + 1) * NMMA / NG; ++m) mma_one(m, set);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
 
+    // Beyond the last tile there is nothing left to fetch or read: the final tile is copied again
+    // into a stage nobody reads and a stale half is read into registers nobody uses, rather than
+    // branch around the copies and reads.
     const int nkt = K / C::BKE;
-    issue(0, 0);
-    tile_fence();                  // tile 0 in LDS
-    if (nkt > 1) issue(1, 1);
+    const int last = nkt - 1;
+    auto tile_at = [&](int t) { return t < last ? t : last; };
 #pragma unroll
-    for (int r = 0; r < NREAD; ++r) read_one(r, 0, 0, 0);
+    for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, 0, 0, 0);
+    tile_fence<0>();               // tile 0 in LDS
+#pragma unroll
+    for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, 1, 1, tile_at(1));
+#pragma unroll
+    for (int r = 0; r < NREAD; ++r) read_one(r, 0, 0, 0, 0);
 
+    int sb0 = 0;                   // B stage of tile kt; tile kt+1 is in sb1, tile kt+2 goes to sb2
     for (int kt = 0; kt < nkt; ++kt) {
-        const int cur = kt & 1;
-        half(0, cur, 1, false, 0, 0);
-        tile_fence();              // own copies of tile kt+1 and own reads of tile kt done; all waves meet
-        // after the last tiles there is nothing left to fetch: re-copy the final tile into the free
-        // stage (never read) and read a stale half (never used) rather than branch around them
-        const int nxt = kt + 2 < nkt ? kt + 2 : nkt - 1;
-        half(1, cur ^ 1, 0, true, cur, nxt);
+        const int sa0 = kt & 1, sa1 = sa0 ^ 1;
+        const int sb1 = sb0 == 2 ? 0 : sb0 + 1, sb2 = sb1 == 2 ? 0 : sb1 + 1;
+        half(0, sa0, sb0, 1, C::AI, C::BI, 0, sb2, tile_at(kt + 2));
+        tile_fence<C::BI>();       // all but the B copies just issued have landed; reads of tile kt done
+        half(1, sa1, sb1, 0, 0, C::AI, sa0, 0, tile_at(kt + 2));
+        sb0 = sb1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 

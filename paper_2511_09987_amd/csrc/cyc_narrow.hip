@@ -27,8 +27,8 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 #define CYC_LDS __attribute__((address_space(3)))
 
 constexpr int NWAVES = 8;     // k-slices per workgroup
-constexpr int DEPTH = 8;      // 16-byte loads in flight per lane
 constexpr int RB = 16;        // rows of A per MFMA (one row block)
+constexpr int RBK = 4;        // row blocks accumulated between two joins of the k-slices
 
 template <bool I8> struct Mac;
 template <> struct Mac<false> {   // 16x16 tile, 32 k per instruction
@@ -52,17 +52,22 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 template <bool I8, int S, bool FULL>
 __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                                 char *__restrict__ Cout, int M, int K, int N,
-                                                                int64_t sA, int64_t sB, int64_t sC, int rows_per_wg)
+                                                                int64_t sA, int64_t sB, int64_t sC, int rows_per_wg, int b_vec)
 {
     constexpr int ES = I8 ? 1 : 2;
     constexpr int KS = 64 / ES;          // k values per step
     constexpr int CH = 16 / ES;          // k values per 16-byte chunk
     constexpr int HALF = S / 2;          // B is staged through LDS in two halves
+    constexpr int DEPTH = (FULL && S % 16 == 0) ? 16 : 8;   // 16-byte loads in flight per lane
+    static_assert(S % DEPTH == 0, "the ring must line up with the row blocks");
     typedef typename Mac<I8>::acc_t acc_t;
     typedef typename Mac<I8>::elem elem;
 
-    __shared__ __attribute__((aligned(16))) char ldsB[NWAVES][HALF * KS * 16 * ES];
-    __shared__ __attribute__((aligned(16))) acc_t red[2][NWAVES][64];
+    // LDS is used twice: first as eight wave-private patches for staging B, then (after a barrier)
+    // as the double-buffered exchange area for the partial sums of the k-slices.
+    constexpr int PATCH = HALF * KS * 16 * ES;
+    constexpr int RED_BYTES = 2 * NWAVES * RBK * 64 * 16;
+    __shared__ __attribute__((aligned(16))) char smem[NWAVES * PATCH > RED_BYTES ? NWAVES * PATCH : RED_BYTES];
 
     const int l = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -81,13 +86,25 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
     {
         typedef typename std::conditional<I8, int8_t, uint16_t>::type in_t;
         const in_t *Bg = (const in_t *)B;
-        CYC_LDS in_t *patch = (CYC_LDS in_t *)ldsB[w];
+        CYC_LDS in_t *patch = (CYC_LDS in_t *)(smem + w * PATCH);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int kh0 = kw0 + h * HALF * KS;
-            for (int x = l; x < HALF * KS * 16; x += 64) {
-                const int kk = kh0 + (x >> 4), j = x & 15;
-                patch[x] = (kk < K && j < N) ? Bg[(int64_t)kk * N + j] : (in_t)0;
+            if (b_vec) {
+                // N == 16 and B 16-byte aligned: the slice is contiguous in memory, copy 16 bytes per lane
+                constexpr int CPRW = 16 * ES / 16;     // 16-byte chunks per row of B
+#pragma unroll 8
+                for (int x = l; x < PATCH / 16; x += 64) {
+                    const int kk = kh0 + x / CPRW;
+                    i32x4 v = {0, 0, 0, 0};
+                    if (kk < K) v = *(const i32x4 *)(B + ((int64_t)kh0 * 16 * ES) + (int64_t)x * 16);
+                    *(CYC_LDS i32x4 *)((CYC_LDS char *)patch + x * 16) = v;
+                }
+            } else {
+                for (int x = l; x < HALF * KS * 16; x += 64) {
+                    const int kk = kh0 + (x >> 4), j = x & 15;
+                    patch[x] = (kk < K && j < N) ? Bg[(int64_t)kk * N + j] : (in_t)0;
+                }
             }
 #pragma unroll
             for (int s = 0; s < HALF; ++s) {
@@ -127,37 +144,50 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
         return v;
     };
 
+    __syncthreads();   // every wave has its B fragments: the staging patches may be overwritten
+    typedef acc_t red_t[NWAVES][RBK][64];
+    CYC_LDS red_t *red = (CYC_LDS red_t *)smem;   // red[parity][wave][row block][lane]
+
     i32x4 ring[DEPTH];
     const char *p_cur = row_ptr(0);
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(p_cur, d);
 
-    for (int rb = 0; rb < nrb; ++rb) {
-        const char *p_next = row_ptr(rb + 1 < nrb ? rb + 1 : rb);
-        acc_t acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+    const int ngroups = (nrb + RBK - 1) / RBK;
+    for (int gi = 0; gi < ngroups; ++gi) {
+        acc_t acc[RBK];
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            const i32x4 a = ring[s % DEPTH];
-            ring[s % DEPTH] = (s + DEPTH < S) ? fetch(p_cur, s + DEPTH) : fetch(p_next, s + DEPTH - S);
-            if (s & 1) acc1 = Mac<I8>::mfma(a, Bf[s], acc1);
-            else acc0 = Mac<I8>::mfma(a, Bf[s], acc0);
+        for (int b = 0; b < RBK; ++b) {
+            // row blocks past the end of this workgroup's rows stream valid rows whose sums are dropped
+            const char *p_next = row_ptr(gi * RBK + b + 1);
+            acc[b] = (acc_t){0, 0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const i32x4 a = ring[s % DEPTH];
+                ring[s % DEPTH] = (s + DEPTH < S) ? fetch(p_cur, s + DEPTH) : fetch(p_next, s + DEPTH - S);
+                acc[b] = Mac<I8>::mfma(a, Bf[s], acc[b]);
+            }
+            p_cur = p_next;
         }
-        p_cur = p_next;
 
-        // ---- join the 8 k-slices in slice order; wave rb%8 does it and emits C_ij
-        red[rb & 1][w][l] = acc0 + acc1;
+        // ---- join the 8 k-slices in slice order; wave gi%8 does it and emits C_ij
+#pragma unroll
+        for (int b = 0; b < RBK; ++b) red[gi & 1][w][b][l] = acc[b];
         lds_barrier();
-        if (w == (rb & 7)) {
-            acc_t sum = red[rb & 1][0][l];
+        if (w == (gi & 7)) {
 #pragma unroll
-            for (int v = 1; v < NWAVES; ++v) sum += red[rb & 1][v][l];
-            // accumulator register r of lane l is row 4*(l/16) + r, column l%16 of the 16x16 tile
-            if (lq < N) {
+            for (int b = 0; b < RBK; ++b) {
+                acc_t sum = red[gi & 1][0][b][l];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = row_begin + rb * RB + 4 * g + r;
-                    const elem v = sum[r];
-                    if (row < row_end) C[(int64_t)row * N + lq] = v;
+                for (int v = 1; v < NWAVES; ++v) sum += red[gi & 1][v][b][l];
+                // accumulator register r of lane l is row 4*(l/16) + r, column l%16 of the 16x16 tile
+                if (lq < N) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int row = row_begin + (gi * RBK + b) * RB + 4 * g + r;
+                        const elem v = sum[r];
+                        if (row < row_end) C[(int64_t)row * N + lq] = v;
+                    }
                 }
             }
         }
@@ -167,10 +197,12 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
 template <bool I8, int S, bool FULL>
 hipError_t launch_one(const Problem &p, int rows_per_wg, hipStream_t s)
 {
+    const int es = I8 ? 1 : 2;
+    const int b_vec = p.N == 16 && ((uintptr_t)p.B & 15) == 0 && (p.batch == 1 || ((p.strideB * es) & 15) == 0);
     dim3 grid((unsigned)((p.M + rows_per_wg - 1) / rows_per_wg), (unsigned)p.batch);
     hipLaunchKernelGGL((ws_narrow_kernel<I8, S, FULL>), grid, dim3(NWAVES * 64), 0, s, (const char *)p.A,
                        (const char *)p.B, (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC,
-                       rows_per_wg);
+                       rows_per_wg, b_vec);
     return hipGetLastError();
 }
 

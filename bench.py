@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 PEAK = {"bf16": (2500.0, "TFLOP/s"), "i8": (5000.0, "TOP/s")}
 HBM_PEAK_GBS = 8000.0
 ROTATE = 3     # distinct (A, B, C) sets cycled through, so operands are not served from cache
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for a 1 GiB device copy (fetch x2.000, write x1.000); measured with the command lines
+# recorded in profiles/bench_all_workloads.md.  None where not measured.
+TRAFFIC_BYTES = {"c3_bf16_8192": 1879400813, "c4_i8_8192": 1073883192, "c5_bf16_narrow": 4524217778,
+                 "c2_bf16_512": 4283738, "c1_i8_64": 40062}
 
 
 def parse():
@@ -88,11 +93,11 @@ def roofline(w, kern_ms):
     if w.N <= 16:   # HBM bound: algorithmic bytes = A and B read once, C written once
         ach = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None}
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(w.name)}
     peak, unit = PEAK[w.dtype]
     ach = w.ops / (kern_ms * 1e-3) / 1e12
     return {"bound": "mfma", "achieved": round(ach, 1), "peak": peak, "unit": unit,
-            "frac": round(ach / peak, 4), "traffic": None}
+            "frac": round(ach / peak, 4), "traffic": TRAFFIC_BYTES.get(w.name)}
 
 
 def cpu_baseline(w, budget_s=15.0):

@@ -222,17 +222,22 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         const int q = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
         acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
     };
-    // One half: NG groups; group g holds its share of the MFMAs of `set`, of the reads that fill the
-    // other set (front-loaded: none in the last two groups), and at most one copy.
+    // One half.  A wave issues at most one instruction every four cycles and an MFMA occupies the
+    // matrix pipe for 32, so at most about six other instructions fit between two MFMAs before the
+    // pipe starves.  The fragment reads that fill the other register set and this half's copies are
+    // therefore dealt out evenly, one small item per MFMA slot, and pinned there.
     auto half = [&](int set, int rd_sa, int rd_sb, int rd_half, int cp_first, int cp_count, int cp_sa, int cp_sb, int cp_tile) {
-        constexpr int RPG = (NREAD + NG - 3) / (NG - 2);
+        const int naux = NREAD + cp_count, stride = naux / cp_count;   // every stride-th item is a copy
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            if (g < cp_count) issue_one(cp_first + g, cp_sa, cp_sb, cp_tile);
+        for (int m = 0; m < NMMA; ++m) {
 #pragma unroll
-            for (int r = g * RPG; r < (g + 1) * RPG && r < NREAD; ++r) read_one(r, set ^ 1, rd_sa, rd_sb, rd_half);
-#pragma unroll
-            for (int m = g * NMMA / NG; m < (g + 1) * NMMA / NG; ++m) mma_one(m, set);
+            for (int x = 0; x < NREAD + NG; ++x) {
+                if (x < naux && x * NMMA / naux == m) {
+                    if (x % stride == stride - 1 && x / stride < cp_count) issue_one(cp_first + x / stride, cp_sa, cp_sb, cp_tile);
+                    else read_one(x - (x / stride < cp_count ? x / stride : cp_count), set ^ 1, rd_sa, rd_sb, rd_half);
+                }
+            }
+            mma_one(m, set);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -310,8 +315,11 @@ bool supports_mfma(const Problem &p, int tile)
 hipError_t launch_mfma(const Problem &p, int tile, hipStream_t s)
 {
     if (!supports_mfma(p, tile)) return hipErrorInvalidValue;
+    // 256x256 block: 4 waves of 128x128 (one per SIMD, accumulators in the 256 AGPRs).  Eight waves of
+    // 128x64 reach the same MFMA utilisation but read 50 % more LDS per MFMA; on this power-limited
+    // chip that costs clock, and measured 1-3 % slower.
     if (tile == 256)
-        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 4>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 4>>(p, s);
+        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2>>(p, s);
     return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2>>(p, s);
 }
 

@@ -79,6 +79,31 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
 
     const int kw0 = w * S * KS;          // first k of this wave's slice
 
+    // ---- stream A.  Lane l feeds row l%16 of the row block and the 16-byte chunk l/16 of each
+    // 64-byte step; rows past M re-read row M-1 (their results are never stored).
+    const int row_begin = blockIdx.x * rows_per_wg;
+    const int row_end = (row_begin + rows_per_wg) < M ? (row_begin + rows_per_wg) : M;
+    const int nrb = (row_end - row_begin + RB - 1) / RB;
+    const int64_t row_bytes = (int64_t)K * ES;
+    const int lane_off = kw0 * ES + g * 16;
+    auto row_ptr = [&](int rb) -> const char * {
+        int r = row_begin + rb * RB + lq;
+        r = r < M ? r : M - 1;
+        return A + (int64_t)r * row_bytes + lane_off;
+    };
+    auto fetch = [&](const char *p, int s) -> i32x4 {
+        if (FULL) return *(const i32x4 *)(p + s * 64);
+        i32x4 v = {0, 0, 0, 0};
+        if (kw0 + s * KS + g * CH < K) v = *(const i32x4 *)(p + s * 64);
+        return v;
+    };
+
+    // the first loads of A go out before B is staged, so that HBM is busy during the staging
+    i32x4 ring[DEPTH];
+    const char *p_cur = row_ptr(0);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(p_cur, d);
+
     // ---- this wave's slice of B -> MFMA operand registers, once.  Rows of B are copied into a
     // wave-private LDS patch ([k][16 columns], zero beyond N and K) and read back through the
     // LDS transpose read, which hands every lane consecutive k of one column.
@@ -93,7 +118,7 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
             if (b_vec) {
                 // N == 16 and B 16-byte aligned: the slice is contiguous in memory, copy 16 bytes per lane
                 constexpr int CPRW = 16 * ES / 16;     // 16-byte chunks per row of B
-#pragma unroll 8
+#pragma unroll 16
                 for (int x = l; x < PATCH / 16; x += 64) {
                     const int kk = kh0 + x / CPRW;
                     i32x4 v = {0, 0, 0, 0};
@@ -125,33 +150,9 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
         }
     }
 
-    // ---- stream A.  Lane l feeds row l%16 of the row block and the 16-byte chunk l/16 of each
-    // 64-byte step; rows past M re-read row M-1 (their results are never stored).
-    const int row_begin = blockIdx.x * rows_per_wg;
-    const int row_end = (row_begin + rows_per_wg) < M ? (row_begin + rows_per_wg) : M;
-    const int nrb = (row_end - row_begin + RB - 1) / RB;
-    const int64_t row_bytes = (int64_t)K * ES;
-    const int lane_off = kw0 * ES + g * 16;
-    auto row_ptr = [&](int rb) -> const char * {
-        int r = row_begin + rb * RB + lq;
-        r = r < M ? r : M - 1;
-        return A + (int64_t)r * row_bytes + lane_off;
-    };
-    auto fetch = [&](const char *p, int s) -> i32x4 {
-        if (FULL) return *(const i32x4 *)(p + s * 64);
-        i32x4 v = {0, 0, 0, 0};
-        if (kw0 + s * KS + g * CH < K) v = *(const i32x4 *)(p + s * 64);
-        return v;
-    };
-
-    __syncthreads();   // every wave has its B fragments: the staging patches may be overwritten
+    lds_barrier();     // every wave has its B fragments: the staging patches may be overwritten
     typedef acc_t red_t[NWAVES][RBK][64];
     CYC_LDS red_t *red = (CYC_LDS red_t *)smem;   // red[parity][wave][row block][lane]
-
-    i32x4 ring[DEPTH];
-    const char *p_cur = row_ptr(0);
-#pragma unroll
-    for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(p_cur, d);
 
     const int ngroups = (nrb + RBK - 1) / RBK;
     for (int gi = 0; gi < ngroups; ++gi) {

@@ -60,6 +60,7 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
     constexpr int HALF = S / 2;          // B is staged through LDS in two halves
     constexpr int DEPTH = (FULL && S % 16 == 0) ? 16 : 8;   // 16-byte loads in flight per lane
     static_assert(S % DEPTH == 0, "the ring must line up with the row blocks");
+    constexpr int BURST = 8;             // ring slots refilled together
     typedef typename Mac<I8>::acc_t acc_t;
     typedef typename Mac<I8>::elem elem;
 
@@ -163,10 +164,19 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
             const char *p_next = row_ptr(gi * RBK + b + 1);
             acc[b] = (acc_t){0, 0, 0, 0};
 #pragma unroll
-            for (int s = 0; s < S; ++s) {
-                const i32x4 a = ring[s % DEPTH];
-                ring[s % DEPTH] = (s + DEPTH < S) ? fetch(p_cur, s + DEPTH) : fetch(p_next, s + DEPTH - S);
-                acc[b] = Mac<I8>::mfma(a, Bf[s], acc[b]);
+            for (int s0 = 0; s0 < S; s0 += BURST) {
+                // consume BURST steps, then refill their ring slots in one burst: the refills ask for
+                // BURST consecutive 64-byte pieces of each row back to back, which the DRAM serves
+                // from open pages; one load per step, trickling, measured 3 % slower
+#pragma unroll
+                for (int u = 0; u < BURST; ++u) acc[b] = Mac<I8>::mfma(ring[(s0 + u) % DEPTH], Bf[s0 + u], acc[b]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int u = 0; u < BURST; ++u) {
+                    const int s = s0 + u;
+                    ring[s % DEPTH] = (s + DEPTH < S) ? fetch(p_cur, s + DEPTH) : fetch(p_next, s + DEPTH - S);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             p_cur = p_next;
         }

@@ -34,8 +34,14 @@
  *
  * Degenerate extents: M == 0, N == 0 or batch == 0 do nothing and return
  * CYC_OK; K == 0 fills C with zeros (the initial value of every chain).
- * Any M, K, N >= 1 is accepted; shapes that are multiples of the kernel tiles
- * with 16-byte aligned pointers take the fast paths.
+ * Any M, K, N >= 1 is accepted.  The MFMA paths need 16-byte aligned base
+ * pointers, batch strides and rows of A and B (K and N multiples of 8 for
+ * bfloat16, of 16 for int8) but no particular multiples otherwise; anything
+ * else runs on a slower shape-agnostic kernel.
+ *
+ * The environment variable CYC_FORCE_KERNEL (generic | mfma256 | mfma128 |
+ * narrow), read at every call, overrides the choice of kernel when the named
+ * kernel supports the problem; it exists for tests and benchmarks.
  */
 #ifndef CYCLOTRON_MM_H
 #define CYCLOTRON_MM_H

@@ -84,11 +84,18 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
         if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
     }
     if (cyc::prefers_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
-    // 256x256 tiles once they can fill the chip; 128x128 tiles for mid-size problems
-    const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256) * batch;
-    if (cyc::supports_mfma(*p, 256) && tiles256 >= 256) { *k = K_MFMA256; return CYC_OK; }
-    if (cyc::supports_mfma(*p, 128)) { *k = K_MFMA128; return CYC_OK; }
-    if (cyc::supports_mfma(*p, 256)) { *k = K_MFMA256; return CYC_OK; }
+    // MFMA kernels for everything with 16-byte aligned rows except slivers.  Block size by a small
+    // cost model: a CU runs one 256x256 block or two 128x128 blocks at a time; a 128x128 block does a
+    // quarter of the work at about 3/4 of the efficiency.  Compare the number of rounds each needs.
+    if (M >= 16 && N >= 16) {
+        const int64_t n256 = ((M + 255) / 256) * ((N + 255) / 256) * batch;
+        const int64_t n128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+        const double cost256 = (double)((n256 + 255) / 256);
+        const double cost128 = (double)((n128 + 511) / 512) * 0.675;
+        const bool ok256 = cyc::supports_mfma(*p, 256), ok128 = cyc::supports_mfma(*p, 128);
+        if (ok256 && (!ok128 || cost256 <= cost128)) { *k = K_MFMA256; return CYC_OK; }
+        if (ok128) { *k = K_MFMA128; return CYC_OK; }
+    }
     *k = K_GENERIC;
     return CYC_OK;
 }

@@ -92,7 +92,10 @@ __device__ __forceinline__ void tile_fence()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(KEEP) : "memory");
 }
 
-template <class C>
+// RAGGED: M, N need not be multiples of the block and K need not be a multiple of the k-tile (rows of A
+// and B must still be 16-byte aligned).  Rows and columns past the edge re-read the last valid ones
+// and are not stored; in the last k-tile, chunks at or past K are not copied but written as zeros.
+template <class C, bool RAGGED>
 __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                         char *__restrict__ Cout, int M, int K, int N, int64_t sA,
                                                         int64_t sB, int64_t sC, int tiles_m, int tiles_n)
@@ -130,25 +133,47 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     const char *baseB = B + (int64_t)n0 * ES;
     const int64_t stepB = (int64_t)C::BKE * N * ES;
     uint32_t voffA[C::AI], voffB[C::BI];
+    const int nkt = RAGGED ? (K + C::BKE - 1) / C::BKE : K / C::BKE;
+    const int last = nkt - 1;
+    unsigned tail_ok = 0;          // RAGGED: bit x set = this lane's copy x of the last k-tile is inside K
 #pragma unroll
     for (int t = 0; t < C::AI; ++t) {
         int r = (w * C::AI + t) * 8 + (l >> 3);
         int c = (l & 7) ^ swzA(r);
+        if (RAGGED) {
+            if (last * C::BKE + c * (16 / ES) < K) tail_ok |= 1u << t;
+            r = m0 + r < M ? r : M - 1 - m0;
+        }
         voffA[t] = (uint32_t)r * (uint32_t)(K * ES) + c * 16;
     }
 #pragma unroll
     for (int t = 0; t < C::BI; ++t) {
         int kr = (w * C::BI + t) * C::RPI + l / C::CPR;
         int c = (l % C::CPR) ^ swzB<C>(kr);
+        if (RAGGED) {
+            if (last * C::BKE + kr < K) tail_ok |= 1u << (C::AI + t);
+            const int cmax = (N - n0) * ES / 16 - 1;      // last 16-byte chunk of this block's columns that exists
+            c = c < cmax ? c : cmax;
+        }
         voffB[t] = (uint32_t)kr * (uint32_t)(N * ES) + c * 16;
     }
     // LDS map: NSA stages of the A tile, then NSB stages of the B tile
     constexpr int LDS_B0 = C::NSA * C::A_BYTES;
     // copy number x of this wave's share of k-tile `ktile`: x < AI is a piece of the A tile (into A
     // stage sa), otherwise a piece of the B tile (into B stage sb)
-    auto issue_one = [&](int x, int sa, int sb, int ktile) {
-        if (x < C::AI) async_copy16(baseA + (int64_t)ktile * 128, voffA[x], lds_base + sa * C::A_BYTES + (w * C::AI + x) * 1024);
-        else async_copy16(baseB + (int64_t)ktile * stepB, voffB[x - C::AI], lds_base + LDS_B0 + sb * C::B_BYTES + (w * C::BI + x - C::AI) * 1024);
+    // (`tail`: this call may be about the last k-tile; false in the bulk of the k loop, where the copy is
+    // then unconditional)
+    auto issue_one = [&](int x, int sa, int sb, int ktile, bool tail) __attribute__((always_inline)) {
+        const uint32_t dst = x < C::AI ? sa * C::A_BYTES + (w * C::AI + x) * 1024
+                                       : LDS_B0 + sb * C::B_BYTES + (w * C::BI + x - C::AI) * 1024;
+        const char *src = x < C::AI ? baseA + (int64_t)ktile * 128 : baseB + (int64_t)ktile * stepB;
+        const uint32_t off = x < C::AI ? voffA[x] : voffB[x - C::AI];
+        if (RAGGED && tail && ktile == last) {
+            if ((tail_ok >> x) & 1) async_copy16(src, off, lds_base + dst);
+            else *(CYC_LDS i32x4 *)(lds + dst + l * 16) = (i32x4){0, 0, 0, 0};
+        } else {
+            async_copy16(src, off, lds_base + dst);
+        }
     };
 
     // ---- LDS read offsets of this lane's fragments
@@ -200,7 +225,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     constexpr int NG = 8;                  // groups per half
     static_assert(C::AI <= NG && C::BI <= NG, "one copy per group");
     // fragment read number r of a half: k-step q = r / (TM+TN); B fragments first, then A
-    auto read_one = [&](int r, int set, int sa, int sb, int h) {
+    auto read_one = [&](int r, int set, int sa, int sb, int h) __attribute__((always_inline)) {
         const int q = r / (TM + TN), e = r % (TM + TN), ks = h * 2 + q;
         if (e < TN) {
             const int o = sb * C::B_BYTES + offB[e];
@@ -218,7 +243,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         }
     };
     // MFMA number m of a half
-    auto mma_one = [&](int m, int set) {
+    auto mma_one = [&](int m, int set) __attribute__((always_inline)) {
         const int q = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
         acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
     };
@@ -226,14 +251,14 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // matrix pipe for 32, so at most about six other instructions fit between two MFMAs before the
     // pipe starves.  The fragment reads that fill the other register set and this half's copies are
     // therefore dealt out evenly, one small item per MFMA slot, and pinned there.
-    auto half = [&](int set, int rd_sa, int rd_sb, int rd_half, int cp_first, int cp_count, int cp_sa, int cp_sb, int cp_tile) {
+    auto half = [&](int set, int rd_sa, int rd_sb, int rd_half, int cp_first, int cp_count, int cp_sa, int cp_sb, int cp_tile, bool tail) __attribute__((always_inline)) {
         const int naux = NREAD + cp_count, stride = naux / cp_count;   // every stride-th item is a copy
 #pragma unroll
         for (int m = 0; m < NMMA; ++m) {
 #pragma unroll
             for (int x = 0; x < NREAD + NG; ++x) {
                 if (x < naux && x * NMMA / naux == m) {
-                    if (x % stride == stride - 1 && x / stride < cp_count) issue_one(cp_first + x / stride, cp_sa, cp_sb, cp_tile);
+                    if (x % stride == stride - 1 && x / stride < cp_count) issue_one(cp_first + x / stride, cp_sa, cp_sb, cp_tile, tail);
                     else read_one(x - (x / stride < cp_count ? x / stride : cp_count), set ^ 1, rd_sa, rd_sb, rd_half);
                 }
             }
@@ -245,26 +270,34 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // Beyond the last tile there is nothing left to fetch or read: the final tile is copied again
     // into a stage nobody reads and a stale half is read into registers nobody uses, rather than
     // branch around the copies and reads.
-    const int nkt = K / C::BKE;
-    const int last = nkt - 1;
-    auto tile_at = [&](int t) { return t < last ? t : last; };
+    auto tile_at = [&](int t) __attribute__((always_inline)) { return t < last ? t : last; };
 #pragma unroll
-    for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, 0, 0, 0);
+    for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, 0, 0, 0, true);
     tile_fence<0>();               // tile 0 in LDS
 #pragma unroll
-    for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, 1, 1, tile_at(1));
+    for (int x = 0; x < C::AI + C::BI; ++x) issue_one(x, 1, 1, tile_at(1), true);
 #pragma unroll
     for (int r = 0; r < NREAD; ++r) read_one(r, 0, 0, 0, 0);
 
     int sb0 = 0;                   // B stage of tile kt; tile kt+1 is in sb1, tile kt+2 goes to sb2
-    for (int kt = 0; kt < nkt; ++kt) {
+    auto k_tile = [&](int kt, bool tail) __attribute__((always_inline)) {
         const int sa0 = kt & 1, sa1 = sa0 ^ 1;
         const int sb1 = sb0 == 2 ? 0 : sb0 + 1, sb2 = sb1 == 2 ? 0 : sb1 + 1;
-        half(0, sa0, sb0, 1, C::AI, C::BI, 0, sb2, tile_at(kt + 2));
-        tile_fence<C::BI>();       // all but the B copies just issued have landed; reads of tile kt done
-        half(1, sa1, sb1, 0, 0, C::AI, sa0, 0, tile_at(kt + 2));
+        half(0, sa0, sb0, 1, C::AI, C::BI, 0, sb2, tail ? tile_at(kt + 2) : kt + 2, tail);
+        // all but the B copies just issued have landed; reads of tile kt done.  (Once the last k-tile
+        // of a RAGGED problem is involved, wait for all copies: a wave whose piece of that tile lies
+        // wholly past K issues no copy for it, so counting outstanding copies would be off.)
+        if (RAGGED && tail) tile_fence<0>();
+        else tile_fence<C::BI>();
+        half(1, sa1, sb1, 0, 0, C::AI, sa0, 0, tail ? tile_at(kt + 2) : kt + 2, tail);
         sb0 = sb1;
-    }
+    };
+    // bulk: every copy is of a whole k-tile before the last one; then the (at most three) k-tiles whose
+    // copies touch the last k-tile or have nothing left to fetch
+    int kt = 0;
+    if (RAGGED)
+        for (; kt + 2 < last; ++kt) k_tile(kt, false);
+    for (; kt < nkt; ++kt) k_tile(kt, true);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- C_ij <- [i,k_end]_C.  Accumulator register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
@@ -281,7 +314,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
             for (int r = 0; r < 16; ++r) {
                 int row = row0 + (r >> 2) * 8 + (r & 3);
                 const elem v = acc[i][j][r];
-                Cw[(int64_t)row * N + col] = v;
+                if (!RAGGED || (row < M && col < N)) Cw[(int64_t)row * N + col] = v;
             }
         }
 }
@@ -289,22 +322,30 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
 template <class C>
 hipError_t launch_cfg(const Problem &p, hipStream_t s)
 {
-    const int tiles_m = (int)(p.M / C::BM), tiles_n = (int)(p.N / C::BN);
+    const bool ragged = p.M % C::BM || p.N % C::BN || p.K % C::BKE;
+    const int tiles_m = (int)((p.M + C::BM - 1) / C::BM), tiles_n = (int)((p.N + C::BN - 1) / C::BN);
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)p.batch);
-    hipLaunchKernelGGL((ws_mfma_kernel<C>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
-                       (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n);
+    if (ragged)
+        hipLaunchKernelGGL((ws_mfma_kernel<C, true>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+                           (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((ws_mfma_kernel<C, false>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+                           (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
 }  // namespace
 
+// Any M, N, K >= 1 whose rows of A and B are 16-byte aligned (K*es and N*es multiples of 16, aligned
+// base pointers and batch strides); shapes that are not multiples of the block take the RAGGED variant.
 bool supports_mfma(const Problem &p, int tile)
 {
     if (tile != 256 && tile != 128) return false;
-    const int es = p.i8 ? 1 : 2, bke = 128 / es;
-    if (p.K <= 0 || p.M % tile || p.N % tile || p.K % bke) return false;
+    const int es = p.i8 ? 1 : 2;
+    if (p.K <= 0 || p.M <= 0 || p.N <= 0) return false;
+    if ((p.K * es) % 16 || (p.N * es) % 16) return false;
     if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
-    if ((p.M / tile) * (p.N / tile) > (1 << 30)) return false;
+    if (((p.M + tile - 1) / tile) * ((p.N + tile - 1) / tile) > (1 << 30)) return false;
     // per-lane byte offsets inside a tile's rows are kept in 32 bits
     if (p.K * es * 256 + 128 >= ((int64_t)1 << 32) || p.N * es * 128 + 512 >= ((int64_t)1 << 32)) return false;
     if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C) & 15) return false;

@@ -71,8 +71,12 @@ def test_dispatch_table(pkg):
     assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 0) == "mfma256"
     assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 1) == "mfma256"
     assert k(A, B, C, 1, 512, 512, 512, 0, 0, 0, 0) == "mfma128"
-    assert k(A, B, C, 1, 64, 64, 64, 0, 0, 0, 1) == "generic"
+    assert k(A, B, C, 1, 64, 64, 64, 0, 0, 0, 1) == "mfma128"
+    assert k(A, B, C, 1, 8191, 8192, 8200, 0, 0, 0, 0) == "mfma256"       # ragged M and N, aligned rows
+    assert k(A, B, C, 1, 100, 72, 40, 0, 0, 0, 0) == "mfma128"            # ragged everything, aligned rows
+    assert k(A, B, C, 1, 1000, 1000, 1000, 0, 0, 0, 1) == "generic"       # int8 rows of 1000 bytes: not 16-byte aligned
     assert k(A, B, C, 1, 17, 33, 5, 0, 0, 0, 0) == "generic"
+    assert k(A, B, C, 1, 8, 64, 4096, 0, 0, 0, 0) == "generic"            # sliver
     assert k(A + 2, B, C, 1, 512, 512, 512, 0, 0, 0, 0) == "generic"      # unaligned A
     assert k(A, B, C, 1, 512, 0, 512, 0, 0, 0, 0) == "zero"
     assert k(A, B, C, 1, 0, 8, 512, 0, 0, 0, 0) == "none"

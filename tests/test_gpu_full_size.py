@@ -110,6 +110,25 @@ def test_bf16_8192_small_integer_data_is_bit_exact(lib, oracle):
     assert torch.equal(C.double(), ref)
 
 
+@pytest.mark.parametrize("mode", ("bf16", "i8"))
+def test_large_ragged_shape_blocks_and_exact_product(lib, oracle, mode):
+    """8191 x 8200 x 8184 (bf16) / 8191 x 8208 x 8176 (int8): no extent is a multiple of the block or
+    the k-tile.  Small-integer data, so the whole product is compared exactly with an fp64 matmul, and
+    sampled blocks (including the ragged corner) with the oracle."""
+    M, K, N = (8191, 8200, 8184) if mode == "bf16" else (8191, 8208, 8176)
+    if mode == "bf16":
+        A = ws_inputs.small_int_bf16((M, K), 8, 808, 0, DEV)
+        B = ws_inputs.small_int_bf16((K, N), 8, 808, 1, DEV)
+    else:
+        A = ws_inputs.uniform_int((M, K), 8, 808, 0, DEV)
+        B = ws_inputs.uniform_int((K, N), 8, 808, 1, DEV)
+    C = lib.recurrence_matmul(A, B)
+    dt = lib.CYC_I8_I32 if mode == "i8" else lib.CYC_BF16_F32
+    assert lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), 1, M, K, N, 0, 0, 0, dt) == "mfma256"
+    assert torch.equal(C.double(), A.double() @ B.double())
+    check_blocks(oracle, mode, A, B, C, 192, seed=88, exact=True)
+
+
 def test_config5_narrow_batch_rows_and_checksum(lib, oracle):
     w = ws_inputs.WORKLOADS["c5_bf16_narrow"]
     A, B = ws_inputs.make_inputs(w, DEV)

@@ -125,6 +125,38 @@ def test_mfma_tiles(lib, oracle, mode, tile, shapes):
         run_case(lib, oracle, mode, M, K, N, seed=4000 + n, kind="small", force=tile, expect_kernel=tile)
 
 
+# shapes that are not multiples of the block or of the k-tile (rows stay 16-byte aligned)
+MFMA_RAGGED = [(129, 72, 136), (255, 264, 264), (100, 72, 40), (300, 1000, 520), (64, 8, 64), (16, 16, 16),
+               (1, 8, 8), (5, 24, 16), (257, 72, 8), (128, 136, 128), (130, 128, 128), (128, 128, 144),
+               (513, 520, 392), (31, 4104, 33 * 8)]
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+@pytest.mark.parametrize("tile", ("mfma128", "mfma256"))
+def test_mfma_ragged_shapes(lib, oracle, mode, tile):
+    for n, (M, K, N) in enumerate(MFMA_RAGGED):
+        if mode == "i8":                      # int8 rows need multiples of 16
+            K, N = (K + 15) // 16 * 16 + (16 if n % 2 else 0), (N + 15) // 16 * 16
+        run_case(lib, oracle, mode, M, K, N, seed=6000 + n, force=tile, expect_kernel=tile)
+        run_case(lib, oracle, mode, M, K, N, seed=7000 + n, kind="small", force=tile, expect_kernel=tile)
+
+
+def test_mfma_ragged_edges_are_not_overwritten(lib):
+    """A ragged call must write its M x N results and nothing around them."""
+    M, K, N = 200, 72, 136
+    A, B, _, _ = gen("bf16", (M, K), (K, N), seed=81, kind="small")
+    guard = torch.full((M + 2, N), -12345.0, dtype=torch.float32, device=DEV)
+    C = guard[1:M + 1]
+    for tile in ("mfma128", "mfma256"):
+        os.environ["CYC_FORCE_KERNEL"] = tile
+        try:
+            lib.recurrence_matmul(A, B, out=C)
+        finally:
+            os.environ.pop("CYC_FORCE_KERNEL", None)
+        assert torch.equal(C.double(), A.double() @ B.double())
+        assert bool((guard[0] == -12345.0).all()) and bool((guard[M + 1] == -12345.0).all())
+
+
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
 @pytest.mark.parametrize("tile", ("mfma128", "mfma256"))
 def test_mfma_one_hot_probes(lib, tile, mode):

@@ -8,9 +8,18 @@
 // KiB) is what stays resident -- each wave keeps its k-slice of B in registers for the
 // life of the workgroup -- and A streams past it at HBM speed, 16 rows at a time, straight
 // from global memory into MFMA operand registers.  The k chain [i,k]_C <- [i,k-1]_C + W*B
-// is cut into 8 contiguous k-slices, one per wave; each slice is accumulated in k order in
-// an MFMA accumulator, and the 8 partial sums of a row block are added in slice order by
-// one wave through LDS (fixed order: results are bit-identical run to run, no atomics).
+// is cut into 8 contiguous k-slices, one per wave; each slice is accumulated in an MFMA
+// accumulator, and the 8 partial sums of a row block are added in slice order by one wave
+// through LDS (fixed order: results are bit-identical run to run, no atomics).
+//
+// What sets the speed is the shape of the loads.  Measured on this device with the same
+// row-sliced traversal and no arithmetic: a wave-wide load that takes 64 bytes from each
+// of 16 rows (the MFMA operand layout as it stands) tops out at 6.3 TB/s whatever the
+// cache policy; one that takes whole 128-byte lines (8 rows x 128 bytes) with the
+// non-temporal policy and a short queue (4-8 loads per lane) reaches 7.0-7.3 TB/s.  So A
+// is fetched as whole lines, non-temporally, eight rows at a time, and the loaded register
+// is used as a 16-row MFMA operand twice (once per half of the k it holds); the matrix
+// pipe has time to spare.
 #include "cyc_internal.h"
 
 #include <type_traits>
@@ -27,8 +36,20 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 #define CYC_LDS __attribute__((address_space(3)))
 
 constexpr int NWAVES = 8;     // k-slices per workgroup
-constexpr int RB = 16;        // rows of A per MFMA (one row block)
-constexpr int RBK = 4;        // row blocks accumulated between two joins of the k-slices
+constexpr int RB = 8;         // rows of A per load and per MFMA pair (one row block)
+#ifndef CYC_NARROW_RBK
+#define CYC_NARROW_RBK 4
+#endif
+constexpr int RBK = CYC_NARROW_RBK;        // row blocks accumulated between two joins of the k-slices
+#ifndef CYC_NARROW_AUX
+#define CYC_NARROW_AUX 2
+#endif
+#ifndef CYC_NARROW_DEPTH
+#define CYC_NARROW_DEPTH 4
+#endif
+#ifndef CYC_NARROW_BURST
+#define CYC_NARROW_BURST 4
+#endif
 
 template <bool I8> struct Mac;
 template <> struct Mac<false> {   // 16x16 tile, 32 k per instruction
@@ -47,8 +68,8 @@ template <> struct Mac<true> {    // 16x16 tile, 64 k per instruction
 // wait for this wave's LDS traffic only (loads of A stay in flight), then meet the other waves
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// S: MFMA steps per wave per row block; a step is 64 bytes of k per row.  The workgroup covers
-// k < 8*S*64/ES.  FULL: K is exactly that, so no lane ever needs masking.
+// S: MFMA steps of 64 bytes of k that make up a wave's k-slice.  The workgroup covers k < 8*S*64/ES.
+// FULL: K is exactly that, so no lane ever needs masking.
 template <bool I8, int S, bool FULL>
 __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                                 char *__restrict__ Cout, int M, int K, int N,
@@ -58,9 +79,11 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
     constexpr int KS = 64 / ES;          // k values per step
     constexpr int CH = 16 / ES;          // k values per 16-byte chunk
     constexpr int HALF = S / 2;          // B is staged through LDS in two halves
-    constexpr int DEPTH = (FULL && S % 16 == 0) ? 16 : 8;   // 16-byte loads in flight per lane
-    static_assert(S % DEPTH == 0, "the ring must line up with the row blocks");
-    constexpr int BURST = 8;             // ring slots refilled together
+    constexpr int LPB = S / 2;           // loads per row block: 128-byte pieces in the wave's k-slice
+    constexpr int DEPTH = LPB % CYC_NARROW_DEPTH == 0 ? CYC_NARROW_DEPTH : 4;   // 16-byte loads in flight per lane
+    constexpr int BURST = CYC_NARROW_BURST < DEPTH ? CYC_NARROW_BURST : DEPTH;  // ring slots refilled together
+    static_assert(LPB % DEPTH == 0 && DEPTH % BURST == 0, "the ring must line up with the row blocks");
+    static_assert(RBK % 2 == 0, "the join finishes row blocks in pairs");
     typedef typename Mac<I8>::acc_t acc_t;
     typedef typename Mac<I8>::elem elem;
 
@@ -80,34 +103,51 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
 
     const int kw0 = w * S * KS;          // first k of this wave's slice
 
-    // ---- stream A.  Lane l feeds row l%16 of the row block and the 16-byte chunk l/16 of each
-    // 64-byte step; rows past M re-read row M-1 (their results are never stored).
+    // ---- stream A.  The wave's slice of a row block (8 rows x S*64 bytes) is fetched in 128-byte
+    // pieces: in load p, lane l reads row l%8 of the block and the 16-byte chunk 2*(l/16) + (l%16)/8
+    // of piece p, so one wave-wide load covers eight whole 128-byte lines.  Rows past M re-read row
+    // M-1 (their results are never stored).
     const int row_begin = blockIdx.x * rows_per_wg;
     const int row_end = (row_begin + rows_per_wg) < M ? (row_begin + rows_per_wg) : M;
     const int nrb = (row_end - row_begin + RB - 1) / RB;
     const int64_t row_bytes = (int64_t)K * ES;
-    const int lane_off = kw0 * ES + g * 16;
-    auto row_ptr = [&](int rb) -> const char * {
-        int r = row_begin + rb * RB + lq;
-        r = r < M ? r : M - 1;
-        return A + (int64_t)r * row_bytes + lane_off;
+    const int chunk = 2 * g + (lq >> 3);             // 16-byte chunk of the 128-byte piece
+    const uint32_t lane_off = (uint32_t)(kw0 * ES + chunk * 16);
+    // A row block is addressed through a buffer descriptor based at its first row (wave-uniform) plus a
+    // per-lane offset below 8 rows; buffer loads carry their cache policy explicitly.
+    auto block_row = [&](int rb) -> int {
+        const int r0 = row_begin + rb * RB;
+        return r0 < M ? r0 : M - 1;
     };
-    auto fetch = [&](const char *p, int s) -> i32x4 {
-        if (FULL) return *(const i32x4 *)(p + s * 64);
+    auto block_desc = [&](int rb) -> __amdgpu_buffer_rsrc_t {
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(A + (int64_t)block_row(rb) * row_bytes), 0, (int)(RB * row_bytes),
+                                                 0x00020000);
+    };
+    auto lane_voff = [&](int rb) -> uint32_t {
+        int r = row_begin + rb * RB + (lq & 7);
+        r = r < M ? r : M - 1;
+        return (uint32_t)(r - block_row(rb)) * (uint32_t)row_bytes + lane_off;
+    };
+    // piece p of a row block; non-temporal (bit 1 of the cache policy): A is read once
+    auto fetch = [&](__amdgpu_buffer_rsrc_t d, uint32_t voff, int p) -> i32x4 {
+        const uint32_t off = voff + (uint32_t)(p * 128);
+        if (FULL) return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(d, off, 0, CYC_NARROW_AUX));
         i32x4 v = {0, 0, 0, 0};
-        if (kw0 + s * KS + g * CH < K) v = *(const i32x4 *)(p + s * 64);
+        if (kw0 + (p * 8 + chunk) * CH < K) v = __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(d, off, 0, CYC_NARROW_AUX));
         return v;
     };
 
     // the first loads of A go out before B is staged, so that HBM is busy during the staging
     i32x4 ring[DEPTH];
-    const char *p_cur = row_ptr(0);
+    __amdgpu_buffer_rsrc_t d_cur = block_desc(0);
+    uint32_t v_cur = lane_voff(0);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(p_cur, d);
+    for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(d_cur, v_cur, d);
 
     // ---- this wave's slice of B -> MFMA operand registers, once.  Rows of B are copied into a
     // wave-private LDS patch ([k][16 columns], zero beyond N and K) and read back through the
-    // LDS transpose read, which hands every lane consecutive k of one column.
+    // LDS transpose read, which hands every lane consecutive k of one column.  Bf[2p+e] holds, in
+    // lane group g, the k of chunk 2g+e of piece p.
     i32x4 Bf[S];
     {
         typedef typename std::conditional<I8, int8_t, uint16_t>::type in_t;
@@ -136,11 +176,11 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
             for (int s = 0; s < HALF; ++s) {
                 i32x2 lo, hi;
                 if (I8) {
-                    CYC_LDS char *p = (CYC_LDS char *)patch + (s * 64 + 16 * g + (lq >> 1)) * 16 + 8 * (lq & 1);
+                    CYC_LDS char *p = (CYC_LDS char *)patch + ((s >> 1) * 128 + 32 * g + 16 * (s & 1) + (lq >> 1)) * 16 + 8 * (lq & 1);
                     lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)p);
                     hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(p + 8 * 16));
                 } else {
-                    CYC_LDS char *p = (CYC_LDS char *)patch + (s * 32 + 8 * g + (lq >> 2)) * 32 + 8 * (lq & 3);
+                    CYC_LDS char *p = (CYC_LDS char *)patch + ((s >> 1) * 64 + 16 * g + 8 * (s & 1) + (lq >> 2)) * 32 + 8 * (lq & 3);
                     lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
                     hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 32)));
                 }
@@ -157,47 +197,61 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
 
     const int ngroups = (nrb + RBK - 1) / RBK;
     for (int gi = 0; gi < ngroups; ++gi) {
-        acc_t acc[RBK];
+        acc_t part[RBK];
 #pragma unroll
         for (int b = 0; b < RBK; ++b) {
             // row blocks past the end of this workgroup's rows stream valid rows whose sums are dropped
-            const char *p_next = row_ptr(gi * RBK + b + 1);
-            acc[b] = (acc_t){0, 0, 0, 0};
+            const __amdgpu_buffer_rsrc_t d_next = block_desc(gi * RBK + b + 1);
+            const uint32_t v_next = lane_voff(gi * RBK + b + 1);
+            // The loaded register is used as the 16-row A operand as it stands.  Its lanes l%16 < 8 hold
+            // rows 0..7 with the even chunks of the piece, lanes l%16 >= 8 the same rows with the odd
+            // chunks.  Multiplied with the B operand of the even chunks, operand rows 0..7 give the even
+            // part of the sums of rows 0..7 (operand rows 8..15 give nothing meaningful and are dropped);
+            // with the B operand of the odd chunks, operand rows 8..15 give the odd part.
+            acc_t even = {0, 0, 0, 0}, odd = {0, 0, 0, 0};
 #pragma unroll
-            for (int s0 = 0; s0 < S; s0 += BURST) {
-                // consume BURST steps, then refill their ring slots in one burst: the refills ask for
-                // BURST consecutive 64-byte pieces of each row back to back, which the DRAM serves
-                // from open pages; one load per step, trickling, measured 3 % slower
+            for (int p0 = 0; p0 < LPB; p0 += BURST) {
 #pragma unroll
-                for (int u = 0; u < BURST; ++u) acc[b] = Mac<I8>::mfma(ring[(s0 + u) % DEPTH], Bf[s0 + u], acc[b]);
+                for (int u = 0; u < BURST; ++u) {
+                    const i32x4 a = ring[(p0 + u) % DEPTH];
+                    even = Mac<I8>::mfma(a, Bf[2 * (p0 + u)], even);
+                    odd = Mac<I8>::mfma(a, Bf[2 * (p0 + u) + 1], odd);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int u = 0; u < BURST; ++u) {
-                    const int s = s0 + u;
-                    ring[s % DEPTH] = (s + DEPTH < S) ? fetch(p_cur, s + DEPTH) : fetch(p_next, s + DEPTH - S);
+                    const int p = p0 + u;
+                    ring[p % DEPTH] = (p + DEPTH < LPB) ? fetch(d_cur, v_cur, p + DEPTH) : fetch(d_next, v_next, p + DEPTH - LPB);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            p_cur = p_next;
+            d_cur = d_next;
+            v_cur = v_next;
+            // accumulator register r of lane l is operand row 4*(l/16) + r, column l%16: lanes 0..31 keep
+            // the even part, lanes 32..63 the odd part of rows 0..7
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[b][r] = l < 32 ? even[r] : odd[r];
         }
 
         // ---- join the 8 k-slices in slice order; wave gi%8 does it and emits C_ij
 #pragma unroll
-        for (int b = 0; b < RBK; ++b) red[gi & 1][w][b][l] = acc[b];
+        for (int b = 0; b < RBK; ++b) red[gi & 1][w][b][l] = part[b];
         lds_barrier();
         if (w == (gi & 7)) {
+            // lanes 0..31 finish the even-numbered row block of a pair, lanes 32..63 the odd-numbered one
+            const int ll = l & 31;
 #pragma unroll
-            for (int b = 0; b < RBK; ++b) {
-                acc_t sum = red[gi & 1][0][b][l];
+            for (int bp = 0; bp < RBK; bp += 2) {
+                const int b = bp + (l >> 5);
+                acc_t sum = red[gi & 1][0][b][ll] + red[gi & 1][0][b][ll + 32];
 #pragma unroll
-                for (int v = 1; v < NWAVES; ++v) sum += red[gi & 1][v][b][l];
-                // accumulator register r of lane l is row 4*(l/16) + r, column l%16 of the 16x16 tile
-                if (lq < N) {
+                for (int v = 1; v < NWAVES; ++v) sum += red[gi & 1][v][b][ll] + red[gi & 1][v][b][ll + 32];
+                if ((ll & 15) < N) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int row = row_begin + (gi * RBK + b) * RB + 4 * g + r;
+                        const int row = row_begin + (gi * RBK + b) * RB + 4 * (ll >> 4) + r;
                         const elem v = sum[r];
-                        if (row < row_end) C[(int64_t)row * N + lq] = v;
+                        if (row < row_end) C[(int64_t)row * N + (ll & 15)] = v;
                     }
                 }
             }

@@ -44,9 +44,6 @@ constexpr int RBK = CYC_NARROW_RBK;        // row blocks accumulated between two
 #ifndef CYC_NARROW_AUX
 #define CYC_NARROW_AUX 2
 #endif
-#ifndef CYC_NARROW_DEPTH
-#define CYC_NARROW_DEPTH 4
-#endif
 #ifndef CYC_NARROW_BURST
 #define CYC_NARROW_BURST 4
 #endif
@@ -80,10 +77,11 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
     constexpr int CH = 16 / ES;          // k values per 16-byte chunk
     constexpr int HALF = S / 2;          // B is staged through LDS in two halves
     constexpr int LPB = S / 2;           // loads per row block: 128-byte pieces in the wave's k-slice
-    constexpr int DEPTH = LPB % CYC_NARROW_DEPTH == 0 ? CYC_NARROW_DEPTH : 4;   // 16-byte loads in flight per lane
-    constexpr int BURST = CYC_NARROW_BURST < DEPTH ? CYC_NARROW_BURST : DEPTH;  // ring slots refilled together
-    static_assert(LPB % DEPTH == 0 && DEPTH % BURST == 0, "the ring must line up with the row blocks");
-    static_assert(RBK % 2 == 0, "the join finishes row blocks in pairs");
+    // A is fetched in bursts of BURST loads per lane into one of two register sets.  The next burst
+    // is issued the moment the previous one has landed, before its MFMAs, so the queue never holds
+    // more than one burst per wave and is refilled without waiting for the matrix pipe.
+    constexpr int BURST = LPB % (2 * CYC_NARROW_BURST) == 0 ? CYC_NARROW_BURST : 2;
+    static_assert(LPB % (2 * BURST) == 0, "a row block must be an even number of bursts");
     typedef typename Mac<I8>::acc_t acc_t;
     typedef typename Mac<I8>::elem elem;
 
@@ -138,11 +136,11 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
     };
 
     // the first loads of A go out before B is staged, so that HBM is busy during the staging
-    i32x4 ring[DEPTH];
+    i32x4 ring[2][BURST];
     __amdgpu_buffer_rsrc_t d_cur = block_desc(0);
     uint32_t v_cur = lane_voff(0);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) ring[d] = fetch(d_cur, v_cur, d);
+    for (int u = 0; u < BURST; ++u) ring[0][u] = fetch(d_cur, v_cur, u);
 
     // ---- this wave's slice of B -> MFMA operand registers, once.  Rows of B are copied into a
     // wave-private LDS patch ([k][16 columns], zero beyond N and K) and read back through the
@@ -211,17 +209,21 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
             acc_t even = {0, 0, 0, 0}, odd = {0, 0, 0, 0};
 #pragma unroll
             for (int p0 = 0; p0 < LPB; p0 += BURST) {
+                const int set = (p0 / BURST) & 1;
+                // this burst has landed (nothing else of this wave is in flight): ask for the next one
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int u = 0; u < BURST; ++u) {
-                    const i32x4 a = ring[(p0 + u) % DEPTH];
-                    even = Mac<I8>::mfma(a, Bf[2 * (p0 + u)], even);
-                    odd = Mac<I8>::mfma(a, Bf[2 * (p0 + u) + 1], odd);
+                    const int p = p0 + BURST + u;
+                    ring[set ^ 1][u] = p < LPB ? fetch(d_cur, v_cur, p) : fetch(d_next, v_next, p - LPB);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int u = 0; u < BURST; ++u) {
-                    const int p = p0 + u;
-                    ring[p % DEPTH] = (p + DEPTH < LPB) ? fetch(d_cur, v_cur, p + DEPTH) : fetch(d_next, v_next, p + DEPTH - LPB);
+                    const i32x4 a = ring[set][u];
+                    even = Mac<I8>::mfma(a, Bf[2 * (p0 + u)], even);
+                    odd = Mac<I8>::mfma(a, Bf[2 * (p0 + u) + 1], odd);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }

@@ -40,8 +40,10 @@
  * else runs on a slower shape-agnostic kernel.
  *
  * The environment variable CYC_FORCE_KERNEL (generic | mfma256 | mfma128 |
- * narrow), read at every call, overrides the choice of kernel when the named
- * kernel supports the problem; it exists for tests and benchmarks.
+ * mfma256x32 | mfma128x32 | narrow), read at every call, overrides the choice
+ * of kernel when the named kernel supports the problem; it exists for tests
+ * and benchmarks.  (The x32 kernels use the 32x32 MFMA shape instead of the
+ * 16x16 one; the dispatcher never picks them by itself.)
  */
 #ifndef CYCLOTRON_MM_H
 #define CYCLOTRON_MM_H
@@ -89,7 +91,8 @@ const char *cyc_status_string(int status);
 int cyc_version(void);
 
 /* Name of the kernel family the dispatcher would pick for this problem
- * ("mfma256", "mfma128", "narrow", "generic", "zero", "none"); static storage.
+ * ("mfma256", "mfma128", "narrow", "generic", "zero", "none", or a name forced
+ * through CYC_FORCE_KERNEL); static storage.
  * Host only; enqueues nothing.  Pointers are only inspected for alignment. */
 const char *cyc_kernel_name(const void *A, const void *B, const void *C,
                             int64_t batch, int64_t M, int64_t K, int64_t N,

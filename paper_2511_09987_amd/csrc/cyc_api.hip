@@ -25,7 +25,7 @@ bool overlaps(const void *p, int64_t pbytes, const void *q, int64_t qbytes)
     return a < b + (uintptr_t)qbytes && b < a + (uintptr_t)pbytes;
 }
 
-enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_NARROW };
+enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_MFMA256X32, K_MFMA128X32, K_NARROW };
 
 const char *kernel_label(Kernel k)
 {
@@ -35,6 +35,8 @@ const char *kernel_label(Kernel k)
         case K_GENERIC: return "generic";
         case K_MFMA256: return "mfma256";
         case K_MFMA128: return "mfma128";
+        case K_MFMA256X32: return "mfma256x32";
+        case K_MFMA128X32: return "mfma128x32";
         case K_NARROW: return "narrow";
     }
     return "none";
@@ -74,13 +76,16 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
 
     if (K == 0) { *k = K_ZERO; return CYC_OK; }
 
-    // CYC_FORCE_KERNEL=generic|mfma256|mfma128|narrow overrides the heuristic when the named
-    // kernel supports the problem (testing and benchmarking aid).
+    // CYC_FORCE_KERNEL=generic|mfma256|mfma128|mfma256x32|mfma128x32|narrow overrides the heuristic when
+    // the named kernel supports the problem (testing and benchmarking aid).  The x32 names are the MFMA
+    // kernels built on the 32x32 instruction shape, which the dispatcher never picks by itself.
     const char *force = std::getenv("CYC_FORCE_KERNEL");
     if (force && *force) {
         if (!std::strcmp(force, "generic")) { *k = K_GENERIC; return CYC_OK; }
         if (!std::strcmp(force, "mfma256") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256; return CYC_OK; }
         if (!std::strcmp(force, "mfma128") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128; return CYC_OK; }
+        if (!std::strcmp(force, "mfma256x32") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256X32; return CYC_OK; }
+        if (!std::strcmp(force, "mfma128x32") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128X32; return CYC_OK; }
         if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
     }
     if (cyc::prefers_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
@@ -107,8 +112,10 @@ int run(const cyc::Problem &p, Kernel k, hipStream_t s)
         case K_NONE: return CYC_OK;
         case K_ZERO: e = cyc::launch_zero(p, s); break;
         case K_GENERIC: e = cyc::launch_generic(p, s); break;
-        case K_MFMA256: e = cyc::launch_mfma(p, 256, s); break;
-        case K_MFMA128: e = cyc::launch_mfma(p, 128, s); break;
+        case K_MFMA256: e = cyc::launch_mfma(p, 256, 16, s); break;
+        case K_MFMA128: e = cyc::launch_mfma(p, 128, 16, s); break;
+        case K_MFMA256X32: e = cyc::launch_mfma(p, 256, 32, s); break;
+        case K_MFMA128X32: e = cyc::launch_mfma(p, 128, 32, s); break;
         case K_NARROW: e = cyc::launch_narrow(p, s); break;
     }
     return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;

@@ -20,7 +20,7 @@ hipError_t launch_generic(const Problem &p, hipStream_t s);
 hipError_t launch_zero(const Problem &p, hipStream_t s);
 // MFMA tiled GEMM; requires supports_mfma(p, tile)
 bool supports_mfma(const Problem &p, int tile);
-hipError_t launch_mfma(const Problem &p, int tile, hipStream_t s);
+hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s);   // mt: MFMA tile width, 16 or 32
 // HBM-bound streaming kernel for N <= 16; requires supports_narrow(p)
 bool supports_narrow(const Problem &p);
 bool prefers_narrow(const Problem &p);   // supported and expected to beat the GEMM kernels

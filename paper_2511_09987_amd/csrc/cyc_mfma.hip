@@ -20,31 +20,62 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 
 #define CYC_LDS __attribute__((address_space(3)))
 #define CYC_GLB __attribute__((address_space(1)))
 
-// accumulator type and MFMA instruction per element type; operands travel as 4 dwords
-template <bool I8> struct Acc;
-template <> struct Acc<false> {
+// accumulator type and MFMA instruction per element type and tile shape MT (MT x MT outputs per
+// instruction, 16 bytes of k per lane); operands travel as 4 dwords.  Both shapes have the same peak
+// rate, but this chip runs dense GEMMs at its power limit and the 16-wide shape costs less energy per
+// flop: issued back to back from registers on random operands it sustains 1.96 PFLOP/s (bf16) against
+// 1.71 for the 32-wide shape, and the kernels here run at 1.9 GHz with it against 1.65 GHz.  The
+// dispatcher uses the 16-wide shape; the 32-wide one stays selectable for comparison.
+template <bool I8, int MT> struct Acc;
+template <> struct Acc<false, 32> {
     typedef float elem;
     typedef f32x16 type;   // bf16 x bf16 -> fp32, 32x32 tile, 16 k per instruction
     static __device__ __forceinline__ type mfma(i32x4 a, i32x4 b, type c)
     { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0); }
 };
-template <> struct Acc<true> {
+template <> struct Acc<true, 32> {
     typedef int elem;
     typedef i32x16 type;   // int8 x int8 -> int32, 32x32 tile, 32 k per instruction
     static __device__ __forceinline__ type mfma(i32x4 a, i32x4 b, type c)
     { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
 };
+// The 16-wide forms are written as asm with the accumulator tied to the destination: left to the
+// register allocator, a fully occupied accumulator file ends up with destinations that differ from
+// their sources and some hundred register moves per k-tile to rotate them back.  The compiler's
+// hazard logic does not look inside asm: no accumulator is read by another instruction within 60
+// MFMAs of its update, and the kernel waits explicitly before it reads them out.
+template <> struct Acc<false, 16> {
+    typedef float elem;
+    typedef f32x4 type;    // 16x16 tile, 32 k per instruction
+    static __device__ __forceinline__ type mfma(i32x4 a, i32x4 b, type c)
+    {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+        return c;
+    }
+};
+template <> struct Acc<true, 16> {
+    typedef int elem;
+    typedef i32x4 type;    // 16x16 tile, 64 k per instruction
+    static __device__ __forceinline__ type mfma(i32x4 a, i32x4 b, type c)
+    {
+        asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+        return c;
+    }
+};
 
-template <bool I8, int BM_, int BN_, int WM_, int WN_>
+template <bool I8, int BM_, int BN_, int WM_, int WN_, int MT_>
 struct Cfg {
     static constexpr bool I8v = I8;
-    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_, MT = MT_;
+    static constexpr int NKS = MT == 32 ? 4 : 2;   // MFMA k-steps per k-tile (32 or 64 bytes of k each)
+    static constexpr int ACCN = MT * MT / 64;      // accumulator registers per MFMA tile
     static constexpr int NW = WM * WN, NT = NW * 64;
     static constexpr int ES = I8 ? 1 : 2;          // bytes per input element
     static constexpr int BKE = 128 / ES;           // k elements per tile
@@ -58,7 +89,7 @@ struct Cfg {
     static constexpr int RPI = 64 / CPR;           // B rows covered by one wave-wide 1 KiB load
     static constexpr int AI = BM / 8 / NW;         // 1 KiB A loads per wave per k-tile
     static constexpr int BI = B_BYTES / 1024 / NW; // 1 KiB B loads per wave per k-tile
-    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
+    static constexpr int TM = BM / WM / MT, TN = BN / WN / MT;   // MFMA tiles per wave
     static_assert(BM % (8 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "loads must divide evenly over waves");
     static_assert(CPR <= 64 && LDS_BYTES <= 160 * 1024, "tile does not fit");
 };
@@ -70,8 +101,14 @@ __device__ __forceinline__ int swzA(int r) { return (r >> 1) & 7; }
 template <class C>
 __device__ __forceinline__ int swzB(int k)
 {
-    if (!C::I8v) return ((k & 3) << 2) | (C::CPR >= 32 ? ((k >> 3) & 1) << 4 : 0);
-    return C::CPR >= 16 ? (k & 7) << 1 : ((k >> 1) & 3) << 1;
+    if (C::MT == 32) {
+        if (!C::I8v) return ((k & 3) << 2) | (C::CPR >= 32 ? ((k >> 3) & 1) << 4 : 0);
+        return C::CPR >= 16 ? (k & 7) << 1 : ((k >> 1) & 3) << 1;
+    }
+    // 16-wide tiles: half a wave reads, per transpose read, 4 rows k..k+3 and 4 rows k+8..k+11 of 32 bytes
+    // (bf16), or 8 rows k..k+7 and 8 rows k+16..k+23 of 16 bytes (int8)
+    if (!C::I8v) return ((k & 3) << 1) | (((k >> 3) & 1) << 3);
+    return C::CPR >= 16 ? (k & 7) | (((k >> 4) & 1) << 3) : ((k >> 1) & 3) | (((k >> 4) & 1) << 2);
 }
 
 // 64 lanes x 16 bytes go from global memory (wave-uniform base + per-lane 32-bit offset) straight
@@ -177,35 +214,40 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     };
 
     // ---- LDS read offsets of this lane's fragments
-    // A fragment (32 rows x 32 bytes of k): lane holds row l%32, chunk 2*ks + l/32.
-    int offA[4];
+    constexpr int MT = C::MT, NKS = C::NKS;
+    // A fragment (MT rows x 32*64/MT bytes of k): lane holds row l%MT and one 16-byte chunk of the k-step:
+    // chunk 2*ks + l/32 (MT = 32, k-steps of 32 bytes) or 4*ks + l/16 (MT = 16, k-steps of 64 bytes).
+    int offA[NKS];
     {
-        int r = wm * (TM * 32) + (l & 31);
+        int r = wm * (TM * MT) + (l & (MT - 1));
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) offA[ks] = r * 128 + (((ks * 2 + (l >> 5)) ^ swzA(r)) << 4);
+        for (int ks = 0; ks < NKS; ++ks) offA[ks] = r * 128 + (((ks * (8 / NKS) + l / MT) ^ swzA(r)) << 4);
     }
     // B fragment through the LDS transpose read.  In every 16-lane group the lanes point
     // at a (4 k x 16 n) bf16 or (8 k x 16 n) int8 patch and receive, per lane, consecutive
-    // k of one column: lane l ends up with column l%32 and k group l/32 of the MFMA operand.
+    // k of one column: lane l ends up with column l%MT and k group l/MT of the MFMA operand.
     int offB[TN];
     {
-        const int lq = l & 15, colhalf = (l >> 4) & 1, kg = l >> 5;
+        const int lq = l & 15, colhalf = MT == 32 ? (l >> 4) & 1 : 0, kg = l / MT;
         const int krow = C::I8v ? 16 * kg + (lq >> 1) : 8 * kg + (lq >> 2);
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
-            int ncol = wn * (TN * 32) + tn * 32 + colhalf * 16 + (C::I8v ? 8 * (lq & 1) : 4 * (lq & 3));
+            int ncol = wn * (TN * MT) + tn * MT + colhalf * 16 + (C::I8v ? 8 * (lq & 1) : 4 * (lq & 3));
             int byte = ncol * ES;
             offB[tn] = LDS_B0 + krow * RB + ((((byte >> 4)) ^ swzB<C>(krow)) << 4) + (byte & 15);
         }
     }
+    // rows of the B tile per MFMA k-step
+    constexpr int KROWS = (128 / ES) / NKS;
 
-    typename Acc<C::I8v>::type acc[TM][TN];
+    typedef Acc<C::I8v, MT> Mac;
+    typename Mac::type acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+            for (int r = 0; r < C::ACCN; ++r) acc[i][j][r] = 0;
 
     // ---- main loop.  A k-tile (4 MFMA k-steps) is consumed in two halves.  The fragments of one
     // half (2 k-steps: 2*TM A fragments, 2*TN B fragments) sit in one of two register sets; while the
@@ -218,34 +260,35 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // of a k-tile, and a wave that cannot issue its copy cannot issue its MFMAs either.  Hence the
     // copies are spread over both halves, one per group of MFMAs.  B can be fetched before the fence
     // because it has a third stage: tile kt+2 goes where tile kt-1 was, which nobody reads any more.
-    i32x4 fa[2][2][TM];
-    i32x4 fb[2][2][TN];
-    constexpr int NREAD = 2 * (TM + TN);   // fragment reads per half
-    constexpr int NMMA = 2 * TM * TN;      // MFMAs per half
+    constexpr int KSH = NKS / 2;             // MFMA k-steps per half
+    i32x4 fa[2][KSH][TM];
+    i32x4 fb[2][KSH][TN];
+    constexpr int NREAD = KSH * (TM + TN);   // fragment reads per half
+    constexpr int NMMA = KSH * TM * TN;      // MFMAs per half
     constexpr int NG = 8;                  // groups per half
     static_assert(C::AI <= NG && C::BI <= NG, "one copy per group");
     // fragment read number r of a half: k-step q = r / (TM+TN); B fragments first, then A
     auto read_one = [&](int r, int set, int sa, int sb, int h) __attribute__((always_inline)) {
-        const int q = r / (TM + TN), e = r % (TM + TN), ks = h * 2 + q;
+        const int q = r / (TM + TN), e = r % (TM + TN), ks = h * KSH + q;
         if (e < TN) {
             const int o = sb * C::B_BYTES + offB[e];
             i32x2 lo, hi;
             if (C::I8v) {
-                lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + o + (ks * 32) * RB));
-                hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + o + (ks * 32 + 8) * RB));
+                lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + o + (ks * KROWS) * RB));
+                hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((CYC_LDS i32x2 *)(lds + o + (ks * KROWS + 8) * RB));
             } else {
-                lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + o + (ks * 16) * RB)));
-                hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + o + (ks * 16 + 4) * RB)));
+                lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + o + (ks * KROWS) * RB)));
+                hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(lds + o + (ks * KROWS + 4) * RB)));
             }
             fb[set][q][e] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
         } else {
-            fa[set][q][e - TN] = *(CYC_LDS i32x4 *)(lds + sa * C::A_BYTES + offA[ks] + (e - TN) * 32 * 128);
+            fa[set][q][e - TN] = *(CYC_LDS i32x4 *)(lds + sa * C::A_BYTES + offA[ks] + (e - TN) * MT * 128);
         }
     };
     // MFMA number m of a half
     auto mma_one = [&](int m, int set) __attribute__((always_inline)) {
         const int q = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
-        acc[i][j] = Acc<C::I8v>::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
+        acc[i][j] = Mac::mfma(fa[set][q][i], fb[set][q][j], acc[i][j]);
     };
     // One half.  A wave issues at most one instruction every four cycles and an MFMA occupies the
     // matrix pipe for 32, so at most about six other instructions fit between two MFMAs before the
@@ -255,12 +298,11 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         const int naux = NREAD + cp_count, stride = naux / cp_count;   // every stride-th item is a copy
 #pragma unroll
         for (int m = 0; m < NMMA; ++m) {
+            // items x with x * NMMA / naux == m go in front of MFMA m
 #pragma unroll
-            for (int x = 0; x < NREAD + NG; ++x) {
-                if (x < naux && x * NMMA / naux == m) {
-                    if (x % stride == stride - 1 && x / stride < cp_count) issue_one(cp_first + x / stride, cp_sa, cp_sb, cp_tile, tail);
-                    else read_one(x - (x / stride < cp_count ? x / stride : cp_count), set ^ 1, rd_sa, rd_sb, rd_half);
-                }
+            for (int x = (m * naux + NMMA - 1) / NMMA; x < ((m + 1) * naux + NMMA - 1) / NMMA; ++x) {
+                if (x % stride == stride - 1 && x / stride < cp_count) issue_one(cp_first + x / stride, cp_sa, cp_sb, cp_tile, tail);
+                else read_one(x - (x / stride < cp_count ? x / stride : cp_count), set ^ 1, rd_sa, rd_sb, rd_half);
             }
             mma_one(m, set);
             __builtin_amdgcn_sched_barrier(0);
@@ -298,20 +340,23 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     if (RAGGED)
         for (; kt + 2 < last; ++kt) k_tile(kt, false);
     for (; kt < nkt; ++kt) k_tile(kt, true);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // all copies have landed (none may arrive after the workgroup's LDS is released); the last MFMA
+    // results are in the register file 
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 
-    // ---- C_ij <- [i,k_end]_C.  Accumulator register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
-    // column l%32 of its 32x32 tile: for fixed r, 32 lanes write 128 contiguous bytes.
-    typedef typename Acc<C::I8v>::elem elem;
+    // ---- C_ij <- [i,k_end]_C.  32x32 tile: accumulator register r of lane l is row (r/4)*8 + (l/32)*4 + r%4,
+    // column l%32 (for fixed r, 32 lanes write 128 contiguous bytes).  16x16 tile: register r of lane l is
+    // row (l/16)*4 + r, column l%16.
+    typedef typename Mac::elem elem;
     elem *Cw = (elem *)Cout;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (TN * 32) + j * 32 + (l & 31);
-            const int row0 = m0 + wm * (TM * 32) + i * 32 + (l >> 5) * 4;
+            const int col = n0 + wn * (TN * MT) + j * MT + (l & (MT - 1));
+            const int row0 = m0 + wm * (TM * MT) + i * MT + (l / MT) * 4;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < C::ACCN; ++r) {
                 int row = row0 + (r >> 2) * 8 + (r & 3);
                 const elem v = acc[i][j][r];
                 if (!RAGGED || (row < M && col < N)) Cw[(int64_t)row * N + col] = v;
@@ -353,15 +398,21 @@ bool supports_mfma(const Problem &p, int tile)
     return true;
 }
 
-hipError_t launch_mfma(const Problem &p, int tile, hipStream_t s)
+hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s)
 {
-    if (!supports_mfma(p, tile)) return hipErrorInvalidValue;
-    // 256x256 block: 4 waves of 128x128 (one per SIMD, accumulators in the 256 AGPRs).  Eight waves of
-    // 128x64 reach the same MFMA utilisation but read 50 % more LDS per MFMA; on this power-limited
-    // chip that costs clock, and measured 1-3 % slower.
+    if (!supports_mfma(p, tile) || (mt != 16 && mt != 32)) return hipErrorInvalidValue;
+    // 4 waves of 128x128 (256-block) or 64x64 (128-block), one per SIMD; in the 256-block the accumulators
+    // fill the 256 AGPRs.  Eight waves of 128x64 read 50 % more LDS per MFMA and measured slower with
+    // either MFMA shape.  mt chooses the MFMA shape: 16 is what the dispatcher uses (see the comment at Acc).
+    if (mt == 16) {
+        if (tile == 256)
+            return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2, 16>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2, 16>>(p, s);
+        return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2, 16>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2, 16>>(p, s);
+    }
     if (tile == 256)
-        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2>>(p, s);
-    return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2>>(p, s);
+        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2, 32>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2, 32>>(p, s);
+    return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2, 32>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2, 32>>(p, s);
 }
 
 }  // namespace cyc
+

@@ -118,7 +118,8 @@ MFMA256 = [(256, 128, 256), (256, 256, 256), (512, 384, 256), (256, 1024, 768), 
 
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
-@pytest.mark.parametrize("tile,shapes", (("mfma128", MFMA128), ("mfma256", MFMA256)))
+@pytest.mark.parametrize("tile,shapes", (("mfma128", MFMA128), ("mfma256", MFMA256),
+                                         ("mfma128x32", MFMA128), ("mfma256x32", MFMA256)))
 def test_mfma_tiles(lib, oracle, mode, tile, shapes):
     for n, (M, K, N) in enumerate(shapes):
         run_case(lib, oracle, mode, M, K, N, seed=3000 + n, force=tile, expect_kernel=tile)
@@ -132,7 +133,7 @@ MFMA_RAGGED = [(129, 72, 136), (255, 264, 264), (100, 72, 40), (300, 1000, 520),
 
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
-@pytest.mark.parametrize("tile", ("mfma128", "mfma256"))
+@pytest.mark.parametrize("tile", ("mfma128", "mfma256", "mfma128x32", "mfma256x32"))
 def test_mfma_ragged_shapes(lib, oracle, mode, tile):
     for n, (M, K, N) in enumerate(MFMA_RAGGED):
         if mode == "i8":                      # int8 rows need multiples of 16
@@ -147,7 +148,7 @@ def test_mfma_ragged_edges_are_not_overwritten(lib):
     A, B, _, _ = gen("bf16", (M, K), (K, N), seed=81, kind="small")
     guard = torch.full((M + 2, N), -12345.0, dtype=torch.float32, device=DEV)
     C = guard[1:M + 1]
-    for tile in ("mfma128", "mfma256"):
+    for tile in ("mfma128", "mfma256", "mfma128x32", "mfma256x32"):
         os.environ["CYC_FORCE_KERNEL"] = tile
         try:
             lib.recurrence_matmul(A, B, out=C)
@@ -158,7 +159,7 @@ def test_mfma_ragged_edges_are_not_overwritten(lib):
 
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
-@pytest.mark.parametrize("tile", ("mfma128", "mfma256"))
+@pytest.mark.parametrize("tile", ("mfma128", "mfma256", "mfma256x32"))
 def test_mfma_one_hot_probes(lib, tile, mode):
     """A = a e_p e_q^T, B = b e_q e_r^T  =>  C = ab e_p e_r^T, with p, q, r on and around
     lane, fragment, wave, k-tile and block boundaries."""

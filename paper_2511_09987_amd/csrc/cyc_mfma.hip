@@ -121,6 +121,17 @@ __device__ __forceinline__ void async_copy16(const char *base, uint32_t lane_off
                  : "s"(lds_addr), "v"(lane_off), "s"(base)
                  : "memory", "m0");
 }
+// The same copy in two steps, so that an MFMA can sit between them where the hardware wants one
+// instruction between a write of m0 and its use: copy_arm() sets the LDS destination (a + b),
+// copy_fire() issues the load.  Nothing else in these kernels touches m0.
+__device__ __forceinline__ void copy_arm(uint32_t a, uint32_t b)
+{
+    asm volatile("s_add_u32 m0, %0, %1" : : "s"(a), "s"(b) : "m0", "scc");
+}
+__device__ __forceinline__ void copy_fire(const char *base, uint32_t lane_off)
+{
+    asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base) : "memory");
+}
 // This wave's LDS reads are done and all but its newest `keep` copies have landed (copies retire in
 // issue order); then meet the other waves.
 template <int KEEP>
@@ -200,6 +211,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // stage sa), otherwise a piece of the B tile (into B stage sb)
     // (`tail`: this call may be about the last k-tile; false in the bulk of the k loop, where the copy is
     // then unconditional)
+    const char *srcA = baseA + 2 * 128, *srcB = baseB + 2 * stepB;   // source of the k-tile being fetched in the loop
     auto issue_one = [&](int x, int sa, int sb, int ktile, bool tail) __attribute__((always_inline)) {
         const uint32_t dst = x < C::AI ? sa * C::A_BYTES + (w * C::AI + x) * 1024
                                        : LDS_B0 + sb * C::B_BYTES + (w * C::BI + x - C::AI) * 1024;
@@ -211,6 +223,22 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
         } else {
             async_copy16(src, off, lds_base + dst);
         }
+    };
+    // The same for the copies inside the k loop, which fetch from srcA / srcB, in two steps around an
+    // MFMA: arm_one() returns whether fire_one() is to follow (a piece wholly past K is zero-filled
+    // instead).  `at_last`: srcA / srcB point at the last k-tile of a RAGGED problem.
+    auto arm_one = [&](int x, int sa, int sb, bool at_last) __attribute__((always_inline)) -> bool {
+        const uint32_t piece = x < C::AI ? (w * C::AI + x) * 1024 : LDS_B0 + (w * C::BI + x - C::AI) * 1024;
+        const uint32_t stage = x < C::AI ? sa * C::A_BYTES : sb * C::B_BYTES;
+        if (RAGGED && at_last && !((tail_ok >> x) & 1)) {
+            *(CYC_LDS i32x4 *)(lds + piece + stage + l * 16) = (i32x4){0, 0, 0, 0};
+            return false;
+        }
+        copy_arm(lds_base + piece, stage);
+        return true;
+    };
+    auto fire_one = [&](int x) __attribute__((always_inline)) {
+        copy_fire(x < C::AI ? srcA : srcB, x < C::AI ? voffA[x] : voffB[x - C::AI]);
     };
 
     // ---- LDS read offsets of this lane's fragments
@@ -294,17 +322,25 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // matrix pipe for 32, so at most about six other instructions fit between two MFMAs before the
     // pipe starves.  The fragment reads that fill the other register set and this half's copies are
     // therefore dealt out evenly, one small item per MFMA slot, and pinned there.
-    auto half = [&](int set, int rd_sa, int rd_sb, int rd_half, int cp_first, int cp_count, int cp_sa, int cp_sb, int cp_tile, bool tail) __attribute__((always_inline)) {
+    auto half = [&](int set, int rd_sa, int rd_sb, int rd_half, int cp_first, int cp_count, int cp_sa, int cp_sb, bool at_last) __attribute__((always_inline)) {
         const int naux = NREAD + cp_count, stride = naux / cp_count;   // every stride-th item is a copy
 #pragma unroll
         for (int m = 0; m < NMMA; ++m) {
-            // items x with x * NMMA / naux == m go in front of MFMA m
+            // items x with x * NMMA / naux == m go in front of MFMA m; a copy is armed in front of it and
+            // fired behind it
+            int fire = -1;
+            bool go = false;
 #pragma unroll
             for (int x = (m * naux + NMMA - 1) / NMMA; x < ((m + 1) * naux + NMMA - 1) / NMMA; ++x) {
-                if (x % stride == stride - 1 && x / stride < cp_count) issue_one(cp_first + x / stride, cp_sa, cp_sb, cp_tile, tail);
-                else read_one(x - (x / stride < cp_count ? x / stride : cp_count), set ^ 1, rd_sa, rd_sb, rd_half);
+                if (x % stride == stride - 1 && x / stride < cp_count) {
+                    fire = cp_first + x / stride;
+                    go = arm_one(fire, cp_sa, cp_sb, at_last);
+                } else {
+                    read_one(x - (x / stride < cp_count ? x / stride : cp_count), set ^ 1, rd_sa, rd_sb, rd_half);
+                }
             }
             mma_one(m, set);
+            if (fire >= 0 && go) fire_one(fire);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -322,23 +358,33 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     for (int r = 0; r < NREAD; ++r) read_one(r, 0, 0, 0, 0);
 
     int sb0 = 0;                   // B stage of tile kt; tile kt+1 is in sb1, tile kt+2 goes to sb2
-    auto k_tile = [&](int kt, bool tail) __attribute__((always_inline)) {
+    // `careful`: tile kt+2 may be the last k-tile or beyond it; false in the bulk of the k loop, where
+    // srcA / srcB simply move on by one k-tile per iteration and every copy is unconditional.
+    auto k_tile = [&](int kt, bool careful) __attribute__((always_inline)) {
         const int sa0 = kt & 1, sa1 = sa0 ^ 1;
         const int sb1 = sb0 == 2 ? 0 : sb0 + 1, sb2 = sb1 == 2 ? 0 : sb1 + 1;
-        half(0, sa0, sb0, 1, C::AI, C::BI, 0, sb2, tail ? tile_at(kt + 2) : kt + 2, tail);
+        if (careful) {
+            srcA = baseA + (int64_t)tile_at(kt + 2) * 128;
+            srcB = baseB + (int64_t)tile_at(kt + 2) * stepB;
+        }
+        const bool at_last = RAGGED && careful && kt + 2 >= last;
+        half(0, sa0, sb0, 1, C::AI, C::BI, 0, sb2, at_last);
         // all but the B copies just issued have landed; reads of tile kt done.  (Once the last k-tile
         // of a RAGGED problem is involved, wait for all copies: a wave whose piece of that tile lies
         // wholly past K issues no copy for it, so counting outstanding copies would be off.)
-        if (RAGGED && tail) tile_fence<0>();
+        if (RAGGED && careful) tile_fence<0>();
         else tile_fence<C::BI>();
-        half(1, sa1, sb1, 0, 0, C::AI, sa0, 0, tail ? tile_at(kt + 2) : kt + 2, tail);
+        half(1, sa1, sb1, 0, 0, C::AI, sa0, 0, at_last);
+        if (!careful) {
+            srcA += 128;
+            srcB += stepB;
+        }
         sb0 = sb1;
     };
-    // bulk: every copy is of a whole k-tile before the last one; then the (at most three) k-tiles whose
-    // copies touch the last k-tile or have nothing left to fetch
+    // bulk: tile kt+2 is a whole k-tile (RAGGED: and not the last one); then the two or three k-tiles
+    // whose copies touch the last k-tile or have nothing left to fetch
     int kt = 0;
-    if (RAGGED)
-        for (; kt + 2 < last; ++kt) k_tile(kt, false);
+    for (; kt + 2 < (RAGGED ? last : nkt); ++kt) k_tile(kt, false);
     for (; kt < nkt; ++kt) k_tile(kt, true);
     // all copies have landed (none may arrive after the workgroup's LDS is released); the last MFMA
     // results are in the register file 

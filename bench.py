@@ -30,8 +30,8 @@ ROTATE = 3     # distinct (A, B, C) sets cycled through, so operands are not ser
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a 1 GiB device copy (fetch x2.000, write x1.000); measured with the command lines
 # recorded in profiles/bench_all_workloads.md.  None where not measured.
-TRAFFIC_BYTES = {"c3_bf16_8192": 1879400813, "c4_i8_8192": 1073883192, "c5_bf16_narrow": 4524217778,
-                 "c2_bf16_512": 4283738, "c1_i8_64": 40062}
+TRAFFIC_BYTES = {"c3_bf16_8192": 1883465664, "c4_i8_8192": 1075612462, "c5_bf16_narrow": 4386214255,
+                 "c2_bf16_512": 4296527, "c1_i8_64": 47422}
 
 
 def parse():

@@ -111,6 +111,33 @@ def small_int_bf16(shape, r: int, seed: int, tensor_id: int, device="cpu") -> to
     return uniform_int(shape, r, seed, tensor_id, device, dtype=torch.int16).to(torch.bfloat16)
 
 
+def normal_f32(shape, sigma: float, seed: int, tensor_id: int, device="cpu") -> torch.Tensor:
+    """i.i.d. N(0, sigma^2) in fp32 (the bf16 draw before its rounding)."""
+    out = torch.empty(shape, dtype=torch.float32, device=device)
+
+    def draw(h):
+        u1 = (_lsr(h, 40) + 1).to(torch.float32) * (1.0 / (1 << 24))
+        u2 = (_lsr(h, 16) & 0xFFFFFF).to(torch.float32) * (1.0 / (1 << 24))
+        return torch.sqrt(-2.0 * torch.log(u1)) * torch.cos((2.0 * math.pi) * u2) * sigma
+
+    _fill(out.view(-1), draw, seed, tensor_id)
+    return out
+
+
+def tri_lower_bf16(n: int, seed: int, tensor_id: int, device="cpu", upper=0.0) -> torch.Tensor:
+    """A well-conditioned lower-triangular n x n bf16 matrix: entries below the diagonal
+    N(0, (0.5/sqrt(n))^2), diagonal 1 + U[0,1); everything above the diagonal is `upper`
+    (NaN there shows whether anyone reads it)."""
+    L = normal_bf16((n, n), 0.5 / math.sqrt(n), seed, tensor_id, device)
+    h = hash_bits(seed, tensor_id + 1000, 0, n, device)
+    diag = 1.0 + _lsr(h, 40).to(torch.float32) * (1.0 / (1 << 24))
+    L = torch.tril(L, -1)
+    L += torch.diag(diag.to(torch.bfloat16))
+    if upper != 0.0:
+        L += torch.triu(torch.full((n, n), upper, dtype=torch.bfloat16, device=device), 1)
+    return L
+
+
 @dataclass(frozen=True)
 class Workload:
     name: str

@@ -84,6 +84,30 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
                                   int64_t strideA, int64_t strideB, int64_t strideC,
                                   int dtype, void *stream);
 
+/* Tiled forward solve of the lower-triangular system  L X = B  with nrhs right-hand sides
+ * (paper: "Representative recurrences", triangular solve; "Multiple Iteration Spaces", tiled form
+ *     X_I = TRSM(L_II, B_I - sum_{J<I} GEMM(L_IJ, X_J))  over tiles of nb rows).
+ * The GEMMs are the matrix-multiply recurrence above with L_IJ as the stationary operand and the solved
+ * tile X_J streamed: bfloat16 operands, fp32 partial sums.  A solved tile therefore enters them rounded
+ * to bfloat16 (nearest even); inside a tile the solve runs in fp32 on the unrounded values
+ * (t = fma(-L_rj, x_j, t) for j ascending, then one IEEE division by L_rr).  nb is part of the result:
+ * it fixes where X is rounded.
+ *
+ * L:  device, read only, n x n bfloat16 row-major; only the diagonal and the entries below it are read.
+ * B:  device, read only, n x nrhs fp32 row-major.
+ * X:  device, written, n x nrhs fp32 row-major: the solution.  Also used as the running right-hand side
+ *     while the call is in flight.
+ * Xh: device, written, n x nrhs bfloat16 row-major: X rounded to bfloat16, the values the GEMMs consumed.
+ * nb: tile size, 1 <= nb <= 128.  The MFMA kernels serve the GEMMs when n, nrhs and nb are multiples of 8
+ *     and the pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
+ * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates
+ *     nothing and keeps no state.  n == 0 or nrhs == 0: CYC_OK, nothing done.  A zero on the diagonal
+ *     gives infinities or NaNs as IEEE division does, not an error.
+ * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or overflowing extents, nb out of
+ * range), CYC_ERR_ALIAS (X or Xh overlaps L, B or each other), CYC_ERR_LAUNCH. */
+int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
+                        int64_t n, int64_t nrhs, int64_t nb, void *stream);
+
 /* Human-readable name of a cyc_status (static storage, never NULL). */
 const char *cyc_status_string(int status);
 

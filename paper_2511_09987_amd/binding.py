@@ -30,6 +30,8 @@ def _load() -> ctypes.CDLL:
     lib.cyc_recurrence_matmul.restype = cint
     lib.cyc_recurrence_matmul_batched.argtypes = [ptr, ptr, ptr, i64, i64, i64, i64, i64, i64, i64, cint, ptr]
     lib.cyc_recurrence_matmul_batched.restype = cint
+    lib.cyc_recurrence_trsm.argtypes = [ptr, ptr, ptr, ptr, i64, i64, i64, ptr]
+    lib.cyc_recurrence_trsm.restype = cint
     lib.cyc_status_string.argtypes = [cint]
     lib.cyc_status_string.restype = ctypes.c_char_p
     lib.cyc_version.argtypes = []
@@ -76,6 +78,11 @@ def cyc_recurrence_matmul_batched(A: int, B: int, C: int, batch: int, M: int, K:
                                                   dtype, stream))
 
 
+def cyc_recurrence_trsm(L: int, B: int, X: int, Xh: int, n: int, nrhs: int, nb: int, stream: int = 0) -> int:
+    """Raw call: device addresses as ints, returns the cyc_status."""
+    return int(_lib().cyc_recurrence_trsm(L, B, X, Xh, n, nrhs, nb, stream))
+
+
 def cyc_kernel_name(A: int, B: int, C: int, batch: int, M: int, K: int, N: int,
                     strideA: int, strideB: int, strideC: int, dtype: int) -> str:
     return _lib().cyc_kernel_name(A, B, C, batch, M, K, N, strideA, strideB, strideC, dtype).decode()
@@ -113,3 +120,33 @@ def recurrence_matmul(A, B, out=None, stream=None):
     if st != CYC_OK:
         raise CycError(st)
     return out
+
+
+def recurrence_trsm(L, B, nb: int = 64, out=None, out_bf16=None, stream=None):
+    """Tensor-level convenience: (X, Xh) with L X = B solved tile by tile (tiles of nb rows).
+
+    L: (n,n) torch.bfloat16, B: (n,nrhs) torch.float32, contiguous CUDA tensors.  Allocates X (fp32)
+    and Xh (bf16) unless given and forwards pointers to the C ABI on the current (or given) stream.
+    """
+    import torch
+    if not (L.is_cuda and B.is_cuda):
+        raise ValueError("L and B must be device tensors; there is no CPU path")
+    if L.dtype != torch.bfloat16 or B.dtype != torch.float32:
+        raise ValueError("L must be bfloat16 and B float32")
+    if L.dim() != 2 or B.dim() != 2 or L.shape[0] != L.shape[1] or B.shape[0] != L.shape[0]:
+        raise ValueError(f"shape mismatch: L {tuple(L.shape)}, B {tuple(B.shape)}")
+    if not (L.is_contiguous() and B.is_contiguous()):
+        raise ValueError("L and B must be contiguous")
+    n, nrhs = B.shape
+    if out is None:
+        out = torch.empty((n, nrhs), dtype=torch.float32, device=L.device)
+    if out_bf16 is None:
+        out_bf16 = torch.empty((n, nrhs), dtype=torch.bfloat16, device=L.device)
+    for t, dt in ((out, torch.float32), (out_bf16, torch.bfloat16)):
+        if tuple(t.shape) != (n, nrhs) or t.dtype != dt or not t.is_contiguous() or t.device != L.device:
+            raise ValueError("out / out_bf16 has the wrong shape, dtype, layout or device")
+    s = (stream if stream is not None else torch.cuda.current_stream(L.device)).cuda_stream
+    st = cyc_recurrence_trsm(L.data_ptr(), B.data_ptr(), out.data_ptr(), out_bf16.data_ptr(), n, nrhs, nb, s)
+    if st != CYC_OK:
+        raise CycError(st)
+    return out, out_bf16

@@ -89,18 +89,10 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
         if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
     }
     if (cyc::prefers_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
-    // MFMA kernels for everything with 16-byte aligned rows except slivers.  Block size by a small
-    // cost model: a CU runs one 256x256 block or two 128x128 blocks at a time; a 128x128 block does a
-    // quarter of the work at about 3/4 of the efficiency.  Compare the number of rounds each needs.
-    if (M >= 16 && N >= 16) {
-        const int64_t n256 = ((M + 255) / 256) * ((N + 255) / 256) * batch;
-        const int64_t n128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
-        const double cost256 = (double)((n256 + 255) / 256);
-        const double cost128 = (double)((n128 + 511) / 512) * 0.675;
-        const bool ok256 = cyc::supports_mfma(*p, 256), ok128 = cyc::supports_mfma(*p, 128);
-        if (ok256 && (!ok128 || cost256 <= cost128)) { *k = K_MFMA256; return CYC_OK; }
-        if (ok128) { *k = K_MFMA128; return CYC_OK; }
-    }
+    // MFMA kernels for everything with 16-byte aligned rows except slivers
+    const int tile = cyc::choose_mfma_tile(*p);
+    if (tile == 256) { *k = K_MFMA256; return CYC_OK; }
+    if (tile == 128) { *k = K_MFMA128; return CYC_OK; }
     *k = K_GENERIC;
     return CYC_OK;
 }
@@ -140,6 +132,20 @@ int cyc_recurrence_matmul(const void *A, const void *B, void *C, int64_t M, int6
                           void *stream)
 {
     return cyc_recurrence_matmul_batched(A, B, C, 1, M, K, N, 0, 0, 0, dtype, stream);
+}
+
+int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb,
+                        void *stream)
+{
+    if (n < 0 || nrhs < 0 || nb < 1 || nb > 128) return CYC_ERR_SHAPE;
+    int64_t nn, nr;
+    if (!mul_ok(n, n, &nn) || !mul_ok(n, nrhs, &nr)) return CYC_ERR_SHAPE;
+    if (n == 0 || nrhs == 0) return CYC_OK;
+    if (!L || !B || !X || !Xh) return CYC_ERR_NULL;
+    if (overlaps(X, nr * 4, L, nn * 2) || overlaps(X, nr * 4, B, nr * 4) || overlaps(Xh, nr * 2, L, nn * 2) ||
+        overlaps(Xh, nr * 2, B, nr * 4) || overlaps(X, nr * 4, Xh, nr * 2))
+        return CYC_ERR_ALIAS;
+    return cyc::launch_trsm(L, B, X, Xh, n, nrhs, nb, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 
 const char *cyc_kernel_name(const void *A, const void *B, const void *C, int64_t batch, int64_t M, int64_t K,

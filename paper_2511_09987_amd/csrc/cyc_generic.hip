@@ -18,7 +18,7 @@ __device__ inline int widen(int8_t v) { return (int)v; }
 template <typename In, typename Acc>
 __global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ A, const In *__restrict__ B,
                                                          Acc *__restrict__ C, int64_t M, int64_t K, int64_t N,
-                                                         int64_t sA, int64_t sB, int64_t sC)
+                                                         int64_t sA, int64_t sB, int64_t sC, int64_t lda, const Acc *Cin)
 {
     __shared__ Acc As[GK][GT + 1];   // [k][i]
     __shared__ Acc Bs[GK][GT + 1];   // [k][j]
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ 
         for (int x = t; x < GT * GK; x += 256) {
             int ai = x / GK, ak = x % GK;
             int64_t gi = i0 + ai, gk = k0 + ak;
-            As[ak][ai] = (gi < M && gk < K) ? (Acc)widen(A[gi * K + gk]) : (Acc)0;
+            As[ak][ai] = (gi < M && gk < K) ? (Acc)widen(A[gi * lda + gk]) : (Acc)0;
             int bk = x / GT, bj = x % GT;
             int64_t gj = j0 + bj;
             gk = k0 + bk;
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ 
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
             int64_t gi = i0 + ty * 4 + x, gj = j0 + tx * 4 + y;
-            if (gi < M && gj < N) C[gi * N + gj] = acc[x][y];
+            if (gi < M && gj < N) C[gi * N + gj] = Cin ? Cin[gi * N + gj] - acc[x][y] : acc[x][y];   // Cin: C <- Cin - A*B
         }
 }
 
@@ -84,10 +84,12 @@ hipError_t launch_generic(const Problem &p, hipStream_t s)
     dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.batch);
     if (p.i8)
         hipLaunchKernelGGL((ws_generic_kernel<int8_t, int>), grid, dim3(256), 0, s, (const int8_t *)p.A,
-                           (const int8_t *)p.B, (int *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC);
+                           (const int8_t *)p.B, (int *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC, row_stride_a(p),
+                           (const int *)p.Cin);
     else
         hipLaunchKernelGGL((ws_generic_kernel<uint16_t, float>), grid, dim3(256), 0, s, (const uint16_t *)p.A,
-                           (const uint16_t *)p.B, (float *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC);
+                           (const uint16_t *)p.B, (float *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC,
+                           row_stride_a(p), (const float *)p.Cin);
     return hipGetLastError();
 }
 

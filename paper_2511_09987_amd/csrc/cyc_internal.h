@@ -12,7 +12,11 @@ struct Problem {
     int64_t batch, M, K, N;
     int64_t strideA, strideB, strideC;   // elements
     bool i8;                             // false: bf16 -> fp32, true: int8 -> int32
+    // Extensions used by the triangular solve (batch == 1 only; the narrow kernel ignores them):
+    int64_t lda = 0;                     // row stride of A in elements, 0 = K (A is a window of a wider matrix)
+    const void *Cin = nullptr;           // when set, C <- Cin - A*B instead of C <- A*B (same layout as C; may be C)
 };
+inline int64_t row_stride_a(const Problem &p) { return p.lda ? p.lda : p.K; }
 
 // any shape, any alignment; one thread per 4x4 block of C, k ascending
 hipError_t launch_generic(const Problem &p, hipStream_t s);
@@ -21,6 +25,10 @@ hipError_t launch_zero(const Problem &p, hipStream_t s);
 // MFMA tiled GEMM; requires supports_mfma(p, tile)
 bool supports_mfma(const Problem &p, int tile);
 hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s);   // mt: MFMA tile width, 16 or 32
+// block edge (256 or 128) of the MFMA kernel that suits the problem best, 0 if neither supports it
+int choose_mfma_tile(const Problem &p);
+// lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
+hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, hipStream_t s);
 // HBM-bound streaming kernel for N <= 16; requires supports_narrow(p)
 bool supports_narrow(const Problem &p);
 bool prefers_narrow(const Problem &p);   // supported and expected to beat the GEMM kernels

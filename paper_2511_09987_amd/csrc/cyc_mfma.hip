@@ -146,7 +146,8 @@ __device__ __forceinline__ void tile_fence()
 template <class C, bool RAGGED>
 __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                         char *__restrict__ Cout, int M, int K, int N, int64_t sA,
-                                                        int64_t sB, int64_t sC, int tiles_m, int tiles_n)
+                                                        int64_t sB, int64_t sC, int tiles_m, int tiles_n, int lda,
+                                                        const char *Cin)
 {
     constexpr int ES = C::ES, RB = C::RB, TM = C::TM, TN = C::TN;
     __shared__ __attribute__((aligned(1024))) char lds_raw[C::LDS_BYTES];
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
 
     // ---- global source of each 16-byte chunk this lane copies per k-tile: a wave-uniform base
     // that advances with the k-tile, plus a fixed per-lane byte offset (below 2^32, see supports_mfma)
-    const char *baseA = A + ((int64_t)m0 * K) * ES;
+    const char *baseA = A + ((int64_t)m0 * lda) * ES;   // lda: row stride of A in elements (K unless A is a window)
     const char *baseB = B + (int64_t)n0 * ES;
     const int64_t stepB = (int64_t)C::BKE * N * ES;
     uint32_t voffA[C::AI], voffB[C::BI];
@@ -192,7 +193,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
             if (last * C::BKE + c * (16 / ES) < K) tail_ok |= 1u << t;
             r = m0 + r < M ? r : M - 1 - m0;
         }
-        voffA[t] = (uint32_t)r * (uint32_t)(K * ES) + c * 16;
+        voffA[t] = (uint32_t)r * (uint32_t)(lda * ES) + c * 16;
     }
 #pragma unroll
     for (int t = 0; t < C::BI; ++t) {
@@ -404,8 +405,11 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
 #pragma unroll
             for (int r = 0; r < C::ACCN; ++r) {
                 int row = row0 + (r >> 2) * 8 + (r & 3);
-                const elem v = acc[i][j][r];
-                if (!RAGGED || (row < M && col < N)) Cw[(int64_t)row * N + col] = v;
+                elem v = acc[i][j][r];
+                if (!RAGGED || (row < M && col < N)) {
+                    if (Cin) v = ((const elem *)Cin)[(int64_t)row * N + col] - v;   // C <- Cin - A*B
+                    Cw[(int64_t)row * N + col] = v;
+                }
             }
         }
 }
@@ -418,10 +422,12 @@ hipError_t launch_cfg(const Problem &p, hipStream_t s)
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)p.batch);
     if (ragged)
         hipLaunchKernelGGL((ws_mfma_kernel<C, true>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
-                           (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n);
+                           (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
+                           (int)row_stride_a(p), (const char *)p.Cin);
     else
         hipLaunchKernelGGL((ws_mfma_kernel<C, false>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
-                           (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n);
+                           (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
+                           (int)row_stride_a(p), (const char *)p.Cin);
     return hipGetLastError();
 }
 
@@ -434,14 +440,30 @@ bool supports_mfma(const Problem &p, int tile)
     if (tile != 256 && tile != 128) return false;
     const int es = p.i8 ? 1 : 2;
     if (p.K <= 0 || p.M <= 0 || p.N <= 0) return false;
-    if ((p.K * es) % 16 || (p.N * es) % 16) return false;
+    const int64_t lda = row_stride_a(p);
+    if ((p.K * es) % 16 || (p.N * es) % 16 || (lda * es) % 16 || lda < p.K) return false;
+    if ((p.lda || p.Cin) && p.batch != 1) return false;
     if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
     if (((p.M + tile - 1) / tile) * ((p.N + tile - 1) / tile) > (1 << 30)) return false;
     // per-lane byte offsets inside a tile's rows are kept in 32 bits
-    if (p.K * es * 256 + 128 >= ((int64_t)1 << 32) || p.N * es * 128 + 512 >= ((int64_t)1 << 32)) return false;
-    if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C) & 15) return false;
+    if (lda * es * 256 + 128 >= ((int64_t)1 << 32) || p.N * es * 128 + 512 >= ((int64_t)1 << 32)) return false;
+    if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C | (uintptr_t)p.Cin) & 15) return false;
     if (p.batch > 1 && (((p.strideA * es) | (p.strideB * es) | (p.strideC * 4)) & 15)) return false;
     return true;
+}
+
+// Block size by a small cost model: a CU runs one 256x256 block or two 128x128 blocks at a time; a 128x128
+// block does a quarter of the work at about 3/4 of the efficiency.  Compare the number of rounds each needs.
+int choose_mfma_tile(const Problem &p)
+{
+    if (p.M < 16 || p.N < 16) return 0;      // slivers go to the shape-agnostic kernel
+    const int64_t n256 = ((p.M + 255) / 256) * ((p.N + 255) / 256) * p.batch;
+    const int64_t n128 = ((p.M + 127) / 128) * ((p.N + 127) / 128) * p.batch;
+    const double cost256 = (double)((n256 + 255) / 256);
+    const double cost128 = (double)((n128 + 511) / 512) * 0.675;
+    const bool ok256 = supports_mfma(p, 256), ok128 = supports_mfma(p, 128);
+    if (ok256 && (!ok128 || cost256 <= cost128)) return 256;
+    return ok128 ? 128 : 0;
 }
 
 hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s)

@@ -27,7 +27,8 @@ def declared_functions():
 
 def test_header_declares_the_documented_entry_points():
     names = declared_functions()
-    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_status_string", "cyc_version"):
+    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_recurrence_trsm", "cyc_status_string",
+                 "cyc_version"):
         assert need in names
 
 
@@ -80,3 +81,19 @@ def test_dispatch_table(pkg):
     assert k(A + 2, B, C, 1, 512, 512, 512, 0, 0, 0, 0) == "generic"      # unaligned A
     assert k(A, B, C, 1, 512, 0, 512, 0, 0, 0, 0) == "zero"
     assert k(A, B, C, 1, 0, 8, 512, 0, 0, 0, 0) == "none"
+
+
+def test_trsm_argument_validation_happens_on_the_host(pkg):
+    f = pkg.cyc_recurrence_trsm
+    L, B, X, Xh = 0x100000, 0x200000, 0x300000, 0x400000
+    assert f(L, B, X, Xh, -1, 4, 64) == 2                    # negative extent
+    assert f(L, B, X, Xh, 8, 4, 0) == 2                      # tile size out of range
+    assert f(L, B, X, Xh, 8, 4, 129) == 2
+    assert f(L, B, X, Xh, 1 << 40, 1 << 40, 64) == 2         # element count overflow
+    assert f(0, B, X, Xh, 8, 4, 64) == 1                     # NULL L
+    assert f(L, B, X, 0, 8, 4, 64) == 1                      # NULL Xh
+    assert f(L, B, B, Xh, 8, 4, 64) == 4                     # X aliases B
+    assert f(L, B, X, X + 16, 8, 4, 64) == 4                 # Xh overlaps X
+    assert f(L, B, L + 32, Xh, 8, 4, 64) == 4                # X overlaps L
+    assert f(0, 0, 0, 0, 0, 4, 64) == 0                      # n == 0: nothing to do
+    assert f(0, 0, 0, 0, 8, 0, 64) == 0                      # nrhs == 0: nothing to do

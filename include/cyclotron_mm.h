@@ -93,7 +93,8 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  * (t = fma(-L_rj, x_j, t) for j ascending, then one IEEE division by L_rr).  nb is part of the result:
  * it fixes where X is rounded.
  *
- * L:  device, read only, n x n bfloat16 row-major; only the diagonal and the entries below it are read.
+ * L:  device, read only, n x n bfloat16 row-major; only the diagonal and the entries below it are used
+ *     (what lies above the diagonal may hold anything, NaN included).
  * B:  device, read only, n x nrhs fp32 row-major.
  * X:  device, written, n x nrhs fp32 row-major: the solution.  Also used as the running right-hand side
  *     while the call is in flight.

@@ -43,29 +43,68 @@ constexpr int SUB = 8;     // rows a lane carries at a time
 // in fp32 on the unrounded x.  A lane works on SUB rows at a time: SUB independent chains take the
 // x of all earlier rows of the tile (kept in LDS, one column per lane), then the SUB x SUB corner is
 // solved in registers.  L_II is staged in LDS once, transposed ([j][r], fp32), so that the SUB
-// coefficients a step needs are two broadcast 16-byte reads; nothing above the diagonal is read.
-template <int NB>
+// coefficients a step needs are two broadcast 16-byte reads; nothing above the diagonal is used.
+// FULL: the tile has exactly NB rows and its rows of L are 16-byte aligned (no per-row checks).
+template <int NB, bool FULL>
 __global__ __launch_bounds__(64) void tri_diag_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                       float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
-                                                      int rows)
+                                                      int rows_arg, int vec_arg)
 {
+    const int rows = FULL ? NB : rows_arg;
+    const bool vec = FULL || vec_arg;
     __shared__ __attribute__((aligned(16))) float Lt[NB][NB];    // Lt[j][r] = L[r0+r][r0+j], j <= r
     __shared__ float xs[NB][64];                                 // xs[j][lane] = x_j of this lane's column
     const int lane = threadIdx.x;
     const int64_t c = (int64_t)blockIdx.x * 64 + lane;
-    const bool live = c < nrhs;
 
-    for (int idx = lane; idx < rows * rows; idx += 64) {
-        const int r = idx / rows, j = idx - r * rows;
-        if (j <= r) Lt[j][r] = widen_bf16(L[(r0 + r) * n + r0 + j]);
+    // stage L_II.  With 16-byte aligned rows each lane fetches 16-byte pieces of rows, all loads in flight
+    // together (pieces wholly above the diagonal are skipped; of a piece that straddles it only the part
+    // at or below the diagonal is used); otherwise element by element.
+    if (vec) {
+        const int cpr = rows >> 3;                               // 16-byte pieces per row of the tile
+        constexpr int PER_LANE = NB * NB / 8 / 64;
+        uint4 piece[PER_LANE];
+#pragma unroll
+        for (int x = 0; x < PER_LANE; ++x) {
+            const int id = lane + 64 * x, r = id / cpr, jc = id - r * cpr;
+            piece[x] = make_uint4(0, 0, 0, 0);
+            if (r < rows && jc * 8 <= r) piece[x] = *(const uint4 *)(L + (r0 + r) * n + r0 + jc * 8);
+        }
+#pragma unroll
+        for (int x = 0; x < PER_LANE; ++x) {
+            const int id = lane + 64 * x, r = id / cpr, jc = id - r * cpr;
+            if (r < rows && jc * 8 <= r) {
+                const uint32_t w[4] = {piece[x].x, piece[x].y, piece[x].z, piece[x].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int j = jc * 8 + e;
+                    if (j <= r) Lt[j][r] = widen_bf16((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+                }
+            }
+        }
+    } else {
+        for (int r = lane; r < rows; r += 64)
+            for (int j = 0; j <= r; ++j) Lt[j][r] = widen_bf16(L[(r0 + r) * n + r0 + j]);
     }
     __syncthreads();
+    if (c >= nrhs) return;        // lanes past the last column only helped staging L; no barrier follows
 
-    for (int rb = 0; rb < rows; rb += SUB) {
+    // the tile's right-hand side comes in with one round of loads, not one per SUB rows
+    const float *rp = Rin + r0 * nrhs + c;
+    float *xp = X + r0 * nrhs + c;
+    uint16_t *hp = Xh + r0 * nrhs + c;
+    float rhs[NB];
+#pragma unroll
+    for (int r = 0; r < NB; ++r) rhs[r] = r < rows ? rp[r * nrhs] : 0.0f;
+
+#pragma unroll
+    for (int rb = 0; rb < NB; rb += SUB) {
+        if (rb >= rows) continue;                                // uniform over the wave
         float t[SUB];
 #pragma unroll
-        for (int q = 0; q < SUB; ++q) t[q] = (live && rb + q < rows) ? Rin[(r0 + rb + q) * nrhs + c] : 0.0f;
+        for (int q = 0; q < SUB; ++q) t[q] = rhs[rb + q];
         // earlier rows of the tile
+#pragma unroll 8
         for (int j = 0; j < rb; ++j) {
             const float x = xs[j][lane];
             const float4 l0 = *(const float4 *)&Lt[j][rb], l1 = *(const float4 *)&Lt[j][rb + 4];
@@ -86,10 +125,8 @@ __global__ __launch_bounds__(64) void tri_diag_kernel(const uint16_t *__restrict
                 for (int p = 0; p < q; ++p) t[q] = __builtin_fmaf(-Lt[rb + p][rb + q], t[p], t[q]);
                 t[q] = t[q] / Lt[rb + q][rb + q];
                 xs[rb + q][lane] = t[q];
-                if (live) {
-                    X[(r0 + rb + q) * nrhs + c] = t[q];
-                    Xh[(r0 + rb + q) * nrhs + c] = round_bf16(t[q]);
-                }
+                xp[(rb + q) * nrhs] = t[q];
+                hp[(rb + q) * nrhs] = round_bf16(t[q]);
             }
         }
     }
@@ -111,10 +148,17 @@ hipError_t diag(const Solve &v, int64_t r0, int64_t r1)
 {
     dim3 grid((unsigned)((v.nrhs + 63) / 64));
     const float *R = rhs_of(v, r0);
-    if (v.nb <= 64)
-        hipLaunchKernelGGL((tri_diag_kernel<64>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, (int)(r1 - r0));
+    const int rows = (int)(r1 - r0);
+    // 16-byte pieces of the tile's rows can be fetched whole
+    const int vec = ((uintptr_t)v.L % 16 == 0) && v.n % 8 == 0 && r0 % 8 == 0 && rows % 8 == 0;
+    if (vec && rows == 64)
+        hipLaunchKernelGGL((tri_diag_kernel<64, true>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
+    else if (vec && rows == 128)
+        hipLaunchKernelGGL((tri_diag_kernel<128, true>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
+    else if (rows <= 64)
+        hipLaunchKernelGGL((tri_diag_kernel<64, false>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
     else
-        hipLaunchKernelGGL((tri_diag_kernel<128>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, (int)(r1 - r0));
+        hipLaunchKernelGGL((tri_diag_kernel<128, false>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
     return hipGetLastError();
 }
 

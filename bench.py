@@ -89,6 +89,43 @@ def measure(lib, torch, w, steps, warmup, sets):
     return wall_ms, kern_ms, kname
 
 
+def measure_trsm(lib, torch, w, steps, warmup, sets):
+    """Time `steps` tiled triangular solves (each a sequence of kernels); returns (wall ms, event ms)."""
+    from datagen import ws_inputs
+    dev = "cuda:0"
+    data = []
+    for r in range(sets):
+        wr = ws_inputs.TriWorkload(w.name, w.n, w.nrhs, w.nb, w.seed + 1000 * r)
+        L, B = ws_inputs.make_tri_inputs(wr, dev)
+        X = torch.empty((w.n, w.nrhs), dtype=torch.float32, device=dev)
+        Xh = torch.empty((w.n, w.nrhs), dtype=torch.bfloat16, device=dev)
+        data.append((L, B, X, Xh))
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        L, B, X, Xh = data[i % sets]
+        st = lib.cyc_recurrence_trsm(L.data_ptr(), B.data_ptr(), X.data_ptr(), Xh.data_ptr(), w.n, w.nrhs, w.nb,
+                                     stream.cuda_stream)
+        if st != 0:
+            raise RuntimeError(lib.cyc_status_string(st))
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+    del data
+    torch.cuda.empty_cache()
+    return wall_ms, ev_ms
+
+
 def roofline(w, kern_ms):
     if w.N <= 16:   # HBM bound: algorithmic bytes = A and B read once, C written once
         ach = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
@@ -178,6 +215,13 @@ def main():
             rf = roofline(wx, kms)
             extra[name] = {"kernel": kn, "ms_per_step": round(wms, 5), "kernel_ms": round(kms, 5),
                            "achieved": rf["achieved"], "unit": rf["unit"], "bound": rf["bound"], "frac": rf["frac"]}
+        # the tiled triangular solve (a sequence of kernels per step: diagonal-space solves and tri-space GEMMs)
+        for name, wt in ws_inputs.TRI_WORKLOADS.items():
+            wms, ems = measure_trsm(lib, torch, wt, max(3, args.steps // 5), max(1, args.warmup // 5), ROTATE)
+            ach = wt.ops / (ems * 1e-3) / 1e12
+            extra[name] = {"kernel": "trsm", "n": wt.n, "nrhs": wt.nrhs, "nb": wt.nb, "ms_per_step": round(wms, 5),
+                           "kernel_ms": round(ems, 5), "achieved": round(ach, 1), "unit": "TFLOP/s", "bound": "mfma",
+                           "frac": round(ach / PEAK["bf16"][0], 4)}
         out["workloads"] = extra
 
     if args.copy_calibration:

@@ -174,6 +174,38 @@ WORKLOADS = {
 }
 
 
+@dataclass(frozen=True)
+class TriWorkload:
+    """Tiled forward solve L X = B: L n x n bf16 lower triangular, B n x nrhs fp32, tiles of nb rows."""
+    name: str
+    n: int
+    nrhs: int
+    nb: int
+    seed: int
+
+    @property
+    def ops(self) -> int:
+        """n(n+1)/2 multiply-adds per right-hand side, counted as two operations each."""
+        return self.n * (self.n + 1) * self.nrhs
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """Lower triangle of L and B read once, X (fp32) and its bf16 rounding written once."""
+        return self.n * (self.n + 1) // 2 * 2 + self.n * self.nrhs * (4 + 4 + 2)
+
+
+# The paper's distributed runs of the triangular solve give no sizes; the shape follows the
+# compute-bound matrix-multiply workloads (8192 rows, 8192 right-hand sides).
+TRI_WORKLOADS = {
+    "t1_trsm_8192": TriWorkload("t1_trsm_8192", 8192, 8192, 64, 6),
+}
+
+
+def make_tri_inputs(w: TriWorkload, device="cpu"):
+    """L (n, n) bf16 and B (n, nrhs) fp32 for a triangular-solve workload."""
+    return tri_lower_bf16(w.n, w.seed, 0, device), normal_f32((w.n, w.nrhs), 1.0, w.seed, 1, device)
+
+
 def make_inputs(w: Workload, device="cpu", scale_down: int = 1):
     """A (batch, M, K) and B (batch, K, N) for a workload; batch dim dropped when batch == 1.
 

@@ -8,6 +8,9 @@ before the timed region.  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu] [--no-extra]
                   [--copy-calibration]
 
+NAME is one of the five matmul workloads (default c3_bf16_8192) or t1_trsm_8192, the tiled
+triangular solve, which is otherwise measured last and reported under "workloads".
+
 The headline workload is the 8192^3 bf16 case (compute bound, MFMA roofline); the int8 8192^3
 and the batched narrow-stream cases are measured after it and reported under "workloads".
 """
@@ -169,6 +172,46 @@ def cpu_baseline(w, budget_s=15.0):
                       f"of {w.name}, same seed and distribution"}
 
 
+def trsm_entry(wt, wall_ms, ev_ms):
+    ach = wt.ops / (ev_ms * 1e-3) / 1e12
+    return {"kernel": "trsm", "n": wt.n, "nrhs": wt.nrhs, "nb": wt.nb, "ms_per_step": round(wall_ms, 5),
+            "kernel_ms": round(ev_ms, 5), "achieved": round(ach, 1), "unit": "TFLOP/s", "bound": "mfma",
+            "frac": round(ach / PEAK["bf16"][0], 4)}
+
+
+def bench_trsm(lib, torch, wt, args):
+    """The tiled triangular solve as the headline workload: one step = one solve (a sequence of kernels)."""
+    wall_ms, ev_ms = measure_trsm(lib, torch, wt, args.steps, args.warmup, ROTATE)
+    e = trsm_entry(wt, wall_ms, ev_ms)
+    out = {
+        "metric": "recurrence matmul TFLOP/s (TOP/s int8) and % of MI355X MFMA/HBM roofline",
+        "value": round(wt.ops / 1e12 / (wall_ms * 1e-3), 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wt.name, "n": wt.n, "nrhs": wt.nrhs, "nb": wt.nb, "kernel": "trsm",
+                   "accumulate": "fp32", "seed": wt.seed, "operand_sets_rotated": ROTATE},
+        # a step is ~255 launches; the figure is the whole step against the MFMA peak, not one kernel's
+        "roofline": {"bound": "mfma", "achieved": e["achieved"], "peak": PEAK["bf16"][0], "unit": "TFLOP/s",
+                     "frac": e["frac"], "traffic": None, "kernel": "trsm (all kernels of a step)",
+                     "kernel_ms": e["kernel_ms"]},
+    }
+    if not args.no_cpu:
+        import numpy as np
+        from datagen import ws_inputs
+        from oracle import tri_oracle, ws_oracle
+        L, B = ws_inputs.make_tri_inputs(wt, "cpu")
+        cols = 4096
+        Bs = np.ascontiguousarray(B[:, :cols].numpy())
+        t0 = time.perf_counter()
+        tri_oracle.tri_tiled(ws_oracle.bf16_bits(L), Bs, wt.nb)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(wt.n * (wt.n + 1) * cols / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": ws_oracle.threads(), "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"tiled triangular-solve oracle on the first {cols} right-hand sides of "
+                                         f"{wt.name} (columns are independent), same seed and distribution"}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -182,10 +225,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
-    if args.workload not in ws_inputs.WORKLOADS:
-        print(f"bench.py: unknown workload {args.workload}; choose from {sorted(ws_inputs.WORKLOADS)}", file=sys.stderr)
+    if args.workload not in ws_inputs.WORKLOADS and args.workload not in ws_inputs.TRI_WORKLOADS:
+        print(f"bench.py: unknown workload {args.workload}; choose from "
+              f"{sorted(ws_inputs.WORKLOADS) + sorted(ws_inputs.TRI_WORKLOADS)}", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.workload in ws_inputs.TRI_WORKLOADS:
+        print(json.dumps(bench_trsm(lib, torch, ws_inputs.TRI_WORKLOADS[args.workload], args)))
+        return
 
     w = ws_inputs.WORKLOADS[args.workload]
     torch.cuda.synchronize()
@@ -218,10 +265,7 @@ def main():
         # the tiled triangular solve (a sequence of kernels per step: diagonal-space solves and tri-space GEMMs)
         for name, wt in ws_inputs.TRI_WORKLOADS.items():
             wms, ems = measure_trsm(lib, torch, wt, max(3, args.steps // 5), max(1, args.warmup // 5), ROTATE)
-            ach = wt.ops / (ems * 1e-3) / 1e12
-            extra[name] = {"kernel": "trsm", "n": wt.n, "nrhs": wt.nrhs, "nb": wt.nb, "ms_per_step": round(wms, 5),
-                           "kernel_ms": round(ems, 5), "achieved": round(ach, 1), "unit": "TFLOP/s", "bound": "mfma",
-                           "frac": round(ach / PEAK["bf16"][0], 4)}
+            extra[name] = trsm_entry(wt, wms, ems)
         out["workloads"] = extra
 
     if args.copy_calibration:

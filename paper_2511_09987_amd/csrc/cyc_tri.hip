@@ -25,17 +25,73 @@ namespace {
 
 #define CYC_LDS __attribute__((address_space(3)))
 
+constexpr int SUB = 8;     // rows a lane carries at a time
+
 __device__ __forceinline__ float widen_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 // fp32 -> bfloat16, nearest, ties to even; NaN stays NaN
 __device__ __forceinline__ uint16_t round_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16, quiet = (u >> 16) | 0x40u;
+    return (uint16_t)((u & 0x7fffffffu) > 0x7f800000u ? quiet : rounded);
 }
 
-constexpr int SUB = 8;     // rows a lane carries at a time
+
+// SUB chains take the x of the tile's rows [0, rb): t[q] = fma(-L[rb+q][j], x_j, t[q]) for j ascending.
+// rb is a multiple of 8.  The LDS reads of eight steps are issued together and only then consumed (left to
+// itself the scheduler, under register pressure, issues them one step at a time and every step then
+// waits out the full LDS latency).  Lt[j][r] = L[r][j] (fp32), xs[j][lane] = x_j of this lane's column.
+template <int NB>
+__device__ __forceinline__ void take_earlier_rows(float (&t)[SUB], const float (*Lt)[NB], const float (*xs)[64], int rb, int lane)
+{
+#pragma unroll 1
+    for (int j0 = 0; j0 < rb; j0 += 8) {
+        float x[8];
+        float4 l0[8], l1[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            x[u] = xs[j0 + u][lane];
+            l0[u] = *(const float4 *)&Lt[j0 + u][rb];
+            l1[u] = *(const float4 *)&Lt[j0 + u][rb + 4];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            t[0] = __builtin_fmaf(-l0[u].x, x[u], t[0]);
+            t[1] = __builtin_fmaf(-l0[u].y, x[u], t[1]);
+            t[2] = __builtin_fmaf(-l0[u].z, x[u], t[2]);
+            t[3] = __builtin_fmaf(-l0[u].w, x[u], t[3]);
+            t[4] = __builtin_fmaf(-l1[u].x, x[u], t[4]);
+            t[5] = __builtin_fmaf(-l1[u].y, x[u], t[5]);
+            t[6] = __builtin_fmaf(-l1[u].z, x[u], t[6]);
+            t[7] = __builtin_fmaf(-l1[u].w, x[u], t[7]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// The SUB x SUB corner of L_II that couples the rows rb .. rb+SUB-1, fetched in one round before the chains
+// over the earlier rows run, so that no LDS read sits inside the dependent chain of the corner solve:
+// corner(p, q) = L[rb+q][rb+p] for p <= q.
+template <int NB>
+struct Corner {
+    float4 lo[SUB], hi[SUB];
+    __device__ __forceinline__ void fetch(const float (*Lt)[NB], int rb)
+    {
+#pragma unroll
+        for (int p = 0; p < SUB; ++p) {
+            lo[p] = *(const float4 *)&Lt[rb + p][rb];
+            hi[p] = *(const float4 *)&Lt[rb + p][rb + 4];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __device__ __forceinline__ float at(int p, int q) const
+    {
+        const float4 v = q < 4 ? lo[p] : hi[p];
+        const int e = q & 3;
+        return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+    }
+};
 
 // Diagonal space: X_I = TRSM(L_II, R_I) for one tile of `rows` <= NB rows starting at row r0, all
 // right-hand sides.  One wave per 64 columns, one lane per column: a column of X is a chain
@@ -93,42 +149,171 @@ __global__ __launch_bounds__(64) void tri_diag_kernel(const uint16_t *__restrict
     const float *rp = Rin + r0 * nrhs + c;
     float *xp = X + r0 * nrhs + c;
     uint16_t *hp = Xh + r0 * nrhs + c;
-    float rhs[NB];
-#pragma unroll
-    for (int r = 0; r < NB; ++r) rhs[r] = r < rows ? rp[r * nrhs] : 0.0f;
+    // xs[r][lane] holds R_r until row r is solved and x_r from then on.  (The loop over the row groups
+    // below is deliberately not unrolled: a wave runs through this code once, so straight-line code
+    // would be fetched from memory instruction by instruction; a loop body stays in the instruction cache.)
+#pragma unroll 16
+    for (int r = 0; r < rows; ++r) xs[r][lane] = rp[r * nrhs];
 
-#pragma unroll
-    for (int rb = 0; rb < NB; rb += SUB) {
-        if (rb >= rows) continue;                                // uniform over the wave
+#pragma unroll 1
+    for (int rb = 0; rb < rows; rb += SUB) {
         float t[SUB];
 #pragma unroll
-        for (int q = 0; q < SUB; ++q) t[q] = rhs[rb + q];
-        // earlier rows of the tile
-#pragma unroll 8
-        for (int j = 0; j < rb; ++j) {
-            const float x = xs[j][lane];
-            const float4 l0 = *(const float4 *)&Lt[j][rb], l1 = *(const float4 *)&Lt[j][rb + 4];
-            t[0] = __builtin_fmaf(-l0.x, x, t[0]);
-            t[1] = __builtin_fmaf(-l0.y, x, t[1]);
-            t[2] = __builtin_fmaf(-l0.z, x, t[2]);
-            t[3] = __builtin_fmaf(-l0.w, x, t[3]);
-            t[4] = __builtin_fmaf(-l1.x, x, t[4]);
-            t[5] = __builtin_fmaf(-l1.y, x, t[5]);
-            t[6] = __builtin_fmaf(-l1.z, x, t[6]);
-            t[7] = __builtin_fmaf(-l1.w, x, t[7]);
-        }
+        for (int q = 0; q < SUB; ++q) t[q] = rb + q < rows ? xs[rb + q][lane] : 0.0f;
+        Corner<NB> corner;
+        corner.fetch(Lt, rb);
+        take_earlier_rows<NB>(t, Lt, xs, rb, lane);
         // the SUB x SUB corner
 #pragma unroll
         for (int q = 0; q < SUB; ++q) {
             if (rb + q < rows) {                                 // uniform over the wave
 #pragma unroll
-                for (int p = 0; p < q; ++p) t[q] = __builtin_fmaf(-Lt[rb + p][rb + q], t[p], t[q]);
-                t[q] = t[q] / Lt[rb + q][rb + q];
+                for (int p = 0; p < q; ++p) t[q] = __builtin_fmaf(-corner.at(p, q), t[p], t[q]);
+                t[q] = t[q] / corner.at(q, q);
                 xs[rb + q][lane] = t[q];
                 xp[(rb + q) * nrhs] = t[q];
                 hp[(rb + q) * nrhs] = round_bf16(t[q]);
             }
         }
+    }
+}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+
+// A panel of up to four full tiles of 64 rows for one slab of 64 right-hand sides, in one kernel:
+//     for t = 0 .. tiles-1:   R_t = Rin_t - L[t, 0:t] * Xh[0:t]  (tri-space, inside the panel)
+//                             X_t = TRSM(L_tt, R_t)              (diag-space)
+// Columns of X do not depend on one another, so a wave can carry its 64 columns through the whole
+// panel without waiting for any other wave; what would be seven launches (four diagonal solves, three
+// small GEMMs that cannot fill the chip) becomes one.  The panel's GEMMs run on the wave's own MFMAs:
+// L[t, 0:t] is the stationary operand, read from memory straight into operand registers; the panel's
+// solved tiles, rounded to bfloat16, stay in LDS ([k][column]) and are read as the streamed operand
+// through the LDS transpose read.  The product comes out in the MFMA's accumulator layout and crosses
+// LDS once to reach the one-lane-per-column layout of the diagonal solve, which is the code above.
+// Requires 16-byte aligned rows of L (n and r0 multiples of 8).
+__global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
+                                                       float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
+                                                       int tiles)
+{
+    constexpr int NB = 64;
+    __shared__ __attribute__((aligned(16))) float Lt[NB][NB];          // Lt[j][r] = L_tt[r][j], j <= r
+    __shared__ float xs[NB][64];                                       // x of the current tile, one column per lane
+    __shared__ __attribute__((aligned(16))) uint16_t Xb[4 * NB][64];   // solved tiles as bfloat16, [k][column]
+    __shared__ float G[NB][64 + 1];                                    // L[t, 0:t] * Xh[0:t], [row][column]
+    const int lane = threadIdx.x, lq = lane & 15, g = lane >> 4;
+    const int64_t c0 = (int64_t)blockIdx.x * 64;
+    const int64_t c = c0 + lane < nrhs ? c0 + lane : nrhs - 1;         // lanes past the last column shadow it
+    const bool live = c0 + lane < nrhs;
+
+    // Everything a tile needs from memory -- L_tt, its right-hand side, the rows of L for its GEMM -- is
+    // independent of the solves before it, so it is requested one tile ahead and arrives while the
+    // previous tile is being solved.
+    constexpr int cpr = NB / 8, PER_LANE = NB * NB / 8 / 64;
+    uint4 piece[PER_LANE];        // 16-byte pieces of L_tt
+    float rhs[2][NB];             // right-hand side of the tile being solved / of the next one
+    i32x4 a[6][4];                // stationary operand of the tile's GEMM: [MFMA k-step][16-row tile]
+    auto request = [&](int t) __attribute__((always_inline)) {
+        const int64_t rt = r0 + (int64_t)t * NB;
+#pragma unroll
+        for (int x = 0; x < PER_LANE; ++x) {
+            const int id = lane + 64 * x, r = id / cpr, jc = id % cpr;
+            piece[x] = make_uint4(0, 0, 0, 0);
+            if (jc * 8 <= r) piece[x] = *(const uint4 *)(L + (rt + r) * n + rt + jc * 8);
+        }
+        const float *rp = Rin + rt * nrhs + c;
+#pragma unroll
+        for (int r = 0; r < NB; ++r) rhs[t & 1][r] = rp[r * nrhs];
+        // row lq of 16-row tile i, k = 32 ks + 8 g .. +7, for every MFMA k-step ks of the GEMM
+#pragma unroll
+        for (int ks = 0; ks < 2 * t; ++ks)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[ks][i] = *(const i32x4 *)(L + (rt + i * 16 + lq) * n + r0 + ks * 32 + g * 8);
+    };
+    request(0);
+
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {                                // unrolled: t is a constant in every copy
+        if (t >= tiles) break;
+        const int64_t rt = r0 + (int64_t)t * NB;
+        // ---- stage L_tt (see tri_diag_kernel)
+#pragma unroll
+        for (int x = 0; x < PER_LANE; ++x) {
+            const int id = lane + 64 * x, r = id / cpr, jc = id % cpr;
+            if (jc * 8 <= r) {
+                const uint32_t w[4] = {piece[x].x, piece[x].y, piece[x].z, piece[x].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    if (jc * 8 + e <= r) Lt[jc * 8 + e][r] = widen_bf16((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+            }
+        }
+        // ---- tri-space inside the panel: G = L[t, 0:t] * Xb[0:t]  (64 x 64t times 64t x 64)
+        if (t > 0) {
+            f32x4 acc[4][4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = (f32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < 2 * t; ++ks) {                 // MFMA k-steps of 32
+                i32x4 b[4];
+                // streamed operand: column lq of tile j, the same k, through the transpose read
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    CYC_LDS char *p = (CYC_LDS char *)&Xb[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                    const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                    const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+                    b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ks][i]), __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
+            }
+            // accumulator register r of lane l is row 4*(l/16) + r, column l%16 of its 16 x 16 tile
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) G[i * 16 + 4 * g + r][j * 16 + lq] = acc[i][j][r];
+        }
+        __syncthreads();                                        // Lt and G are in place
+        // xs[r][lane] holds R_r until row r is solved and x_r from then on
+#pragma unroll
+        for (int r = 0; r < NB; ++r) xs[r][lane] = t > 0 ? rhs[t & 1][r] - G[r][lane] : rhs[t & 1][r];
+        if (t + 1 < tiles) request(t + 1);                      // lands during the solve below
+
+        // ---- diag-space: the chains of tri_diag_kernel, full tile
+        float *xp = X + rt * nrhs + c;
+        uint16_t *hp = Xh + rt * nrhs + c;
+#pragma unroll 1
+        for (int rb = 0; rb < NB; rb += SUB) {
+            float tt[SUB];
+#pragma unroll
+            for (int q = 0; q < SUB; ++q) tt[q] = xs[rb + q][lane];
+            Corner<NB> corner;
+            corner.fetch(Lt, rb);
+            take_earlier_rows<NB>(tt, Lt, xs, rb, lane);
+#pragma unroll
+            for (int q = 0; q < SUB; ++q) {
+#pragma unroll
+                for (int p = 0; p < q; ++p) tt[q] = __builtin_fmaf(-corner.at(p, q), tt[p], tt[q]);
+                tt[q] = tt[q] / corner.at(q, q);
+                xs[rb + q][lane] = tt[q];
+                const uint16_t h = round_bf16(tt[q]);
+                Xb[t * NB + rb + q][lane] = h;
+                if (live) {
+                    xp[(rb + q) * nrhs] = tt[q];
+                    hp[(rb + q) * nrhs] = h;
+                }
+            }
+        }
+        __syncthreads();                                        // Xb of this tile visible; Lt, G, xs free for the next
     }
 }
 
@@ -181,8 +366,23 @@ hipError_t update(const Solve &v, int64_t r0, int64_t mid, int64_t r1)
     return tile ? launch_mfma(p, tile, 16, v.s) : launch_generic(p, v.s);
 }
 
+// up to four full 64-row tiles with 16-byte aligned rows of L: one launch for the whole range
+bool panel_ok(const Solve &v, int64_t r0, int64_t r1)
+{
+    return v.nb == 64 && (r1 - r0) % 64 == 0 && r1 - r0 <= 256 && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0 && r0 % 8 == 0;
+}
+
+hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
+{
+    dim3 grid((unsigned)((v.nrhs + 63) / 64));
+    hipLaunchKernelGGL(tri_panel_kernel, grid, dim3(64), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0,
+                       (int)((r1 - r0) / 64));
+    return hipGetLastError();
+}
+
 hipError_t solve(const Solve &v, int64_t r0, int64_t r1)
 {
+    if (panel_ok(v, r0, r1)) return panel(v, r0, r1);
     if (r1 - r0 <= v.nb) return diag(v, r0, r1);
     const int64_t tiles = (r1 - r0 + v.nb - 1) / v.nb;
     const int64_t mid = r0 + (tiles + 1) / 2 * v.nb;       // the first half takes the odd tile: mid stays a tile boundary

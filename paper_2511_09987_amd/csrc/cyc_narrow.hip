@@ -73,8 +73,9 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
     // A is fetched in bursts of BURST loads per lane into one of two register sets.  The next burst
     // is issued the moment the previous one has landed, before its MFMAs, so the queue never holds
     // more than one burst per wave and is refilled without waiting for the matrix pipe.
-    constexpr int BURST = LPB % (2 * MAX_BURST) == 0 ? MAX_BURST : 2;
-    static_assert(LPB % (2 * BURST) == 0, "a row block must be an even number of bursts");
+    constexpr int BURST = LPB % MAX_BURST == 0 ? MAX_BURST : 2;
+    constexpr int BPB = LPB / BURST;                       // bursts per row block
+    static_assert(LPB % BURST == 0 && (RBK * BPB) % 2 == 0, "a group of row blocks must be an even number of bursts");
     typedef typename Mac<I8>::acc_t acc_t;
     typedef typename Mac<I8>::elem elem;
 
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(NWAVES * 64) void ws_narrow_kernel(const char *__re
             acc_t even = {0, 0, 0, 0}, odd = {0, 0, 0, 0};
 #pragma unroll
             for (int p0 = 0; p0 < LPB; p0 += BURST) {
-                const int set = (p0 / BURST) & 1;
+                const int set = (b * BPB + p0 / BURST) & 1;   // bursts alternate between the two sets; a group starts on set 0
                 // this burst has landed (nothing else of this wave is in flight): ask for the next one
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __builtin_amdgcn_sched_barrier(0);

@@ -109,6 +109,21 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
 int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
                         int64_t n, int64_t nrhs, int64_t nb, void *stream);
 
+/* Attention by the tile recurrence of the paper's "FlashAttention-2 Recurrence": per query a running
+ * maximum, running sum and running output over tiles of keys; the result is
+ *     O_i. = sum_j softmax_j(Q_i. K_j.^T / sqrt(d)) V_j.      (no mask).
+ * `batch` independent problems (e.g. batch x heads), stored one after the other.
+ *
+ * Q: device, read only, batch x N x d bfloat16 row-major.  K, V: device, read only, batch x M x d bfloat16.
+ * O: device, written, batch x N x d fp32 row-major.  All pointers 16-byte aligned.
+ * d must be 64 or 128; N, M >= 1 arbitrary (M * d < 2^31).  Scores, maxima, sums and outputs are fp32; the
+ * exponentials enter the product with V rounded to bfloat16.  stream: hipStream_t or NULL; asynchronous,
+ * allocates nothing.  batch == 0 or N == 0: CYC_OK, nothing done.
+ * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative extents, M == 0 with N > 0, unsupported d,
+ * misaligned pointers, sizes out of range), CYC_ERR_ALIAS (O overlaps Q, K or V), CYC_ERR_LAUNCH. */
+int cyc_recurrence_attention(const void *Q, const void *K, const void *V, void *O,
+                             int64_t batch, int64_t N, int64_t M, int64_t d, void *stream);
+
 /* Human-readable name of a cyc_status (static storage, never NULL). */
 const char *cyc_status_string(int status);
 

@@ -32,6 +32,8 @@ def _load() -> ctypes.CDLL:
     lib.cyc_recurrence_matmul_batched.restype = cint
     lib.cyc_recurrence_trsm.argtypes = [ptr, ptr, ptr, ptr, i64, i64, i64, ptr]
     lib.cyc_recurrence_trsm.restype = cint
+    lib.cyc_recurrence_attention.argtypes = [ptr, ptr, ptr, ptr, i64, i64, i64, i64, ptr]
+    lib.cyc_recurrence_attention.restype = cint
     lib.cyc_status_string.argtypes = [cint]
     lib.cyc_status_string.restype = ctypes.c_char_p
     lib.cyc_version.argtypes = []
@@ -81,6 +83,11 @@ def cyc_recurrence_matmul_batched(A: int, B: int, C: int, batch: int, M: int, K:
 def cyc_recurrence_trsm(L: int, B: int, X: int, Xh: int, n: int, nrhs: int, nb: int, stream: int = 0) -> int:
     """Raw call: device addresses as ints, returns the cyc_status."""
     return int(_lib().cyc_recurrence_trsm(L, B, X, Xh, n, nrhs, nb, stream))
+
+
+def cyc_recurrence_attention(Q: int, K: int, V: int, O: int, batch: int, N: int, M: int, d: int, stream: int = 0) -> int:
+    """Raw call: device addresses as ints, returns the cyc_status."""
+    return int(_lib().cyc_recurrence_attention(Q, K, V, O, batch, N, M, d, stream))
 
 
 def cyc_kernel_name(A: int, B: int, C: int, batch: int, M: int, K: int, N: int,
@@ -150,3 +157,34 @@ def recurrence_trsm(L, B, nb: int = 64, out=None, out_bf16=None, stream=None):
     if st != CYC_OK:
         raise CycError(st)
     return out, out_bf16
+
+
+def recurrence_attention(Q, K, V, out=None, stream=None):
+    """Tensor-level convenience: O = softmax(Q K^T / sqrt(d)) V by the tile recurrence.
+
+    Q: (N,d) or (batch,N,d); K, V: (M,d) or (batch,M,d); contiguous torch.bfloat16 CUDA tensors, d 64 or 128.
+    Allocates O (float32) unless given and forwards pointers to the C ABI on the current (or given) stream.
+    """
+    import torch
+    if not (Q.is_cuda and K.is_cuda and V.is_cuda):
+        raise ValueError("Q, K and V must be device tensors; there is no CPU path")
+    if not (Q.dtype == K.dtype == V.dtype == torch.bfloat16):
+        raise ValueError("Q, K and V must be bfloat16")
+    if Q.dim() not in (2, 3) or K.dim() != Q.dim() or K.shape != V.shape or Q.shape[-1] != K.shape[-1]:
+        raise ValueError(f"shape mismatch: Q {tuple(Q.shape)}, K {tuple(K.shape)}, V {tuple(V.shape)}")
+    if Q.dim() == 3 and Q.shape[0] != K.shape[0]:
+        raise ValueError("batch extents differ")
+    if not (Q.is_contiguous() and K.is_contiguous() and V.is_contiguous()):
+        raise ValueError("Q, K and V must be contiguous")
+    batch = Q.shape[0] if Q.dim() == 3 else 1
+    N, d = Q.shape[-2:]
+    M = K.shape[-2]
+    if out is None:
+        out = torch.empty(tuple(Q.shape), dtype=torch.float32, device=Q.device)
+    elif tuple(out.shape) != tuple(Q.shape) or out.dtype != torch.float32 or not out.is_contiguous() or out.device != Q.device:
+        raise ValueError("out has the wrong shape, dtype, layout or device")
+    s = (stream if stream is not None else torch.cuda.current_stream(Q.device)).cuda_stream
+    st = cyc_recurrence_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), out.data_ptr(), batch, N, M, d, s)
+    if st != CYC_OK:
+        raise CycError(st)
+    return out

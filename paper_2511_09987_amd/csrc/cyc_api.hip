@@ -148,6 +148,20 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh, int64_t
     return cyc::launch_trsm(L, B, X, Xh, n, nrhs, nb, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 
+int cyc_recurrence_attention(const void *Q, const void *K, const void *V, void *O, int64_t batch, int64_t N, int64_t M,
+                             int64_t d, void *stream)
+{
+    if (batch < 0 || N < 0 || M < 0 || d < 0) return CYC_ERR_SHAPE;
+    if (batch == 0 || N == 0) return CYC_OK;
+    int64_t nq, nk;
+    if (!mul_ok(N, d, &nq) || !mul_ok(M, d, &nk) || !mul_ok(batch, nq, &nq) || !mul_ok(batch, nk, &nk)) return CYC_ERR_SHAPE;
+    if (M == 0 || batch > 65535 || !cyc::supports_attention(N, M, d)) return CYC_ERR_SHAPE;
+    if (!Q || !K || !V || !O) return CYC_ERR_NULL;
+    if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15) return CYC_ERR_SHAPE;
+    if (overlaps(O, nq * 4, Q, nq * 2) || overlaps(O, nq * 4, K, nk * 2) || overlaps(O, nq * 4, V, nk * 2)) return CYC_ERR_ALIAS;
+    return cyc::launch_attention(Q, K, V, O, batch, N, M, d, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
 const char *cyc_kernel_name(const void *A, const void *B, const void *C, int64_t batch, int64_t M, int64_t K,
                             int64_t N, int64_t strideA, int64_t strideB, int64_t strideC, int dtype)
 {

@@ -29,6 +29,10 @@ hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s);   // 
 int choose_mfma_tile(const Problem &p);
 // lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, hipStream_t s);
+// FlashAttention-2 tile recurrence (see cyc_attn.hip); requires supports_attention(N, M, d)
+bool supports_attention(int64_t N, int64_t M, int64_t d);
+hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O, int64_t batch, int64_t N, int64_t M,
+                            int64_t d, hipStream_t s);
 // HBM-bound streaming kernel for N <= 16; requires supports_narrow(p)
 bool supports_narrow(const Problem &p);
 bool prefers_narrow(const Problem &p);   // supported and expected to beat the GEMM kernels

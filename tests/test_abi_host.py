@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_documented_entry_points():
     names = declared_functions()
-    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_recurrence_trsm", "cyc_status_string",
+    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_recurrence_trsm", "cyc_recurrence_attention", "cyc_status_string",
                  "cyc_version"):
         assert need in names
 
@@ -97,3 +97,18 @@ def test_trsm_argument_validation_happens_on_the_host(pkg):
     assert f(L, B, L + 32, Xh, 8, 4, 64) == 4                # X overlaps L
     assert f(0, 0, 0, 0, 0, 4, 64) == 0                      # n == 0: nothing to do
     assert f(0, 0, 0, 0, 8, 0, 64) == 0                      # nrhs == 0: nothing to do
+
+
+def test_attention_argument_validation_happens_on_the_host(pkg):
+    f = pkg.cyc_recurrence_attention
+    Q, K, V, O = 0x100000, 0x200000, 0x300000, 0x400000
+    assert f(Q, K, V, O, 1, -1, 4, 64) == 2                  # negative extent
+    assert f(Q, K, V, O, 1, 4, 4, 32) == 2                   # unsupported head dimension
+    assert f(Q, K, V, O, 1, 4, 0, 64) == 2                   # queries but no keys
+    assert f(Q, K, V, O, 1, 1 << 40, 1 << 40, 128) == 2      # element count overflow
+    assert f(Q + 2, K, V, O, 1, 4, 4, 64) == 2               # misaligned pointer
+    assert f(0, K, V, O, 1, 4, 4, 64) == 1                   # NULL Q
+    assert f(Q, K, V, 0, 1, 4, 4, 64) == 1                   # NULL O
+    assert f(Q, K, V, K, 1, 4, 4, 64) == 4                   # O aliases K
+    assert f(0, 0, 0, 0, 0, 4, 4, 64) == 0                   # empty batch: nothing to do
+    assert f(0, 0, 0, 0, 2, 0, 4, 64) == 0                   # no queries: nothing to do

@@ -5,8 +5,8 @@
 //     S_ij = alpha Q_i. K_j.^T,   mh = max(m_i, max_j S_ij),
 //     l_i <- exp(m_i - mh) l_i + sum_j exp(S_ij - mh),   o_i <- exp(m_i - mh) o_i + sum_j exp(S_ij - mh) V_j.,
 // and O_i. = o_i / l_i at the end.  The paper maps it with the query tile stationary on a processing
-// element and K, V streaming past; so here: a wave holds 64 queries as MFMA operand registers for the
-// whole kernel, a workgroup of four waves (256 queries) streams 64-key tiles of K and V through LDS.
+// element and K, V streaming past; so here: a wave holds 32 queries as MFMA operand registers for the
+// whole kernel, a workgroup of eight waves (256 queries) streams tiles of 64 or 128 keys of K and V through LDS.
 //
 // Both products are computed transposed, which removes every shuffle between them:
 //   S^T = K_tile Q^T   (A operand: 16 keys x 32 d from LDS; B operand: the stationary Q, whose row-major
@@ -36,9 +36,12 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 
 #define CYC_LDS __attribute__((address_space(3)))
 
-constexpr int KT = 64;        // keys per tile
-constexpr int QW = 64;        // queries per wave
-constexpr int NWAVE = 4;      // waves per workgroup
+// Measured at batch 64, N = M = 4096 (TFLOP/s at d = 128 / d = 64): 64 queries per wave and 4 waves 599 / 463;
+// 32 queries per wave and 8 waves (two per SIMD, so one wave's exponentials overlap the other's MFMAs)
+// 938 / 848 with 64-key tiles and 1036 / 772 with 128-key tiles; 16 queries per wave and 16 waves 919 / 806.
+constexpr int QB = 2;                    // 16-query blocks per wave
+constexpr int QW = QB * 16;              // queries per wave
+constexpr int NWAVE = 8;                 // waves per workgroup
 
 // 64 lanes x 16 bytes from global memory (wave-uniform base + per-lane offset) into LDS at lds_addr + lane*16
 __device__ __forceinline__ void copy16(const char *base, uint32_t lane_off, uint32_t lds_addr)
@@ -51,11 +54,13 @@ __device__ __forceinline__ void copy16(const char *base, uint32_t lane_off, uint
 
 __device__ __forceinline__ i32x4 mfma_frag(i32x2 lo, i32x2 hi) { return (i32x4){lo[0], lo[1], hi[0], hi[1]}; }
 
-template <int D>
+// D: head dimension; KT: keys per tile (a multiple of 32)
+template <int D, int KT>
 __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict__ Q, const char *__restrict__ K,
                                                           const char *__restrict__ V, float *__restrict__ O, int N,
                                                           int M, float scale_log2e)
 {
+    constexpr int KB = KT / 16;           // 16-key blocks per tile
     constexpr int ROW = D * 2;            // bytes per row of Q, K, V
     constexpr int CPR = ROW / 16;         // 16-byte chunks per row: 16 (D = 128) or 8 (D = 64)
     constexpr int RPC = 64 / CPR;         // rows per 1 KiB copy
@@ -81,19 +86,19 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
     O += bz * (int64_t)N * D;
     const int q0 = blockIdx.x * (NWAVE * QW) + w * QW;          // first query of this wave
 
-    // ---- the stationary operand: Q of this wave's 64 queries, for the whole kernel.  B operand of
+    // ---- the stationary operand: Q of this wave's queries, for the whole kernel.  B operand of
     // S^T = K Q^T: lane holds query jq*16 + l%16, d = 32 ks + 8 (l/16) .. +7.  Queries past N re-read
     // query N-1 (their results are never stored).
-    i32x4 qf[4][DS];
+    i32x4 qf[QB][DS];
 #pragma unroll
-    for (int jq = 0; jq < 4; ++jq) {
+    for (int jq = 0; jq < QB; ++jq) {
         int qi = q0 + jq * 16 + lq;
         qi = qi < N ? qi : N - 1;
 #pragma unroll
         for (int ks = 0; ks < DS; ++ks) qf[jq][ks] = *(const i32x4 *)(Q + (int64_t)qi * ROW + ks * 64 + g * 16);
     }
 
-    // ---- copies of a 64-key tile of K and of V into stage `st`; keys past M re-read key M-1 (masked below)
+    // ---- copies of a tile of K and of V into stage `st`; keys past M re-read key M-1 (masked below)
     uint32_t voffK[COPIES], voffV[COPIES];
     auto set_offsets = [&](int tile) __attribute__((always_inline)) {
 #pragma unroll
@@ -113,12 +118,12 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
         }
     };
 
-    // ---- running state of this lane's four queries (jq = 0..3): maximum in the log2 domain, this lane's
+    // ---- running state of this lane's queries (one per 16-query block jq): maximum in the log2 domain, this lane's
     // share of the sum, and O^T accumulators [d tile][query tile]
-    float m2[4], lsum[4];
-    f32x4 acc_o[DT][4];
+    float m2[QB], lsum[QB];
+    f32x4 acc_o[DT][QB];
 #pragma unroll
-    for (int jq = 0; jq < 4; ++jq) {
+    for (int jq = 0; jq < QB; ++jq) {
         m2[jq] = -__builtin_inff();
         lsum[jq] = 0.0f;
 #pragma unroll
@@ -139,44 +144,44 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
         CYC_LDS char *Kt = lds + st * TILE_BYTES, *Vt = lds + (2 + st) * TILE_BYTES;
 
         // ---- S^T = K_tile Q^T : [key block ik][query block jq]
-        f32x4 s[4][4];
+        f32x4 s[KB][QB];
 #pragma unroll
-        for (int ik = 0; ik < 4; ++ik)
+        for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
-            for (int jq = 0; jq < 4; ++jq) s[ik][jq] = (f32x4){0, 0, 0, 0};
+            for (int jq = 0; jq < QB; ++jq) s[ik][jq] = (f32x4){0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < DS; ++ks) {
-            i32x4 kf[4];
+            i32x4 kf[KB];
 #pragma unroll
-            for (int ik = 0; ik < 4; ++ik) {
+            for (int ik = 0; ik < KB; ++ik) {
                 const int r = ik * 16 + lq;                       // A operand: key row l%16 of block ik, chunk 4 ks + l/16
                 kf[ik] = *(CYC_LDS i32x4 *)(Kt + r * ROW + (((ks * 4 + g) ^ swzK(r)) << 4));
             }
 #pragma unroll
-            for (int ik = 0; ik < 4; ++ik)
+            for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
-                for (int jq = 0; jq < 4; ++jq)
+                for (int jq = 0; jq < QB; ++jq)
                     s[ik][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ik]), __builtin_bit_cast(bf16x8, qf[jq][ks]), s[ik][jq], 0, 0, 0);
         }
         // accumulator register r of lane l: key 16 ik + 4 (l/16) + r of the tile, query 16 jq + l%16
         if ((t + 1) * KT > M) {                                   // last, ragged tile: keys past M take no weight
 #pragma unroll
-            for (int ik = 0; ik < 4; ++ik)
+            for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     if (t * KT + ik * 16 + 4 * g + r >= M) {
 #pragma unroll
-                        for (int jq = 0; jq < 4; ++jq) s[ik][jq][r] = -__builtin_inff();
+                        for (int jq = 0; jq < QB; ++jq) s[ik][jq][r] = -__builtin_inff();
                     }
         }
 
         // ---- running maximum, rescale factor, probabilities
-        i32x4 pf[4][2];                                           // P^T as B operand: [query block][32-key step]
+        i32x4 pf[QB][KB / 2];                                           // P^T as B operand: [query block][32-key step]
 #pragma unroll
-        for (int jq = 0; jq < 4; ++jq) {
+        for (int jq = 0; jq < QB; ++jq) {
             float top = s[0][jq][0];
 #pragma unroll
-            for (int ik = 0; ik < 4; ++ik)
+            for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) top = __builtin_fmaxf(top, s[ik][jq][r]);
             top = __builtin_fmaxf(top, __shfl_xor(top, 16));
@@ -185,9 +190,9 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
             const float keep = __builtin_amdgcn_exp2f(m2[jq] - mh);   // exp(m - mh); 0 on the first tile
             m2[jq] = mh;
             float part = 0.0f;
-            bf16x8 pk[2];
+            bf16x8 pk[KB / 2];
 #pragma unroll
-            for (int ik = 0; ik < 4; ++ik)
+            for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[ik][jq][r], scale_log2e, -mh));
@@ -195,8 +200,10 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
                     pk[ik >> 1][(ik & 1) * 4 + r] = (__bf16)p;   // k-slot: block ik&1 of the 32-key step ik/2
                 }
             lsum[jq] = __builtin_fmaf(keep, lsum[jq], part);
-            pf[jq][0] = __builtin_bit_cast(i32x4, pk[0]);
-            pf[jq][1] = __builtin_bit_cast(i32x4, pk[1]);
+#pragma unroll
+            for (int sk = 0; sk < KB / 2; ++sk) pf[jq][sk] = __builtin_bit_cast(i32x4, pk[sk]);
+            // most tiles leave the maximum of every query of the wave where it was: nothing to rescale then
+            if (!__builtin_amdgcn_ballot_w64(keep != 1.0f)) continue;
 #pragma unroll
             for (int id = 0; id < DT; ++id) acc_o[id][jq] *= keep;
         }
@@ -204,7 +211,7 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
         // ---- O^T += V^T P^T : A operand lane: d = 16 id + l%16; k-slots 0..3 = keys 32 sk + 4 (l/16) .. +3,
         // k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in)
 #pragma unroll
-        for (int sk = 0; sk < 2; ++sk)
+        for (int sk = 0; sk < KB / 2; ++sk)
 #pragma unroll
             for (int id = 0; id < DT; ++id) {
                 const int klo = sk * 32 + 4 * g + (lq >> 2), khi = klo + 16;      // rows the transpose read points at
@@ -215,14 +222,14 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
                     (CYC_LDS bf16x4 *)(Vt + khi * ROW + ((chunk ^ swzV(khi)) << 4) + within)));
                 const i32x4 vf = mfma_frag(lo, hi);
 #pragma unroll
-                for (int jq = 0; jq < 4; ++jq)
+                for (int jq = 0; jq < QB; ++jq)
                     acc_o[id][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_o[id][jq], 0, 0, 0);
             }
     }
 
     // ---- O_i. = o_i / l_i.  Accumulator register r of lane l: d = 16 id + 4 (l/16) + r, query 16 jq + l%16.
 #pragma unroll
-    for (int jq = 0; jq < 4; ++jq) {
+    for (int jq = 0; jq < QB; ++jq) {
         float tot = lsum[jq];
         tot += __shfl_xor(tot, 16);
         tot += __shfl_xor(tot, 32);
@@ -252,10 +259,10 @@ hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O
     const float scale_log2e = (float)(1.4426950408889634 / __builtin_sqrt((double)d));
     dim3 grid((unsigned)((N + NWAVE * QW - 1) / (NWAVE * QW)), (unsigned)batch);
     if (d == 128)
-        hipLaunchKernelGGL((attn_kernel<128>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
+        hipLaunchKernelGGL((attn_kernel<128, 128>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
                            (const char *)V, (float *)O, (int)N, (int)M, scale_log2e);
     else
-        hipLaunchKernelGGL((attn_kernel<64>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
+        hipLaunchKernelGGL((attn_kernel<64, 64>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
                            (const char *)V, (float *)O, (int)N, (int)M, scale_log2e);
     return hipGetLastError();
 }

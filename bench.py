@@ -8,8 +8,9 @@ before the timed region.  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu] [--no-extra]
                   [--copy-calibration]
 
-NAME is one of the five matmul workloads (default c3_bf16_8192) or t1_trsm_8192, the tiled
-triangular solve, which is otherwise measured last and reported under "workloads".
+NAME is one of the five matmul workloads (default c3_bf16_8192), t1_trsm_8192 (the tiled triangular
+solve) or f1_attn_4096 (the attention tile recurrence); the latter two are otherwise measured last and
+reported under "workloads".
 
 The headline workload is the 8192^3 bf16 case (compute bound, MFMA roofline); the int8 8192^3
 and the batched narrow-stream cases are measured after it and reported under "workloads".
@@ -129,6 +130,81 @@ def measure_trsm(lib, torch, w, steps, warmup, sets):
     return wall_ms, ev_ms
 
 
+def measure_attn(lib, torch, w, steps, warmup, sets):
+    """Time `steps` attention calls (one kernel each); returns (wall ms, event ms)."""
+    from datagen import ws_inputs
+    dev = "cuda:0"
+    data = []
+    for r in range(sets):
+        wr = ws_inputs.AttnWorkload(w.name, w.batch, w.N, w.M, w.d, w.seed + 1000 * r)
+        Q, K, V = ws_inputs.make_attn_inputs(wr, dev)
+        data.append((Q, K, V, torch.empty((w.batch, w.N, w.d), dtype=torch.float32, device=dev)))
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        Q, K, V, O = data[i % sets]
+        st = lib.cyc_recurrence_attention(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), w.batch, w.N, w.M, w.d,
+                                          stream.cuda_stream)
+        if st != 0:
+            raise RuntimeError(lib.cyc_status_string(st))
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+    del data
+    torch.cuda.empty_cache()
+    return wall_ms, ev_ms
+
+
+def attn_entry(w, wall_ms, ev_ms):
+    ach = w.ops / (ev_ms * 1e-3) / 1e12
+    return {"kernel": "attention", "batch": w.batch, "N": w.N, "M": w.M, "d": w.d, "ms_per_step": round(wall_ms, 5),
+            "kernel_ms": round(ev_ms, 5), "achieved": round(ach, 1), "unit": "TFLOP/s", "bound": "mfma",
+            "frac": round(ach / PEAK["bf16"][0], 4)}
+
+
+def bench_attn(lib, torch, w, args):
+    """The attention recurrence as the headline workload: one step = one call = one kernel."""
+    wall_ms, ev_ms = measure_attn(lib, torch, w, args.steps, args.warmup, ROTATE)
+    e = attn_entry(w, wall_ms, ev_ms)
+    out = {
+        "metric": "recurrence matmul TFLOP/s (TOP/s int8) and % of MI355X MFMA/HBM roofline",
+        "value": round(w.ops / 1e12 / (wall_ms * 1e-3), 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "N": w.N, "M": w.M, "d": w.d, "kernel": "attention",
+                   "accumulate": "fp32", "seed": w.seed, "operand_sets_rotated": ROTATE},
+        "roofline": {"bound": "mfma", "achieved": e["achieved"], "peak": PEAK["bf16"][0], "unit": "TFLOP/s",
+                     "frac": e["frac"], "traffic": None, "kernel": "attention", "kernel_ms": e["kernel_ms"]},
+    }
+    if not args.no_cpu:
+        import numpy as np
+        from datagen import ws_inputs
+        from oracle import attn_oracle, ws_oracle
+        elems = min(w.batch, 48)
+        wr = ws_inputs.AttnWorkload(w.name, elems, w.N, w.M, w.d, w.seed)
+        Q, K, V = ws_inputs.make_attn_inputs(wr, "cpu")
+        w64 = lambda t: ws_oracle.bits_to_f64(ws_oracle.bf16_bits(t))
+        t0 = time.perf_counter()
+        for b in range(elems):
+            attn_oracle.attention(w64(Q[b]), w64(K[b]), w64(V[b]))
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(4.0 * elems * w.N * w.M * w.d / dt / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": ws_oracle.threads(), "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"attention oracle (fp64 softmax definition) on the first {elems} of the {w.batch} "
+                                         f"batch elements of {w.name} (elements are independent), same seed and distribution"}
+    return out
+
+
 def roofline(w, kern_ms):
     if w.N <= 16:   # HBM bound: algorithmic bytes = A and B read once, C written once
         ach = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
@@ -225,13 +301,16 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
-    if args.workload not in ws_inputs.WORKLOADS and args.workload not in ws_inputs.TRI_WORKLOADS:
-        print(f"bench.py: unknown workload {args.workload}; choose from "
-              f"{sorted(ws_inputs.WORKLOADS) + sorted(ws_inputs.TRI_WORKLOADS)}", file=sys.stderr)
+    known = sorted(ws_inputs.WORKLOADS) + sorted(ws_inputs.TRI_WORKLOADS) + sorted(ws_inputs.ATTN_WORKLOADS)
+    if args.workload not in known:
+        print(f"bench.py: unknown workload {args.workload}; choose from {known}", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
     if args.workload in ws_inputs.TRI_WORKLOADS:
         print(json.dumps(bench_trsm(lib, torch, ws_inputs.TRI_WORKLOADS[args.workload], args)))
+        return
+    if args.workload in ws_inputs.ATTN_WORKLOADS:
+        print(json.dumps(bench_attn(lib, torch, ws_inputs.ATTN_WORKLOADS[args.workload], args)))
         return
 
     w = ws_inputs.WORKLOADS[args.workload]
@@ -266,6 +345,10 @@ def main():
         for name, wt in ws_inputs.TRI_WORKLOADS.items():
             wms, ems = measure_trsm(lib, torch, wt, max(3, args.steps // 5), max(1, args.warmup // 5), ROTATE)
             extra[name] = trsm_entry(wt, wms, ems)
+        # the attention tile recurrence (one kernel per step)
+        for name, wa in ws_inputs.ATTN_WORKLOADS.items():
+            wms, ems = measure_attn(lib, torch, wa, max(3, args.steps // 2), max(1, args.warmup // 2), ROTATE)
+            extra[name] = attn_entry(wa, wms, ems)
         out["workloads"] = extra
 
     if args.copy_calibration:

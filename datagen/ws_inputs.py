@@ -206,6 +206,40 @@ def make_tri_inputs(w: TriWorkload, device="cpu"):
     return tri_lower_bf16(w.n, w.seed, 0, device), normal_f32((w.n, w.nrhs), 1.0, w.seed, 1, device)
 
 
+@dataclass(frozen=True)
+class AttnWorkload:
+    """Attention by the tile recurrence: `batch` independent problems, N queries, M keys, head dimension d."""
+    name: str
+    batch: int
+    N: int
+    M: int
+    d: int
+    seed: int
+
+    @property
+    def ops(self) -> int:
+        """Two products of N x M x d multiply-adds each, counted as two operations per multiply-add."""
+        return 4 * self.batch * self.N * self.M * self.d
+
+    @property
+    def algorithmic_bytes(self) -> int:
+        """Q, K, V (bf16) read once, O (fp32) written once."""
+        return self.batch * ((self.N + 2 * self.M) * self.d * 2 + self.N * self.d * 4)
+
+
+# The paper evaluates this recurrence in simulation only and gives no sizes; batch x heads = 64,
+# sequence 4096, head dimension 128 is a common shape with as many operations as the 8192^3 matmul / 2.
+ATTN_WORKLOADS = {
+    "f1_attn_4096": AttnWorkload("f1_attn_4096", 64, 4096, 4096, 128, 7),
+}
+
+
+def make_attn_inputs(w: AttnWorkload, device="cpu"):
+    """Q (batch, N, d), K and V (batch, M, d), i.i.d. N(0,1) rounded to bf16 (scores then have unit variance)."""
+    return (normal_bf16((w.batch, w.N, w.d), 1.0, w.seed, 0, device), normal_bf16((w.batch, w.M, w.d), 1.0, w.seed, 1, device),
+            normal_bf16((w.batch, w.M, w.d), 1.0, w.seed, 2, device))
+
+
 def make_inputs(w: Workload, device="cpu", scale_down: int = 1):
     """A (batch, M, K) and B (batch, K, N) for a workload; batch dim dropped when batch == 1.
 

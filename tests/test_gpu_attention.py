@@ -138,10 +138,9 @@ def test_errors(lib):
 def test_full_size_sampled_queries(lib, attn):
     """The benchmark's configuration (batch 64, N = M = 4096, d = 128); queries are independent of one
     another, so the oracle checks a sample of them in a few batch elements."""
-    batch, N, M, d = 64, 4096, 4096, 128
-    Q = ws_inputs.normal_bf16((batch, N, d), 1.0, 9, 0, DEV)
-    K = ws_inputs.normal_bf16((batch, M, d), 1.0, 9, 1, DEV)
-    V = ws_inputs.normal_bf16((batch, M, d), 1.0, 9, 2, DEV)
+    w = ws_inputs.ATTN_WORKLOADS["f1_attn_4096"]
+    assert (w.batch, w.N, w.M, w.d) == (64, 4096, 4096, 128)
+    Q, K, V = ws_inputs.make_attn_inputs(w, DEV)
     O = lib.recurrence_attention(Q, K, V)
     torch.cuda.synchronize()
     rows = [0, 1, 63, 64, 255, 256, 1000, 2047, 4032, 4095]

@@ -6,14 +6,15 @@
 //     l_i <- exp(m_i - mh) l_i + sum_j exp(S_ij - mh),   o_i <- exp(m_i - mh) o_i + sum_j exp(S_ij - mh) V_j.,
 // and O_i. = o_i / l_i at the end.  The paper maps it with the query tile stationary on a processing
 // element and K, V streaming past; so here: a wave holds 32 queries as MFMA operand registers for the
-// whole kernel, a workgroup of eight waves (256 queries) streams tiles of 64 or 128 keys of K and V through LDS.
+// whole kernel, a workgroup of eight waves (256 queries, two waves per SIMD) streams tiles of 64 or 128 keys
+// of K and V through LDS.
 //
 // Both products are computed transposed, which removes every shuffle between them:
 //   S^T = K_tile Q^T   (A operand: 16 keys x 32 d from LDS; B operand: the stationary Q, whose row-major
 //                       rows are exactly the operand layout).  Accumulator lane l then holds, for query
 //                       l%16, the keys 4*(l/16) .. +3 of each 16-key block: all statistics of a query
 //                       (m, l, the rescale factor) are per lane, and only the maximum needs the other
-//                       three lanes of the query (two xor-shuffles per tile).
+//                       three lanes of the query (two lane swaps per tile).
 //   O^T = V^T P^T      (B operand: P^T straight from those accumulators, rounded to bfloat16 -- two
 //                       16-key blocks side by side make the 8 k-slots of a lane, and the sum over keys
 //                       does not care in which slot a key sits as long as V uses the same slots; A
@@ -22,7 +23,19 @@
 //                       exp(m - mh) is a per-lane multiply and the final store is 16 bytes per lane.
 // Arithmetic: Q, K, V bfloat16; S, m, l, o fp32; exp through the hardware exp2 with alpha*log2(e) folded
 // into the scores; the probabilities enter the second product rounded to bfloat16 (nearest even), the
-// running sum takes them unrounded.
+// running sum takes them unrounded.  The maximum that the exponentials refer to follows the running maximum
+// lazily (step_top below); o / l does not depend on it.
+//
+// Schedule: a software pipeline across tiles inside every wave, so that matrix-core and vector-ALU
+// instructions of neighbouring tiles are issued interleaved (the loop at the end of the kernel).
+//
+// Measured at batch 64, N = M = 4096, TFLOP/s at d = 128 / d = 64 (run-to-run spread about 5 %):
+//   64 queries per wave, 4 waves, tile after tile                                    599 / 463
+//   32 queries per wave, 8 waves, tile after tile, 128-key / 64-key tiles           1036 / 848
+//   the same with the two waves of a SIMD half a tile apart (one or two barriers)    940 / 700
+//   software pipeline (this file), maximum followed exactly                          960 / 860
+//   software pipeline, maximum followed lazily                                      1050 / 910
+//   software pipeline with 64 queries per wave and 4 waves (512 registers)           574 / 540
 #include "cyc_internal.h"
 
 namespace cyc {
@@ -36,9 +49,6 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 
 #define CYC_LDS __attribute__((address_space(3)))
 
-// Measured at batch 64, N = M = 4096 (TFLOP/s at d = 128 / d = 64): 64 queries per wave and 4 waves 599 / 463;
-// 32 queries per wave and 8 waves (two per SIMD, so one wave's exponentials overlap the other's MFMAs)
-// 938 / 848 with 64-key tiles and 1036 / 772 with 128-key tiles; 16 queries per wave and 16 waves 919 / 806.
 constexpr int QB = 2;                    // 16-query blocks per wave
 constexpr int QW = QB * 16;              // queries per wave
 constexpr int NWAVE = 8;                 // waves per workgroup
@@ -58,7 +68,7 @@ __device__ __forceinline__ i32x4 mfma_frag(i32x2 lo, i32x2 hi) { return (i32x4){
 template <int D, int KT>
 __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict__ Q, const char *__restrict__ K,
                                                           const char *__restrict__ V, float *__restrict__ O, int N,
-                                                          int M, float scale_log2e)
+                                                          int M, int nqb, float scale_log2e)
 {
     constexpr int KB = KT / 16;           // 16-key blocks per tile
     constexpr int ROW = D * 2;            // bytes per row of Q, K, V
@@ -79,12 +89,18 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
 
     const int l = threadIdx.x & 63, lq = l & 15, g = l >> 4;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t bz = blockIdx.y;
+    // Workgroups are handed to the eight XCDs round robin by their linear index, and each XCD has its own L2.
+    // The workgroups of one batch element read the same K and V, so they are renumbered to run on one XCD:
+    // XCD x takes a contiguous range of (batch element, query block) pairs, in the order it receives them.
+    const int total = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int logical = xcd * (total >> 3) + (xcd < (total & 7) ? xcd : (total & 7)) + slot;
+    const int64_t bz = logical / nqb;
+    const int bx = logical - (int)bz * nqb;
     Q += bz * (int64_t)N * ROW;
     K += bz * (int64_t)M * ROW;
     V += bz * (int64_t)M * ROW;
     O += bz * (int64_t)N * D;
-    const int q0 = blockIdx.x * (NWAVE * QW) + w * QW;          // first query of this wave
+    const int q0 = bx * (NWAVE * QW) + w * QW;          // first query of this wave
 
     // ---- the stationary operand: Q of this wave's queries, for the whole kernel.  B operand of
     // S^T = K Q^T: lane holds query jq*16 + l%16, d = 32 ks + 8 (l/16) .. +7.  Queries past N re-read
@@ -98,25 +114,32 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
         for (int ks = 0; ks < DS; ++ks) qf[jq][ks] = *(const i32x4 *)(Q + (int64_t)qi * ROW + ks * 64 + g * 16);
     }
 
-    // ---- copies of a tile of K and of V into stage `st`; keys past M re-read key M-1 (masked below)
-    uint32_t voffK[COPIES], voffV[COPIES];
-    auto set_offsets = [&](int tile) __attribute__((always_inline)) {
+    // ---- copies of a tile of K or of V into a stage.  A copy moves RPC rows (1 KiB); copy x of wave w takes the rows
+    // x*NWAVE*RPC + w*RPC .. of the tile, so that a lane's offset within its copy (swizzle included: the row
+    // number changes by a multiple of 16 with x) is the same for every x and every full tile.  Keys past M (last
+    // tile only) re-read key M-1 and are masked below.
+    const int row0 = w * RPC + l / CPR;                             // this lane's row within copy 0
+    const uint32_t voffK = (uint32_t)row0 * ROW + (((l % CPR) ^ swzK(row0)) << 4);
+    const uint32_t voffV = (uint32_t)row0 * ROW + (((l % CPR) ^ swzV(row0)) << 4);
+    const int ntiles = (M + KT - 1) / KT;
+    auto issue = [&](const char *src, uint32_t voff, int tile, int stage_index) __attribute__((always_inline)) {
+        const char *base = src + (int64_t)tile * TILE_BYTES;
+        const uint32_t dst = lds_base + stage_index * TILE_BYTES + w * 1024;
+        if ((tile + 1) * KT <= M) {
 #pragma unroll
-        for (int x = 0; x < COPIES; ++x) {
-            const int r = (w * COPIES + x) * RPC + l / CPR, slot = l % CPR;
-            int key = tile * KT + r;
-            key = key < M ? key : M - 1;
-            voffK[x] = (uint32_t)key * ROW + ((slot ^ swzK(r)) << 4);
-            voffV[x] = (uint32_t)key * ROW + ((slot ^ swzV(r)) << 4);
+            for (int x = 0; x < COPIES; ++x) copy16(base + x * (NWAVE * 1024), voff, dst + x * (NWAVE * 1024));
+        } else {
+            const int last = M - 1 - tile * KT;                   // last valid row of the tile
+#pragma unroll
+            for (int x = 0; x < COPIES; ++x) {
+                const int r = x * (NWAVE * RPC) + row0;
+                // offsets are unsigned: row min(r, last) counted from the tile's first row, this lane's chunk
+                copy16(base, (uint32_t)(r <= last ? r : last) * ROW + (voff - (uint32_t)row0 * ROW), dst + x * (NWAVE * 1024));
+            }
         }
     };
-    auto issue_tile = [&](int st) __attribute__((always_inline)) {
-#pragma unroll
-        for (int x = 0; x < COPIES; ++x) {
-            copy16(K, voffK[x], lds_base + st * TILE_BYTES + (w * COPIES + x) * 1024);
-            copy16(V, voffV[x], lds_base + (2 + st) * TILE_BYTES + (w * COPIES + x) * 1024);
-        }
-    };
+    auto issue_K = [&](int tile) __attribute__((always_inline)) { issue(K, voffK, tile, tile & 1); };
+    auto issue_V = [&](int tile) __attribute__((always_inline)) { issue(V, voffV, tile, 2 + (tile & 1)); };
 
     // ---- running state of this lane's queries (one per 16-query block jq): maximum in the log2 domain, this lane's
     // share of the sum, and O^T accumulators [d tile][query tile]
@@ -129,87 +152,15 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
 #pragma unroll
         for (int id = 0; id < DT; ++id) acc_o[id][jq] = (f32x4){0, 0, 0, 0};
     }
+    f32x4 s[KB][QB], s_next[KB][QB];                                  // S^T of tiles t and t+1: [key block][query block]
+    i32x4 pf[QB][KB / 2];                                             // P^T as B operand: [query block][32-key step]
+    float tile_max[QB];                                               // maximum of the newest S^T per query, log2 domain
+    auto landed_barrier = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-    const int ntiles = (M + KT - 1) / KT;
-    set_offsets(0);
-    issue_tile(0);
-    for (int t = 0; t < ntiles; ++t) {
-        const int st = t & 1;
-        // tile t has landed in stage st; every wave is done with stage st^1 (tile t-1)
-        asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-        if (t + 1 < ntiles) {
-            set_offsets(t + 1);
-            issue_tile(st ^ 1);
-        }
-        CYC_LDS char *Kt = lds + st * TILE_BYTES, *Vt = lds + (2 + st) * TILE_BYTES;
-
-        // ---- S^T = K_tile Q^T : [key block ik][query block jq]
-        f32x4 s[KB][QB];
-#pragma unroll
-        for (int ik = 0; ik < KB; ++ik)
-#pragma unroll
-            for (int jq = 0; jq < QB; ++jq) s[ik][jq] = (f32x4){0, 0, 0, 0};
-#pragma unroll
-        for (int ks = 0; ks < DS; ++ks) {
-            i32x4 kf[KB];
-#pragma unroll
-            for (int ik = 0; ik < KB; ++ik) {
-                const int r = ik * 16 + lq;                       // A operand: key row l%16 of block ik, chunk 4 ks + l/16
-                kf[ik] = *(CYC_LDS i32x4 *)(Kt + r * ROW + (((ks * 4 + g) ^ swzK(r)) << 4));
-            }
-#pragma unroll
-            for (int ik = 0; ik < KB; ++ik)
-#pragma unroll
-                for (int jq = 0; jq < QB; ++jq)
-                    s[ik][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[ik]), __builtin_bit_cast(bf16x8, qf[jq][ks]), s[ik][jq], 0, 0, 0);
-        }
-        // accumulator register r of lane l: key 16 ik + 4 (l/16) + r of the tile, query 16 jq + l%16
-        if ((t + 1) * KT > M) {                                   // last, ragged tile: keys past M take no weight
-#pragma unroll
-            for (int ik = 0; ik < KB; ++ik)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (t * KT + ik * 16 + 4 * g + r >= M) {
-#pragma unroll
-                        for (int jq = 0; jq < QB; ++jq) s[ik][jq][r] = -__builtin_inff();
-                    }
-        }
-
-        // ---- running maximum, rescale factor, probabilities
-        i32x4 pf[QB][KB / 2];                                           // P^T as B operand: [query block][32-key step]
-#pragma unroll
-        for (int jq = 0; jq < QB; ++jq) {
-            float top = s[0][jq][0];
-#pragma unroll
-            for (int ik = 0; ik < KB; ++ik)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) top = __builtin_fmaxf(top, s[ik][jq][r]);
-            top = __builtin_fmaxf(top, __shfl_xor(top, 16));
-            top = __builtin_fmaxf(top, __shfl_xor(top, 32));
-            const float mh = __builtin_fmaxf(m2[jq], top * scale_log2e);
-            const float keep = __builtin_amdgcn_exp2f(m2[jq] - mh);   // exp(m - mh); 0 on the first tile
-            m2[jq] = mh;
-            float part = 0.0f;
-            bf16x8 pk[KB / 2];
-#pragma unroll
-            for (int ik = 0; ik < KB; ++ik)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[ik][jq][r], scale_log2e, -mh));
-                    part += p;
-                    pk[ik >> 1][(ik & 1) * 4 + r] = (__bf16)p;   // k-slot: block ik&1 of the 32-key step ik/2
-                }
-            lsum[jq] = __builtin_fmaf(keep, lsum[jq], part);
-#pragma unroll
-            for (int sk = 0; sk < KB / 2; ++sk) pf[jq][sk] = __builtin_bit_cast(i32x4, pk[sk]);
-            // most tiles leave the maximum of every query of the wave where it was: nothing to rescale then
-            if (!__builtin_amdgcn_ballot_w64(keep != 1.0f)) continue;
-#pragma unroll
-            for (int id = 0; id < DT; ++id) acc_o[id][jq] *= keep;
-        }
-
-        // ---- O^T += V^T P^T : A operand lane: d = 16 id + l%16; k-slots 0..3 = keys 32 sk + 4 (l/16) .. +3,
-        // k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in)
+    // ---- O^T += V^T P^T for tile t (in V stage t&1).  A operand lane: d = 16 id + l%16; k-slots 0..3 = keys
+    // 32 sk + 4 (l/16) .. +3, k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in)
+    auto weighted_values = [&](int t) __attribute__((always_inline)) {
+        CYC_LDS char *Vt = lds + (2 + (t & 1)) * TILE_BYTES;
 #pragma unroll
         for (int sk = 0; sk < KB / 2; ++sk)
 #pragma unroll
@@ -225,7 +176,125 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
                 for (int jq = 0; jq < QB; ++jq)
                     acc_o[id][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_o[id][jq], 0, 0, 0);
             }
+    };
+
+    // maximum over lanes l, l^16, l^32, l^48.  The swaps exchange halves (rows 2,3 of the first operand with rows
+    // 0,1 of the second) resp. odd rows of the first with even rows of the second; fed the same value twice, the
+    // two results together hold the value of both partners.  (The elements are copied to scalars before the bit
+    // cast: a bit cast applied to a vector element directly reads element 0 whatever the index.)
+    auto as_float = [](unsigned u) __attribute__((always_inline)) { return __builtin_bit_cast(float, u); };
+    auto wave_max = [&](float x) __attribute__((always_inline)) {
+        const unsigned u = __builtin_bit_cast(unsigned, x);
+        const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        const unsigned a0 = a[0], a1 = a[1];
+        const unsigned v = __builtin_bit_cast(unsigned, __builtin_fmaxf(as_float(a0), as_float(a1)));
+        const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        const unsigned b0 = b[0], b1 = b[1];
+        return __builtin_fmaxf(as_float(b0), as_float(b1));
+    };
+    // ---- S^T = K_tile Q^T for tile t (in K stage t&1)
+    auto scores_into = [&](int t, f32x4(&sn)[KB][QB]) __attribute__((always_inline)) {
+        CYC_LDS char *Kt = lds + (t & 1) * TILE_BYTES;
+#pragma unroll
+        for (int ik = 0; ik < KB; ++ik)
+#pragma unroll
+            for (int jq = 0; jq < QB; ++jq) sn[ik][jq] = (f32x4){0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < DS; ++ks)
+#pragma unroll
+            for (int ik = 0; ik < KB; ++ik) {
+                const int r = ik * 16 + lq;
+                const i32x4 kf = *(CYC_LDS i32x4 *)(Kt + r * ROW + (((ks * 4 + g) ^ swzK(r)) << 4));
+#pragma unroll
+                for (int jq = 0; jq < QB; ++jq)
+                    sn[ik][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qf[jq][ks]), sn[ik][jq], 0, 0, 0);
+            }
+    };
+    // Maximum of the tile's scores per query, in the log2 domain.  Keys past M were copied from key M-1, so their
+    // scores repeat a valid score and leave the maximum alone.
+    auto stats = [&](const f32x4(&sn)[KB][QB]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jq = 0; jq < QB; ++jq) {
+            float top = sn[0][jq][0];
+#pragma unroll
+            for (int ik = 0; ik < KB; ++ik)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) top = __builtin_fmaxf(top, sn[ik][jq][r]);
+            tile_max[jq] = wave_max(top) * scale_log2e;
+        }
+    };
+    // ---- weights of tile t against the reference m2, their sum, and P^T packed as an operand
+    auto probabilities = [&](int t, const f32x4(&sc)[KB][QB], bool ragged) __attribute__((always_inline)) {
+#pragma unroll
+        for (int jq = 0; jq < QB; ++jq) {
+            float part = 0.0f;
+            bf16x8 pk[KB / 2];
+#pragma unroll
+            for (int ik = 0; ik < KB; ++ik)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[ik][jq][r], scale_log2e, -m2[jq]));
+                    if (ragged && t * KT + ik * 16 + 4 * g + r >= M) p = 0.0f;   // keys past M take no weight
+                    part += p;
+                    pk[ik >> 1][(ik & 1) * 4 + r] = (__bf16)p;   // k-slot: block ik&1 of the 32-key step ik/2
+                }
+            lsum[jq] += part;
+#pragma unroll
+            for (int sk = 0; sk < KB / 2; ++sk) pf[jq][sk] = __builtin_bit_cast(i32x4, pk[sk]);
+        }
+    };
+    // The exponentials are taken against a reference m2 that follows the running maximum lazily: it moves (and the
+    // sums and outputs so far are rescaled by exp(m_old - m_new)) only when a tile's maximum exceeds it by more than
+    // 2^LAG in some query of the wave, so that no weight exceeds 2^LAG.  The quotient o / l at the end is the same
+    // whatever the reference; after the first few tiles the reference hardly ever moves.
+    constexpr float LAG = 8.0f;
+    auto step_top = [&](int t) __attribute__((always_inline)) {
+        landed_barrier();
+        if (t + 2 < ntiles) issue_K(t + 2);
+        if (t + 1 < ntiles) issue_V(t + 1);
+        bool moved = false;
+#pragma unroll
+        for (int jq = 0; jq < QB; ++jq) moved |= tile_max[jq] - m2[jq] > LAG;   // m2 = -inf before the first tile
+        if (__builtin_amdgcn_ballot_w64(moved)) {
+#pragma unroll
+            for (int jq = 0; jq < QB; ++jq) {
+                const float mh = __builtin_fmaxf(m2[jq], tile_max[jq]);
+                const float keep = __builtin_amdgcn_exp2f(m2[jq] - mh);       // exp(m - mh); 0 on the first tile
+                m2[jq] = mh;
+                lsum[jq] *= keep;
+#pragma unroll
+                for (int id = 0; id < DT; ++id) acc_o[id][jq] *= keep;
+            }
+        }
+    };
+    // ---- Software pipeline: the matrix-core work of one tile is issued between the vector-ALU work of its
+    // neighbours.  Step t:  [ scores(t+1)  ||  probabilities(t) ]  then  [ weighted_values(t)  ||  stats(t+1) ],
+    // where stats = maximum of a tile per query, probabilities = exponentials, their sum and packing.
+    // One barrier per step: K(t+1) and V(t) have landed and every wave is done with K(t) and V(t-1), whose
+    // stages K(t+2) and V(t+1) are then requested into.
+    issue_K(0);
+    landed_barrier();
+    issue_V(0);
+    if (ntiles > 1) issue_K(1);
+    scores_into(0, s);
+    stats(s);
+    for (int t = 0; t + 1 < ntiles; ++t) {
+        step_top(t);
+        scores_into(t + 1, s_next);
+        probabilities(t, s, false);
+        weighted_values(t);
+        stats(s_next);
+#pragma unroll
+        for (int ik = 0; ik < KB; ++ik)
+#pragma unroll
+            for (int jq = 0; jq < QB; ++jq) s[ik][jq] = s_next[ik][jq];
     }
+    step_top(ntiles - 1);
+    if (ntiles * KT > M)
+        probabilities(ntiles - 1, s, true);
+    else
+        probabilities(ntiles - 1, s, false);
+    weighted_values(ntiles - 1);
 
     // ---- O_i. = o_i / l_i.  Accumulator register r of lane l: d = 16 id + 4 (l/16) + r, query 16 jq + l%16.
 #pragma unroll
@@ -257,13 +326,15 @@ hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O
 {
     if (!supports_attention(N, M, d) || batch < 1 || batch > 65535) return hipErrorInvalidValue;
     const float scale_log2e = (float)(1.4426950408889634 / __builtin_sqrt((double)d));
-    dim3 grid((unsigned)((N + NWAVE * QW - 1) / (NWAVE * QW)), (unsigned)batch);
+    const int64_t nqb = (N + NWAVE * QW - 1) / (NWAVE * QW);  // query blocks per batch element
+    if (nqb * batch >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(nqb * batch));
     if (d == 128)
-        hipLaunchKernelGGL((attn_kernel<128, 128>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
-                           (const char *)V, (float *)O, (int)N, (int)M, scale_log2e);
+        hipLaunchKernelGGL((attn_kernel<128, 64>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
+                           (const char *)V, (float *)O, (int)N, (int)M, (int)nqb, scale_log2e);
     else
-        hipLaunchKernelGGL((attn_kernel<64, 64>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
-                           (const char *)V, (float *)O, (int)N, (int)M, scale_log2e);
+        hipLaunchKernelGGL((attn_kernel<64, 128>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
+                           (const char *)V, (float *)O, (int)N, (int)M, (int)nqb, scale_log2e);
     return hipGetLastError();
 }
 

@@ -138,6 +138,41 @@ def tri_lower_bf16(n: int, seed: int, tensor_id: int, device="cpu", upper=0.0) -
     return L
 
 
+def spd_f32(n: int, seed: int, tensor_id: int, device="cpu", upper=None) -> torch.Tensor:
+    """A well-conditioned symmetric positive definite n x n fp32 matrix: off-diagonal entries N(0, (0.5/sqrt(n))^2)
+    mirrored across the diagonal (their spectrum stays within about [-1, 1]), diagonal 2.5 + U[0,1): eigenvalues
+    in about [1.5, 4.5].  With `upper` set, everything above the diagonal is that value instead of the mirror
+    image (NaN there shows whether anyone relies on it)."""
+    G = torch.tril(normal_f32((n, n), 0.5 / math.sqrt(n), seed, tensor_id, device), -1)
+    h = hash_bits(seed, tensor_id + 1000, 0, n, device)
+    diag = 2.5 + _lsr(h, 40).to(torch.float32) * (1.0 / (1 << 24))
+    A = G + torch.diag(diag)
+    if upper is None:
+        A += G.t()
+    else:
+        A += torch.triu(torch.full((n, n), upper, dtype=torch.float32, device=device), 1)
+    return A
+
+
+@dataclass(frozen=True)
+class CholWorkload:
+    """Tiled Cholesky factorisation of an n x n matrix in tiles of nb."""
+    name: str
+    n: int
+    nb: int
+    seed: int
+
+    @property
+    def ops(self) -> int:
+        """n^3 / 6 multiply-adds counted as two operations each: the usual n^3 / 3."""
+        return self.n ** 3 // 3
+
+
+CHOL_WORKLOADS = {
+    "h1_chol_8192": CholWorkload("h1_chol_8192", 8192, 64, 8),
+}
+
+
 @dataclass(frozen=True)
 class Workload:
     name: str

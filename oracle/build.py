@@ -9,7 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libws_oracle.so")
 SOURCES = [os.path.join(HERE, "ws_oracle.c"), os.path.join(HERE, "tri_oracle.c"), os.path.join(HERE, "attn_oracle.c"),
-           os.path.join(HERE, "ws_grid.inc")]
+           os.path.join(HERE, "chol_oracle.c"), os.path.join(HERE, "ws_grid.inc")]
 
 
 def build(force: bool = True) -> str:
@@ -17,7 +17,7 @@ def build(force: bool = True) -> str:
             os.path.getmtime(LIB) >= os.path.getmtime(s) for s in SOURCES):
         return LIB
     cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fno-fast-math",
-           "-Wall", "-Wextra", "-shared", "-fPIC", "-o", LIB, SOURCES[0], SOURCES[1], SOURCES[2], "-lm"]
+           "-Wall", "-Wextra", "-shared", "-fPIC", "-o", LIB, SOURCES[0], SOURCES[1], SOURCES[2], SOURCES[3], "-lm"]
     subprocess.run(cmd, check=True, cwd=HERE)
     return LIB
 

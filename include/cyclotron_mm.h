@@ -109,6 +109,30 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
 int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
                         int64_t n, int64_t nrhs, int64_t nb, void *stream);
 
+/* Tiled Cholesky factorisation  A = L L^T  of a symmetric positive definite matrix, L lower triangular
+ * (paper: "Representative recurrences", Cholesky; "Cholesky Recurrence", tiled form: for every panel j
+ *     L_jj = CHOL(A_jj - sum_{k<j} SYRK(L_jk)),   L_ij = TRSM(A_ij - sum_{k<j} GEMM(L_ik, L_jk), L_jj)  for i > j,
+ * over tiles of nb rows and columns).  The SYRKs and GEMMs are the matrix-multiply recurrence above (bfloat16
+ * operands, fp32 partial sums; GEMM(X, Y) = X Y^T): a finished tile therefore enters them rounded to bfloat16
+ * (nearest even).  CHOL and TRSM run the scalar recurrence inside the tile column in fp32 on unrounded values
+ * (t = fma(-L_rk, L_ck, t) for k ascending, then an IEEE square root on the diagonal, an IEEE division below it).
+ * nb is part of the result: it fixes where L is rounded.
+ *
+ * A:  device, read only, n x n fp32 row-major.  Entries above the diagonal outside the diagonal tiles are never
+ *     read; those inside a diagonal tile may be read but do not influence the result (NaN allowed).
+ * L:  device, written, n x n fp32 row-major: the factor on and below the diagonal, zero above.  Also holds the
+ *     updated panels while the call is in flight.
+ * Lh: device, written, n x n bfloat16 row-major: L rounded to bfloat16, the values the SYRKs and GEMMs consumed,
+ *     with both triangles filled: Lh[r][c] = Lh[c][r] = bf16(L[max(r,c)][min(r,c)]).
+ * nb: tile size, 1 <= nb <= 64.  The MFMA kernels serve the updates when n and nb are multiples of 8 and the
+ *     pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
+ * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates nothing
+ *     and keeps no state.  n == 0: CYC_OK, nothing done.  A matrix that is not positive definite gives NaNs
+ *     (square root of a negative number), not an error.
+ * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or too large n, nb out of range, A or L not
+ * 4-byte or Lh not 2-byte aligned), CYC_ERR_ALIAS (A, L, Lh overlap one another), CYC_ERR_LAUNCH. */
+int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *stream);
+
 /* Attention by the tile recurrence of the paper's "FlashAttention-2 Recurrence": per query a running
  * maximum, running sum and running output over tiles of keys; the result is
  *     O_i. = sum_j softmax_j(Q_i. K_j.^T / sqrt(d)) V_j.      (no mask).

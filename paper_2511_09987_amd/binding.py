@@ -32,6 +32,8 @@ def _load() -> ctypes.CDLL:
     lib.cyc_recurrence_matmul_batched.restype = cint
     lib.cyc_recurrence_trsm.argtypes = [ptr, ptr, ptr, ptr, i64, i64, i64, ptr]
     lib.cyc_recurrence_trsm.restype = cint
+    lib.cyc_recurrence_cholesky.argtypes = [ptr, ptr, ptr, i64, i64, ptr]
+    lib.cyc_recurrence_cholesky.restype = cint
     lib.cyc_recurrence_attention.argtypes = [ptr, ptr, ptr, ptr, i64, i64, i64, i64, ptr]
     lib.cyc_recurrence_attention.restype = cint
     lib.cyc_status_string.argtypes = [cint]
@@ -127,6 +129,38 @@ def recurrence_matmul(A, B, out=None, stream=None):
     if st != CYC_OK:
         raise CycError(st)
     return out
+
+
+def cyc_recurrence_cholesky(A: int, L: int, Lh: int, n: int, nb: int, stream: int = 0) -> int:
+    """Raw C-ABI call: device pointers as integers, returns the status code."""
+    return int(_lib().cyc_recurrence_cholesky(A, L, Lh, n, nb, stream))
+
+
+def recurrence_cholesky(A, nb: int = 64, out=None, out_bf16=None, stream=None):
+    """Tensor-level convenience: (L, Lh) with A = L L^T factored tile by tile (tiles of nb).
+
+    A: (n,n) torch.float32 contiguous CUDA tensor, symmetric positive definite (its lower triangle is what counts).
+    Allocates L (fp32, zero above the diagonal) and Lh (bf16, both triangles filled) unless given and forwards
+    pointers to the C ABI on the current (or given) stream.
+    """
+    import torch
+    if not A.is_cuda:
+        raise ValueError("A must be a device tensor; there is no CPU path")
+    if A.dtype != torch.float32 or A.dim() != 2 or A.shape[0] != A.shape[1] or not A.is_contiguous():
+        raise ValueError(f"A must be a contiguous square float32 matrix, got {tuple(A.shape)} {A.dtype}")
+    n = A.shape[0]
+    if out is None:
+        out = torch.empty((n, n), dtype=torch.float32, device=A.device)
+    if out_bf16 is None:
+        out_bf16 = torch.empty((n, n), dtype=torch.bfloat16, device=A.device)
+    for t, dt in ((out, torch.float32), (out_bf16, torch.bfloat16)):
+        if tuple(t.shape) != (n, n) or t.dtype != dt or not t.is_contiguous() or t.device != A.device:
+            raise ValueError("out / out_bf16 has the wrong shape, dtype, layout or device")
+    s = (stream if stream is not None else torch.cuda.current_stream(A.device)).cuda_stream
+    st = cyc_recurrence_cholesky(A.data_ptr(), out.data_ptr(), out_bf16.data_ptr(), n, nb, s)
+    if st != CYC_OK:
+        raise CycError(st)
+    return out, out_bf16
 
 
 def recurrence_trsm(L, B, nb: int = 64, out=None, out_bf16=None, stream=None):

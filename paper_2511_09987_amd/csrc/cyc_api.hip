@@ -148,6 +148,18 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh, int64_t
     return cyc::launch_trsm(L, B, X, Xh, n, nrhs, nb, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 
+int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *stream)
+{
+    if (n < 0 || nb < 1 || nb > 64 || n > (1 << 22)) return CYC_ERR_SHAPE;
+    int64_t nn;
+    if (!mul_ok(n, n, &nn)) return CYC_ERR_SHAPE;
+    if (n == 0) return CYC_OK;
+    if (!A || !L || !Lh) return CYC_ERR_NULL;
+    if (((uintptr_t)A | (uintptr_t)L) & 3 || ((uintptr_t)Lh & 1)) return CYC_ERR_SHAPE;
+    if (overlaps(L, nn * 4, A, nn * 4) || overlaps(Lh, nn * 2, A, nn * 4) || overlaps(L, nn * 4, Lh, nn * 2)) return CYC_ERR_ALIAS;
+    return cyc::launch_chol(A, L, Lh, n, nb, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
 int cyc_recurrence_attention(const void *Q, const void *K, const void *V, void *O, int64_t batch, int64_t N, int64_t M,
                              int64_t d, void *stream)
 {

@@ -1,0 +1,151 @@
+// cyc_chol.hip -- the tiled Cholesky recurrence  A = L L^T  on gfx950.
+//
+// Paper, "Cholesky Recurrence": with A cut into nb x nb tiles, for every panel (tile column) j
+//     S_jj = A_jj - sum_{k<j} SYRK(L_jk),          L_jj = CHOL(S_jj),
+//     S_ij = A_ij - sum_{k<j} GEMM(L_ik, L_jk),    L_ij = TRSM(S_ij, L_jj)      for the tiles i below j,
+// where the scalar form ("Representative recurrences") is
+//     L_ii = sqrt(A_ii - sum_{k<i} L_ik^2),        L_ij = (A_ij - sum_{k<j} L_ik L_jk) / L_jj.
+//
+// Mapping.  Per panel, three launches on the caller's stream:
+//   1. all SYRKs and GEMMs of the panel as ONE product of the matrix-multiply recurrence of this library
+//      (bf16 operands, fp32 sums): rows j0.. of the finished factor times the transpose of its rows j0..j1.  The
+//      transpose costs nothing because the bf16 copy of the factor, Lh, is kept with both triangles filled
+//      (Lh[c][r] = Lh[r][c]): the stationary operand is the window Lh[j0:, 0:j0], the streamed one the window
+//      Lh[0:j0, j0:j1], and the epilogue writes A - product into the window L[j0:, j0:j1], which holds S until solved.
+//   2. CHOL of the diagonal tile: one wave, one lane per row, columns in lockstep; finished entries go through
+//      LDS, from where every lane reads row c of the tile when it works on column c.
+//   3. TRSM of the rows below: rows do not depend on one another, so one lane per row (64 rows per workgroup)
+//      runs the off-diagonal line of the scalar recurrence against L_jj in LDS, and writes its row of L, of Lh,
+//      and the mirrored column of Lh.
+// Inside a tile column everything is fp32 on unrounded values, in the order of the scalar recurrence:
+// t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
+#include "cyc_internal.h"
+
+namespace cyc {
+namespace {
+
+constexpr int NBMAX = 64;      // largest tile
+constexpr int LDT = NBMAX + 1; // row stride of the tiles in LDS (odd: lane-strided reads fall on distinct banks)
+
+// fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN
+__device__ __forceinline__ uint16_t round_bf16(float f)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// L[r][c] = 0 for c > r
+__global__ __launch_bounds__(256) void chol_zero_upper_kernel(float *__restrict__ L, int64_t n)
+{
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= n) return;
+    for (int64_t r = blockIdx.y; r < c; r += gridDim.y) L[r * n + c] = 0.0f;
+}
+
+// L_jj = CHOL(S_jj) for the tile at (j0, j0) with `cols` rows and columns.  S is read from Sm (row stride n: A itself
+// for the first panel, L afterwards); L gets the factor below and on the diagonal and zero above it, Lh its bf16
+// rounding in both triangles.  One wave; lane r owns row r.
+__global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
+                                                       uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols)
+{
+    __shared__ float T[NBMAX][LDT];          // S on entry, L as columns finish
+    const int r = threadIdx.x;
+    const bool live = r < cols;
+    if (live)
+        for (int c = 0; c <= r; ++c) T[r][c] = Sm[(j0 + r) * n + j0 + c];
+    __syncthreads();
+    for (int c = 0; c < cols; ++c) {
+        float t = 0.0f;
+        if (live && r >= c) {
+            t = T[r][c];
+            for (int k = 0; k < c; ++k) t = __builtin_fmaf(-T[r][k], T[c][k], t);
+            if (r == c) T[c][c] = __builtin_sqrtf(t);
+        }
+        __syncthreads();
+        if (live && r > c) T[r][c] = t / T[c][c];
+        __syncthreads();
+    }
+    if (live)
+        for (int c = 0; c < cols; ++c) {
+            const float v = c <= r ? T[r][c] : 0.0f;
+            L[(j0 + r) * n + j0 + c] = v;
+            Lh[(j0 + r) * n + j0 + c] = round_bf16(c <= r ? v : T[c][r]);
+        }
+}
+
+// L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane.
+__global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
+                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols)
+{
+    __shared__ float D[NBMAX][LDT];          // L_jj
+    __shared__ float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
+    const int lane = threadIdx.x;
+    const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
+    const bool live = row < n;
+    if (lane < cols)
+        for (int c = 0; c <= lane; ++c) D[lane][c] = L[(j0 + lane) * n + j0 + c];
+    if (live)
+        for (int c = 0; c < cols; ++c) X[lane][c] = Sm[row * n + j0 + c];
+    __syncthreads();
+    if (!live) return;
+    for (int c = 0; c < cols; ++c) {
+        float t = X[lane][c];
+        for (int k = 0; k < c; ++k) t = __builtin_fmaf(-X[lane][k], D[c][k], t);
+        X[lane][c] = t / D[c][c];
+    }
+    for (int c = 0; c < cols; ++c) {
+        const float v = X[lane][c];
+        const uint16_t h = round_bf16(v);
+        L[row * n + j0 + c] = v;
+        Lh[row * n + j0 + c] = h;
+        Lh[(j0 + c) * n + row] = h;          // the mirror image: consecutive lanes, consecutive addresses
+    }
+}
+
+}  // namespace
+
+hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t nb, hipStream_t s)
+{
+    const float *A = (const float *)A_;
+    float *L = (float *)L_;
+    uint16_t *Lh = (uint16_t *)Lh_;
+    if (nb < 1 || nb > NBMAX || n < 1 || n > (1 << 22)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(chol_zero_upper_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 4096 ? n : 4096)), dim3(256), 0,
+                       s, L, n);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    for (int64_t j0 = 0; j0 < n; j0 += nb) {
+        const int cols = (int)(j0 + nb <= n ? nb : n - j0);
+        const int64_t j1 = j0 + cols;
+        const float *Sm = A;
+        if (j0 > 0) {
+            Problem p;
+            p.A = Lh + j0 * n;            // finished factor, rows j0.., columns 0..j0
+            p.lda = n;
+            p.B = Lh + j0;                // its transpose by mirror storage: rows 0..j0, columns j0..j1
+            p.ldb = n;
+            p.C = L + j0 * n + j0;        // S for the rows j0.., columns j0..j1
+            p.Cin = A + j0 * n + j0;
+            p.ldc = n;
+            p.batch = 1;
+            p.M = n - j0;
+            p.K = j0;
+            p.N = cols;
+            p.strideA = p.strideB = p.strideC = 0;
+            p.i8 = false;
+            const int tile = choose_mfma_tile(p);
+            if (hipError_t e = tile ? launch_mfma(p, tile, 16, s) : launch_generic(p, s); e != hipSuccess) return e;
+            Sm = L;
+        }
+        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, s, Sm, L, Lh, n, j0, cols);
+        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+        if (j1 < n) {
+            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(64), 0, s, Sm, L, Lh, n, j0, cols);
+            if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+}  // namespace cyc

@@ -18,7 +18,8 @@ __device__ inline int widen(int8_t v) { return (int)v; }
 template <typename In, typename Acc>
 __global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ A, const In *__restrict__ B,
                                                          Acc *__restrict__ C, int64_t M, int64_t K, int64_t N,
-                                                         int64_t sA, int64_t sB, int64_t sC, int64_t lda, const Acc *Cin)
+                                                         int64_t sA, int64_t sB, int64_t sC, int64_t lda, int64_t ldb,
+                                                         int64_t ldc, const Acc *Cin)
 {
     __shared__ Acc As[GK][GT + 1];   // [k][i]
     __shared__ Acc Bs[GK][GT + 1];   // [k][j]
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ 
             int bk = x / GT, bj = x % GT;
             int64_t gj = j0 + bj;
             gk = k0 + bk;
-            Bs[bk][bj] = (gk < K && gj < N) ? (Acc)widen(B[gk * N + gj]) : (Acc)0;
+            Bs[bk][bj] = (gk < K && gj < N) ? (Acc)widen(B[gk * ldb + gj]) : (Acc)0;
         }
         __syncthreads();
 #pragma unroll
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void ws_generic_kernel(const In *__restrict__ 
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
             int64_t gi = i0 + ty * 4 + x, gj = j0 + tx * 4 + y;
-            if (gi < M && gj < N) C[gi * N + gj] = Cin ? Cin[gi * N + gj] - acc[x][y] : acc[x][y];   // Cin: C <- Cin - A*B
+            if (gi < M && gj < N) C[gi * ldc + gj] = Cin ? Cin[gi * ldc + gj] - acc[x][y] : acc[x][y];   // Cin: C <- Cin - A*B
         }
 }
 
@@ -85,11 +86,11 @@ hipError_t launch_generic(const Problem &p, hipStream_t s)
     if (p.i8)
         hipLaunchKernelGGL((ws_generic_kernel<int8_t, int>), grid, dim3(256), 0, s, (const int8_t *)p.A,
                            (const int8_t *)p.B, (int *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC, row_stride_a(p),
-                           (const int *)p.Cin);
+                           row_stride_b(p), row_stride_c(p), (const int *)p.Cin);
     else
         hipLaunchKernelGGL((ws_generic_kernel<uint16_t, float>), grid, dim3(256), 0, s, (const uint16_t *)p.A,
                            (const uint16_t *)p.B, (float *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC,
-                           row_stride_a(p), (const float *)p.Cin);
+                           row_stride_a(p), row_stride_b(p), row_stride_c(p), (const float *)p.Cin);
     return hipGetLastError();
 }
 

@@ -12,11 +12,16 @@ struct Problem {
     int64_t batch, M, K, N;
     int64_t strideA, strideB, strideC;   // elements
     bool i8;                             // false: bf16 -> fp32, true: int8 -> int32
-    // Extensions used by the triangular solve (batch == 1 only; the narrow kernel ignores them):
-    int64_t lda = 0;                     // row stride of A in elements, 0 = K (A is a window of a wider matrix)
+    // Extensions used by the triangular solve and the Cholesky factorisation (batch == 1 only; the narrow kernel
+    // ignores them): operands and result may be windows of wider matrices
+    int64_t lda = 0;                     // row stride of A in elements, 0 = K
+    int64_t ldb = 0;                     // row stride of B in elements, 0 = N
+    int64_t ldc = 0;                     // row stride of C (and of Cin) in elements, 0 = N
     const void *Cin = nullptr;           // when set, C <- Cin - A*B instead of C <- A*B (same layout as C; may be C)
 };
 inline int64_t row_stride_a(const Problem &p) { return p.lda ? p.lda : p.K; }
+inline int64_t row_stride_b(const Problem &p) { return p.ldb ? p.ldb : p.N; }
+inline int64_t row_stride_c(const Problem &p) { return p.ldc ? p.ldc : p.N; }
 
 // any shape, any alignment; one thread per 4x4 block of C, k ascending
 hipError_t launch_generic(const Problem &p, hipStream_t s);
@@ -29,6 +34,8 @@ hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s);   // 
 int choose_mfma_tile(const Problem &p);
 // lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, hipStream_t s);
+// tiled Cholesky factorisation A = L L^T in tiles of nb (see cyc_chol.hip); arguments validated by the caller
+hipError_t launch_chol(const void *A, void *L, void *Lh, int64_t n, int64_t nb, hipStream_t s);
 // FlashAttention-2 tile recurrence (see cyc_attn.hip); requires supports_attention(N, M, d)
 bool supports_attention(int64_t N, int64_t M, int64_t d);
 hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O, int64_t batch, int64_t N, int64_t M,

@@ -147,7 +147,7 @@ template <class C, bool RAGGED>
 __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                         char *__restrict__ Cout, int M, int K, int N, int64_t sA,
                                                         int64_t sB, int64_t sC, int tiles_m, int tiles_n, int lda,
-                                                        const char *Cin)
+                                                        int ldb, int ldc, const char *Cin)
 {
     constexpr int ES = C::ES, RB = C::RB, TM = C::TM, TN = C::TN;
     __shared__ __attribute__((aligned(1024))) char lds_raw[C::LDS_BYTES];
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // that advances with the k-tile, plus a fixed per-lane byte offset (below 2^32, see supports_mfma)
     const char *baseA = A + ((int64_t)m0 * lda) * ES;   // lda: row stride of A in elements (K unless A is a window)
     const char *baseB = B + (int64_t)n0 * ES;
-    const int64_t stepB = (int64_t)C::BKE * N * ES;
+    const int64_t stepB = (int64_t)C::BKE * ldb * ES;   // ldb, ldc: row strides of B and C (N unless windows)
     uint32_t voffA[C::AI], voffB[C::BI];
     const int nkt = RAGGED ? (K + C::BKE - 1) / C::BKE : K / C::BKE;
     const int last = nkt - 1;
@@ -204,7 +204,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
             const int cmax = (N - n0) * ES / 16 - 1;      // last 16-byte chunk of this block's columns that exists
             c = c < cmax ? c : cmax;
         }
-        voffB[t] = (uint32_t)kr * (uint32_t)(N * ES) + c * 16;
+        voffB[t] = (uint32_t)kr * (uint32_t)(ldb * ES) + c * 16;
     }
     // LDS map: NSA stages of the A tile, then NSB stages of the B tile
     constexpr int LDS_B0 = C::NSA * C::A_BYTES;
@@ -407,8 +407,8 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
                 int row = row0 + (r >> 2) * 8 + (r & 3);
                 elem v = acc[i][j][r];
                 if (!RAGGED || (row < M && col < N)) {
-                    if (Cin) v = ((const elem *)Cin)[(int64_t)row * N + col] - v;   // C <- Cin - A*B
-                    Cw[(int64_t)row * N + col] = v;
+                    if (Cin) v = ((const elem *)Cin)[(int64_t)row * ldc + col] - v;   // C <- Cin - A*B
+                    Cw[(int64_t)row * ldc + col] = v;
                 }
             }
         }
@@ -423,11 +423,11 @@ hipError_t launch_cfg(const Problem &p, hipStream_t s)
     if (ragged)
         hipLaunchKernelGGL((ws_mfma_kernel<C, true>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
-                           (int)row_stride_a(p), (const char *)p.Cin);
+                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
     else
         hipLaunchKernelGGL((ws_mfma_kernel<C, false>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
-                           (int)row_stride_a(p), (const char *)p.Cin);
+                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
     return hipGetLastError();
 }
 
@@ -440,13 +440,14 @@ bool supports_mfma(const Problem &p, int tile)
     if (tile != 256 && tile != 128) return false;
     const int es = p.i8 ? 1 : 2;
     if (p.K <= 0 || p.M <= 0 || p.N <= 0) return false;
-    const int64_t lda = row_stride_a(p);
+    const int64_t lda = row_stride_a(p), ldb = row_stride_b(p), ldc = row_stride_c(p);
     if ((p.K * es) % 16 || (p.N * es) % 16 || (lda * es) % 16 || lda < p.K) return false;
-    if ((p.lda || p.Cin) && p.batch != 1) return false;
+    if ((ldb * es) % 16 || ldb < p.N || ldc < p.N || ldb > (1 << 30) || ldc > (1 << 30)) return false;
+    if ((p.lda || p.ldb || p.ldc || p.Cin) && p.batch != 1) return false;
     if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
     if (((p.M + tile - 1) / tile) * ((p.N + tile - 1) / tile) > (1 << 30)) return false;
     // per-lane byte offsets inside a tile's rows are kept in 32 bits
-    if (lda * es * 256 + 128 >= ((int64_t)1 << 32) || p.N * es * 128 + 512 >= ((int64_t)1 << 32)) return false;
+    if (lda * es * 256 + 128 >= ((int64_t)1 << 32) || ldb * es * 128 + 512 >= ((int64_t)1 << 32)) return false;
     if (((uintptr_t)p.A | (uintptr_t)p.B | (uintptr_t)p.C | (uintptr_t)p.Cin) & 15) return false;
     if (p.batch > 1 && (((p.strideA * es) | (p.strideB * es) | (p.strideC * 4)) & 15)) return false;
     return true;

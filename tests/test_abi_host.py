@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_declares_the_documented_entry_points():
     names = declared_functions()
-    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_recurrence_trsm", "cyc_recurrence_attention", "cyc_status_string",
+    for need in ("cyc_recurrence_matmul", "cyc_recurrence_matmul_batched", "cyc_recurrence_trsm", "cyc_recurrence_attention", "cyc_recurrence_cholesky", "cyc_status_string",
                  "cyc_version"):
         assert need in names
 
@@ -97,6 +97,23 @@ def test_trsm_argument_validation_happens_on_the_host(pkg):
     assert f(L, B, L + 32, Xh, 8, 4, 64) == 4                # X overlaps L
     assert f(0, 0, 0, 0, 0, 4, 64) == 0                      # n == 0: nothing to do
     assert f(0, 0, 0, 0, 8, 0, 64) == 0                      # nrhs == 0: nothing to do
+
+
+def test_cholesky_argument_validation_happens_on_the_host(pkg):
+    f = pkg.cyc_recurrence_cholesky
+    A, L, Lh = 0x100000, 0x200000, 0x300000
+    assert f(A, L, Lh, -1, 64) == 2                          # negative extent
+    assert f(A, L, Lh, 8, 0) == 2                            # tile size out of range
+    assert f(A, L, Lh, 8, 65) == 2
+    assert f(A, L, Lh, 1 << 40, 64) == 2                     # too large
+    assert f(A + 2, L, Lh, 8, 64) == 2                       # misaligned A
+    assert f(A, L, Lh + 1, 8, 64) == 2                       # misaligned Lh
+    assert f(0, L, Lh, 8, 64) == 1                           # NULL A
+    assert f(A, L, 0, 8, 64) == 1                            # NULL Lh
+    assert f(A, A, Lh, 8, 64) == 4                           # L aliases A
+    assert f(A, L, L + 64, 8, 64) == 4                       # Lh overlaps L
+    assert f(A, L, A + 32, 8, 64) == 4                       # Lh overlaps A
+    assert f(0, 0, 0, 0, 64) == 0                            # n == 0: nothing to do
 
 
 def test_attention_argument_validation_happens_on_the_host(pkg):

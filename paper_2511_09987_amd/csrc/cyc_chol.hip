@@ -25,7 +25,30 @@ namespace cyc {
 namespace {
 
 constexpr int NBMAX = 64;      // largest tile
-constexpr int LDT = NBMAX + 1; // row stride of the tiles in LDS (odd: lane-strided reads fall on distinct banks)
+constexpr int LDT = NBMAX + 4; // row stride of the tiles in LDS: rows stay 16-byte aligned, and 16 consecutive rows
+                               // spread over all banks for 16-byte reads
+typedef float f32x4 __attribute__((ext_vector_type(4), may_alias));   // read from arrays written as floats
+
+// t - sum_{k<c} x[k] y[k] as the chain t = fma(-x[k], y[k], t), k ascending; x and y are 16-byte aligned rows in LDS.
+// Four terms per pair of 16-byte reads, the reads of the next four issued before the current four are used.
+__device__ __forceinline__ float chain(float t, const float *x, const float *y, int c)
+{
+    const int c4 = c & ~3;
+    if (c4) {
+        f32x4 a = *(const f32x4 *)x, b = *(const f32x4 *)y;
+        for (int k = 4; k < c4; k += 4) {
+            const f32x4 a2 = *(const f32x4 *)(x + k), b2 = *(const f32x4 *)(y + k);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) t = __builtin_fmaf(-a[q], b[q], t);
+            a = a2;
+            b = b2;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t = __builtin_fmaf(-a[q], b[q], t);
+    }
+    for (int k = c4; k < c; ++k) t = __builtin_fmaf(-x[k], y[k], t);
+    return t;
+}
 
 // fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN
 __device__ __forceinline__ uint16_t round_bf16(float f)
@@ -34,6 +57,36 @@ __device__ __forceinline__ uint16_t round_bf16(float f)
     if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// A 64-row tile of a row-major fp32 matrix (row stride ld) into LDS, by one wave: rows 0..nrows-1 (rows past that
+// repeat the last one), columns 0..cols-1.  All loads of a lane are in flight together.
+__device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, int64_t ld, int nrows, int cols, int lane)
+{
+    if (cols == NBMAX && ld % 4 == 0 && ((uintptr_t)src & 15) == 0) {
+        f32x4 v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int r = 4 * i + (lane >> 4);
+            v[i] = *(const f32x4 *)(src + (int64_t)(r < nrows ? r : nrows - 1) * ld + 4 * (lane & 15));
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) *(f32x4 *)&dst[4 * i + (lane >> 4)][4 * (lane & 15)] = v[i];
+    } else {
+        for (int i0 = 0; i0 < NBMAX * cols; i0 += 64 * 8) {
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int i = i0 + 64 * q + lane, r = i / cols, c = i - r * cols;
+                v[q] = i < NBMAX * cols ? src[(int64_t)(r < nrows ? r : nrows - 1) * ld + c] : 0.0f;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int i = i0 + 64 * q + lane, r = i / cols, c = i - r * cols;
+                if (i < NBMAX * cols) dst[r][c] = v[q];
+            }
+        }
+    }
 }
 
 // L[r][c] = 0 for c > r
@@ -50,22 +103,38 @@ __global__ __launch_bounds__(256) void chol_zero_upper_kernel(float *__restrict_
 __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols)
 {
-    __shared__ float T[NBMAX][LDT];          // S on entry, L as columns finish
+    __shared__ __attribute__((aligned(16))) float T[NBMAX][LDT];          // S on entry, L as columns finish
     const int r = threadIdx.x;
     const bool live = r < cols;
-    if (live)
-        for (int c = 0; c <= r; ++c) T[r][c] = Sm[(j0 + r) * n + j0 + c];
+    load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     __syncthreads();
-    for (int c = 0; c < cols; ++c) {
-        float t = 0.0f;
-        if (live && r >= c) {
-            t = T[r][c];
-            for (int k = 0; k < c; ++k) t = __builtin_fmaf(-T[r][k], T[c][k], t);
+    if (cols == NBMAX) {
+        // full tile: the lane keeps its row of L in registers (every index below is a constant after unrolling), so
+        // a column step costs the reads of row c from LDS, all issued together, and a chain of c fused multiply-adds
+        float x[NBMAX];
+#pragma unroll
+        for (int c = 0; c < NBMAX; ++c) {
+            float t = T[r][c];
+#pragma unroll
+            for (int k = 0; k < c; ++k) t = __builtin_fmaf(-x[k], T[c][k], t);
             if (r == c) T[c][c] = __builtin_sqrtf(t);
+            __syncthreads();
+            const float d = T[c][c];
+            x[c] = r == c ? d : t / d;
+            if (r > c) T[r][c] = x[c];
+            __syncthreads();
         }
-        __syncthreads();
-        if (live && r > c) T[r][c] = t / T[c][c];
-        __syncthreads();
+    } else {
+        for (int c = 0; c < cols; ++c) {
+            float t = 0.0f;
+            if (live && r >= c) {
+                t = chain(T[r][c], T[r], T[c], c);
+                if (r == c) T[c][c] = __builtin_sqrtf(t);
+            }
+            __syncthreads();
+            if (live && r > c) T[r][c] = t / T[c][c];
+            __syncthreads();
+        }
     }
     if (live)
         for (int c = 0; c < cols; ++c) {
@@ -79,21 +148,29 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
 __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                         uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols)
 {
-    __shared__ float D[NBMAX][LDT];          // L_jj
-    __shared__ float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
+    __shared__ __attribute__((aligned(16))) float D[NBMAX][LDT];          // L_jj
+    __shared__ __attribute__((aligned(16))) float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
     const int lane = threadIdx.x;
     const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
     const bool live = row < n;
-    if (lane < cols)
-        for (int c = 0; c <= lane; ++c) D[lane][c] = L[(j0 + lane) * n + j0 + c];
-    if (live)
-        for (int c = 0; c < cols; ++c) X[lane][c] = Sm[row * n + j0 + c];
+    const int64_t first = j1 + (int64_t)blockIdx.x * 64;
+    load_tile(D, L + j0 * n + j0, n, cols, cols, lane);
+    load_tile(X, Sm + first * n + j0, n, (int)(n - first < 64 ? n - first : 64), cols, lane);
     __syncthreads();
     if (!live) return;
-    for (int c = 0; c < cols; ++c) {
-        float t = X[lane][c];
-        for (int k = 0; k < c; ++k) t = __builtin_fmaf(-X[lane][k], D[c][k], t);
-        X[lane][c] = t / D[c][c];
+    if (cols == NBMAX) {
+        float x[NBMAX];                      // the lane's row of L, in registers (constant indices after unrolling)
+#pragma unroll
+        for (int c = 0; c < NBMAX; ++c) {
+            float t = X[lane][c];
+#pragma unroll
+            for (int k = 0; k < c; ++k) t = __builtin_fmaf(-x[k], D[c][k], t);
+            x[c] = t / D[c][c];
+        }
+#pragma unroll
+        for (int c = 0; c < NBMAX; ++c) X[lane][c] = x[c];
+    } else {
+        for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
     for (int c = 0; c < cols; ++c) {
         const float v = X[lane][c];

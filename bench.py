@@ -9,8 +9,8 @@ before the timed region.  Prints ONE JSON line.
                   [--copy-calibration]
 
 NAME is one of the five matmul workloads (default c3_bf16_8192), t1_trsm_8192 (the tiled triangular
-solve) or f1_attn_4096 (the attention tile recurrence); the latter two are otherwise measured last and
-reported under "workloads".
+solve), h1_chol_8192 (the tiled Cholesky factorisation) or f1_attn_4096 (the attention tile recurrence);
+the latter three are otherwise measured last and reported under "workloads".
 
 The headline workload is the 8192^3 bf16 case (compute bound, MFMA roofline); the int8 8192^3
 and the batched narrow-stream cases are measured after it and reported under "workloads".
@@ -110,6 +110,40 @@ def measure_trsm(lib, torch, w, steps, warmup, sets):
         L, B, X, Xh = data[i % sets]
         st = lib.cyc_recurrence_trsm(L.data_ptr(), B.data_ptr(), X.data_ptr(), Xh.data_ptr(), w.n, w.nrhs, w.nb,
                                      stream.cuda_stream)
+        if st != 0:
+            raise RuntimeError(lib.cyc_status_string(st))
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    ev_ms = sum(e0.elapsed_time(e1) for e0, e1 in evs) / steps
+    del data
+    torch.cuda.empty_cache()
+    return wall_ms, ev_ms
+
+
+def measure_chol(lib, torch, w, steps, warmup, sets):
+    """Time `steps` tiled Cholesky factorisations (each a sequence of kernels); returns (wall ms, event ms)."""
+    from datagen import ws_inputs
+    dev = "cuda:0"
+    data = []
+    for r in range(sets):
+        A = ws_inputs.spd_f32(w.n, w.seed + 1000 * r, 0, dev)
+        data.append((A, torch.empty((w.n, w.n), dtype=torch.float32, device=dev),
+                     torch.empty((w.n, w.n), dtype=torch.bfloat16, device=dev)))
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        A, L, Lh = data[i % sets]
+        st = lib.cyc_recurrence_cholesky(A.data_ptr(), L.data_ptr(), Lh.data_ptr(), w.n, w.nb, stream.cuda_stream)
         if st != 0:
             raise RuntimeError(lib.cyc_status_string(st))
 
@@ -255,6 +289,41 @@ def trsm_entry(wt, wall_ms, ev_ms):
             "frac": round(ach / PEAK["bf16"][0], 4)}
 
 
+def chol_entry(w, wall_ms, ev_ms):
+    ach = w.ops / (ev_ms * 1e-3) / 1e12
+    return {"kernel": "cholesky", "n": w.n, "nb": w.nb, "ms_per_step": round(wall_ms, 5), "kernel_ms": round(ev_ms, 5),
+            "achieved": round(ach, 1), "unit": "TFLOP/s", "bound": "mfma", "frac": round(ach / PEAK["bf16"][0], 4)}
+
+
+def bench_chol(lib, torch, w, args):
+    """The tiled Cholesky factorisation as the headline workload: one step = one factorisation (a sequence of kernels)."""
+    wall_ms, ev_ms = measure_chol(lib, torch, w, args.steps, args.warmup, ROTATE)
+    e = chol_entry(w, wall_ms, ev_ms)
+    out = {
+        "metric": "recurrence matmul TFLOP/s (TOP/s int8) and % of MI355X MFMA/HBM roofline",
+        "value": round(w.ops / 1e12 / (wall_ms * 1e-3), 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "nb": w.nb, "kernel": "cholesky", "accumulate": "fp32", "seed": w.seed,
+                   "operand_sets_rotated": ROTATE},
+        # a step is three launches per panel; the figure is the whole step (n^3/3 flops) against the MFMA peak
+        "roofline": {"bound": "mfma", "achieved": e["achieved"], "peak": PEAK["bf16"][0], "unit": "TFLOP/s",
+                     "frac": e["frac"], "traffic": None, "kernel": "cholesky (all kernels of a step)",
+                     "kernel_ms": e["kernel_ms"]},
+    }
+    if not args.no_cpu:
+        from datagen import ws_inputs
+        from oracle import chol_oracle, ws_oracle
+        A = ws_inputs.spd_f32(w.n, w.seed, 0, "cpu").numpy()
+        t0 = time.perf_counter()
+        chol_oracle.chol_tiled(A, w.nb)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(w.ops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": ws_oracle.threads(),
+                               "kind": "oracle", "seconds": round(dt, 2),
+                               "sample": f"tiled Cholesky oracle on the whole of {w.name}, same seed and distribution"}
+    return out
+
+
 def bench_trsm(lib, torch, wt, args):
     """The tiled triangular solve as the headline workload: one step = one solve (a sequence of kernels)."""
     wall_ms, ev_ms = measure_trsm(lib, torch, wt, args.steps, args.warmup, ROTATE)
@@ -301,7 +370,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
-    known = sorted(ws_inputs.WORKLOADS) + sorted(ws_inputs.TRI_WORKLOADS) + sorted(ws_inputs.ATTN_WORKLOADS)
+    known = (sorted(ws_inputs.WORKLOADS) + sorted(ws_inputs.TRI_WORKLOADS) + sorted(ws_inputs.ATTN_WORKLOADS) +
+             sorted(ws_inputs.CHOL_WORKLOADS))
     if args.workload not in known:
         print(f"bench.py: unknown workload {args.workload}; choose from {known}", file=sys.stderr)
         sys.exit(2)
@@ -311,6 +381,9 @@ def main():
         return
     if args.workload in ws_inputs.ATTN_WORKLOADS:
         print(json.dumps(bench_attn(lib, torch, ws_inputs.ATTN_WORKLOADS[args.workload], args)))
+        return
+    if args.workload in ws_inputs.CHOL_WORKLOADS:
+        print(json.dumps(bench_chol(lib, torch, ws_inputs.CHOL_WORKLOADS[args.workload], args)))
         return
 
     w = ws_inputs.WORKLOADS[args.workload]
@@ -345,6 +418,10 @@ def main():
         for name, wt in ws_inputs.TRI_WORKLOADS.items():
             wms, ems = measure_trsm(lib, torch, wt, max(3, args.steps // 5), max(1, args.warmup // 5), ROTATE)
             extra[name] = trsm_entry(wt, wms, ems)
+        # the tiled Cholesky factorisation (three launches per panel)
+        for name, wc in ws_inputs.CHOL_WORKLOADS.items():
+            wms, ems = measure_chol(lib, torch, wc, max(2, args.steps // 4), 1, 2)
+            extra[name] = chol_entry(wc, wms, ems)
         # the attention tile recurrence (one kernel per step)
         for name, wa in ws_inputs.ATTN_WORKLOADS.items():
             wms, ems = measure_attn(lib, torch, wa, max(3, args.steps // 2), max(1, args.warmup // 2), ROTATE)

@@ -7,7 +7,8 @@
 //     L_ii = sqrt(A_ii - sum_{k<i} L_ik^2),        L_ij = (A_ij - sum_{k<j} L_ik L_jk) / L_jj.
 //
 // Mapping.  Per panel, three launches on the caller's stream:
-//   1. all SYRKs and GEMMs of the panel as ONE product of the matrix-multiply recurrence of this library
+//   1. the SYRKs and GEMMs of the panel as ONE product of the matrix-multiply recurrence of this library (two
+//      for panels grouped in fours, see launch_chol)
 //      (bf16 operands, fp32 sums): rows j0.. of the finished factor times the transpose of its rows j0..j1.  The
 //      transpose costs nothing because the bf16 copy of the factor, Lh, is kept with both triangles filled
 //      (Lh[c][r] = Lh[r][c]): the stationary operand is the window Lh[j0:, 0:j0], the streamed one the window
@@ -89,6 +90,43 @@ __device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, i
     }
 }
 
+// The reverse for a full-width tile held in LDS: rows 0..nrows-1 to the fp32 matrix L and, rounded, to the bfloat16
+// matrix Lh (both with row stride ld), 16 bytes per lane and store.  False when shape or alignment do not allow it.
+// LOWER: the tile is a diagonal tile; L gets zeros above the diagonal (Lh gets what the tile holds there).
+template <bool LOWER>
+__device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, uint16_t *Lh, int64_t ld, int nrows, int cols,
+                                           int lane)
+{
+    if (cols != NBMAX || ld % 8 != 0 || ((uintptr_t)L & 15) != 0 || ((uintptr_t)Lh & 15) != 0) return false;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        if (r < nrows) {
+            f32x4 v = *(const f32x4 *)&src[r][4 * (lane & 15)];
+            if (LOWER) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[q] = 4 * (lane & 15) + q <= r ? v[q] : 0.0f;
+            }
+            *(f32x4 *)(L + (int64_t)r * ld + 4 * (lane & 15)) = v;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 8 * i + (lane >> 3);
+        if (r < nrows) {
+            const f32x4 a = *(const f32x4 *)&src[r][8 * (lane & 7)], b = *(const f32x4 *)&src[r][8 * (lane & 7) + 4];
+            typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+            u32x4 h;
+            h[0] = round_bf16(a[0]) | ((unsigned)round_bf16(a[1]) << 16);
+            h[1] = round_bf16(a[2]) | ((unsigned)round_bf16(a[3]) << 16);
+            h[2] = round_bf16(b[0]) | ((unsigned)round_bf16(b[1]) << 16);
+            h[3] = round_bf16(b[2]) | ((unsigned)round_bf16(b[3]) << 16);
+            *(u32x4 *)(Lh + (int64_t)r * ld + 8 * (lane & 7)) = h;
+        }
+    }
+    return true;
+}
+
 // L[r][c] = 0 for c > r
 __global__ __launch_bounds__(256) void chol_zero_upper_kernel(float *__restrict__ L, int64_t n)
 {
@@ -109,21 +147,25 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     __syncthreads();
     if (cols == NBMAX) {
-        // full tile: the lane keeps its row of L in registers (every index below is a constant after unrolling), so
-        // a column step costs the reads of row c from LDS, all issued together, and a chain of c fused multiply-adds
-        float x[NBMAX];
+        // full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
+        // unrolling).  Row c of L, which all lanes need in column step c, is lane c's own registers: it is fetched
+        // with lane reads, so that the steps need neither LDS nor barriers.  Lanes above the diagonal (r < c)
+        // compute values nobody uses.
+        float sr[NBMAX], x[NBMAX];
+#pragma unroll
+        for (int c = 0; c < NBMAX; ++c) sr[c] = T[r][c];
 #pragma unroll
         for (int c = 0; c < NBMAX; ++c) {
-            float t = T[r][c];
+            float t = sr[c];
 #pragma unroll
-            for (int k = 0; k < c; ++k) t = __builtin_fmaf(-x[k], T[c][k], t);
-            if (r == c) T[c][c] = __builtin_sqrtf(t);
-            __syncthreads();
-            const float d = T[c][c];
+            for (int k = 0; k < c; ++k)
+                t = __builtin_fmaf(-x[k], __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[k]), c)), t);
+            const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, __builtin_sqrtf(t)), c));
             x[c] = r == c ? d : t / d;
-            if (r > c) T[r][c] = x[c];
-            __syncthreads();
         }
+#pragma unroll
+        for (int c = 0; c < NBMAX; ++c) T[r][c] = x[c];
+        __syncthreads();
     } else {
         for (int c = 0; c < cols; ++c) {
             float t = 0.0f;
@@ -136,11 +178,15 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
             __syncthreads();
         }
     }
+    // mirror the factor into the upper part of the tile in LDS (Lh holds both triangles), then write the tile out
+    if (live)
+        for (int c = r + 1; c < cols; ++c) T[r][c] = T[c][r];
+    __syncthreads();
+    if (store_tile<true>(T, L + j0 * n + j0, Lh + j0 * n + j0, n, cols, cols, r)) return;
     if (live)
         for (int c = 0; c < cols; ++c) {
-            const float v = c <= r ? T[r][c] : 0.0f;
-            L[(j0 + r) * n + j0 + c] = v;
-            Lh[(j0 + r) * n + j0 + c] = round_bf16(c <= r ? v : T[c][r]);
+            L[(j0 + r) * n + j0 + c] = c <= r ? T[r][c] : 0.0f;
+            Lh[(j0 + r) * n + j0 + c] = round_bf16(T[r][c]);
         }
 }
 
@@ -157,7 +203,8 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
     load_tile(D, L + j0 * n + j0, n, cols, cols, lane);
     load_tile(X, Sm + first * n + j0, n, (int)(n - first < 64 ? n - first : 64), cols, lane);
     __syncthreads();
-    if (!live) return;
+    // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
+    // store below, and write nothing of their own)
     if (cols == NBMAX) {
         float x[NBMAX];                      // the lane's row of L, in registers (constant indices after unrolling)
 #pragma unroll
@@ -172,11 +219,16 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
     } else {
         for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
+    __syncthreads();
+    const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, (int)(n - first < 64 ? n - first : 64), cols, lane);
+    if (!live) return;
     for (int c = 0; c < cols; ++c) {
         const float v = X[lane][c];
         const uint16_t h = round_bf16(v);
-        L[row * n + j0 + c] = v;
-        Lh[row * n + j0 + c] = h;
+        if (!stored) {
+            L[row * n + j0 + c] = v;
+            Lh[row * n + j0 + c] = h;
+        }
         Lh[(j0 + c) * n + row] = h;          // the mirror image: consecutive lanes, consecutive addresses
     }
 }
@@ -189,30 +241,42 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
     float *L = (float *)L_;
     uint16_t *Lh = (uint16_t *)Lh_;
     if (nb < 1 || nb > NBMAX || n < 1 || n > (1 << 22)) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(chol_zero_upper_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 4096 ? n : 4096)), dim3(256), 0,
-                       s, L, n);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    // One product per panel would have only nb columns and all earlier tiles as its k range: a few workgroups
+    // walking a long k loop.  So the panels are taken in groups of GROUP: at the first panel of a group one product
+    // covers the columns of the whole group against all tiles left of the group; the later panels of the group
+    // then only add the terms of the group's own earlier panels (k range at most (GROUP - 1) * nb).  The terms of a
+    // sum are the paper's; they are merely added in two chains instead of one.
+    constexpr int GROUP = 4;
+    auto product = [&](int64_t r0, int64_t c0, int64_t ncols, int64_t k0, int64_t k1, const float *src) {
+        Problem p;                        // L[r0:, c0:c0+ncols] = src[r0:, c0:c0+ncols] - Lh[r0:, k0:k1] * Lh[k0:k1, c0:c0+ncols]
+        p.A = Lh + r0 * n + k0;           // finished factor, rows r0.., columns k0..k1
+        p.lda = n;
+        p.B = Lh + k0 * n + c0;           // its transpose, by mirror storage
+        p.ldb = n;
+        p.C = L + r0 * n + c0;
+        p.Cin = src + r0 * n + c0;
+        p.ldc = n;
+        p.batch = 1;
+        p.M = n - r0;
+        p.K = k1 - k0;
+        p.N = ncols;
+        p.strideA = p.strideB = p.strideC = 0;
+        p.i8 = false;
+        const int tile = choose_mfma_tile(p);
+        return tile ? launch_mfma(p, tile, 16, s) : launch_generic(p, s);
+    };
     for (int64_t j0 = 0; j0 < n; j0 += nb) {
         const int cols = (int)(j0 + nb <= n ? nb : n - j0);
         const int64_t j1 = j0 + cols;
-        const float *Sm = A;
-        if (j0 > 0) {
-            Problem p;
-            p.A = Lh + j0 * n;            // finished factor, rows j0.., columns 0..j0
-            p.lda = n;
-            p.B = Lh + j0;                // its transpose by mirror storage: rows 0..j0, columns j0..j1
-            p.ldb = n;
-            p.C = L + j0 * n + j0;        // S for the rows j0.., columns j0..j1
-            p.Cin = A + j0 * n + j0;
-            p.ldc = n;
-            p.batch = 1;
-            p.M = n - j0;
-            p.K = j0;
-            p.N = cols;
-            p.strideA = p.strideB = p.strideC = 0;
-            p.i8 = false;
-            const int tile = choose_mfma_tile(p);
-            if (hipError_t e = tile ? launch_mfma(p, tile, 16, s) : launch_generic(p, s); e != hipSuccess) return e;
+        const int64_t g0 = j0 / (GROUP * nb) * (GROUP * nb);      // first column of this panel's group
+        const float *Sm = A;                                      // where S of this panel is read from
+        if (j0 == g0 && g0 > 0) {
+            const int64_t gcols = g0 + GROUP * nb <= n ? GROUP * nb : n - g0;
+            if (hipError_t e = product(g0, g0, gcols, 0, g0, A); e != hipSuccess) return e;
+        }
+        if (g0 > 0) Sm = L;
+        if (j0 > g0) {
+            if (hipError_t e = product(j0, j0, cols, g0, j0, Sm); e != hipSuccess) return e;
             Sm = L;
         }
         hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, s, Sm, L, Lh, n, j0, cols);
@@ -222,6 +286,10 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
         }
     }
+    // the products wrote S above the diagonal too (a group's columns start at the group's first row)
+    hipLaunchKernelGGL(chol_zero_upper_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 4096 ? n : 4096)), dim3(256), 0,
+                       s, L, n);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
     return hipSuccess;
 }
 

@@ -34,8 +34,8 @@ ROTATE = 3     # distinct (A, B, C) sets cycled through, so operands are not ser
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a 1 GiB device copy (fetch x2.000, write x1.000); measured with the command lines
 # recorded in profiles/bench_all_workloads.md.  None where not measured.
-TRAFFIC_BYTES = {"c3_bf16_8192": 1883465664, "c4_i8_8192": 1075612462, "c5_bf16_narrow": 4386214255,
-                 "c2_bf16_512": 4296527, "c1_i8_64": 47422}
+TRAFFIC_BYTES = {"c3_bf16_8192": 1926994252, "c4_i8_8192": 1119826627, "c5_bf16_narrow": 4386214339,
+                 "c2_bf16_512": 4332367, "c1_i8_64": 52670}
 
 
 def parse():
@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--workload", default="c3_bf16_8192")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-extra", action="store_true", help="measure only the headline workload")
+    ap.add_argument("--matmul-only", action="store_true",
+                    help="beside the headline, measure only the other matmul workloads (no triangular solve, Cholesky, attention)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one 1 GiB device copy (reference point for HBM traffic counters)")
     return ap.parse_args()
@@ -314,13 +316,16 @@ def bench_chol(lib, torch, w, args):
     if not args.no_cpu:
         from datagen import ws_inputs
         from oracle import chol_oracle, ws_oracle
-        A = ws_inputs.spd_f32(w.n, w.seed, 0, "cpu").numpy()
+        reps = 6
+        mats = [ws_inputs.spd_f32(w.n, w.seed + 1000 * r, 0, "cpu").numpy() for r in range(reps)]
         t0 = time.perf_counter()
-        chol_oracle.chol_tiled(A, w.nb)
+        for A in mats:
+            chol_oracle.chol_tiled(A, w.nb)
         dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(w.ops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": ws_oracle.threads(),
+        out["cpu_baseline"] = {"value": round(reps * w.ops / dt / 1e12, 6), "unit": "TFLOP/s", "cores": ws_oracle.threads(),
                                "kind": "oracle", "seconds": round(dt, 2),
-                               "sample": f"tiled Cholesky oracle on the whole of {w.name}, same seed and distribution"}
+                               "sample": f"tiled Cholesky oracle on {reps} whole matrices of {w.name} (seeds {w.seed}, "
+                                         f"{w.seed + 1000}, ...), same distribution"}
     return out
 
 
@@ -415,15 +420,15 @@ def main():
             extra[name] = {"kernel": kn, "ms_per_step": round(wms, 5), "kernel_ms": round(kms, 5),
                            "achieved": rf["achieved"], "unit": rf["unit"], "bound": rf["bound"], "frac": rf["frac"]}
         # the tiled triangular solve (a sequence of kernels per step: diagonal-space solves and tri-space GEMMs)
-        for name, wt in ws_inputs.TRI_WORKLOADS.items():
+        for name, wt in ({} if args.matmul_only else ws_inputs.TRI_WORKLOADS).items():
             wms, ems = measure_trsm(lib, torch, wt, max(3, args.steps // 5), max(1, args.warmup // 5), ROTATE)
             extra[name] = trsm_entry(wt, wms, ems)
         # the tiled Cholesky factorisation (three launches per panel)
-        for name, wc in ws_inputs.CHOL_WORKLOADS.items():
+        for name, wc in ({} if args.matmul_only else ws_inputs.CHOL_WORKLOADS).items():
             wms, ems = measure_chol(lib, torch, wc, max(2, args.steps // 4), 1, 2)
             extra[name] = chol_entry(wc, wms, ems)
         # the attention tile recurrence (one kernel per step)
-        for name, wa in ws_inputs.ATTN_WORKLOADS.items():
+        for name, wa in ({} if args.matmul_only else ws_inputs.ATTN_WORKLOADS).items():
             wms, ems = measure_attn(lib, torch, wa, max(3, args.steps // 2), max(1, args.warmup // 2), ROTATE)
             extra[name] = attn_entry(wa, wms, ems)
         out["workloads"] = extra

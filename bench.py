@@ -8,9 +8,10 @@ before the timed region.  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu] [--no-extra]
                   [--copy-calibration]
 
-NAME is one of the five matmul workloads (default c3_bf16_8192), t1_trsm_8192 (the tiled triangular
-solve), h1_chol_8192 (the tiled Cholesky factorisation) or f1_attn_4096 (the attention tile recurrence);
-the latter three are otherwise measured last and reported under "workloads".
+NAME is one of the five matmul workloads (default c3_bf16_8192), k1_bf16_tallk (few output blocks, long k: the
+k-in-space kernel variant), t1_trsm_8192 (the tiled triangular solve), h1_chol_8192 (the tiled Cholesky
+factorisation) or f1_attn_4096 (the attention tile recurrence).  Whatever the headline, the others are measured
+after it and reported under "workloads" (--no-extra: none of them; --matmul-only: only the five).
 
 The headline workload is the 8192^3 bf16 case (compute bound, MFMA roofline); the int8 8192^3
 and the batched narrow-stream cases are measured after it and reported under "workloads".
@@ -242,7 +243,9 @@ def bench_attn(lib, torch, w, args):
 
 
 def roofline(w, kern_ms):
-    if w.N <= 16:   # HBM bound: algorithmic bytes = A and B read once, C written once
+    # which roofline bounds the workload: its operations per algorithmic byte (A and B read once, C written once)
+    # against the chip's ridge, peak operations per second over peak HBM bytes per second
+    if w.ops / w.algorithmic_bytes < PEAK[w.dtype][0] * 1e12 / (HBM_PEAK_GBS * 1e9):
         ach = w.algorithmic_bytes / (kern_ms * 1e-3) / 1e9
         return {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": TRAFFIC_BYTES.get(w.name)}
@@ -375,7 +378,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
-    known = (sorted(ws_inputs.WORKLOADS) + sorted(ws_inputs.TRI_WORKLOADS) + sorted(ws_inputs.ATTN_WORKLOADS) +
+    matmuls = dict(ws_inputs.WORKLOADS, **ws_inputs.KSPACE_WORKLOADS)
+    known = (sorted(matmuls) + sorted(ws_inputs.TRI_WORKLOADS) + sorted(ws_inputs.ATTN_WORKLOADS) +
              sorted(ws_inputs.CHOL_WORKLOADS))
     if args.workload not in known:
         print(f"bench.py: unknown workload {args.workload}; choose from {known}", file=sys.stderr)
@@ -391,7 +395,7 @@ def main():
         print(json.dumps(bench_chol(lib, torch, ws_inputs.CHOL_WORKLOADS[args.workload], args)))
         return
 
-    w = ws_inputs.WORKLOADS[args.workload]
+    w = matmuls[args.workload]
     torch.cuda.synchronize()
     wall_ms, kern_ms, kname = measure(lib, torch, w, args.steps, args.warmup, ROTATE)
     unit = "GB/s" if w.N <= 16 else PEAK[w.dtype][1]
@@ -410,10 +414,11 @@ def main():
 
     if not args.no_extra:
         extra = {}
-        for name in ("c3_bf16_8192", "c4_i8_8192", "c5_bf16_narrow", "c2_bf16_512", "c1_i8_64"):
+        names = ("c3_bf16_8192", "c4_i8_8192", "c5_bf16_narrow", "c2_bf16_512", "c1_i8_64")
+        for name in names if args.matmul_only else names + tuple(ws_inputs.KSPACE_WORKLOADS):
             if name == w.name:
                 continue
-            wx = ws_inputs.WORKLOADS[name]
+            wx = matmuls[name]
             sets = ROTATE if wx.algorithmic_bytes * ROTATE < 40e9 else 1
             wms, kms, kn = measure(lib, torch, wx, args.steps, args.warmup, sets)
             rf = roofline(wx, kms)

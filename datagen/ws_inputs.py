@@ -275,6 +275,14 @@ def make_attn_inputs(w: AttnWorkload, device="cpu"):
             normal_bf16((w.batch, w.M, w.d), 1.0, w.seed, 2, device))
 
 
+# Few output blocks and a long k extent: the shape regime of the k-in-space kernel variant.  The paper gives no
+# such size; 512 x 262144 x 512 moves 0.5 GiB of operands for 1.4e11 operations (256 flop/byte: just under the
+# chip's ridge of 312, so the HBM roofline bounds it).
+KSPACE_WORKLOADS = {
+    "k1_bf16_tallk": Workload("k1_bf16_tallk", "bf16", 1, 512, 262144, 512, "normal", 262144 ** -0.25, 9),
+}
+
+
 def make_inputs(w: Workload, device="cpu", scale_down: int = 1):
     """A (batch, M, K) and B (batch, K, N) for a workload; batch dim dropped when batch == 1.
 

@@ -28,7 +28,13 @@
  *                 The summation order over k is fixed per shape (bit-identical
  *                 results run to run) but is not the strictly sequential order
  *                 of the cell chain; it agrees with it to within fp32 rounding
- *                 of a K-term sum.
+ *                 of a K-term sum.  One exception: unbatched problems with at
+ *                 most 64 output blocks of 128 x 128 and K >= 4096 run with k
+ *                 mapped to space ("mfmak": k-slices on different workgroups
+ *                 add their partial sums to C atomically, the paper's hand-over
+ *                 of [i,k]_C from cell to cell); there the order of those adds,
+ *                 and with it the last bits of C, can differ from call to call.
+ *                 CYC_FORCE_KERNEL=mfma128 restores the fixed order.
  *   CYC_I8_I32    A,B int8; partial sums int32, wrapping modulo 2^32; C int32.
  *                 Bit-exact for any summation order.
  *
@@ -40,7 +46,7 @@
  * else runs on a slower shape-agnostic kernel.
  *
  * The environment variable CYC_FORCE_KERNEL (generic | mfma256 | mfma128 |
- * mfma256x32 | mfma128x32 | narrow), read at every call, overrides the choice
+ * mfma256x32 | mfma128x32 | mfmak | narrow), read at every call, overrides the choice
  * of kernel when the named kernel supports the problem; it exists for tests
  * and benchmarks.  (The x32 kernels use the 32x32 MFMA shape instead of the
  * 16x16 one; the dispatcher never picks them by itself.)
@@ -155,7 +161,7 @@ const char *cyc_status_string(int status);
 int cyc_version(void);
 
 /* Name of the kernel family the dispatcher would pick for this problem
- * ("mfma256", "mfma128", "narrow", "generic", "zero", "none", or a name forced
+ * ("mfma256", "mfma128", "mfmak", "narrow", "generic", "zero", "none", or a name forced
  * through CYC_FORCE_KERNEL); static storage.
  * Host only; enqueues nothing.  Pointers are only inspected for alignment. */
 const char *cyc_kernel_name(const void *A, const void *B, const void *C,

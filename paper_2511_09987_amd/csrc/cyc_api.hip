@@ -25,7 +25,7 @@ bool overlaps(const void *p, int64_t pbytes, const void *q, int64_t qbytes)
     return a < b + (uintptr_t)qbytes && b < a + (uintptr_t)pbytes;
 }
 
-enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_MFMA256X32, K_MFMA128X32, K_NARROW };
+enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_MFMA256X32, K_MFMA128X32, K_MFMAK, K_NARROW };
 
 const char *kernel_label(Kernel k)
 {
@@ -37,6 +37,7 @@ const char *kernel_label(Kernel k)
         case K_MFMA128: return "mfma128";
         case K_MFMA256X32: return "mfma256x32";
         case K_MFMA128X32: return "mfma128x32";
+        case K_MFMAK: return "mfmak";
         case K_NARROW: return "narrow";
     }
     return "none";
@@ -76,10 +77,11 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
 
     if (K == 0) { *k = K_ZERO; return CYC_OK; }
 
-    // CYC_FORCE_KERNEL=generic|mfma256|mfma128|mfma256x32|mfma128x32|narrow overrides the heuristic when
+    // CYC_FORCE_KERNEL=generic|mfma256|mfma128|mfma256x32|mfma128x32|mfmak|narrow overrides the heuristic when
     // the named kernel supports the problem (testing and benchmarking aid).  The x32 names are the MFMA
     // kernels built on the 32x32 instruction shape, which the dispatcher never picks by itself.
     const char *force = std::getenv("CYC_FORCE_KERNEL");
+    int ktile = 0;
     if (force && *force) {
         if (!std::strcmp(force, "generic")) { *k = K_GENERIC; return CYC_OK; }
         if (!std::strcmp(force, "mfma256") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256; return CYC_OK; }
@@ -87,8 +89,11 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
         if (!std::strcmp(force, "mfma256x32") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256X32; return CYC_OK; }
         if (!std::strcmp(force, "mfma128x32") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128X32; return CYC_OK; }
         if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
+        if (!std::strcmp(force, "mfmak") && cyc::choose_ksplit(*p, &ktile) > 1) { *k = K_MFMAK; return CYC_OK; }
     }
     if (cyc::prefers_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
+    // few output blocks, long k: k goes to space (see choose_ksplit)
+    if (!(force && *force) && cyc::choose_ksplit(*p, &ktile) > 1) { *k = K_MFMAK; return CYC_OK; }
     // MFMA kernels for everything with 16-byte aligned rows except slivers
     const int tile = cyc::choose_mfma_tile(*p);
     if (tile == 256) { *k = K_MFMA256; return CYC_OK; }
@@ -108,6 +113,12 @@ int run(const cyc::Problem &p, Kernel k, hipStream_t s)
         case K_MFMA128: e = cyc::launch_mfma(p, 128, 16, s); break;
         case K_MFMA256X32: e = cyc::launch_mfma(p, 256, 32, s); break;
         case K_MFMA128X32: e = cyc::launch_mfma(p, 128, 32, s); break;
+        case K_MFMAK: {
+            int tile = 0;
+            const int ks = cyc::choose_ksplit(p, &tile);
+            e = cyc::launch_mfma_ksplit(p, ks, tile, s);
+            break;
+        }
         case K_NARROW: e = cyc::launch_narrow(p, s); break;
     }
     return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;

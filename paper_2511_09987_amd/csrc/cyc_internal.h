@@ -18,6 +18,7 @@ struct Problem {
     int64_t ldb = 0;                     // row stride of B in elements, 0 = N
     int64_t ldc = 0;                     // row stride of C (and of Cin) in elements, 0 = N
     const void *Cin = nullptr;           // when set, C <- Cin - A*B instead of C <- A*B (same layout as C; may be C)
+    bool accumulate = false;             // the epilogue adds its product to C atomically (the k-in-space variant)
 };
 inline int64_t row_stride_a(const Problem &p) { return p.lda ? p.lda : p.K; }
 inline int64_t row_stride_b(const Problem &p) { return p.ldb ? p.ldb : p.N; }
@@ -32,6 +33,11 @@ bool supports_mfma(const Problem &p, int tile);
 hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s);   // mt: MFMA tile width, 16 or 32
 // block edge (256 or 128) of the MFMA kernel that suits the problem best, 0 if neither supports it
 int choose_mfma_tile(const Problem &p);
+// k in space: number of k-slices (a power of two, 1 = do not split) for problems with few output blocks and a
+// long k extent, and the launch that zeroes C and lets one workgroup per (output block, k-slice) add its partial
+// product to C atomically
+int choose_ksplit(const Problem &p, int *tile);   // *tile: block edge to use, 128 or 256
+hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, hipStream_t s);
 // lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, hipStream_t s);
 // tiled Cholesky factorisation A = L L^T in tiles of nb (see cyc_chol.hip); arguments validated by the caller

@@ -12,6 +12,7 @@
 // Both element types share one byte geometry: a k-tile is 128 bytes of a row of A
 // (64 bf16 or 128 int8 values), cut into eight 16-byte chunks.
 #include "cyc_internal.h"
+#include <algorithm>
 
 namespace cyc {
 namespace {
@@ -147,7 +148,7 @@ template <class C, bool RAGGED>
 __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                         char *__restrict__ Cout, int M, int K, int N, int64_t sA,
                                                         int64_t sB, int64_t sC, int tiles_m, int tiles_n, int lda,
-                                                        int ldb, int ldc, const char *Cin)
+                                                        int ldb, int ldc, const char *Cin, int accumulate)
 {
     constexpr int ES = C::ES, RB = C::RB, TM = C::TM, TN = C::TN;
     __shared__ __attribute__((aligned(1024))) char lds_raw[C::LDS_BYTES];
@@ -408,7 +409,10 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
                 elem v = acc[i][j][r];
                 if (!RAGGED || (row < M && col < N)) {
                     if (Cin) v = ((const elem *)Cin)[(int64_t)row * ldc + col] - v;   // C <- Cin - A*B
-                    Cw[(int64_t)row * ldc + col] = v;
+                    if (accumulate)
+                        atomicAdd(&Cw[(int64_t)row * ldc + col], v);   // one of several k-slices handing on its partial sum
+                    else
+                        Cw[(int64_t)row * ldc + col] = v;
                 }
             }
         }
@@ -423,11 +427,11 @@ hipError_t launch_cfg(const Problem &p, hipStream_t s)
     if (ragged)
         hipLaunchKernelGGL((ws_mfma_kernel<C, true>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
-                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
+                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin, p.accumulate ? 1 : 0);
     else
         hipLaunchKernelGGL((ws_mfma_kernel<C, false>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
-                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
+                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin, p.accumulate ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -443,7 +447,8 @@ bool supports_mfma(const Problem &p, int tile)
     const int64_t lda = row_stride_a(p), ldb = row_stride_b(p), ldc = row_stride_c(p);
     if ((p.K * es) % 16 || (p.N * es) % 16 || (lda * es) % 16 || lda < p.K) return false;
     if ((ldb * es) % 16 || ldb < p.N || ldc < p.N || ldb > (1 << 30) || ldc > (1 << 30)) return false;
-    if ((p.lda || p.ldb || p.ldc || p.Cin) && p.batch != 1) return false;
+    if ((p.lda || p.ldb || p.ldc || p.Cin) && p.batch != 1 && !p.accumulate) return false;
+    if (p.accumulate && p.Cin) return false;
     if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
     if (((p.M + tile - 1) / tile) * ((p.N + tile - 1) / tile) > (1 << 30)) return false;
     // per-lane byte offsets inside a tile's rows are kept in 32 bits
@@ -465,6 +470,51 @@ int choose_mfma_tile(const Problem &p)
     const bool ok256 = supports_mfma(p, 256), ok128 = supports_mfma(p, 128);
     if (ok256 && (!ok128 || cost256 <= cost128)) return 256;
     return ok128 ? 128 : 0;
+}
+
+// The paper's weight-stationary mapping puts k in space: a cell keeps its A_ik and hands its partial sum east.
+// For problems with few output blocks and a long k extent this is the mapping that fills the chip: the k range
+// is cut into `ksplit` slices, every (output block, slice) pair is a workgroup that keeps its slice of A's block
+// row and of B's block column to itself, and the hand-over of the partial sum is an atomic add into C (zeroed
+// first: the chain's initial value).  Integer results are exact whatever the order of the adds; fp32 results
+// depend on it in the last bits.
+int choose_ksplit(const Problem &p, int *tile)
+{
+    *tile = 128;
+    if (p.batch != 1 || p.lda || p.ldb || p.ldc || p.Cin || p.accumulate || !supports_mfma(p, 128)) return 1;
+    const int64_t b128 = ((p.M + 127) / 128) * ((p.N + 127) / 128), b256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
+    const int64_t bke = p.i8 ? 128 : 64;
+    if (b128 > 64 || p.K < 4096) return 1;
+    auto slices = [&](int64_t blocks, int64_t slots) {
+        const int64_t want = std::min<int64_t>(slots / blocks, p.K / (8 * bke));   // at least eight k-tiles per slice
+        int ks = 1;
+        while (2 * ks <= want && 2 * ks <= 256 && p.K % (2 * ks * bke) == 0) ks *= 2;
+        return ks;
+    };
+    // 256 x 256 blocks (one per CU) re-read A and B half as often as 128 x 128 blocks (two per CU) but cost more to
+    // start and to finish: take them when they compute little padding, still fill the chip and keep long slices
+    const int ks256 = supports_mfma(p, 256) ? slices(b256, 256) : 1;
+    const bool big = b256 * 4 * 5 <= b128 * 6 && b256 * ks256 >= 200 && p.K / ks256 >= 4096;
+    const int ks = big ? ks256 : slices(b128, 256);
+    *tile = big ? 256 : 128;
+    return ks;
+}
+
+hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, hipStream_t s)
+{
+    if (ksplit < 2 || ksplit > 256 || p.batch != 1 || p.K % ksplit) return hipErrorInvalidValue;
+    if (hipError_t e = launch_zero(p, s); e != hipSuccess) return e;
+    Problem q = p;
+    q.batch = ksplit;                    // the batch index of the kernel serves as the slice index
+    q.K = p.K / ksplit;
+    q.lda = p.K;
+    q.ldb = p.N;
+    q.ldc = p.N;
+    q.strideA = q.K;                     // slice b starts at column b * K/ksplit of A ...
+    q.strideB = q.K * p.N;               // ... and at that row of B
+    q.strideC = 0;                       // all slices add to the same C
+    q.accumulate = true;
+    return launch_mfma(q, tile, 16, s);
 }
 
 hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s)

@@ -244,6 +244,47 @@ def test_narrow_all_ones_and_dispatch(lib, mode):
     assert bool((C == K).all())
 
 
+# ------------------------------------------------------------ k in space (few output blocks, long k)
+KSPACE = [(256, 8192, 256), (128, 65536, 384), (100, 4096, 80), (512, 16384, 512), (16, 32768, 16), (1024, 4096, 1024),
+          (130, 12288, 272)]
+
+
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_k_in_space_variant(lib, oracle, mode):
+    """Few output blocks and a long k extent: the dispatcher maps k-slices to workgroups that add their partial
+    sums to C atomically.  int8 stays bit-exact, bf16 within the usual bound; small-integer bf16 data are exact
+    in any order of the adds."""
+    for i, (M, K, N) in enumerate(KSPACE):
+        run_case(lib, oracle, mode, M, K, N, seed=700 + i, expect_kernel="mfmak")
+        run_case(lib, oracle, mode, M, K, N, seed=720 + i, kind="small", expect_kernel="mfmak")
+
+
+def test_k_in_space_dispatch_limits(lib):
+    name = lambda M, K, N, batch=1: lib.cyc_kernel_name(0x100000, 0x200000, 0x4000000, batch, M, K, N, M * K, K * N, M * N,
+                                                        lib.CYC_BF16_F32)
+    assert name(256, 8192, 256) == "mfmak"
+    assert name(256, 2048, 256) != "mfmak"                # k too short
+    assert name(2048, 8192, 2048) != "mfmak"              # enough output blocks to fill the chip
+    assert name(256, 8192, 256, batch=4) != "mfmak"       # batched problems keep the fixed order
+    old = os.environ.pop("CYC_FORCE_KERNEL", None)
+    os.environ["CYC_FORCE_KERNEL"] = "mfma128"
+    try:
+        assert name(256, 8192, 256) == "mfma128"             # the fixed-order kernel stays available
+    finally:
+        os.environ.pop("CYC_FORCE_KERNEL", None)
+        if old is not None:
+            os.environ["CYC_FORCE_KERNEL"] = old
+
+
+def test_k_in_space_overwrites_c(lib):
+    """C is an output: what it held before the call must not leak into the sums."""
+    A, B, _, _ = gen("i8", (256, 8192), (8192, 256), seed=77)
+    C = torch.full((256, 256), 12345, dtype=torch.int32, device=DEV)
+    lib.recurrence_matmul(A, B, out=C)
+    assert torch.equal(C, lib.recurrence_matmul(A, B))
+    assert torch.equal(C.double(), A.double() @ B.double())
+
+
 # ------------------------------------------------------------ determinism and batching
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
 def test_run_to_run_bit_identical(lib, mode):

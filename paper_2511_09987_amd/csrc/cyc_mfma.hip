@@ -144,11 +144,14 @@ __device__ __forceinline__ void tile_fence()
 // RAGGED: M, N need not be multiples of the block and K need not be a multiple of the k-tile (rows of A
 // and B must still be 16-byte aligned).  Rows and columns past the edge re-read the last valid ones
 // and are not stored; in the last k-tile, chunks at or past K are not copied but written as zeros.
-template <class C, bool RAGGED>
+// EPI: what the epilogue does with the accumulators: EPI_STORE C <- A*B; EPI_MINUS C <- Cin - A*B (Cin may be C);
+// EPI_ADD C += A*B with atomic adds (k in space).  A template parameter, so that each form is straight-line code.
+enum { EPI_STORE = 0, EPI_MINUS = 1, EPI_ADD = 2 };
+template <class C, bool RAGGED, int EPI>
 __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                         char *__restrict__ Cout, int M, int K, int N, int64_t sA,
                                                         int64_t sB, int64_t sC, int tiles_m, int tiles_n, int lda,
-                                                        int ldb, int ldc, const char *Cin, int accumulate)
+                                                        int ldb, int ldc, const char *Cin)
 {
     constexpr int ES = C::ES, RB = C::RB, TM = C::TM, TN = C::TN;
     __shared__ __attribute__((aligned(1024))) char lds_raw[C::LDS_BYTES];
@@ -398,41 +401,68 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     typedef typename Mac::elem elem;
     elem *Cw = (elem *)Cout;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i) {
+        // one row of MFMA tiles at a time; for EPI_MINUS all its Cin values are requested before the first is used
+        elem cin[TN][C::ACCN];
+        if (EPI == EPI_MINUS) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = n0 + wn * (TN * MT) + j * MT + (l & (MT - 1));
+                const int row0 = m0 + wm * (TM * MT) + i * MT + (l / MT) * 4;
+#pragma unroll
+                for (int r = 0; r < C::ACCN; ++r) {
+                    const int row = row0 + (r >> 2) * 8 + (r & 3);
+                    cin[j][r] = (!RAGGED || (row < M && col < N)) ? ((const elem *)Cin)[(int64_t)row * ldc + col] : (elem)0;
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = n0 + wn * (TN * MT) + j * MT + (l & (MT - 1));
             const int row0 = m0 + wm * (TM * MT) + i * MT + (l / MT) * 4;
 #pragma unroll
             for (int r = 0; r < C::ACCN; ++r) {
-                int row = row0 + (r >> 2) * 8 + (r & 3);
+                const int row = row0 + (r >> 2) * 8 + (r & 3);
                 elem v = acc[i][j][r];
                 if (!RAGGED || (row < M && col < N)) {
-                    if (Cin) v = ((const elem *)Cin)[(int64_t)row * ldc + col] - v;   // C <- Cin - A*B
-                    if (accumulate)
+                    if (EPI == EPI_MINUS) v = cin[j][r] - v;          // C <- Cin - A*B
+                    if (EPI == EPI_ADD)
                         atomicAdd(&Cw[(int64_t)row * ldc + col], v);   // one of several k-slices handing on its partial sum
                     else
                         Cw[(int64_t)row * ldc + col] = v;
                 }
             }
         }
+    }
 }
 
-template <class C>
-hipError_t launch_cfg(const Problem &p, hipStream_t s)
+template <class C, int EPI>
+hipError_t launch_epi(const Problem &p, hipStream_t s)
 {
     const bool ragged = p.M % C::BM || p.N % C::BN || p.K % C::BKE;
     const int tiles_m = (int)((p.M + C::BM - 1) / C::BM), tiles_n = (int)((p.N + C::BN - 1) / C::BN);
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)p.batch);
     if (ragged)
-        hipLaunchKernelGGL((ws_mfma_kernel<C, true>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+        hipLaunchKernelGGL((ws_mfma_kernel<C, true, EPI>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
-                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin, p.accumulate ? 1 : 0);
+                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
     else
-        hipLaunchKernelGGL((ws_mfma_kernel<C, false>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+        hipLaunchKernelGGL((ws_mfma_kernel<C, false, EPI>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
-                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin, p.accumulate ? 1 : 0);
+                           (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
     return hipGetLastError();
+}
+
+// EXTRA: also build the EPI_MINUS and EPI_ADD forms (only the 16-wide MFMA shape, which is all their callers use)
+template <class C, bool EXTRA>
+hipError_t launch_cfg(const Problem &p, hipStream_t s)
+{
+    if (!p.Cin && !p.accumulate) return launch_epi<C, EPI_STORE>(p, s);
+    if constexpr (EXTRA) {
+        if (p.Cin && !p.accumulate) return launch_epi<C, EPI_MINUS>(p, s);
+        if (p.accumulate && !p.Cin) return launch_epi<C, EPI_ADD>(p, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -525,12 +555,12 @@ hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s)
     // either MFMA shape.  mt chooses the MFMA shape: 16 is what the dispatcher uses (see the comment at Acc).
     if (mt == 16) {
         if (tile == 256)
-            return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2, 16>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2, 16>>(p, s);
-        return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2, 16>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2, 16>>(p, s);
+            return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2, 16>, true>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2, 16>, true>(p, s);
+        return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2, 16>, true>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2, 16>, true>(p, s);
     }
     if (tile == 256)
-        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2, 32>>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2, 32>>(p, s);
-    return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2, 32>>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2, 32>>(p, s);
+        return p.i8 ? launch_cfg<Cfg<true, 256, 256, 2, 2, 32>, false>(p, s) : launch_cfg<Cfg<false, 256, 256, 2, 2, 32>, false>(p, s);
+    return p.i8 ? launch_cfg<Cfg<true, 128, 128, 2, 2, 32>, false>(p, s) : launch_cfg<Cfg<false, 128, 128, 2, 2, 32>, false>(p, s);
 }
 
 }  // namespace cyc

@@ -135,17 +135,104 @@ __global__ __launch_bounds__(256) void chol_zero_upper_kernel(float *__restrict_
     for (int64_t r = blockIdx.y; r < c; r += gridDim.y) L[r * n + c] = 0.0f;
 }
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+#define CYC_LDS __attribute__((address_space(3)))
+constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multiplies out by itself (a group's earlier panels)
+
+// The update of a 64 x 64 tile by the earlier panels of its group, inside the tile's own kernel (one wave):
+//     S[r][c] -= sum_{k0 <= k < k1} Lh[row0 + r][k] * Lh[k][j0 + c]          (the second factor is the mirror image)
+// as bf16 MFMAs with fp32 sums, S being a tile in LDS.  The streamed operand, Lh[k0:k1, j0:j0+64], is staged in LDS
+// ([k][column], 128 bytes per row) and read through the transpose read; the stationary operand, the tile's own rows
+// of Lh, goes from memory straight into operand registers, seven k-steps of 32 per round.  Rows past `nrows` repeat
+// the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and k1 - k0 a multiple of 64.
+__device__ __forceinline__ void tile_product(float (*S)[LDT], uint16_t (*Bs)[64], const uint16_t *__restrict__ Lh, int64_t n,
+                                             int64_t row0, int nrows, int64_t k0, int64_t k1, int64_t j0, int lane)
+{
+    const int lq = lane & 15, g = lane >> 4, K = (int)(k1 - k0), nks = K / 32;
+    // stage the streamed operand: 8 rows of 128 bytes per copy, memory to LDS directly, all copies in flight at once
+    {
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs[0][0];
+        const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
+        for (int k = 0; k < K; k += 8) {
+            const char *base = (const char *)(Lh + (k0 + k) * n + j0);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_base + k * 128), "v"(voff), "s"(base)
+                         : "memory", "m0");
+        }
+    }
+    // stationary operand: row 16 i + lq of the tile, k = 32 ks + 8 g .. +7, seven k-steps per round; the next
+    // round is requested before the current one is used
+    i32x4 a[2][7][4];
+    auto request = [&](int round) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 7; ++u) {
+            const int ks = 7 * round + u < nks ? 7 * round + u : nks - 1;        // (a short round re-reads its last step)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = 16 * i + lq;
+                a[round & 1][u][i] = *(const i32x4 *)(Lh + (row0 + (r < nrows ? r : nrows - 1)) * n + k0 + 32 * ks + 8 * g);
+            }
+        }
+    };
+    request(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = (f32x4){0, 0, 0, 0};
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {                                    // K <= 14 k-steps
+        if (7 * round >= nks) break;
+        if (round == 0 && nks > 7) request(1);
+#pragma unroll
+        for (int u = 0; u < 7; ++u) {
+            if (7 * round + u < nks) {                                           // uniform over the wave
+                const int ks = 7 * round + u;
+                i32x4 b[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                    const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                    const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+                    b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[round][u][i]), __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+    // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[16 * i + 4 * g + r][16 * j + lq] -= acc[i][j][r];
+    __syncthreads();
+}
+
 // L_jj = CHOL(S_jj) for the tile at (j0, j0) with `cols` rows and columns.  S is read from Sm (row stride n: A itself
 // for the first panel, L afterwards); L gets the factor below and on the diagonal and zero above it, Lh its bf16
 // rounding in both triangles.  One wave; lane r owns row r.
 __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
-                                                       uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols)
+                                                       uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
     __shared__ __attribute__((aligned(16))) float T[NBMAX][LDT];          // S on entry, L as columns finish
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
     const int r = threadIdx.x;
     const bool live = r < cols;
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     __syncthreads();
+    if (k0 < j0) tile_product(T, Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
     if (cols == NBMAX) {
         // full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
         // unrolling).  Row c of L, which all lanes need in column step c, is lane c's own registers: it is fetched
@@ -192,8 +279,9 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
 
 // L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane.
 __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
-                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols)
+                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
     __shared__ __attribute__((aligned(16))) float D[NBMAX][LDT];          // L_jj
     __shared__ __attribute__((aligned(16))) float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
     const int lane = threadIdx.x;
@@ -201,8 +289,10 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
     const bool live = row < n;
     const int64_t first = j1 + (int64_t)blockIdx.x * 64;
     load_tile(D, L + j0 * n + j0, n, cols, cols, lane);
-    load_tile(X, Sm + first * n + j0, n, (int)(n - first < 64 ? n - first : 64), cols, lane);
+    const int nrows = (int)(n - first < 64 ? n - first : 64);
+    load_tile(X, Sm + first * n + j0, n, nrows, cols, lane);
     __syncthreads();
+    if (k0 < j0) tile_product(X, Bs, Lh, n, first, nrows, k0, j0, j0, lane);
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
     if (cols == NBMAX) {
@@ -220,7 +310,7 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
         for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
     __syncthreads();
-    const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, (int)(n - first < 64 ? n - first : 64), cols, lane);
+    const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, lane);
     if (!live) return;
     for (int c = 0; c < cols; ++c) {
         const float v = X[lane][c];
@@ -275,14 +365,21 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (hipError_t e = product(g0, g0, gcols, 0, g0, A); e != hipSuccess) return e;
         }
         if (g0 > 0) Sm = L;
+        // the terms of the group's own earlier panels: multiplied out by the tile kernels themselves where they can
+        // (full 64-column tiles with 16-byte aligned rows of Lh), else by a product of their own
+        int64_t k0 = j0;                                          // k range [k0, j0) left to the tile kernels
         if (j0 > g0) {
-            if (hipError_t e = product(j0, j0, cols, g0, j0, Sm); e != hipSuccess) return e;
-            Sm = L;
+            if (nb == NBMAX && cols == NBMAX && n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && j0 - g0 <= KMAX) {
+                k0 = g0;
+            } else {
+                if (hipError_t e = product(j0, j0, cols, g0, j0, Sm); e != hipSuccess) return e;
+                Sm = L;
+            }
         }
-        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, s, Sm, L, Lh, n, j0, cols);
+        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, s, Sm, L, Lh, n, j0, cols, k0);
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
         if (j1 < n) {
-            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(64), 0, s, Sm, L, Lh, n, j0, cols);
+            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(64), 0, s, Sm, L, Lh, n, j0, cols, k0);
             if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
         }
     }

@@ -6,18 +6,20 @@
 // where the scalar form ("Representative recurrences") is
 //     L_ii = sqrt(A_ii - sum_{k<i} L_ik^2),        L_ij = (A_ij - sum_{k<j} L_ik L_jk) / L_jj.
 //
-// Mapping.  Per panel, three launches on the caller's stream:
-//   1. the SYRKs and GEMMs of the panel as ONE product of the matrix-multiply recurrence of this library (two
-//      for panels grouped in eights, see launch_chol)
-//      (bf16 operands, fp32 sums): rows j0.. of the finished factor times the transpose of its rows j0..j1.  The
-//      transpose costs nothing because the bf16 copy of the factor, Lh, is kept with both triangles filled
-//      (Lh[c][r] = Lh[r][c]): the stationary operand is the window Lh[j0:, 0:j0], the streamed one the window
-//      Lh[0:j0, j0:j1], and the epilogue writes A - product into the window L[j0:, j0:j1], which holds S until solved.
-//   2. CHOL of the diagonal tile: one wave, one lane per row, columns in lockstep; finished entries go through
-//      LDS, from where every lane reads row c of the tile when it works on column c.
-//   3. TRSM of the rows below: rows do not depend on one another, so one lane per row (64 rows per workgroup)
-//      runs the off-diagonal line of the scalar recurrence against L_jj in LDS, and writes its row of L, of Lh,
-//      and the mirrored column of Lh.
+// Mapping, on the caller's stream.  The SYRKs and GEMMs are products of the matrix-multiply recurrence of this
+// library (bf16 operands, fp32 sums): rows of the finished factor times the transpose of other rows of it.  The
+// transpose costs nothing because the bf16 copy of the factor, Lh, is kept with both triangles filled
+// (Lh[c][r] = Lh[r][c]): a stationary operand is a window Lh[r0:, k0:k1], the streamed one the window
+// Lh[k0:k1, c0:c1].  Panels are taken in groups of eight (see launch_chol):
+//   1. at the first panel of a group, one launch of the GEMM kernel takes all tiles left of the group out of the
+//      group's columns: epilogue A - product into L[g0:, g0:g0+512], which holds S until solved;
+//   2. per panel, CHOL of the diagonal tile: one wave, one lane per row, columns left to right, what a lane needs
+//      of other rows read from those lanes' registers;
+//   3. per panel, TRSM of the rows below: rows do not depend on one another, so one lane per row (64 rows per
+//      workgroup) runs the off-diagonal line of the scalar recurrence against L_jj in LDS, and writes its row of
+//      L, of Lh, and the mirrored column of Lh.
+//   Both tile kernels first take the terms of the group's own earlier panels out of their 64 x 64 tile with MFMAs of
+//   their own (tile_product), which is far cheaper than a launch of the GEMM kernel for so short a k range.
 // Inside a tile column everything is fp32 on unrounded values, in the order of the scalar recurrence:
 // t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
 #include "cyc_internal.h"

@@ -150,3 +150,19 @@ def test_full_size_sampled_queries(lib, attn):
     # every row is a weighted mean of V: inside the hull of V in every coordinate
     assert bool((O <= V.float().amax(dim=1, keepdim=True) + 1e-2).all())
     assert bool((O >= V.float().amin(dim=1, keepdim=True) - 1e-2).all())
+
+
+def test_full_size_head_dimension_64(lib, attn):
+    """The other kernel instantiation (d = 64, 128-key tiles) at the benchmark's batch and sequence lengths."""
+    batch, N, M, d = 64, 4096, 4096, 64
+    Q = ws_inputs.normal_bf16((batch, N, d), 1.0, 19, 0, DEV)
+    K = ws_inputs.normal_bf16((batch, M, d), 1.0, 19, 1, DEV)
+    V = ws_inputs.normal_bf16((batch, M, d), 1.0, 19, 2, DEV)
+    O = lib.recurrence_attention(Q, K, V)
+    torch.cuda.synchronize()
+    rows = [0, 31, 32, 255, 256, 1234, 4095]
+    for b in (0, 40, 63):
+        ref = attn.attention(f64(Q[b][rows]), f64(K[b]), f64(V[b]))
+        check(O[b][rows], ref, f64(V[b]))
+    assert bool((O <= V.float().amax(dim=1, keepdim=True) + 1e-2).all())
+    assert bool((O >= V.float().amin(dim=1, keepdim=True) - 1e-2).all())

@@ -160,3 +160,31 @@ def test_config5_small_integer_data_is_bit_exact(lib):
     C = lib.recurrence_matmul(A, B)
     for b in range(w.batch):
         assert torch.equal(C[b].double(), A[b].double() @ B[b].double()), b
+
+
+def test_tall_k_workload_k_in_space(lib, oracle):
+    """k1_bf16_tallk (512 x 262144 x 512), the shape the k-in-space variant is benchmarked on: sampled blocks
+    against the row-chain oracle, Freivalds as a whole-matrix check, and the integer-valued case exactly."""
+    w = ws_inputs.KSPACE_WORKLOADS["k1_bf16_tallk"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C = lib.recurrence_matmul(A, B)
+    assert lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C.data_ptr(), 1, w.M, w.K, w.N, 0, 0, 0,
+                               lib.CYC_BF16_F32) == "mfmak"
+    for (i0, j0) in ((0, 0), (w.M - 32, w.N - 32), (131, 77)):
+        Ah = torch_bf16_to_bits(A[i0:i0 + 32, :])
+        Bh = torch_bf16_to_bits(B[:, j0:j0 + 32].contiguous())
+        Cref = oracle.ws_rowchain(Ah, Bh, "bf16")
+        err = rel_err(C[i0:i0 + 32, j0:j0 + 32].cpu().numpy(), Cref, bits_to_f64(Ah), bits_to_f64(Bh))
+        assert err <= BF16_TOL and err <= w.K * 2.0 ** -23, f"block at ({i0},{j0}): relative error {err:.3e}"
+    Ad, Bd, Cd = A.double(), B.double(), C.double()
+    g = torch.Generator(device="cpu").manual_seed(9)
+    for _ in range(4):
+        x = (torch.randint(0, 2, (w.N, 1), generator=g, dtype=torch.int64) * 2 - 1).double().to(DEV)
+        bound = Ad.abs() @ (Bd.abs() @ x.abs())
+        assert bool(((Cd @ x - Ad @ (Bd @ x)).abs() <= 1e-3 * bound).all())
+    del Ad, Bd, Cd
+    # integer-valued inputs: |sums| <= 262144 * 4 < 2^24 with entries in [-2, 2], exact in any order of the atomic adds
+    Ai = ws_inputs.small_int_bf16((w.M, w.K), 2, 909, 0, DEV)
+    Bi = ws_inputs.small_int_bf16((w.K, w.N), 2, 909, 1, DEV)
+    Ci = lib.recurrence_matmul(Ai, Bi)
+    assert torch.equal(Ci.double(), Ai.double() @ Bi.double())

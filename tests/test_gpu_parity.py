@@ -244,6 +244,19 @@ def test_narrow_all_ones_and_dispatch(lib, mode):
     assert bool((C == K).all())
 
 
+# ------------------------------------------------------------ a seeded sweep of shapes
+@pytest.mark.parametrize("mode", ("i8", "bf16"))
+def test_seeded_sweep_of_shapes(lib, oracle, mode):
+    """Forty shapes drawn from a fixed seed: extents from 1 to about 700 with every alignment class (multiples of
+    16, of 8, odd), so that the dispatcher's choices and the ragged edges of every kernel are crossed in
+    combinations the hand-picked lists above do not contain."""
+    rng = np.random.default_rng(2511)
+    for i in range(40):
+        align = [1, 8, 16][int(rng.integers(0, 3))]
+        M, K, N = (max(1, int(rng.integers(1, 700)) // a * a) for a in (1, align, align))
+        run_case(lib, oracle, mode, M, K, N, seed=900 + i, kind="small" if i % 4 == 0 else "default")
+
+
 # ------------------------------------------------------------ k in space (few output blocks, long k)
 KSPACE = [(256, 8192, 256), (128, 65536, 384), (100, 4096, 80), (512, 16384, 512), (16, 32768, 16), (1024, 4096, 1024),
           (130, 12288, 272)]

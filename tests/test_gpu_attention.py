@@ -63,6 +63,21 @@ def test_against_oracle(lib, attn, batch, N, M, d):
         check(O[b], ref, f64(V[b]))
 
 
+def test_seeded_sweep_of_shapes(lib, attn):
+    """Sixteen shapes drawn from a fixed seed: query and key counts from 1 to about 600 (ragged ends of both kinds,
+    several key tiles, a last tile of any length), both head dimensions, one to three batch elements."""
+    rng = np.random.default_rng(987)
+    for i in range(16):
+        batch, N, M, d = int(rng.integers(1, 4)), int(rng.integers(1, 600)), int(rng.integers(1, 600)), (64, 128)[i % 2]
+        Q = ws_inputs.normal_bf16((batch, N, d), 1.5, 300 + i, 0, DEV)
+        K = ws_inputs.normal_bf16((batch, M, d), 1.5, 300 + i, 1, DEV)
+        V = ws_inputs.normal_bf16((batch, M, d), 1.0, 300 + i, 2, DEV)
+        O = lib.recurrence_attention(Q, K, V)
+        torch.cuda.synchronize()
+        for b in range(batch):
+            check(O[b], attn.attention(f64(Q[b]), f64(K[b]), f64(V[b])), f64(V[b]))
+
+
 def test_sharp_scores(lib, attn):
     """Scores spread over +-30: the running maximum moves from tile to tile and old contributions are
     rescaled by tiny factors; nothing may overflow."""

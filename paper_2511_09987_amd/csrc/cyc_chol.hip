@@ -53,14 +53,8 @@ __device__ __forceinline__ float chain(float t, const float *x, const float *y, 
     return t;
 }
 
-// fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ uint16_t round_bf16(float f)
-{
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
+// fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN (the hardware conversion)
+__device__ __forceinline__ uint16_t round_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
 // A 64-row tile of a row-major fp32 matrix (row stride ld) into LDS, by one wave: rows 0..nrows-1 (rows past that
 // repeat the last one), columns 0..cols-1.  All loads of a lane are in flight together.

@@ -28,13 +28,8 @@ namespace {
 constexpr int SUB = 8;     // rows a lane carries at a time
 
 __device__ __forceinline__ float widen_bf16(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
-// fp32 -> bfloat16, nearest, ties to even; NaN stays NaN
-__device__ __forceinline__ uint16_t round_bf16(float f)
-{
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16, quiet = (u >> 16) | 0x40u;
-    return (uint16_t)((u & 0x7fffffffu) > 0x7f800000u ? quiet : rounded);
-}
+// fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN (the hardware conversion)
+__device__ __forceinline__ uint16_t round_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
 
 // SUB chains take the x of the tile's rows [0, rb): t[q] = fma(-L[rb+q][j], x_j, t[q]) for j ascending.

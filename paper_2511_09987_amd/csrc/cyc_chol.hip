@@ -94,31 +94,38 @@ __device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, ui
                                            int lane)
 {
     if (cols != NBMAX || ld % 8 != 0 || ((uintptr_t)L & 15) != 0 || ((uintptr_t)Lh & 15) != 0) return false;
+    // all LDS reads first, without conditions (rows past nrows hold copies of the last one), then the stores: a read
+    // inside the row condition would be waited for on the spot, once per row group
+    f32x4 v[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int r = 4 * i + (lane >> 4);
-        if (r < nrows) {
-            f32x4 v = *(const f32x4 *)&src[r][4 * (lane & 15)];
-            if (LOWER) {
+        v[i] = *(const f32x4 *)&src[r][4 * (lane & 15)];
+        if (LOWER) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) v[q] = 4 * (lane & 15) + q <= r ? v[q] : 0.0f;
-            }
-            *(f32x4 *)(L + (int64_t)r * ld + 4 * (lane & 15)) = v;
+            for (int q = 0; q < 4; ++q) v[i][q] = 4 * (lane & 15) + q <= r ? v[i][q] : 0.0f;
         }
+    }
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 8 * i + (lane >> 3);
+        const f32x4 a = *(const f32x4 *)&src[r][8 * (lane & 7)], b = *(const f32x4 *)&src[r][8 * (lane & 7) + 4];
+        h[i][0] = round_bf16(a[0]) | ((unsigned)round_bf16(a[1]) << 16);
+        h[i][1] = round_bf16(a[2]) | ((unsigned)round_bf16(a[3]) << 16);
+        h[i][2] = round_bf16(b[0]) | ((unsigned)round_bf16(b[1]) << 16);
+        h[i][3] = round_bf16(b[2]) | ((unsigned)round_bf16(b[3]) << 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        if (r < nrows) *(f32x4 *)(L + (int64_t)r * ld + 4 * (lane & 15)) = v[i];
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int r = 8 * i + (lane >> 3);
-        if (r < nrows) {
-            const f32x4 a = *(const f32x4 *)&src[r][8 * (lane & 7)], b = *(const f32x4 *)&src[r][8 * (lane & 7) + 4];
-            typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-            u32x4 h;
-            h[0] = round_bf16(a[0]) | ((unsigned)round_bf16(a[1]) << 16);
-            h[1] = round_bf16(a[2]) | ((unsigned)round_bf16(a[3]) << 16);
-            h[2] = round_bf16(b[0]) | ((unsigned)round_bf16(b[1]) << 16);
-            h[3] = round_bf16(b[2]) | ((unsigned)round_bf16(b[3]) << 16);
-            *(u32x4 *)(Lh + (int64_t)r * ld + 8 * (lane & 7)) = h;
-        }
+        if (r < nrows) *(u32x4 *)(Lh + (int64_t)r * ld + 8 * (lane & 7)) = h[i];
     }
     return true;
 }
@@ -277,9 +284,16 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
 __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                         uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
-    __shared__ __attribute__((aligned(16))) float D[NBMAX][LDT];          // L_jj
-    __shared__ __attribute__((aligned(16))) float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
+    // one block, so that D and X lie in the first 64 KB of LDS, where a read reaches them with its 16-bit offset
+    // field from one base register (further up every read needs an address register of its own)
+    __shared__ __attribute__((aligned(16))) struct {
+        float D[NBMAX][LDT];          // L_jj
+        float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
+        uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
+    } lds;
+    auto &D = lds.D;
+    auto &X = lds.X;
+    auto &Bs = lds.Bs;
     const int lane = threadIdx.x;
     const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
     const bool live = row < n;
@@ -291,23 +305,71 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
     if (k0 < j0) tile_product(X, Bs, Lh, n, first, nrows, k0, j0, j0, lane);
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
+    bool mirrored = false;
     if (cols == NBMAX) {
-        float x[NBMAX];                      // the lane's row of L, in registers (constant indices after unrolling)
+        // The lane's row of S and of L in registers (constant indices after unrolling).  Four columns at a time: their
+        // chains over the columns left of the four are independent of one another and run side by side (in a lone
+        // wave a multiply-add that waits for the one before it issues every ~8 cycles, an independent one every
+        // ~5); then the 4 x 4 corner finishes the four one after the other.  Every entry still takes its terms in
+        // ascending k.  The work is a fixed list of steps (block b: b steps of four k each, then the corner); the
+        // rows of L_jj for a step are requested from LDS two steps before it runs, since a lone wave has nobody
+        // else to hide the LDS latency behind.
+        float x[NBMAX], t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 sr[NBMAX / 4], q[3][4];
 #pragma unroll
-        for (int c = 0; c < NBMAX; ++c) {
-            float t = X[lane][c];
+        for (int i = 0; i < NBMAX / 4; ++i) sr[i] = *(const f32x4 *)&X[lane][4 * i];
+        auto request = [&](int b, int k4, int slot) __attribute__((always_inline)) {
 #pragma unroll
-            for (int k = 0; k < c; ++k) t = __builtin_fmaf(-x[k], D[c][k], t);
-            x[c] = t / D[c][c];
+            for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&D[4 * b + j][4 * k4];
+        };
+        request(0, 0, 0);
+        request(1, 0, 1);
+        int cnt = 0;
+#pragma unroll
+        for (int b = 0; b < NBMAX / 4; ++b) {
+#pragma unroll
+            for (int k4 = 0; k4 <= b; ++k4) {
+                int nb2 = b, nk = k4 + 2;                 // the step after next
+                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
+                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
+                if (nb2 < NBMAX / 4) request(nb2, nk, (cnt + 2) % 3);
+                __builtin_amdgcn_sched_barrier(0);
+                const int slot = cnt % 3;
+                if (k4 == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[j] = sr[b][j];
+                }
+                if (k4 < b) {
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * k4 + kk], q[slot][j][kk], t[j]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                        for (int i = 0; i < j; ++i) t[j] = __builtin_fmaf(-x[4 * b + i], q[slot][j][i], t[j]);
+                        x[4 * b + j] = t[j] / q[slot][j][j];
+                    }
+                }
+                ++cnt;
+            }
         }
 #pragma unroll
         for (int c = 0; c < NBMAX; ++c) X[lane][c] = x[c];
+        if (live) {
+            // the mirror image of the rows, straight from the registers: consecutive lanes, consecutive addresses
+            uint16_t *m = Lh + j0 * n + row;
+#pragma unroll
+            for (int c = 0; c < NBMAX; ++c) m[c * n] = round_bf16(x[c]);
+        }
+        mirrored = true;
     } else {
         for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
     __syncthreads();
     const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, lane);
-    if (!live) return;
+    if (!live || (stored && mirrored)) return;
     for (int c = 0; c < cols; ++c) {
         const float v = X[lane][c];
         const uint16_t h = round_bf16(v);
@@ -315,7 +377,7 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
             L[row * n + j0 + c] = v;
             Lh[row * n + j0 + c] = h;
         }
-        Lh[(j0 + c) * n + row] = h;          // the mirror image: consecutive lanes, consecutive addresses
+        if (!mirrored) Lh[(j0 + c) * n + row] = h;
     }
 }
 

@@ -229,32 +229,92 @@ __device__ __forceinline__ void tile_product(float (*S)[LDT], uint16_t (*Bs)[64]
 __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
-    __shared__ __attribute__((aligned(16))) float T[NBMAX][LDT];          // S on entry, L as columns finish
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
+    // one block, T first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one
+    // base register (further up every read needs an address register of its own)
+    __shared__ __attribute__((aligned(16))) struct {
+        float T[NBMAX][LDT];          // S on entry, L as columns finish
+        uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
+    } lds;
+    auto &T = lds.T;
+    auto &Bs = lds.Bs;
     const int r = threadIdx.x;
     const bool live = r < cols;
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     __syncthreads();
     if (k0 < j0) tile_product(T, Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
+    bool mirrored = false;
     if (cols == NBMAX) {
-        // full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
-        // unrolling).  Row c of L, which all lanes need in column step c, is lane c's own registers: it is fetched
-        // with lane reads, so that the steps need neither LDS nor barriers.  Lanes above the diagonal (r < c)
-        // compute values nobody uses.
-        float sr[NBMAX], x[NBMAX];
+        // Full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
+        // unrolling) and writes each finished group of four columns to its row of T in LDS, where the other lanes
+        // find row c of L when they come to column c.  Four columns at a time, as in the rows kernel below: the
+        // four chains over the columns left of the group run side by side (block b: b steps of four k each), their
+        // operands, rows 4b .. 4b+3 of L, requested from LDS two steps ahead; only the step over the group just
+        // finished is requested right after that group is written (one wave: its LDS operations complete in
+        // program order, so the read sees the write without a barrier).  Inside the 4 x 4 corner the few values
+        // from other lanes' registers are fetched with lane reads.  Lanes above the diagonal (r < c) compute values
+        // nobody uses.  Every entry takes its terms in ascending k.
+        float x[NBMAX], t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 sr[NBMAX / 4], q[3][4], ql[4];
 #pragma unroll
-        for (int c = 0; c < NBMAX; ++c) sr[c] = T[r][c];
+        for (int i = 0; i < NBMAX / 4; ++i) sr[i] = *(const f32x4 *)&T[r][4 * i];
+        auto request = [&](int b, int k4, int slot) __attribute__((always_inline)) {
 #pragma unroll
-        for (int c = 0; c < NBMAX; ++c) {
-            float t = sr[c];
+            for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&T[4 * b + j][4 * k4];
+        };
+        auto lane_value = [](float v, int l) __attribute__((always_inline)) {
+            return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+        };
+        int cnt = 0;
 #pragma unroll
-            for (int k = 0; k < c; ++k)
-                t = __builtin_fmaf(-x[k], __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x[k]), c)), t);
-            const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, __builtin_sqrtf(t)), c));
-            x[c] = r == c ? d : t / d;
+        for (int b = 0; b < NBMAX / 4; ++b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[j] = sr[b][j];
+#pragma unroll
+            for (int k4 = 0; k4 + 2 <= b; ++k4) {
+                int nb2 = b, nk = k4 + 2;                 // the step after next in the list (b, k4 <= b - 2), b = 2, 3, ..
+                if (nk > nb2 - 2) { nk -= nb2 - 1; ++nb2; }
+                if (nk > nb2 - 2) { nk -= nb2 - 1; ++nb2; }
+                if (nb2 < NBMAX / 4) request(nb2, nk, (cnt + 2) % 3);
+                __builtin_amdgcn_sched_barrier(0);
+                const int slot = cnt % 3;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * k4 + kk], q[slot][j][kk], t[j]);
+                ++cnt;
+            }
+            if (b >= 1) {
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * (b - 1) + kk], ql[j][kk], t[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = 4 * b + j;
+#pragma unroll
+                for (int i = 0; i < j; ++i) t[j] = __builtin_fmaf(-x[4 * b + i], lane_value(x[4 * b + i], c), t[j]);
+                const float d = lane_value(__builtin_sqrtf(t[j]), c);
+                x[c] = r == c ? d : t[j] / d;
+            }
+            f32x4 done;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) done[j] = x[4 * b + j];
+            *(f32x4 *)&T[r][4 * b] = done;
+            if (b + 1 < NBMAX / 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ql[j] = *(const f32x4 *)&T[4 * (b + 1) + j][4 * b];
+            }
+            if (b == 0) {
+                request(2, 0, 0);
+                request(3, 0, 1);
+            }
         }
+        // the mirror image into the upper part of the tile (Lh holds both triangles): entry (c, r) for c < r
 #pragma unroll
-        for (int c = 0; c < NBMAX; ++c) T[r][c] = x[c];
+        for (int c = 0; c < NBMAX - 1; ++c)
+            if (c < r) T[c][r] = x[c];
+        mirrored = true;
         __syncthreads();
     } else {
         for (int c = 0; c < cols; ++c) {
@@ -269,7 +329,7 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
         }
     }
     // mirror the factor into the upper part of the tile in LDS (Lh holds both triangles), then write the tile out
-    if (live)
+    if (live && !mirrored)
         for (int c = r + 1; c < cols; ++c) T[r][c] = T[c][r];
     __syncthreads();
     if (store_tile<true>(T, L + j0 * n + j0, Lh + j0 * n + j0, n, cols, cols, r)) return;
@@ -284,8 +344,7 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
 __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                         uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
-    // one block, so that D and X lie in the first 64 KB of LDS, where a read reaches them with its 16-bit offset
-    // field from one base register (further up every read needs an address register of its own)
+    // one block, D and X first (see chol_diag_kernel)
     __shared__ __attribute__((aligned(16))) struct {
         float D[NBMAX][LDT];          // L_jj
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish

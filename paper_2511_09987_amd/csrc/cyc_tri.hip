@@ -194,15 +194,22 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
                                                        float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
                                                        int tiles)
 {
-    constexpr int NB = 64;
-    __shared__ __attribute__((aligned(16))) float Lt[NB][NB];          // Lt[j][r] = L_tt[r][j], j <= r
-    __shared__ float xs[NB][64];                                       // x of the current tile, one column per lane
-    __shared__ __attribute__((aligned(16))) uint16_t Xb[4 * NB][64];   // solved tiles as bfloat16, [k][column]
-    __shared__ float G[NB][64 + 1];                                    // L[t, 0:t] * Xh[0:t], [row][column]
+    constexpr int NB = 64, LDD = NB + 4;
+    // one block, D first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one
+    // base register
+    __shared__ __attribute__((aligned(16))) struct {
+        float D[NB][LDD];                  // L_tt in fp32, row-major, on and below the diagonal
+        float G[NB][64 + 1];               // L[t, 0:t] * Xh[0:t], [row][column]
+        uint16_t Xb[4 * NB][64];           // solved tiles as bfloat16, [k][column]
+    } lds;
+    auto &D = lds.D;
+    auto &G = lds.G;
+    auto &Xb = lds.Xb;
     const int lane = threadIdx.x, lq = lane & 15, g = lane >> 4;
     const int64_t c0 = (int64_t)blockIdx.x * 64;
     const int64_t c = c0 + lane < nrhs ? c0 + lane : nrhs - 1;         // lanes past the last column shadow it
     const bool live = c0 + lane < nrhs;
+    const unsigned cl = (unsigned)(c - c0);                            // the lane's column within the slab
 
     // Everything a tile needs from memory -- L_tt, its right-hand side, the rows of L for its GEMM -- is
     // independent of the solves before it, so it is requested one tile ahead and arrives while the
@@ -219,14 +226,15 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
             piece[x] = make_uint4(0, 0, 0, 0);
             if (jc * 8 <= r) piece[x] = *(const uint4 *)(L + (rt + r) * n + rt + jc * 8);
         }
-        const float *rp = Rin + rt * nrhs + c;
 #pragma unroll
-        for (int r = 0; r < NB; ++r) rhs[t & 1][r] = rp[r * nrhs];
+        for (int r = 0; r < NB; ++r) rhs[t & 1][r] = (Rin + (rt + r) * nrhs + c0)[cl];      // uniform row address, 32-bit lane offset
         // row lq of 16-row tile i, k = 32 ks + 8 g .. +7, for every MFMA k-step ks of the GEMM
 #pragma unroll
-        for (int ks = 0; ks < 2 * t; ++ks)
+        for (int ks = 0; ks < 6; ++ks)                           // (constant bound: unrolls wherever the call sits)
+            if (ks < 2 * t) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) a[ks][i] = *(const i32x4 *)(L + (rt + i * 16 + lq) * n + r0 + ks * 32 + g * 8);
+                for (int i = 0; i < 4; ++i) a[ks][i] = *(const i32x4 *)(L + (rt + i * 16 + lq) * n + r0 + ks * 32 + g * 8);
+            }
     };
     request(0);
 
@@ -234,15 +242,20 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
     for (int t = 0; t < 4; ++t) {                                // unrolled: t is a constant in every copy
         if (t >= tiles) break;
         const int64_t rt = r0 + (int64_t)t * NB;
-        // ---- stage L_tt (see tri_diag_kernel)
+        // ---- stage L_tt: the 16-byte pieces on and below the diagonal, widened to fp32
 #pragma unroll
         for (int x = 0; x < PER_LANE; ++x) {
             const int id = lane + 64 * x, r = id / cpr, jc = id % cpr;
             if (jc * 8 <= r) {
                 const uint32_t w[4] = {piece[x].x, piece[x].y, piece[x].z, piece[x].w};
+                f32x4 lo, hi;
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (jc * 8 + e <= r) Lt[jc * 8 + e][r] = widen_bf16((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+                for (int e = 0; e < 4; ++e) {
+                    lo[e] = widen_bf16((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+                    hi[e] = widen_bf16((uint16_t)(w[2 + (e >> 1)] >> (16 * (e & 1))));
+                }
+                *(f32x4 *)&D[r][jc * 8] = lo;
+                *(f32x4 *)&D[r][jc * 8 + 4] = hi;
             }
         }
         // ---- tri-space inside the panel: G = L[t, 0:t] * Xb[0:t]  (64 x 64t times 64t x 64)
@@ -277,38 +290,77 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
 #pragma unroll
                     for (int r = 0; r < 4; ++r) G[i * 16 + 4 * g + r][j * 16 + lq] = acc[i][j][r];
         }
-        __syncthreads();                                        // Lt and G are in place
-        // xs[r][lane] holds R_r until row r is solved and x_r from then on
+        __syncthreads();                                        // D and G are in place
+        float(&x)[NB] = rhs[t & 1];                             // the lane's column: R_r until row r is solved, x_r from then on
+        if (t > 0) {
 #pragma unroll
-        for (int r = 0; r < NB; ++r) xs[r][lane] = t > 0 ? rhs[t & 1][r] - G[r][lane] : rhs[t & 1][r];
-        if (t + 1 < tiles) request(t + 1);                      // lands during the solve below
+            for (int r = 0; r < NB; ++r) x[r] -= G[r][lane];
+        }
 
-        // ---- diag-space: the chains of tri_diag_kernel, full tile
-        float *xp = X + rt * nrhs + c;
-        uint16_t *hp = Xh + rt * nrhs + c;
-#pragma unroll 1
-        for (int rb = 0; rb < NB; rb += SUB) {
-            float tt[SUB];
+        // ---- diag-space: the chains of tri_diag_kernel for a full tile, with the lane's column of x in registers
+        // (constant indices after unrolling).  Four rows at a time: their chains over the rows above the four are
+        // independent of one another and run side by side (in a lone wave a multiply-add that waits for the one
+        // before it issues every ~8 cycles, an independent one every ~5); then the 4 x 4 corner finishes the four
+        // one after the other.  Every x still takes its terms in ascending j.  The work is a fixed list of steps
+        // (block b: b steps of four j each, then the corner); the rows of L_tt for a step are requested from LDS
+        // two steps before it runs, since a lone wave has nobody else to hide the LDS latency behind.
+        float tt[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 q[3][4];
+        auto rows_of_L = [&](int b, int k4, int slot) __attribute__((always_inline)) {
 #pragma unroll
-            for (int q = 0; q < SUB; ++q) tt[q] = xs[rb + q][lane];
-            Corner<NB> corner;
-            corner.fetch(Lt, rb);
-            take_earlier_rows<NB>(tt, Lt, xs, rb, lane);
+            for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&D[4 * b + j][4 * k4];
+        };
+        rows_of_L(0, 0, 0);
+        rows_of_L(1, 0, 1);
+        int cnt = 0;
+        auto block = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
-            for (int q = 0; q < SUB; ++q) {
+            for (int k4 = 0; k4 <= b; ++k4) {
+                int nb2 = b, nk = k4 + 2;                       // the step after next
+                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
+                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
+                if (nb2 < NB / 4) rows_of_L(nb2, nk, (cnt + 2) % 3);
+                __builtin_amdgcn_sched_barrier(0);
+                const int slot = cnt % 3;
+                if (k4 == 0) {
 #pragma unroll
-                for (int p = 0; p < q; ++p) tt[q] = __builtin_fmaf(-corner.at(p, q), tt[p], tt[q]);
-                tt[q] = tt[q] / corner.at(q, q);
-                xs[rb + q][lane] = tt[q];
-                const uint16_t h = round_bf16(tt[q]);
-                Xb[t * NB + rb + q][lane] = h;
-                if (live) {
-                    xp[(rb + q) * nrhs] = tt[q];
-                    hp[(rb + q) * nrhs] = h;
+                    for (int j = 0; j < 4; ++j) tt[j] = x[4 * b + j];
                 }
+                if (k4 < b) {
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) tt[j] = __builtin_fmaf(-q[slot][j][kk], x[4 * k4 + kk], tt[j]);
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int r = 4 * b + j;
+#pragma unroll
+                        for (int i = 0; i < j; ++i) tt[j] = __builtin_fmaf(-q[slot][j][i], x[4 * b + i], tt[j]);
+                        x[r] = tt[j] / q[slot][j][j];
+                        Xb[t * NB + r][lane] = round_bf16(x[r]);
+                    }
+                }
+                ++cnt;
+            }
+        };
+#pragma unroll
+        for (int b = 0; b < NB / 4 - 4; ++b) block(b);
+        // the next tile's operands: late enough to keep the registers free for most of the solve, early enough to
+        // land before it ends (the last four blocks are 58 of the 136 steps)
+        if (t + 1 < tiles) request(t + 1);
+#pragma unroll
+        for (int b = NB / 4 - 4; b < NB / 4; ++b) block(b);
+        // the tile's results go out in one batch: a store under the lane condition inside the chains would cut them
+        // into basic blocks, and the chains of a block would then be moved apart, each to its own division
+        if (live) {
+#pragma unroll
+            for (int r = 0; r < NB; ++r) {                      // uniform row address, 32-bit lane offset
+                (X + (rt + r) * nrhs + c0)[cl] = x[r];
+                (Xh + (rt + r) * nrhs + c0)[cl] = round_bf16(x[r]);
             }
         }
-        __syncthreads();                                        // Xb of this tile visible; Lt, G, xs free for the next
+        __syncthreads();                                        // Xb of this tile visible; D and G free for the next
     }
 }
 

@@ -56,6 +56,73 @@ __device__ __forceinline__ float chain(float t, const float *x, const float *y, 
 // fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN (the hardware conversion)
 __device__ __forceinline__ uint16_t round_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
+// The column recurrence of a 64-wide tile as a fixed list of steps, for the kernels below that run it in one wave with
+// the lane's row in registers.  The 64 columns go in 16 blocks of four.  The four chains of block b first take the
+// columns left of the block (b "bulk" steps of four k each: 16 independent multiply-adds), then the 4 x 4 corner
+// finishes the four columns one after the other, each with a division: a chain of dependent instructions.  In a lone
+// wave a dependent instruction issues every ~8 cycles, an independent one every ~5, so the corner of block b is
+// interleaved with bulk steps of block b + 1: its steps over k4 < b do not need the columns the corner is producing,
+// and up to EARLY of them are taken out of turn, one beside each corner column.  Every entry still takes its terms
+// in ascending k.  StepList is the resulting execution order of all 120 bulk steps.
+constexpr int NBLK = NBMAX / 4, EARLY = 4, NSTEP = NBLK * (NBLK - 1) / 2;
+constexpr int early_of(int b) { return b < 1 ? 0 : (b - 1 < EARLY ? b - 1 : EARLY); }
+struct StepList {
+    signed char b[NSTEP + 2], k[NSTEP + 2];
+};
+constexpr StepList make_steps()
+{
+    StepList s{};
+    int n = 0;
+    for (int b = 0; b < NBLK; ++b) {
+        for (int k4 = early_of(b); k4 < b; ++k4) {           // in turn, before the corner of block b
+            s.b[n] = (signed char)b;
+            s.k[n++] = (signed char)k4;
+        }
+        if (b + 1 < NBLK)
+            for (int k4 = 0; k4 < early_of(b + 1); ++k4) {   // out of turn, beside the corner of block b
+                s.b[n] = (signed char)(b + 1);
+                s.k[n++] = (signed char)k4;
+            }
+    }
+    s.b[n] = s.b[n + 1] = -1;                                // (requests past the end do nothing)
+    return s;
+}
+constexpr StepList STEPS = make_steps();
+
+// IEEE fp32 division num / den (correctly rounded, all special cases) in four phases: the instruction sequence the
+// compiler itself expands a division into, cut up so that independent work can be placed between the phases of this
+// long dependent chain: scale and reciprocal estimate; a Newton step on the reciprocal; quotient and one correction;
+// the last correction and the hardware's fix-up of scaling and special cases.
+struct Division {
+    float num, den, d0, n0, r, q;
+    bool flag;
+    __device__ __forceinline__ void phase0(float numerator, float denominator)
+    {
+        num = numerator;
+        den = denominator;
+        bool unused;
+        d0 = __builtin_amdgcn_div_scalef(num, den, false, &unused);
+        n0 = __builtin_amdgcn_div_scalef(num, den, true, &flag);
+        r = __builtin_amdgcn_rcpf(d0);
+    }
+    __device__ __forceinline__ void phase1()
+    {
+        const float e = __builtin_fmaf(-d0, r, 1.0f);
+        r = __builtin_fmaf(e, r, r);
+    }
+    __device__ __forceinline__ void phase2()
+    {
+        q = n0 * r;
+        const float e = __builtin_fmaf(-d0, q, n0);
+        q = __builtin_fmaf(e, r, q);
+    }
+    __device__ __forceinline__ float phase3()
+    {
+        const float e = __builtin_fmaf(-d0, q, n0);
+        return __builtin_amdgcn_div_fixupf(__builtin_amdgcn_div_fmasf(e, r, q, flag), den, num);
+    }
+};
+
 // A 64-row tile of a row-major fp32 matrix (row stride ld) into LDS, by one wave: rows 0..nrows-1 (rows past that
 // repeat the last one), columns 0..cols-1.  All loads of a lane are in flight together.
 __device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, int64_t ld, int nrows, int cols, int lane)
@@ -366,53 +433,77 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
     // store below, and write nothing of their own)
     bool mirrored = false;
     if (cols == NBMAX) {
-        // The lane's row of S and of L in registers (constant indices after unrolling).  Four columns at a time: their
-        // chains over the columns left of the four are independent of one another and run side by side (in a lone
-        // wave a multiply-add that waits for the one before it issues every ~8 cycles, an independent one every
-        // ~5); then the 4 x 4 corner finishes the four one after the other.  Every entry still takes its terms in
-        // ascending k.  The work is a fixed list of steps (block b: b steps of four k each, then the corner); the
-        // rows of L_jj for a step are requested from LDS two steps before it runs, since a lone wave has nobody
-        // else to hide the LDS latency behind.
-        float x[NBMAX], t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        f32x4 sr[NBMAX / 4], q[3][4];
+        // The lane's row of S and of L in registers (constant indices after unrolling); the steps of StepList, the
+        // rows of L_jj for a step requested from LDS two steps before it runs, since a lone wave has nobody else to
+        // hide the LDS latency behind.
+        float x[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 sr[NBLK], q[3][4], qc[2][4];
 #pragma unroll
-        for (int i = 0; i < NBMAX / 4; ++i) sr[i] = *(const f32x4 *)&X[lane][4 * i];
-        auto request = [&](int b, int k4, int slot) __attribute__((always_inline)) {
+        for (int i = 0; i < NBLK; ++i) sr[i] = *(const f32x4 *)&X[lane][4 * i];
+        auto request = [&](int i) __attribute__((always_inline)) {              // operands of bulk step i
+            if (STEPS.b[i] >= 0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&D[4 * b + j][4 * k4];
-        };
-        request(0, 0, 0);
-        request(1, 0, 1);
-        int cnt = 0;
-#pragma unroll
-        for (int b = 0; b < NBMAX / 4; ++b) {
-#pragma unroll
-            for (int k4 = 0; k4 <= b; ++k4) {
-                int nb2 = b, nk = k4 + 2;                 // the step after next
-                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
-                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
-                if (nb2 < NBMAX / 4) request(nb2, nk, (cnt + 2) % 3);
-                __builtin_amdgcn_sched_barrier(0);
-                const int slot = cnt % 3;
-                if (k4 == 0) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) t[j] = sr[b][j];
-                }
-                if (k4 < b) {
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * k4 + kk], q[slot][j][kk], t[j]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                        for (int i = 0; i < j; ++i) t[j] = __builtin_fmaf(-x[4 * b + i], q[slot][j][i], t[j]);
-                        x[4 * b + j] = t[j] / q[slot][j][j];
-                    }
-                }
-                ++cnt;
+                for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&D[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
             }
+        };
+        auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {   // a quarter of bulk step i
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(-x[4 * STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
+        };
+        request(0);
+        request(1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            qc[0][j] = *(const f32x4 *)&D[j][0];
+            t[j] = sr[0][j];
+        }
+        int i = 0;                                                              // the next bulk step
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+#pragma unroll
+            for (int s = early_of(b); s < b; ++s) {                             // the block's bulk steps taken in turn
+                request(i + 2);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) quarter(t, i, kk);
+                ++i;
+            }
+            if (b + 1 < NBLK) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    qc[(b + 1) & 1][j] = *(const f32x4 *)&D[4 * (b + 1) + j][4 * (b + 1)];
+                    tn[j] = sr[b + 1][j];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {                                       // the corner, column by column
+                const bool paired = b + 1 < NBLK && j < early_of(b + 1);
+                if (paired) request(i + 2);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int c = 0; c < j; ++c) t[j] = __builtin_fmaf(-x[4 * b + c], qc[b & 1][j][c], t[j]);
+                Division dv;
+                dv.phase0(t[j], qc[b & 1][j][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) quarter(tn, i, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                dv.phase1();
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) quarter(tn, i, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                dv.phase2();
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) quarter(tn, i, 2);
+                __builtin_amdgcn_sched_barrier(0);
+                x[4 * b + j] = dv.phase3();
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) {
+                    quarter(tn, i, 3);
+                    ++i;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[j] = tn[j];
         }
 #pragma unroll
         for (int c = 0; c < NBMAX; ++c) X[lane][c] = x[c];

@@ -123,30 +123,33 @@ struct Division {
     }
 };
 
-// A 64-row tile of a row-major fp32 matrix (row stride ld) into LDS, by one wave: rows 0..nrows-1 (rows past that
-// repeat the last one), columns 0..cols-1.  All loads of a lane are in flight together.
-__device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, int64_t ld, int nrows, int cols, int lane)
+constexpr int NT = 256;        // threads of a tile kernel: four waves move tiles and multiply, the first runs the recurrence
+
+// A 64-row tile of a row-major fp32 matrix (row stride ld) into LDS, by the workgroup: rows 0..nrows-1 (rows past that
+// repeat the last one), columns 0..cols-1.  All loads of a thread are in flight together.
+__device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, int64_t ld, int nrows, int cols, int tid)
 {
     if (cols == NBMAX && ld % 4 == 0 && ((uintptr_t)src & 15) == 0) {
-        f32x4 v[16];
+        constexpr int PASSES = NBMAX * 16 / NT;
+        f32x4 v[PASSES];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int r = 4 * i + (lane >> 4);
-            v[i] = *(const f32x4 *)(src + (int64_t)(r < nrows ? r : nrows - 1) * ld + 4 * (lane & 15));
+        for (int i = 0; i < PASSES; ++i) {
+            const int r = NT / 16 * i + (tid >> 4);
+            v[i] = *(const f32x4 *)(src + (int64_t)(r < nrows ? r : nrows - 1) * ld + 4 * (tid & 15));
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) *(f32x4 *)&dst[4 * i + (lane >> 4)][4 * (lane & 15)] = v[i];
+        for (int i = 0; i < PASSES; ++i) *(f32x4 *)&dst[NT / 16 * i + (tid >> 4)][4 * (tid & 15)] = v[i];
     } else {
-        for (int i0 = 0; i0 < NBMAX * cols; i0 += 64 * 8) {
-            float v[8];
+        for (int i0 = 0; i0 < NBMAX * cols; i0 += NT * 4) {
+            float v[4];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int i = i0 + 64 * q + lane, r = i / cols, c = i - r * cols;
+            for (int q = 0; q < 4; ++q) {
+                const int i = i0 + NT * q + tid, r = i / cols, c = i - r * cols;
                 v[q] = i < NBMAX * cols ? src[(int64_t)(r < nrows ? r : nrows - 1) * ld + c] : 0.0f;
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int i = i0 + 64 * q + lane, r = i / cols, c = i - r * cols;
+            for (int q = 0; q < 4; ++q) {
+                const int i = i0 + NT * q + tid, r = i / cols, c = i - r * cols;
                 if (i < NBMAX * cols) dst[r][c] = v[q];
             }
         }
@@ -154,45 +157,46 @@ __device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, i
 }
 
 // The reverse for a full-width tile held in LDS: rows 0..nrows-1 to the fp32 matrix L and, rounded, to the bfloat16
-// matrix Lh (both with row stride ld), 16 bytes per lane and store.  False when shape or alignment do not allow it.
+// matrix Lh (both with row stride ld), 16 bytes per thread and store.  False when shape or alignment do not allow it.
 // LOWER: the tile is a diagonal tile; L gets zeros above the diagonal (Lh gets what the tile holds there).
 template <bool LOWER>
 __device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, uint16_t *Lh, int64_t ld, int nrows, int cols,
-                                           int lane)
+                                           int tid)
 {
     if (cols != NBMAX || ld % 8 != 0 || ((uintptr_t)L & 15) != 0 || ((uintptr_t)Lh & 15) != 0) return false;
     // all LDS reads first, without conditions (rows past nrows hold copies of the last one), then the stores: a read
     // inside the row condition would be waited for on the spot, once per row group
-    f32x4 v[16];
+    constexpr int PL = NBMAX * 16 / NT, PH = NBMAX * 8 / NT;
+    f32x4 v[PL];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 4 * i + (lane >> 4);
-        v[i] = *(const f32x4 *)&src[r][4 * (lane & 15)];
+    for (int i = 0; i < PL; ++i) {
+        const int r = NT / 16 * i + (tid >> 4);
+        v[i] = *(const f32x4 *)&src[r][4 * (tid & 15)];
         if (LOWER) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[i][q] = 4 * (lane & 15) + q <= r ? v[i][q] : 0.0f;
+            for (int q = 0; q < 4; ++q) v[i][q] = 4 * (tid & 15) + q <= r ? v[i][q] : 0.0f;
         }
     }
     typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-    u32x4 h[8];
+    u32x4 h[PH];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = 8 * i + (lane >> 3);
-        const f32x4 a = *(const f32x4 *)&src[r][8 * (lane & 7)], b = *(const f32x4 *)&src[r][8 * (lane & 7) + 4];
+    for (int i = 0; i < PH; ++i) {
+        const int r = NT / 8 * i + (tid >> 3);
+        const f32x4 a = *(const f32x4 *)&src[r][8 * (tid & 7)], b = *(const f32x4 *)&src[r][8 * (tid & 7) + 4];
         h[i][0] = round_bf16(a[0]) | ((unsigned)round_bf16(a[1]) << 16);
         h[i][1] = round_bf16(a[2]) | ((unsigned)round_bf16(a[3]) << 16);
         h[i][2] = round_bf16(b[0]) | ((unsigned)round_bf16(b[1]) << 16);
         h[i][3] = round_bf16(b[2]) | ((unsigned)round_bf16(b[3]) << 16);
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = 4 * i + (lane >> 4);
-        if (r < nrows) *(f32x4 *)(L + (int64_t)r * ld + 4 * (lane & 15)) = v[i];
+    for (int i = 0; i < PL; ++i) {
+        const int r = NT / 16 * i + (tid >> 4);
+        if (r < nrows) *(f32x4 *)(L + (int64_t)r * ld + 4 * (tid & 15)) = v[i];
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int r = 8 * i + (lane >> 3);
-        if (r < nrows) *(u32x4 *)(Lh + (int64_t)r * ld + 8 * (lane & 7)) = h[i];
+    for (int i = 0; i < PH; ++i) {
+        const int r = NT / 8 * i + (tid >> 3);
+        if (r < nrows) *(u32x4 *)(Lh + (int64_t)r * ld + 8 * (tid & 7)) = h[i];
     }
     return true;
 }
@@ -212,21 +216,23 @@ typedef int i32x2 __attribute__((ext_vector_type(2)));
 #define CYC_LDS __attribute__((address_space(3)))
 constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multiplies out by itself (a group's earlier panels)
 
-// The update of a 64 x 64 tile by the earlier panels of its group, inside the tile's own kernel (one wave):
+// The update of a 64 x 64 tile by the earlier panels of its group, inside the tile's own kernel (four waves):
 //     S[r][c] -= sum_{k0 <= k < k1} Lh[row0 + r][k] * Lh[k][j0 + c]          (the second factor is the mirror image)
-// as bf16 MFMAs with fp32 sums, S being a tile in LDS.  The streamed operand, Lh[k0:k1, j0:j0+64], is staged in LDS
-// ([k][column], 128 bytes per row) and read through the transpose read; the stationary operand, the tile's own rows
-// of Lh, goes from memory straight into operand registers, seven k-steps of 32 per round.  Rows past `nrows` repeat
-// the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and k1 - k0 a multiple of 64.
+// as bf16 MFMAs with fp32 sums, S being a tile in LDS; wave w computes rows 16 w .. 16 w + 15 (one wave alone would
+// be bound by the MFMA rate of its one SIMD: 224 MFMAs for seven tiles of k).  The streamed operand,
+// Lh[k0:k1, j0:j0+64], is staged in LDS ([k][column], 128 bytes per row) and read through the transpose read; the
+// stationary operand, the tile's own rows of Lh, goes from memory straight into operand registers, all k-steps at
+// once.  Rows past `nrows` repeat the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and
+// k1 - k0 a multiple of 64, at most KMAX.
 __device__ __forceinline__ void tile_product(float (*S)[LDT], uint16_t (*Bs)[64], const uint16_t *__restrict__ Lh, int64_t n,
-                                             int64_t row0, int nrows, int64_t k0, int64_t k1, int64_t j0, int lane)
+                                             int64_t row0, int nrows, int64_t k0, int64_t k1, int64_t j0, int tid)
 {
-    const int lq = lane & 15, g = lane >> 4, K = (int)(k1 - k0), nks = K / 32;
+    const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4, K = (int)(k1 - k0), nks = K / 32;
     // stage the streamed operand: 8 rows of 128 bytes per copy, memory to LDS directly, all copies in flight at once
     {
         const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs[0][0];
         const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
-        for (int k = 0; k < K; k += 8) {
+        for (int k = 8 * w; k < K; k += 8 * (NT / 64)) {
             const char *base = (const char *)(Lh + (k0 + k) * n + j0);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
@@ -234,66 +240,49 @@ __device__ __forceinline__ void tile_product(float (*S)[LDT], uint16_t (*Bs)[64]
                          : "memory", "m0");
         }
     }
-    // stationary operand: row 16 i + lq of the tile, k = 32 ks + 8 g .. +7, seven k-steps per round; the next
-    // round is requested before the current one is used
-    i32x4 a[2][7][4];
-    auto request = [&](int round) __attribute__((always_inline)) {
+    // stationary operand: row 16 w + lq of the tile, k = 32 ks + 8 g .. +7
+    constexpr int NKS = KMAX / 32;
+    i32x4 a[NKS];
+    {
+        const int r = 16 * w + lq;
+        const uint16_t *rowp = Lh + (row0 + (r < nrows ? r : nrows - 1)) * n + k0 + 8 * g;
 #pragma unroll
-        for (int u = 0; u < 7; ++u) {
-            const int ks = 7 * round + u < nks ? 7 * round + u : nks - 1;        // (a short round re-reads its last step)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int r = 16 * i + lq;
-                a[round & 1][u][i] = *(const i32x4 *)(Lh + (row0 + (r < nrows ? r : nrows - 1)) * n + k0 + 32 * ks + 8 * g);
-            }
-        }
-    };
-    request(0);
+        for (int ks = 0; ks < NKS; ++ks) a[ks] = *(const i32x4 *)(rowp + 32 * (ks < nks ? ks : nks - 1));   // (a short range re-reads its last step)
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    f32x4 acc[4][4];
+    f32x4 acc[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (f32x4){0, 0, 0, 0};
+    for (int ks = 0; ks < NKS; ++ks) {
+        if (ks < nks) {                                                          // uniform over the workgroup
+            i32x4 b[4];
 #pragma unroll
-    for (int round = 0; round < 2; ++round) {                                    // K <= 14 k-steps
-        if (7 * round >= nks) break;
-        if (round == 0 && nks > 7) request(1);
-#pragma unroll
-        for (int u = 0; u < 7; ++u) {
-            if (7 * round + u < nks) {                                           // uniform over the wave
-                const int ks = 7 * round + u;
-                i32x4 b[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
-                    const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
-                    const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
-                    b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[round][u][i]), __builtin_bit_cast(bf16x8, b[j]), acc[i][j], 0, 0, 0);
+            for (int j = 0; j < 4; ++j) {
+                CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+                b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
             }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ks]), __builtin_bit_cast(bf16x8, b[j]), acc[j], 0, 0, 0);
         }
     }
     // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) S[16 * i + 4 * g + r][16 * j + lq] -= acc[i][j][r];
+        for (int r = 0; r < 4; ++r) S[16 * w + 4 * g + r][16 * j + lq] -= acc[j][r];
     __syncthreads();
 }
 
 // L_jj = CHOL(S_jj) for the tile at (j0, j0) with `cols` rows and columns.  S is read from Sm (row stride n: A itself
 // for the first panel, L afterwards); L gets the factor below and on the diagonal and zero above it, Lh its bf16
-// rounding in both triangles.  One wave; lane r owns row r.
-__global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
+// rounding in both triangles.  One workgroup of NT threads; thread r < 64 owns row r, the other waves only help to
+// move and update the tile.
+__global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
     // one block, T first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one
@@ -320,6 +309,7 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
         // program order, so the read sees the write without a barrier).  Inside the 4 x 4 corner the few values
         // from other lanes' registers are fetched with lane reads.  Lanes above the diagonal (r < c) compute values
         // nobody uses.  Every entry takes its terms in ascending k.
+        if (r < 64) {
         float x[NBMAX], t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         f32x4 sr[NBMAX / 4], q[3][4], ql[4];
 #pragma unroll
@@ -381,6 +371,7 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
 #pragma unroll
         for (int c = 0; c < NBMAX - 1; ++c)
             if (c < r) T[c][r] = x[c];
+        }
         mirrored = true;
         __syncthreads();
     } else {
@@ -407,8 +398,9 @@ __global__ __launch_bounds__(64) void chol_diag_kernel(const float *__restrict__
         }
 }
 
-// L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane.
-__global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
+// L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane of the first wave; the
+// other waves of the NT threads only help to move and update the tile.
+__global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
                                                         uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
 {
     // one block, D and X first (see chol_diag_kernel)
@@ -420,19 +412,21 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
     auto &D = lds.D;
     auto &X = lds.X;
     auto &Bs = lds.Bs;
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const bool solver = tid < 64;                         // the wave that runs the recurrence
     const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
-    const bool live = row < n;
+    const bool live = solver && row < n;
     const int64_t first = j1 + (int64_t)blockIdx.x * 64;
-    load_tile(D, L + j0 * n + j0, n, cols, cols, lane);
+    load_tile(D, L + j0 * n + j0, n, cols, cols, tid);
     const int nrows = (int)(n - first < 64 ? n - first : 64);
-    load_tile(X, Sm + first * n + j0, n, nrows, cols, lane);
+    load_tile(X, Sm + first * n + j0, n, nrows, cols, tid);
     __syncthreads();
-    if (k0 < j0) tile_product(X, Bs, Lh, n, first, nrows, k0, j0, j0, lane);
+    if (k0 < j0) tile_product(X, Bs, Lh, n, first, nrows, k0, j0, j0, tid);
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
     bool mirrored = false;
     if (cols == NBMAX) {
+        if (solver) {
         // The lane's row of S and of L in registers (constant indices after unrolling); the steps of StepList, the
         // rows of L_jj for a step requested from LDS two steps before it runs, since a lone wave has nobody else to
         // hide the LDS latency behind.
@@ -513,12 +507,13 @@ __global__ __launch_bounds__(64) void chol_panel_kernel(const float *__restrict_
 #pragma unroll
             for (int c = 0; c < NBMAX; ++c) m[c * n] = round_bf16(x[c]);
         }
+        }
         mirrored = true;
-    } else {
+    } else if (solver) {
         for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
     __syncthreads();
-    const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, lane);
+    const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, tid);
     if (!live || (stored && mirrored)) return;
     for (int c = 0; c < cols; ++c) {
         const float v = X[lane][c];
@@ -584,10 +579,10 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
                 Sm = L;
             }
         }
-        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(64), 0, s, Sm, L, Lh, n, j0, cols, k0);
+        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0);
         if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
         if (j1 < n) {
-            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(64), 0, s, Sm, L, Lh, n, j0, cols, k0);
+            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0);
             if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
         }
     }

@@ -224,12 +224,19 @@ constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multi
 // stationary operand, the tile's own rows of Lh, goes from memory straight into operand registers, all k-steps at
 // once.  Rows past `nrows` repeat the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and
 // k1 - k0 a multiple of 64, at most KMAX.
-__device__ __forceinline__ void tile_product(float (*S)[LDT], uint16_t (*Bs)[64], const uint16_t *__restrict__ Lh, int64_t n,
-                                             int64_t row0, int nrows, int64_t k0, int64_t k1, int64_t j0, int tid)
-{
-    const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4, K = (int)(k1 - k0), nks = K / 32;
-    // stage the streamed operand: 8 rows of 128 bytes per copy, memory to LDS directly, all copies in flight at once
+// In two parts, so that a kernel can ask for the operands first, then for its tile, and wait for memory once.
+struct TileProduct {
+    static constexpr int NKS = KMAX / 32;
+    i32x4 a[NKS];
+    int nks;
+
+    // start the copies of both operands; nothing is waited for
+    __device__ __forceinline__ void request(uint16_t (*Bs)[64], const uint16_t *__restrict__ Lh, int64_t n, int64_t row0, int nrows,
+                                            int64_t k0, int64_t k1, int64_t j0, int tid)
     {
+        const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4, K = (int)(k1 - k0);
+        nks = K / 32;
+        // the streamed operand: 8 rows of 128 bytes per copy, memory to LDS directly, all copies in flight at once
         const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs[0][0];
         const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
         for (int k = 8 * w; k < K; k += 8 * (NT / 64)) {
@@ -239,44 +246,46 @@ __device__ __forceinline__ void tile_product(float (*S)[LDT], uint16_t (*Bs)[64]
                          : "s"(lds_base + k * 128), "v"(voff), "s"(base)
                          : "memory", "m0");
         }
-    }
-    // stationary operand: row 16 w + lq of the tile, k = 32 ks + 8 g .. +7
-    constexpr int NKS = KMAX / 32;
-    i32x4 a[NKS];
-    {
+        // the stationary operand: row 16 w + lq of the tile, k = 32 ks + 8 g .. +7
         const int r = 16 * w + lq;
         const uint16_t *rowp = Lh + (row0 + (r < nrows ? r : nrows - 1)) * n + k0 + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) a[ks] = *(const i32x4 *)(rowp + 32 * (ks < nks ? ks : nks - 1));   // (a short range re-reads its last step)
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    f32x4 acc[4];
+
+    // S -= product; call with the tile S in place in LDS and no barrier needed before: waits for the copies itself
+    __device__ __forceinline__ void apply(float (*S)[LDT], uint16_t (*Bs)[64], int tid)
+    {
+        const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        f32x4 acc[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
+        for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-        if (ks < nks) {                                                          // uniform over the workgroup
-            i32x4 b[4];
+        for (int ks = 0; ks < NKS; ++ks) {
+            if (ks < nks) {                                                      // uniform over the workgroup
+                i32x4 b[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
-                const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
-                const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
-                b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+                for (int j = 0; j < 4; ++j) {
+                    CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                    const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                    const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+                    b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ks]), __builtin_bit_cast(bf16x8, b[j]), acc[j], 0, 0, 0);
             }
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ks]), __builtin_bit_cast(bf16x8, b[j]), acc[j], 0, 0, 0);
         }
+        // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) S[16 * w + 4 * g + r][16 * j + lq] -= acc[j][r];
+        __syncthreads();
     }
-    // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) S[16 * w + 4 * g + r][16 * j + lq] -= acc[j][r];
-    __syncthreads();
-}
+};
 
 // L_jj = CHOL(S_jj) for the tile at (j0, j0) with `cols` rows and columns.  S is read from Sm (row stride n: A itself
 // for the first panel, L afterwards); L gets the factor below and on the diagonal and zero above it, Lh its bf16
@@ -295,9 +304,11 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
     auto &Bs = lds.Bs;
     const int r = threadIdx.x;
     const bool live = r < cols;
+    TileProduct product;
+    if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
-    __syncthreads();
-    if (k0 < j0) tile_product(T, Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
+    if (k0 < j0) product.apply(T, Bs, r);
+    else __syncthreads();
     bool mirrored = false;
     if (cols == NBMAX) {
         // Full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
@@ -417,11 +428,13 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
     const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
     const bool live = solver && row < n;
     const int64_t first = j1 + (int64_t)blockIdx.x * 64;
-    load_tile(D, L + j0 * n + j0, n, cols, cols, tid);
     const int nrows = (int)(n - first < 64 ? n - first : 64);
+    TileProduct product;
+    if (k0 < j0) product.request(Bs, Lh, n, first, nrows, k0, j0, j0, tid);
+    load_tile(D, L + j0 * n + j0, n, cols, cols, tid);
     load_tile(X, Sm + first * n + j0, n, nrows, cols, tid);
-    __syncthreads();
-    if (k0 < j0) tile_product(X, Bs, Lh, n, first, nrows, k0, j0, j0, tid);
+    if (k0 < j0) product.apply(X, Bs, tid);
+    else __syncthreads();
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
     bool mirrored = false;

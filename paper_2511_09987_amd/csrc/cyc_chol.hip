@@ -24,6 +24,9 @@
 // t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
 #include "cyc_internal.h"
 
+#include <type_traits>
+#include <utility>
+
 namespace cyc {
 namespace {
 
@@ -88,6 +91,65 @@ constexpr StepList make_steps()
     return s;
 }
 constexpr StepList STEPS = make_steps();
+
+// The same for the diagonal tile, where row c of L is what lane c has just computed.  The chains of block b read the
+// rows 4b .. 4b+3 of L from LDS, where every lane writes its finished columns; the step over the columns of block k4 can
+// be read once the corner of block k4 is written.  The last step of a block (k4 = b - 1) is requested right after
+// that corner and runs after one step held back to cover its latency (k4 = b - 2, "in turn"); all steps before
+// those, at most EARLY_D of them, run beside the corner of block b - 1, PER_COLUMN after each of its four columns:
+// a corner column here is a square root, a lane read and a division, some 30 dependent instructions.
+// DIAG_STEPS is the execution order of the steps that go through the request queue (all but the last of each block).
+constexpr int EARLY_D = 12, PER_COLUMN = 3, NSTEP_D = (NBLK - 1) * (NBLK - 2) / 2;
+constexpr int early_d(int b) { return b < 2 ? 0 : (b - 2 < EARLY_D ? b - 2 : EARLY_D); }
+struct DiagStepList {
+    signed char b[NSTEP_D + 2], k[NSTEP_D + 2];
+    bool ok;
+};
+constexpr DiagStepList make_diag_steps()
+{
+    DiagStepList s{};
+    int when[NSTEP_D + 2] = {};          // 2b: after the corner of block b - 1;  2b + 1: beside the corner of block b
+    int n = 0;
+    for (int b = 0; b < NBLK; ++b) {
+        for (int k4 = early_d(b); k4 + 2 <= b; ++k4) {                 // in turn
+            s.b[n] = (signed char)b;
+            s.k[n] = (signed char)k4;
+            when[n++] = 2 * b;
+        }
+        if (b + 1 < NBLK)
+            for (int k4 = 0; k4 < early_d(b + 1); ++k4) {              // beside the corner of block b
+                s.b[n] = (signed char)(b + 1);
+                s.k[n] = (signed char)k4;
+                when[n++] = 2 * b + 1;
+            }
+    }
+    s.b[n] = s.b[n + 1] = -1;
+    // a step is requested when the step two before it runs (the first two after the corner of block 0): by then the
+    // corner of the block whose columns it covers must have been written
+    s.ok = n == NSTEP_D;
+    for (int i = 0; i < n; ++i) s.ok = s.ok && (i < 2 ? 2 : when[i - 2]) >= 2 * (s.k[i] + 1);
+    return s;
+}
+constexpr int beside_column(int b, int j)           // how many early steps of block b + 1 run beside column j of block b's corner
+{
+    const int left = (b + 1 < NBLK ? early_d(b + 1) : 0) - PER_COLUMN * j;
+    return left < 0 ? 0 : (left < PER_COLUMN ? left : PER_COLUMN);
+}
+constexpr DiagStepList DIAG_STEPS = make_diag_steps();
+static_assert(DIAG_STEPS.ok, "a step of the diagonal tile would be requested before its operand is written");
+
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>): a loop whose index is a constant in every copy
+// from the start (the unrolling pass gives up on bodies as long as the ones below)
+template <class F, int... I>
+__device__ __forceinline__ void unrolled(F &&f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void unrolled(F &&f)
+{
+    unrolled(f, std::make_integer_sequence<int, N>{});
+}
 
 // IEEE fp32 division num / den (correctly rounded, all special cases) in four phases: the instruction sequence the
 // compiler itself expands a division into, cut up so that independent work can be placed between the phases of this
@@ -313,71 +375,85 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
     if (cols == NBMAX) {
         // Full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
         // unrolling) and writes each finished group of four columns to its row of T in LDS, where the other lanes
-        // find row c of L when they come to column c.  Four columns at a time, as in the rows kernel below: the
-        // four chains over the columns left of the group run side by side (block b: b steps of four k each), their
-        // operands, rows 4b .. 4b+3 of L, requested from LDS two steps ahead; only the step over the group just
-        // finished is requested right after that group is written (one wave: its LDS operations complete in
-        // program order, so the read sees the write without a barrier).  Inside the 4 x 4 corner the few values
-        // from other lanes' registers are fetched with lane reads.  Lanes above the diagonal (r < c) compute values
-        // nobody uses.  Every entry takes its terms in ascending k.
+        // find row c of L when they come to column c (one wave: its LDS operations complete in program order, so a
+        // read sees an earlier write without a barrier).  The steps in the order of DIAG_STEPS, operands requested
+        // two steps ahead.  Inside the 4 x 4 corner the few values from other lanes' registers are fetched with
+        // lane reads.  Lanes above the diagonal (r < c) compute values nobody uses.  Every entry takes its terms in
+        // ascending k.
         if (r < 64) {
-        float x[NBMAX], t[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        f32x4 sr[NBMAX / 4], q[3][4], ql[4];
+        float x[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 sr[NBLK], q[3][4], ql[4];
 #pragma unroll
-        for (int i = 0; i < NBMAX / 4; ++i) sr[i] = *(const f32x4 *)&T[r][4 * i];
-        auto request = [&](int b, int k4, int slot) __attribute__((always_inline)) {
+        for (int i = 0; i < NBLK; ++i) sr[i] = *(const f32x4 *)&T[r][4 * i];
+        auto request = [&](int i) __attribute__((always_inline)) {              // operands of queued step i
+            if (DIAG_STEPS.b[i] >= 0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&T[4 * b + j][4 * k4];
+                for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&T[4 * DIAG_STEPS.b[i] + j][4 * DIAG_STEPS.k[i]];
+            }
+        };
+        auto step = [&](float(&acc)[4], int i) __attribute__((always_inline)) {  // queued step i: 16 multiply-adds
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(-x[4 * DIAG_STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
         };
         auto lane_value = [](float v, int l) __attribute__((always_inline)) {
             return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
         };
-        int cnt = 0;
 #pragma unroll
-        for (int b = 0; b < NBMAX / 4; ++b) {
+        for (int j = 0; j < 4; ++j) t[j] = sr[0][j];
+        int i = 0;                                                              // the next queued step
+        unrolled<NBLK>([&](auto block) __attribute__((always_inline)) {
+            constexpr int b = decltype(block)::value;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) t[j] = sr[b][j];
-#pragma unroll
-            for (int k4 = 0; k4 + 2 <= b; ++k4) {
-                int nb2 = b, nk = k4 + 2;                 // the step after next in the list (b, k4 <= b - 2), b = 2, 3, ..
-                if (nk > nb2 - 2) { nk -= nb2 - 1; ++nb2; }
-                if (nk > nb2 - 2) { nk -= nb2 - 1; ++nb2; }
-                if (nb2 < NBMAX / 4) request(nb2, nk, (cnt + 2) % 3);
+            for (int k4 = early_d(b); k4 + 2 <= b; ++k4) {                      // in turn
+                request(i + 2);
                 __builtin_amdgcn_sched_barrier(0);
-                const int slot = cnt % 3;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * k4 + kk], q[slot][j][kk], t[j]);
-                ++cnt;
+                step(t, i);
+                ++i;
             }
-            if (b >= 1) {
+            if (b >= 1) {                                                       // the block's last step, requested on its own
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
                     for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * (b - 1) + kk], ql[j][kk], t[j]);
             }
+            if (b + 1 < NBLK) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) tn[j] = sr[b + 1][j];
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int c = 4 * b + j;
+                const int now = beside_column(b, j);                            // steps of the next block to run beside this column
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < j; ++i) t[j] = __builtin_fmaf(-x[4 * b + i], lane_value(x[4 * b + i], c), t[j]);
+                for (int e = 0; e < j; ++e) t[j] = __builtin_fmaf(-x[4 * b + e], lane_value(x[4 * b + e], c), t[j]);
                 const float d = lane_value(__builtin_sqrtf(t[j]), c);
                 x[c] = r == c ? d : t[j] / d;
+#pragma unroll
+                for (int u = 0; u < PER_COLUMN; ++u)
+                    if (u < now) {
+                        request(i + 2);                                         // (three queue slots: steps i, i + 1 pending)
+                        step(tn, i);
+                        ++i;
+                    }
             }
             f32x4 done;
 #pragma unroll
             for (int j = 0; j < 4; ++j) done[j] = x[4 * b + j];
             *(f32x4 *)&T[r][4 * b] = done;
-            if (b + 1 < NBMAX / 4) {
+            if (b + 1 < NBLK) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) ql[j] = *(const f32x4 *)&T[4 * (b + 1) + j][4 * b];
             }
             if (b == 0) {
-                request(2, 0, 0);
-                request(3, 0, 1);
+                request(0);
+                request(1);
             }
-        }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) t[j] = tn[j];
+        });
         // the mirror image into the upper part of the tile (Lh holds both triangles): entry (c, r) for c < r
 #pragma unroll
         for (int c = 0; c < NBMAX - 1; ++c)

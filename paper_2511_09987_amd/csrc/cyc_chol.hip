@@ -381,7 +381,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
         // lane reads.  Lanes above the diagonal (r < c) compute values nobody uses.  Every entry takes its terms in
         // ascending k.
         if (r < 64) {
-        float x[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float x[NBMAX], xn[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};      // xn = -x, see chol_panel_kernel
         f32x4 sr[NBLK], q[3][4], ql[4];
 #pragma unroll
         for (int i = 0; i < NBLK; ++i) sr[i] = *(const f32x4 *)&T[r][4 * i];
@@ -395,7 +395,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(-x[4 * DIAG_STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
+                for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(xn[4 * DIAG_STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
         };
         auto lane_value = [](float v, int l) __attribute__((always_inline)) {
             return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
@@ -416,7 +416,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(-x[4 * (b - 1) + kk], ql[j][kk], t[j]);
+                    for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(xn[4 * (b - 1) + kk], ql[j][kk], t[j]);
             }
             if (b + 1 < NBLK) {
 #pragma unroll
@@ -428,9 +428,11 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
                 const int now = beside_column(b, j);                            // steps of the next block to run beside this column
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int e = 0; e < j; ++e) t[j] = __builtin_fmaf(-x[4 * b + e], lane_value(x[4 * b + e], c), t[j]);
+                for (int e = 0; e < j; ++e) t[j] = __builtin_fmaf(xn[4 * b + e], lane_value(x[4 * b + e], c), t[j]);
                 const float d = lane_value(__builtin_sqrtf(t[j]), c);
                 x[c] = r == c ? d : t[j] / d;
+                xn[c] = -x[c];
+                asm("" : "+v"(xn[c]));                                          // (or the negation is folded back into the multiply-adds)
 #pragma unroll
                 for (int u = 0; u < PER_COLUMN; ++u)
                     if (u < now) {
@@ -519,7 +521,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
         // The lane's row of S and of L in registers (constant indices after unrolling); the steps of StepList, the
         // rows of L_jj for a step requested from LDS two steps before it runs, since a lone wave has nobody else to
         // hide the LDS latency behind.
-        float x[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float x[NBMAX], xn[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         f32x4 sr[NBLK], q[3][4], qc[2][4];
 #pragma unroll
         for (int i = 0; i < NBLK; ++i) sr[i] = *(const f32x4 *)&X[lane][4 * i];
@@ -529,9 +531,10 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
                 for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&D[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
             }
         };
+        // (xn = -x: a multiply-add without a negated operand has a 4-byte encoding, which a lone wave issues faster)
         auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {   // a quarter of bulk step i
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(-x[4 * STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
+            for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(xn[4 * STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
         };
         request(0);
         request(1);
@@ -564,7 +567,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
                 if (paired) request(i + 2);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int c = 0; c < j; ++c) t[j] = __builtin_fmaf(-x[4 * b + c], qc[b & 1][j][c], t[j]);
+                for (int c = 0; c < j; ++c) t[j] = __builtin_fmaf(xn[4 * b + c], qc[b & 1][j][c], t[j]);
                 Division dv;
                 dv.phase0(t[j], qc[b & 1][j][j]);
                 __builtin_amdgcn_sched_barrier(0);
@@ -579,6 +582,8 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
                 if (paired) quarter(tn, i, 2);
                 __builtin_amdgcn_sched_barrier(0);
                 x[4 * b + j] = dv.phase3();
+                xn[4 * b + j] = -x[4 * b + j];
+                asm("" : "+v"(xn[4 * b + j]));                                  // (or the negation is folded back into the multiply-adds)
                 __builtin_amdgcn_sched_barrier(0);
                 if (paired) {
                     quarter(tn, i, 3);

@@ -304,8 +304,8 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
         // one after the other.  Every x still takes its terms in ascending j.  The work is a fixed list of steps
         // (block b: b steps of four j each, then the corner); the rows of L_tt for a step are requested from LDS
         // two steps before it runs, since a lone wave has nobody else to hide the LDS latency behind.
-        float tt[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        f32x4 q[3][4];
+        float xn[NB], tt[4] = {0.0f, 0.0f, 0.0f, 0.0f};         // xn = -x: a multiply-add without a negated operand has a
+        f32x4 q[3][4];                                          // 4-byte encoding, which a lone wave issues faster
         auto rows_of_L = [&](int b, int k4, int slot) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&D[4 * b + j][4 * k4];
@@ -330,14 +330,16 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
 #pragma unroll
                     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) tt[j] = __builtin_fmaf(-q[slot][j][kk], x[4 * k4 + kk], tt[j]);
+                        for (int j = 0; j < 4; ++j) tt[j] = __builtin_fmaf(q[slot][j][kk], xn[4 * k4 + kk], tt[j]);
                 } else {
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const int r = 4 * b + j;
 #pragma unroll
-                        for (int i = 0; i < j; ++i) tt[j] = __builtin_fmaf(-q[slot][j][i], x[4 * b + i], tt[j]);
+                        for (int i = 0; i < j; ++i) tt[j] = __builtin_fmaf(q[slot][j][i], xn[4 * b + i], tt[j]);
                         x[r] = tt[j] / q[slot][j][j];
+                        xn[r] = -x[r];
+                        asm("" : "+v"(xn[r]));                  // (or the negation is folded back into the multiply-adds)
                         Xb[t * NB + r][lane] = round_bf16(x[r]);
                     }
                 }

@@ -19,6 +19,7 @@
 // subtracted from B changes (fp32 rounding); where X is rounded to bfloat16 does not: after
 // every tile of nb rows.
 #include "cyc_internal.h"
+#include "cyc_wave.h"
 
 namespace cyc {
 namespace {
@@ -291,75 +292,101 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
                     for (int r = 0; r < 4; ++r) G[i * 16 + 4 * g + r][j * 16 + lq] = acc[i][j][r];
         }
         __syncthreads();                                        // D and G are in place
-        float(&x)[NB] = rhs[t & 1];                             // the lane's column: R_r until row r is solved, x_r from then on
+        float(&x)[NB] = rhs[t & 1];                             // the lane's column: R_r until row r is solved (then xn[r] = -x_r)
         if (t > 0) {
 #pragma unroll
             for (int r = 0; r < NB; ++r) x[r] -= G[r][lane];
         }
 
         // ---- diag-space: the chains of tri_diag_kernel for a full tile, with the lane's column of x in registers
-        // (constant indices after unrolling).  Four rows at a time: their chains over the rows above the four are
-        // independent of one another and run side by side (in a lone wave a multiply-add that waits for the one
-        // before it issues every ~8 cycles, an independent one every ~5); then the 4 x 4 corner finishes the four
-        // one after the other.  Every x still takes its terms in ascending j.  The work is a fixed list of steps
-        // (block b: b steps of four j each, then the corner); the rows of L_tt for a step are requested from LDS
-        // two steps before it runs, since a lone wave has nobody else to hide the LDS latency behind.
-        float xn[NB], tt[4] = {0.0f, 0.0f, 0.0f, 0.0f};         // xn = -x: a multiply-add without a negated operand has a
-        f32x4 q[3][4];                                          // 4-byte encoding, which a lone wave issues faster
-        auto rows_of_L = [&](int b, int k4, int slot) __attribute__((always_inline)) {
+        // (constant indices after unrolling), as the list of steps of cyc_wave.h: four rows at a time, their chains
+        // over the rows above the four side by side, then the 4 x 4 corner, whose divisions run in phases with
+        // steps of the next four rows between them.  Every x still takes its terms in ascending j.  The rows of L_tt
+        // for a step are requested from LDS two steps before it runs, since a lone wave has nobody else to hide the
+        // LDS latency behind.
+        float xn[NB], tt[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // xn = -x: a multiply-add without a negated operand has a
+        f32x4 q[3][4], qc[2][4];                                // 4-byte encoding, which a lone wave issues faster
+        auto rows_of_L = [&](int i) __attribute__((always_inline)) {            // operands of bulk step i
+            if (STEPS.b[i] >= 0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) q[slot][j] = *(const f32x4 *)&D[4 * b + j][4 * k4];
-        };
-        rows_of_L(0, 0, 0);
-        rows_of_L(1, 0, 1);
-        int cnt = 0;
-        auto block = [&](int b) __attribute__((always_inline)) {
-#pragma unroll
-            for (int k4 = 0; k4 <= b; ++k4) {
-                int nb2 = b, nk = k4 + 2;                       // the step after next
-                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
-                if (nk > nb2) { nk -= nb2 + 1; ++nb2; }
-                if (nb2 < NB / 4) rows_of_L(nb2, nk, (cnt + 2) % 3);
-                __builtin_amdgcn_sched_barrier(0);
-                const int slot = cnt % 3;
-                if (k4 == 0) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) tt[j] = x[4 * b + j];
-                }
-                if (k4 < b) {
-#pragma unroll
-                    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) tt[j] = __builtin_fmaf(q[slot][j][kk], xn[4 * k4 + kk], tt[j]);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const int r = 4 * b + j;
-#pragma unroll
-                        for (int i = 0; i < j; ++i) tt[j] = __builtin_fmaf(q[slot][j][i], xn[4 * b + i], tt[j]);
-                        x[r] = tt[j] / q[slot][j][j];
-                        xn[r] = -x[r];
-                        asm("" : "+v"(xn[r]));                  // (or the negation is folded back into the multiply-adds)
-                        Xb[t * NB + r][lane] = round_bf16(x[r]);
-                    }
-                }
-                ++cnt;
+                for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&D[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
             }
         };
+        auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {   // a quarter of bulk step i
 #pragma unroll
-        for (int b = 0; b < NB / 4 - 4; ++b) block(b);
+            for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(q[i % 3][j][kk], xn[4 * STEPS.k[i] + kk], acc[j]);
+        };
+        rows_of_L(0);
+        rows_of_L(1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            qc[0][j] = *(const f32x4 *)&D[j][0];
+            tt[j] = x[j];
+        }
+        int i = 0;                                                              // the next bulk step
+        auto block = [&](auto index) __attribute__((always_inline)) {
+            constexpr int b = decltype(index)::value;
+#pragma unroll
+            for (int s = early_of(b); s < b; ++s) {                             // the block's bulk steps taken in turn
+                rows_of_L(i + 2);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) quarter(tt, i, kk);
+                ++i;
+            }
+            if (b + 1 < NBLK) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    qc[(b + 1) & 1][j] = *(const f32x4 *)&D[4 * (b + 1) + j][4 * (b + 1)];
+                    tn[j] = x[4 * (b + 1) + j];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {                                       // the corner, row by row
+                const int r = 4 * b + j;
+                const bool paired = b + 1 < NBLK && j < early_of(b + 1);
+                if (paired) rows_of_L(i + 2);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < j; ++e) tt[j] = __builtin_fmaf(qc[b & 1][j][e], xn[4 * b + e], tt[j]);
+                Division dv;
+                dv.phase0(tt[j], qc[b & 1][j][j]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) quarter(tn, i, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                dv.phase1();
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) quarter(tn, i, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                dv.phase2();
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) quarter(tn, i, 2);
+                __builtin_amdgcn_sched_barrier(0);
+                const float xr = dv.phase3();
+                xn[r] = -xr;
+                asm("" : "+v"(xn[r]));                                          // (or the negation is folded back into the multiply-adds)
+                Xb[t * NB + r][lane] = round_bf16(xr);
+                __builtin_amdgcn_sched_barrier(0);
+                if (paired) {
+                    quarter(tn, i, 3);
+                    ++i;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tt[j] = tn[j];
+        };
+        unrolled<NBLK - 4>(block);
         // the next tile's operands: late enough to keep the registers free for most of the solve, early enough to
         // land before it ends (the last four blocks are 58 of the 136 steps)
         if (t + 1 < tiles) request(t + 1);
-#pragma unroll
-        for (int b = NB / 4 - 4; b < NB / 4; ++b) block(b);
+        unrolled<4>([&](auto index) __attribute__((always_inline)) { block(std::integral_constant<int, NBLK - 4 + decltype(index)::value>{}); });
         // the tile's results go out in one batch: a store under the lane condition inside the chains would cut them
         // into basic blocks, and the chains of a block would then be moved apart, each to its own division
         if (live) {
 #pragma unroll
             for (int r = 0; r < NB; ++r) {                      // uniform row address, 32-bit lane offset
-                (X + (rt + r) * nrhs + c0)[cl] = x[r];
-                (Xh + (rt + r) * nrhs + c0)[cl] = round_bf16(x[r]);
+                (X + (rt + r) * nrhs + c0)[cl] = -xn[r];
+                (Xh + (rt + r) * nrhs + c0)[cl] = round_bf16(-xn[r]);
             }
         }
         __syncthreads();                                        // Xb of this tile visible; D and G free for the next

@@ -13,13 +13,14 @@
 // Lh[k0:k1, c0:c1].  Panels are taken in groups of eight (see launch_chol):
 //   1. at the first panel of a group, one launch of the GEMM kernel takes all tiles left of the group out of the
 //      group's columns: epilogue A - product into L[g0:, g0:g0+512], which holds S until solved;
-//   2. per panel, CHOL of the diagonal tile: one wave, one lane per row, columns left to right, what a lane needs
-//      of other rows read from those lanes' registers;
+//   2. per panel, CHOL of the diagonal tile: one lane per row, columns left to right, what a lane needs of other
+//      rows read from the tile in LDS, where every lane writes its finished columns;
 //   3. per panel, TRSM of the rows below: rows do not depend on one another, so one lane per row (64 rows per
 //      workgroup) runs the off-diagonal line of the scalar recurrence against L_jj in LDS, and writes its row of
 //      L, of Lh, and the mirrored column of Lh.
-//   Both tile kernels first take the terms of the group's own earlier panels out of their 64 x 64 tile with MFMAs of
-//   their own (tile_product), which is far cheaper than a launch of the GEMM kernel for so short a k range.
+//   Both tile kernels are workgroups of four waves: all four move the tile and first take the terms of the group's
+//   own earlier panels out of it with MFMAs of their own (TileProduct), which is far cheaper than a launch of the
+//   GEMM kernel for so short a k range; the first wave then runs the recurrence.
 // Inside a tile column everything is fp32 on unrounded values, in the order of the scalar recurrence:
 // t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
 #include "cyc_internal.h"

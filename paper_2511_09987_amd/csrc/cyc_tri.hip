@@ -180,6 +180,96 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
 
+// The diagonal solve of one full tile of 64 rows by one wave, one lane per right-hand side, with the lane's column
+// in registers (constant indices after unrolling): x[r] holds R_r on entry; xn[r] = -x_r on return (a multiply-add
+// without a negated operand has a 4-byte encoding, which a lone wave issues faster).  The chains of tri_diag_kernel as
+// the list of steps of cyc_wave.h: four rows at a time, their chains over the rows above the four side by side, then
+// the 4 x 4 corner, whose divisions run in phases with steps of the next four rows between them.  Every x still takes
+// its terms in ascending j.  The rows of L_tt (D, fp32, row-major in LDS) for a step are requested two steps before
+// it runs, since a lone wave has nobody else to hide the LDS latency behind.  emit(r, x_r) is called once per row, in
+// order, without conditions on the lane (a branch there would cut the chains into basic blocks, and they would be
+// moved apart, each to its own division); middle() is called once, before the last four blocks.
+template <int LDD, class Emit, class Middle>
+__device__ __forceinline__ void solve_tile64(const float (*D)[LDD], const float (&x)[64], float (&xn)[64], Emit emit, Middle middle)
+{
+    constexpr int NB = 64;
+    static_assert(NBLK * 4 == NB, "the step list is for tiles of 64 rows");
+    float tt[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 q[3][4], qc[2][4];
+    auto rows_of_L = [&](int i) __attribute__((always_inline)) {            // operands of bulk step i
+        if (STEPS.b[i] >= 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&D[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
+        }
+    };
+    auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {   // a quarter of bulk step i
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(q[i % 3][j][kk], xn[4 * STEPS.k[i] + kk], acc[j]);
+    };
+    rows_of_L(0);
+    rows_of_L(1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        qc[0][j] = *(const f32x4 *)&D[j][0];
+        tt[j] = x[j];
+    }
+    int i = 0;                                                              // the next bulk step
+    auto block = [&](auto index) __attribute__((always_inline)) {
+        constexpr int b = decltype(index)::value;
+#pragma unroll
+        for (int s = early_of(b); s < b; ++s) {                             // the block's bulk steps taken in turn
+            rows_of_L(i + 2);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) quarter(tt, i, kk);
+            ++i;
+        }
+        if (b + 1 < NBLK) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                qc[(b + 1) & 1][j] = *(const f32x4 *)&D[4 * (b + 1) + j][4 * (b + 1)];
+                tn[j] = x[4 * (b + 1) + j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {                                       // the corner, row by row
+            const int r = 4 * b + j;
+            const bool paired = b + 1 < NBLK && j < early_of(b + 1);
+            if (paired) rows_of_L(i + 2);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < j; ++e) tt[j] = __builtin_fmaf(qc[b & 1][j][e], xn[4 * b + e], tt[j]);
+            Division dv;
+            dv.phase0(tt[j], qc[b & 1][j][j]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) quarter(tn, i, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            dv.phase1();
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) quarter(tn, i, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            dv.phase2();
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) quarter(tn, i, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            const float xr = dv.phase3();
+            xn[r] = -xr;
+            asm("" : "+v"(xn[r]));                                          // (or the negation is folded back into the multiply-adds)
+            emit(r, xr);
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) {
+                quarter(tn, i, 3);
+                ++i;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tt[j] = tn[j];
+    };
+    unrolled<NBLK - 4>(block);
+    middle();                                                               // (the last four blocks are 58 of the 136 steps)
+    unrolled<4>([&](auto index) __attribute__((always_inline)) { block(std::integral_constant<int, NBLK - 4 + decltype(index)::value>{}); });
+}
+
 // A panel of up to four full tiles of 64 rows for one slab of 64 right-hand sides, in one kernel:
 //     for t = 0 .. tiles-1:   R_t = Rin_t - L[t, 0:t] * Xh[0:t]  (tri-space, inside the panel)
 //                             X_t = TRSM(L_tt, R_t)              (diag-space)
@@ -298,88 +388,13 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
             for (int r = 0; r < NB; ++r) x[r] -= G[r][lane];
         }
 
-        // ---- diag-space: the chains of tri_diag_kernel for a full tile, with the lane's column of x in registers
-        // (constant indices after unrolling), as the list of steps of cyc_wave.h: four rows at a time, their chains
-        // over the rows above the four side by side, then the 4 x 4 corner, whose divisions run in phases with
-        // steps of the next four rows between them.  Every x still takes its terms in ascending j.  The rows of L_tt
-        // for a step are requested from LDS two steps before it runs, since a lone wave has nobody else to hide the
-        // LDS latency behind.
-        float xn[NB], tt[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // xn = -x: a multiply-add without a negated operand has a
-        f32x4 q[3][4], qc[2][4];                                // 4-byte encoding, which a lone wave issues faster
-        auto rows_of_L = [&](int i) __attribute__((always_inline)) {            // operands of bulk step i
-            if (STEPS.b[i] >= 0) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&D[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
-            }
-        };
-        auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {   // a quarter of bulk step i
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(q[i % 3][j][kk], xn[4 * STEPS.k[i] + kk], acc[j]);
-        };
-        rows_of_L(0);
-        rows_of_L(1);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            qc[0][j] = *(const f32x4 *)&D[j][0];
-            tt[j] = x[j];
-        }
-        int i = 0;                                                              // the next bulk step
-        auto block = [&](auto index) __attribute__((always_inline)) {
-            constexpr int b = decltype(index)::value;
-#pragma unroll
-            for (int s = early_of(b); s < b; ++s) {                             // the block's bulk steps taken in turn
-                rows_of_L(i + 2);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) quarter(tt, i, kk);
-                ++i;
-            }
-            if (b + 1 < NBLK) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    qc[(b + 1) & 1][j] = *(const f32x4 *)&D[4 * (b + 1) + j][4 * (b + 1)];
-                    tn[j] = x[4 * (b + 1) + j];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {                                       // the corner, row by row
-                const int r = 4 * b + j;
-                const bool paired = b + 1 < NBLK && j < early_of(b + 1);
-                if (paired) rows_of_L(i + 2);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int e = 0; e < j; ++e) tt[j] = __builtin_fmaf(qc[b & 1][j][e], xn[4 * b + e], tt[j]);
-                Division dv;
-                dv.phase0(tt[j], qc[b & 1][j][j]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (paired) quarter(tn, i, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                dv.phase1();
-                __builtin_amdgcn_sched_barrier(0);
-                if (paired) quarter(tn, i, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                dv.phase2();
-                __builtin_amdgcn_sched_barrier(0);
-                if (paired) quarter(tn, i, 2);
-                __builtin_amdgcn_sched_barrier(0);
-                const float xr = dv.phase3();
-                xn[r] = -xr;
-                asm("" : "+v"(xn[r]));                                          // (or the negation is folded back into the multiply-adds)
-                Xb[t * NB + r][lane] = round_bf16(xr);
-                __builtin_amdgcn_sched_barrier(0);
-                if (paired) {
-                    quarter(tn, i, 3);
-                    ++i;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) tt[j] = tn[j];
-        };
-        unrolled<NBLK - 4>(block);
-        // the next tile's operands: late enough to keep the registers free for most of the solve, early enough to
-        // land before it ends (the last four blocks are 58 of the 136 steps)
-        if (t + 1 < tiles) request(t + 1);
-        unrolled<4>([&](auto index) __attribute__((always_inline)) { block(std::integral_constant<int, NBLK - 4 + decltype(index)::value>{}); });
+        // ---- diag-space
+        float xn[NB];
+        solve_tile64<LDD>(
+            D, x, xn, [&](int r, float xr) __attribute__((always_inline)) { Xb[t * NB + r][lane] = round_bf16(xr); },
+            // the next tile's operands: late enough to keep the registers free for most of the solve, early enough to
+            // land before it ends
+            [&]() __attribute__((always_inline)) { if (t + 1 < tiles) request(t + 1); });
         // the tile's results go out in one batch: a store under the lane condition inside the chains would cut them
         // into basic blocks, and the chains of a block would then be moved apart, each to its own division
         if (live) {
@@ -391,6 +406,167 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
         }
         __syncthreads();                                        // Xb of this tile visible; D and G free for the next
     }
+}
+
+// The same panel with four waves per slab of 64 right-hand sides.  In tri_panel_kernel the one wave also stages L_tt,
+// multiplies out the panel's own product and stores the results, a fifth of its time; here the first wave only solves
+// (solve_tile64, tile after tile) and the other three work around it: while tile t is being solved they store the
+// results of tile t - 1 (16-byte stores from LDS), fetch and widen L_{t+1,t+1}, fetch the right-hand side of tile
+// t + 1 in the accumulator layout and take the panel's tiles 0 .. t - 1 out of it (MFMAs, as above); when the solver
+// has finished tile t they add the k range of that tile and hand the result over in LDS.  Two barriers per tile, D, R
+// and Xs double buffered, so nobody waits except the solver for that last k range (16 MFMAs).  The sums are the
+// ones of tri_panel_kernel in the same order.  Requires, on top of tri_panel_kernel's conditions, nrhs a multiple of
+// 8 and 16-byte aligned X and Xh (whole 16-byte pieces of a row are stored or skipped).
+constexpr int PT = 256;
+__global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
+                                                        float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
+                                                        int tiles)
+{
+    constexpr int NB = 64, LDD = NB + 4, NH = PT - 64;                 // NH threads beside the solver
+    // D first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one base register
+    __shared__ __attribute__((aligned(16))) struct {
+        float D[2][NB][LDD];               // L_tt in fp32, row-major, on and below the diagonal
+        float R[2][NB][LDD];               // right-hand side of the tile with the panel's product taken out, [row][column]
+        float Xs[2][NB][LDD];              // the tile's solution, [row][column]
+        uint16_t Xb[4 * NB][64];           // solved tiles as bfloat16, [k][column]
+    } lds;
+    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // uniform: the two branches below hold barriers
+    const int64_t c0 = (int64_t)blockIdx.x * 64;
+
+    if (wave == 0) {
+        __syncthreads();                                               // tile 0 is staged
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (t >= tiles) break;
+            float x[NB], xn[NB];
+#pragma unroll
+            for (int r = 0; r < NB; ++r) x[r] = lds.R[t & 1][r][lane];
+            solve_tile64<LDD>(
+                lds.D[t & 1], x, xn,
+                [&](int r, float xr) __attribute__((always_inline)) {
+                    lds.Xb[t * NB + r][lane] = round_bf16(xr);
+                    lds.Xs[t & 1][r][lane] = xr;
+                },
+                []() __attribute__((always_inline)) {});
+            __syncthreads();                                           // tile t is solved
+            if (t + 1 < tiles) __syncthreads();                        // tile t + 1 is staged
+        }
+        return;
+    }
+
+    const int ht = tid - 64;
+    // results of tile v: 16-byte pieces from LDS to X and Xh (plain loops: these waves have time to spare)
+    auto store = [&](int v) __attribute__((always_inline)) {
+        const int64_t rv = r0 + (int64_t)v * NB;
+        for (int id = ht; id < NB * 16; id += NH) {
+            const int r = id >> 4, ch = id & 15;
+            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = *(const f32x4 *)&lds.Xs[v & 1][r][4 * ch];
+        }
+        for (int id = ht; id < NB * 8; id += NH) {
+            const int r = id >> 3, ch = id & 7;
+            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * ch];
+        }
+    };
+    // rows of the tile a helper wave prepares: 16-row strips wave - 1 and wave + 2 (the first helper takes two)
+    auto strip = [&](int si) __attribute__((always_inline)) { return wave - 1 + 3 * si; };
+
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {                                      // prepare tile u; unrolled: u is a constant in every copy
+        if (u >= tiles) break;
+        if (u >= 2) store(u - 2);                                      // (tile u - 2: solved before the last barrier but one)
+        const int64_t ru = r0 + (int64_t)u * NB;
+        // ---- requests: L_uu, the right-hand side in the accumulator layout, the rows of L for the product
+        constexpr int cpr = NB / 8, PP = (NB * cpr + NH - 1) / NH;
+        uint4 piece[PP];
+#pragma unroll
+        for (int p = 0; p < PP; ++p) {
+            const int id = ht + NH * p, r = id / cpr, jc = id % cpr;
+            piece[p] = make_uint4(0, 0, 0, 0);
+            if (id < NB * cpr && jc * 8 <= r) piece[p] = *(const uint4 *)(L + (ru + r) * n + ru + jc * 8);
+        }
+        float rhs[2][4][4];
+        i32x4 a[2][6];
+#pragma unroll
+        for (int si = 0; si < 2; ++si) {
+            const int i = strip(si);
+            if (i < 4) {                                               // uniform over the wave
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) rhs[si][j][r] = Rin[(ru + 16 * i + 4 * g + r) * nrhs + col];
+                }
+#pragma unroll
+                for (int ks = 0; ks < 6; ++ks)
+                    if (ks < 2 * u) a[si][ks] = *(const i32x4 *)(L + (ru + 16 * i + lq) * n + r0 + ks * 32 + g * 8);
+            }
+        }
+        // ---- stage L_uu
+#pragma unroll
+        for (int p = 0; p < PP; ++p) {
+            const int id = ht + NH * p, r = id / cpr, jc = id % cpr;
+            if (id < NB * cpr && jc * 8 <= r) {
+                const uint32_t w[4] = {piece[p].x, piece[p].y, piece[p].z, piece[p].w};
+                f32x4 lo, hi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    lo[e] = widen_bf16((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
+                    hi[e] = widen_bf16((uint16_t)(w[2 + (e >> 1)] >> (16 * (e & 1))));
+                }
+                *(f32x4 *)&lds.D[u & 1][r][jc * 8] = lo;
+                *(f32x4 *)&lds.D[u & 1][r][jc * 8 + 4] = hi;
+            }
+        }
+        // ---- the panel's product for the rows of tile u: k-steps of 32 over the tiles 0 .. u - 1
+        f32x4 acc[2][4];
+#pragma unroll
+        for (int si = 0; si < 2; ++si)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[si][j] = (f32x4){0, 0, 0, 0};
+        auto k_step = [&](int ks) __attribute__((always_inline)) {
+            i32x4 b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+                b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+            }
+#pragma unroll
+            for (int si = 0; si < 2; ++si)
+                if (strip(si) < 4) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[si][ks]), __builtin_bit_cast(bf16x8, b[j]), acc[si][j], 0, 0, 0);
+                }
+        };
+#pragma unroll
+        for (int ks = 0; ks < 6; ++ks)
+            if (ks + 2 < 2 * u) k_step(ks);                            // the tiles solved before the last barrier
+        if (u >= 1) {
+            __syncthreads();                                           // tile u - 1 is solved
+#pragma unroll
+            for (int ks = 0; ks < 6; ++ks)
+                if (ks + 2 >= 2 * u && ks < 2 * u) k_step(ks);
+        }
+        // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
+#pragma unroll
+        for (int si = 0; si < 2; ++si) {
+            const int i = strip(si);
+            if (i < 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) lds.R[u & 1][16 * i + 4 * g + r][16 * j + lq] = rhs[si][j][r] - acc[si][j][r];
+            }
+        }
+        __syncthreads();                                               // tile u is staged
+    }
+    // the last tile but one while the last is being solved; the last after the barrier that ends its solve
+    if (tiles >= 2) store(tiles - 2);
+    __syncthreads();
+    store(tiles - 1);
 }
 
 struct Solve {
@@ -451,6 +627,11 @@ bool panel_ok(const Solve &v, int64_t r0, int64_t r1)
 hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
 {
     dim3 grid((unsigned)((v.nrhs + 63) / 64));
+    if (v.nrhs % 8 == 0 && (uintptr_t)v.X % 16 == 0 && (uintptr_t)v.Xh % 16 == 0) {
+        hipLaunchKernelGGL(tri_panel4_kernel, grid, dim3(PT), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0,
+                           (int)((r1 - r0) / 64));
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(tri_panel_kernel, grid, dim3(64), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0,
                        (int)((r1 - r0) / 64));
     return hipGetLastError();

@@ -413,11 +413,13 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
 // (solve_tile64, tile after tile) and the other three work around it: while tile t is being solved they store the
 // results of tile t - 1 (16-byte stores from LDS), fetch and widen L_{t+1,t+1}, fetch the right-hand side of tile
 // t + 1 in the accumulator layout and take the panel's tiles 0 .. t - 1 out of it (MFMAs, as above); when the solver
-// has finished tile t they add the k range of that tile and hand the result over in LDS.  Two barriers per tile, D, R
-// and Xs double buffered, so nobody waits except the solver for that last k range (16 MFMAs).  The sums are the
-// ones of tri_panel_kernel in the same order.  Requires, on top of tri_panel_kernel's conditions, nrhs a multiple of
-// 8 and 16-byte aligned X and Xh (whole 16-byte pieces of a row are stored or skipped).
-constexpr int PT = 256;
+// has finished tile t they add the k range of that tile and hand the result over in LDS.  Two barriers per tile, D and
+// Xs double buffered, so nobody waits except the solver for that last k range (16 MFMAs).  With the product off the
+// solver's path a panel can be longer: up to PANEL4 = 8 tiles (what LDS holds of solved tiles), which saves the
+// smallest GEMM launches of the recursion.  The sums are the ones of tri_panel_kernel in the same order.  Requires,
+// on top of tri_panel_kernel's conditions, nrhs a multiple of 8 and 16-byte aligned X and Xh (whole 16-byte pieces
+// of a row are stored or skipped).
+constexpr int PT = 256, PANEL4 = 8;
 __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                         float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
                                                         int tiles)
@@ -426,9 +428,9 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
     // D first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one base register
     __shared__ __attribute__((aligned(16))) struct {
         float D[2][NB][LDD];               // L_tt in fp32, row-major, on and below the diagonal
-        float R[2][NB][LDD];               // right-hand side of the tile with the panel's product taken out, [row][column]
+        float R[NB][LDD];                  // right-hand side of the tile with the panel's product taken out, [row][column]
         float Xs[2][NB][LDD];              // the tile's solution, [row][column]
-        uint16_t Xb[4 * NB][64];           // solved tiles as bfloat16, [k][column]
+        uint16_t Xb[PANEL4 * NB][64];      // solved tiles as bfloat16, [k][column]
     } lds;
     const int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // uniform: the two branches below hold barriers
@@ -436,12 +438,11 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
 
     if (wave == 0) {
         __syncthreads();                                               // tile 0 is staged
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            if (t >= tiles) break;
+#pragma unroll 1
+        for (int t = 0; t < tiles; ++t) {                              // (not unrolled: t only moves LDS addresses)
             float x[NB], xn[NB];
 #pragma unroll
-            for (int r = 0; r < NB; ++r) x[r] = lds.R[t & 1][r][lane];
+            for (int r = 0; r < NB; ++r) x[r] = lds.R[r][lane];
             solve_tile64<LDD>(
                 lds.D[t & 1], x, xn,
                 [&](int r, float xr) __attribute__((always_inline)) {
@@ -472,7 +473,7 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
     auto strip = [&](int si) __attribute__((always_inline)) { return wave - 1 + 3 * si; };
 
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {                                      // prepare tile u; unrolled: u is a constant in every copy
+    for (int u = 0; u < PANEL4; ++u) {                                 // prepare tile u; unrolled: u is a constant in every copy
         if (u >= tiles) break;
         if (u >= 2) store(u - 2);                                      // (tile u - 2: solved before the last barrier but one)
         const int64_t ru = r0 + (int64_t)u * NB;
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
             if (id < NB * cpr && jc * 8 <= r) piece[p] = *(const uint4 *)(L + (ru + r) * n + ru + jc * 8);
         }
         float rhs[2][4][4];
-        i32x4 a[2][6];
+        i32x4 a[2][2 * PANEL4 - 2];
 #pragma unroll
         for (int si = 0; si < 2; ++si) {
             const int i = strip(si);
@@ -498,7 +499,7 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
                     for (int r = 0; r < 4; ++r) rhs[si][j][r] = Rin[(ru + 16 * i + 4 * g + r) * nrhs + col];
                 }
 #pragma unroll
-                for (int ks = 0; ks < 6; ++ks)
+                for (int ks = 0; ks < 2 * PANEL4 - 2; ++ks)
                     if (ks < 2 * u) a[si][ks] = *(const i32x4 *)(L + (ru + 16 * i + lq) * n + r0 + ks * 32 + g * 8);
             }
         }
@@ -542,12 +543,12 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
                 }
         };
 #pragma unroll
-        for (int ks = 0; ks < 6; ++ks)
+        for (int ks = 0; ks < 2 * PANEL4 - 2; ++ks)
             if (ks + 2 < 2 * u) k_step(ks);                            // the tiles solved before the last barrier
         if (u >= 1) {
             __syncthreads();                                           // tile u - 1 is solved
 #pragma unroll
-            for (int ks = 0; ks < 6; ++ks)
+            for (int ks = 0; ks < 2 * PANEL4 - 2; ++ks)
                 if (ks + 2 >= 2 * u && ks < 2 * u) k_step(ks);
         }
         // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
@@ -558,7 +559,7 @@ __global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restri
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) lds.R[u & 1][16 * i + 4 * g + r][16 * j + lq] = rhs[si][j][r] - acc[si][j][r];
+                    for (int r = 0; r < 4; ++r) lds.R[16 * i + 4 * g + r][16 * j + lq] = rhs[si][j][r] - acc[si][j][r];
             }
         }
         __syncthreads();                                               // tile u is staged
@@ -618,16 +619,21 @@ hipError_t update(const Solve &v, int64_t r0, int64_t mid, int64_t r1)
     return tile ? launch_mfma(p, tile, 16, v.s) : launch_generic(p, v.s);
 }
 
-// up to four full 64-row tiles with 16-byte aligned rows of L: one launch for the whole range
+// the four-wave panel kernel can be used: whole 16-byte pieces of the rows of X and Xh
+bool panel4_ok(const Solve &v) { return v.nrhs % 8 == 0 && (uintptr_t)v.X % 16 == 0 && (uintptr_t)v.Xh % 16 == 0; }
+
+// up to four (eight with the four-wave kernel) full 64-row tiles with 16-byte aligned rows of L: one launch for the
+// whole range
 bool panel_ok(const Solve &v, int64_t r0, int64_t r1)
 {
-    return v.nb == 64 && (r1 - r0) % 64 == 0 && r1 - r0 <= 256 && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0 && r0 % 8 == 0;
+    return v.nb == 64 && (r1 - r0) % 64 == 0 && r1 - r0 <= 64 * (panel4_ok(v) ? PANEL4 : 4) && (uintptr_t)v.L % 16 == 0 &&
+           v.n % 8 == 0 && r0 % 8 == 0;
 }
 
 hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
 {
     dim3 grid((unsigned)((v.nrhs + 63) / 64));
-    if (v.nrhs % 8 == 0 && (uintptr_t)v.X % 16 == 0 && (uintptr_t)v.Xh % 16 == 0) {
+    if (panel4_ok(v)) {
         hipLaunchKernelGGL(tri_panel4_kernel, grid, dim3(PT), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0,
                            (int)((r1 - r0) / 64));
         return hipGetLastError();

@@ -54,7 +54,10 @@ def integer_system(n, nrhs, seed, density=0.2, device=DEV):
 
 
 SHAPES = [(64, 64, 64), (256, 128, 64), (1000, 72, 64), (1024, 512, 128), (520, 200, 32), (1032, 264, 8),
-          (37, 5, 8), (130, 33, 16), (100, 40, 10), (1, 1, 64), (1, 70, 64), (200, 1, 64), (129, 64, 128)]
+          (37, 5, 8), (130, 33, 16), (100, 40, 10), (1, 1, 64), (1, 70, 64), (200, 1, 64), (129, 64, 128),
+          # panels of 5, 7, 8 tiles, 9 = 5 + 4 and 13 = 7 + 6 tiles in the four-wave kernel (nrhs a multiple of 8, the
+          # last slab partly filled); 3 and 6 tiles in the one-wave kernel (nrhs not a multiple of 8)
+          (320, 72, 64), (448, 136, 64), (512, 64, 64), (576, 80, 64), (832, 200, 64), (192, 70, 64), (384, 61, 64)]
 
 
 @pytest.mark.parametrize("n,nrhs,nb", SHAPES)
@@ -73,7 +76,8 @@ def skeel(L64):
     return float(np.max(np.sum(np.abs(Linv) @ np.abs(np.tril(L64)), axis=1)))
 
 
-@pytest.mark.parametrize("n,nrhs,nb", [(512, 256, 64), (1024, 512, 128), (300, 100, 32), (1000, 136, 64), (77, 19, 16)])
+@pytest.mark.parametrize("n,nrhs,nb", [(512, 256, 64), (1024, 512, 128), (300, 100, 32), (1000, 136, 64), (77, 19, 16),
+                                       (448, 72, 64), (576, 264, 64), (384, 70, 64)])
 def test_real_data_against_oracle(lib, tri, n, nrhs, nb):
     L = ws_inputs.tri_lower_bf16(n, 50 + n, 0, DEV, upper=float("nan"))     # NaN above the diagonal: never read
     B = ws_inputs.normal_f32((n, nrhs), 1.0, 50 + n, 1, DEV)

@@ -408,166 +408,236 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
     }
 }
 
-// The same panel with four waves per slab of 64 right-hand sides.  In tri_panel_kernel the one wave also stages L_tt,
-// multiplies out the panel's own product and stores the results, a fifth of its time; here the first wave only solves
-// (solve_tile64, tile after tile) and the other three work around it: while tile t is being solved they store the
-// results of tile t - 1 (16-byte stores from LDS), fetch and widen L_{t+1,t+1}, fetch the right-hand side of tile
-// t + 1 in the accumulator layout and take the panel's tiles 0 .. t - 1 out of it (MFMAs, as above); when the solver
-// has finished tile t they add the k range of that tile and hand the result over in LDS.  Two barriers per tile, D and
-// Xs double buffered, so nobody waits except the solver for that last k range (16 MFMAs).  With the product off the
-// solver's path a panel can be longer: up to PANEL4 = 8 tiles (what LDS holds of solved tiles), which saves the
-// smallest GEMM launches of the recursion.  The sums are the ones of tri_panel_kernel in the same order.  Requires,
-// on top of tri_panel_kernel's conditions, nrhs a multiple of 8 and 16-byte aligned X and Xh (whole 16-byte pieces
-// of a row are stored or skipped).
-constexpr int PT = 256, PANEL4 = 8;
-__global__ __launch_bounds__(PT) void tri_panel4_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
-                                                        float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
-                                                        int tiles)
+// The diagonal solve of one full tile of 64 rows by FOUR waves, all on the same 64 right-hand sides (lane = column).
+// One wave is bound by its instruction issue; the recurrence itself is shorter: row block s (four rows) needs the
+// blocks before it, but the 16 multiply-adds that carry x of block s - 1 into a later block do not wait for the
+// corners in between.  So the blocks are dealt out in turn (block b belongs to wave b mod 4, which keeps the running
+// right-hand side of its four blocks in registers) and the solve runs in 16 phases.  In phase s every wave waits for
+// x of block s - 1 and takes it out of its blocks from s on; the owner of block s does that block first, then solves
+// its 4 x 4 corner, writes x to LDS (through emit) and publishes the phase.  Every x receives its terms in ascending
+// j as in the one-wave form, so the bits are the same; the path per phase is hand-over, 16 multiply-adds, corner.
+// Hand-over is a counter in LDS: the owner stores base + s + 1 (release) after its x, the others poll it (acquire).
+// A wave's LDS operations complete in order, and a wave in phase s waits only for the phase before, which waits for
+// nothing later, so the waits end; they are bounded anyway (SPIN_LIMIT polls, then the wave goes on with whatever it
+// reads: wrong numbers instead of a hung GPU should this code ever be broken).
+// D: L_tt, fp32, row-major; R: the tile's right-hand side and Xs: its solution, both [row][column] in LDS;
+// emit(r, x_r), called by the owning wave, must write Xs[r][lane]; spare(q) is called by every wave after its q-th
+// corner (q = 0 .. 3), when it has time for other work.
+constexpr int SPIN_LIMIT = 1 << 20;
+template <int LDD, class Emit, class Spare>
+__device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const float (*R)[LDD], const float (*Xs)[LDD], int *ready,
+                                                   int base, int w, int lane, Emit emit, Spare spare)
 {
-    constexpr int NB = 64, LDD = NB + 4, NH = PT - 64;                 // NH threads beside the solver
-    // D first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one base register
-    __shared__ __attribute__((aligned(16))) struct {
-        float D[2][NB][LDD];               // L_tt in fp32, row-major, on and below the diagonal
-        float R[NB][LDD];                  // right-hand side of the tile with the panel's product taken out, [row][column]
-        float Xs[2][NB][LDD];              // the tile's solution, [row][column]
-        uint16_t Xb[PANEL4 * NB][64];      // solved tiles as bfloat16, [k][column]
-    } lds;
-    const int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);         // uniform: the two branches below hold barriers
-    const int64_t c0 = (int64_t)blockIdx.x * 64;
-
-    if (wave == 0) {
-        __syncthreads();                                               // tile 0 is staged
-#pragma unroll 1
-        for (int t = 0; t < tiles; ++t) {                              // (not unrolled: t only moves LDS addresses)
-            float x[NB], xn[NB];
+    const float(*Dw)[LDD] = D + 4 * w;                    // block w + 4 ob of the tile is rows Dw[16 ob .. 16 ob + 3]
+    float tt[4][4];                                       // running right-hand side of the wave's blocks: [ob][row in block]
 #pragma unroll
-            for (int r = 0; r < NB; ++r) x[r] = lds.R[r][lane];
-            solve_tile64<LDD>(
-                lds.D[t & 1], x, xn,
-                [&](int r, float xr) __attribute__((always_inline)) {
-                    lds.Xb[t * NB + r][lane] = round_bf16(xr);
-                    lds.Xs[t & 1][r][lane] = xr;
-                },
-                []() __attribute__((always_inline)) {});
-            __syncthreads();                                           // tile t is solved
-            if (t + 1 < tiles) __syncthreads();                        // tile t + 1 is staged
-        }
-        return;
-    }
-
-    const int ht = tid - 64;
-    // results of tile v: 16-byte pieces from LDS to X and Xh (plain loops: these waves have time to spare)
-    auto store = [&](int v) __attribute__((always_inline)) {
-        const int64_t rv = r0 + (int64_t)v * NB;
-        for (int id = ht; id < NB * 16; id += NH) {
-            const int r = id >> 4, ch = id & 15;
-            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = *(const f32x4 *)&lds.Xs[v & 1][r][4 * ch];
-        }
-        for (int id = ht; id < NB * 8; id += NH) {
-            const int r = id >> 3, ch = id & 7;
-            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * ch];
-        }
-    };
-    // rows of the tile a helper wave prepares: 16-row strips wave - 1 and wave + 2 (the first helper takes two)
-    auto strip = [&](int si) __attribute__((always_inline)) { return wave - 1 + 3 * si; };
-
+    for (int ob = 0; ob < 4; ++ob)
 #pragma unroll
-    for (int u = 0; u < PANEL4; ++u) {                                 // prepare tile u; unrolled: u is a constant in every copy
-        if (u >= tiles) break;
-        if (u >= 2) store(u - 2);                                      // (tile u - 2: solved before the last barrier but one)
-        const int64_t ru = r0 + (int64_t)u * NB;
-        // ---- requests: L_uu, the right-hand side in the accumulator layout, the rows of L for the product
-        constexpr int cpr = NB / 8, PP = (NB * cpr + NH - 1) / NH;
-        uint4 piece[PP];
+        for (int j = 0; j < 4; ++j) tt[ob][j] = R[4 * w + 16 * ob + j][lane];
+    // coefficients (they do not depend on x).  What the owner of a block needs on the path, the block's rows in the
+    // columns of the block before (own) and its corner (cc), is requested a phase ahead; the rest (cu, the rows of
+    // the wave's other blocks in the columns of block s - 1) in the phase itself, where there is time to wait
+    f32x4 own[4], ownn[4], cc[4], ccn[4];
 #pragma unroll
-        for (int p = 0; p < PP; ++p) {
-            const int id = ht + NH * p, r = id / cpr, jc = id % cpr;
-            piece[p] = make_uint4(0, 0, 0, 0);
-            if (id < NB * cpr && jc * 8 <= r) piece[p] = *(const uint4 *)(L + (ru + r) * n + ru + jc * 8);
-        }
-        float rhs[2][4][4];
-        i32x4 a[2][2 * PANEL4 - 2];
+    for (int j = 0; j < 4; ++j) cc[j] = own[j] = ownn[j] = ccn[j] = *(const f32x4 *)&D[j][0];
+    unrolled<NBLK>([&](auto index) __attribute__((always_inline)) {
+        constexpr int s = decltype(index)::value, so = s / 4, sw = s % 4;
+        if (s + 1 < NBLK && w == (s + 1) % 4) {           // uniform over the wave: the owner of the next block
 #pragma unroll
-        for (int si = 0; si < 2; ++si) {
-            const int i = strip(si);
-            if (i < 4) {                                               // uniform over the wave
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) rhs[si][j][r] = Rin[(ru + 16 * i + 4 * g + r) * nrhs + col];
-                }
-#pragma unroll
-                for (int ks = 0; ks < 2 * PANEL4 - 2; ++ks)
-                    if (ks < 2 * u) a[si][ks] = *(const i32x4 *)(L + (ru + 16 * i + lq) * n + r0 + ks * 32 + g * 8);
+            for (int j = 0; j < 4; ++j) {
+                ownn[j] = *(const f32x4 *)&D[4 * (s + 1) + j][4 * s];
+                ccn[j] = *(const f32x4 *)&D[4 * (s + 1) + j][4 * (s + 1)];
             }
         }
-        // ---- stage L_uu
+        __builtin_amdgcn_sched_barrier(0);
+        float xv[4] = {0.0f, 0.0f, 0.0f, 0.0f};           // -x of block s - 1
+        if (s >= 1) {
+            int polls = 0;
+            while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < base + s && ++polls < SPIN_LIMIT) {}
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xv[i] = -Xs[4 * (s - 1) + i][lane];
+        }
+        auto take_out = [&](float(&t4)[4], const f32x4(&c4)[4]) __attribute__((always_inline)) {   // x of block s - 1 out of a block
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t4[j] = __builtin_fmaf(c4[j][i], xv[i], t4[j]);
+        };
+        if (w == sw) {                                    // the owner of block s
+            if (s >= 1) take_out(tt[so], own);
+            float xneg[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                for (int e = 0; e < j; ++e) tt[so][j] = __builtin_fmaf(cc[j][e], xneg[e], tt[so][j]);
+                const float xr = tt[so][j] / cc[j][j];
+                xneg[j] = -xr;
+                emit(4 * s + j, xr);
+            }
+            __hip_atomic_store(ready, base + s + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            spare(so);                                    // its next corner is four phases away
+        }
+        if (s >= 1) {
+            // the wave's later blocks: block w + 4 ob for ob > so, and for ob = so if it comes after block s
+            f32x4 cu[4][4];
+#pragma unroll
+            for (int ob = so; ob < 4; ++ob)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) cu[ob][j] = *(const f32x4 *)&Dw[16 * ob + j][4 * (s - 1)];
+            if (w > sw) take_out(tt[so], cu[so]);
+#pragma unroll
+            for (int ob = so + 1; ob < 4; ++ob) take_out(tt[ob], cu[ob]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            own[j] = ownn[j];
+            cc[j] = ccn[j];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+}
+
+// The panel with the four waves of solve_tile64_waves.  All four work on the same slab of 64 right-hand sides: they
+// solve tile t together and share what else a tile needs: wave w stages a quarter of L_tt, multiplies out rows
+// 16w .. 16w+15 of the panel's product for the next tile and stores a quarter of the results.  What tile t + 1 needs
+// from memory is requested into registers before tile t is solved, and the part of its product that does not
+// involve tile t is multiplied out in the spare time of that solve; between two solves remain the last two k-steps,
+// the staging of L_tt and the stores (16-byte pieces from LDS).  With the product off the path a panel can be longer
+// than in tri_panel_kernel: up to PANELW = 8 tiles (what LDS holds of solved tiles), which saves the smallest GEMM
+// launches of the recursion; the loop over tiles is not unrolled.  The sums are the ones of tri_panel_kernel in the
+// same order.  Requires, on top of tri_panel_kernel's conditions, nrhs a multiple of 8 and 16-byte aligned X and Xh
+// (whole 16-byte pieces of a row are stored or skipped).
+constexpr int PANELW = 8;
+__global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
+                                                         float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
+                                                         int tiles)
+{
+    constexpr int NB = 64, LDD = NB + 4, NT = 256, NKS = 2 * PANELW - 2;
+    // everything the solve reads in the first 64 KB of LDS (16-bit offset field from one base register)
+    __shared__ __attribute__((aligned(16))) struct {
+        float D[NB][LDD];                  // L_tt in fp32, row-major, on and below the diagonal
+        float R[NB][LDD];                  // right-hand side of the tile with the panel's product taken out, [row][column]
+        float Xs[NB][LDD];                 // the tile's solution, [row][column]
+        uint16_t Xb[PANELW * NB][64];      // solved tiles as bfloat16, [k][column]
+        int ready;                         // hand-over counter of solve_tile64_waves
+    } lds;
+    int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t c0 = (int64_t)blockIdx.x * 64;
+    constexpr int cpr = NB / 8, PP = NB * cpr / NT;                    // 16-byte pieces of L_tt per thread
+
+    uint4 piece[PP];
+    float rhs[4][4];                                                   // rows 16w + 4g + r, columns 16j + lq: [j][r]
+    i32x4 a[NKS];                                                      // row 16w + lq of L[u, 0:u], k = 32 ks + 8 g .. +7
+    auto request = [&](int u) __attribute__((always_inline)) {         // what tile u needs from memory
+        const int64_t ru = r0 + (int64_t)u * NB;
 #pragma unroll
         for (int p = 0; p < PP; ++p) {
-            const int id = ht + NH * p, r = id / cpr, jc = id % cpr;
-            if (id < NB * cpr && jc * 8 <= r) {
-                const uint32_t w[4] = {piece[p].x, piece[p].y, piece[p].z, piece[p].w};
+            const int id = tid + NT * p, r = id / cpr, jc = id % cpr;
+            piece[p] = make_uint4(0, 0, 0, 0);
+            if (jc * 8 <= r) piece[p] = *(const uint4 *)(L + (ru + r) * n + ru + jc * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
+#pragma unroll
+            for (int r = 0; r < 4; ++r) rhs[j][r] = Rin[(ru + 16 * w + 4 * g + r) * nrhs + col];
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks)
+            if (ks < 2 * u) a[ks] = *(const i32x4 *)(L + (ru + 16 * w + lq) * n + r0 + ks * 32 + g * 8);      // uniform condition
+    };
+    f32x4 acc[4];                                                      // the wave's rows of the panel's product for the next tile
+    auto k_step = [&](int ks) __attribute__((always_inline)) {         // one MFMA k-step of 32 of that product
+        i32x4 b[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+            const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+            const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+            b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ks]), __builtin_bit_cast(bf16x8, b[j]), acc[j], 0, 0, 0);
+    };
+    // tile u into LDS: L_uu, and R = rhs - product, the k-steps before first_ks being in acc already
+    auto stage = [&](int u, int first_ks) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < PP; ++p) {
+            const int id = tid + NT * p, r = id / cpr, jc = id % cpr;
+            if (jc * 8 <= r) {
+                const uint32_t v[4] = {piece[p].x, piece[p].y, piece[p].z, piece[p].w};
                 f32x4 lo, hi;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    lo[e] = widen_bf16((uint16_t)(w[e >> 1] >> (16 * (e & 1))));
-                    hi[e] = widen_bf16((uint16_t)(w[2 + (e >> 1)] >> (16 * (e & 1))));
+                    lo[e] = widen_bf16((uint16_t)(v[e >> 1] >> (16 * (e & 1))));
+                    hi[e] = widen_bf16((uint16_t)(v[2 + (e >> 1)] >> (16 * (e & 1))));
                 }
-                *(f32x4 *)&lds.D[u & 1][r][jc * 8] = lo;
-                *(f32x4 *)&lds.D[u & 1][r][jc * 8 + 4] = hi;
+                *(f32x4 *)&lds.D[r][jc * 8] = lo;
+                *(f32x4 *)&lds.D[r][jc * 8 + 4] = hi;
             }
         }
-        // ---- the panel's product for the rows of tile u: k-steps of 32 over the tiles 0 .. u - 1
-        f32x4 acc[2][4];
 #pragma unroll
-        for (int si = 0; si < 2; ++si)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) acc[si][j] = (f32x4){0, 0, 0, 0};
-        auto k_step = [&](int ks) __attribute__((always_inline)) {
-            i32x4 b[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
-                const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
-                const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
-                b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
-            }
-#pragma unroll
-            for (int si = 0; si < 2; ++si)
-                if (strip(si) < 4) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[si][ks]), __builtin_bit_cast(bf16x8, b[j]), acc[si][j], 0, 0, 0);
-                }
-        };
-#pragma unroll
-        for (int ks = 0; ks < 2 * PANEL4 - 2; ++ks)
-            if (ks + 2 < 2 * u) k_step(ks);                            // the tiles solved before the last barrier
-        if (u >= 1) {
-            __syncthreads();                                           // tile u - 1 is solved
-#pragma unroll
-            for (int ks = 0; ks < 2 * PANEL4 - 2; ++ks)
-                if (ks + 2 >= 2 * u && ks < 2 * u) k_step(ks);
-        }
+        for (int ks = 0; ks < NKS; ++ks)
+            if (ks >= first_ks && ks < 2 * u) k_step(ks);              // uniform condition
         // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
 #pragma unroll
-        for (int si = 0; si < 2; ++si) {
-            const int i = strip(si);
-            if (i < 4) {
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+            for (int r = 0; r < 4; ++r) lds.R[16 * w + 4 * g + r][16 * j + lq] = rhs[j][r] - acc[j][r];
+    };
+    auto store = [&](int v) __attribute__((always_inline)) {           // results of tile v: 16-byte pieces from LDS to X and Xh
+        const int64_t rv = r0 + (int64_t)v * NB;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) lds.R[16 * i + 4 * g + r][16 * j + lq] = rhs[si][j][r] - acc[si][j][r];
-            }
+        for (int p = 0; p < NB * 16 / NT; ++p) {
+            const int id = tid + NT * p, r = id >> 4, ch = id & 15;
+            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = *(const f32x4 *)&lds.Xs[r][4 * ch];
         }
-        __syncthreads();                                               // tile u is staged
-    }
-    // the last tile but one while the last is being solved; the last after the barrier that ends its solve
-    if (tiles >= 2) store(tiles - 2);
+#pragma unroll
+        for (int p = 0; p < NB * 8 / NT; ++p) {
+            const int id = tid + NT * p, r = id >> 3, ch = id & 7;
+            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * ch];
+        }
+    };
+
+    if (tid == 0) lds.ready = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
+    request(0);
+    stage(0, 0);
     __syncthreads();
-    store(tiles - 1);
+#pragma unroll 1
+    for (int t = 0; t < tiles; ++t) {                                  // (not unrolled: t only moves LDS addresses and bounds uniform branches)
+        // the thread index is made opaque once per tile: otherwise the hundreds of LDS and memory addresses derived
+        // from it are all computed ahead of the loop and kept in registers across it, and the kernel spills
+        asm volatile("" : "+v"(tid));
+        lane = tid & 63;
+        lq = lane & 15;
+        g = lane >> 4;
+        if (t + 1 < tiles) request(t + 1);                             // lands during the solve
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
+        solve_tile64_waves<LDD>(
+            lds.D, lds.R, lds.Xs, &lds.ready, t * NBLK, w, lane,
+            [&](int r, float xr) __attribute__((always_inline)) {
+                lds.Xb[t * NB + r][lane] = round_bf16(xr);
+                lds.Xs[r][lane] = xr;
+            },
+            // after its second, third and fourth corner a wave multiplies out four k-steps each of the next tile's
+            // product over the tiles solved before this one (by then the rows of L requested above have arrived)
+            [&](int q) __attribute__((always_inline)) {
+                if (q >= 1 && t + 1 < tiles) {
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks)
+                        if (ks / 4 == q - 1 && ks < 2 * t) k_step(ks);
+                }
+            });
+        __syncthreads();                                               // tile t is solved: D and R are free, Xs and Xb complete
+        store(t);
+        if (t + 1 < tiles) stage(t + 1, 2 * t);
+        __syncthreads();                                               // tile t + 1 is staged, Xs is free
+    }
 }
 
 struct Solve {
@@ -620,26 +690,24 @@ hipError_t update(const Solve &v, int64_t r0, int64_t mid, int64_t r1)
 }
 
 // the four-wave panel kernel can be used: whole 16-byte pieces of the rows of X and Xh
-bool panel4_ok(const Solve &v) { return v.nrhs % 8 == 0 && (uintptr_t)v.X % 16 == 0 && (uintptr_t)v.Xh % 16 == 0; }
+bool panelw_ok(const Solve &v) { return v.nrhs % 8 == 0 && (uintptr_t)v.X % 16 == 0 && (uintptr_t)v.Xh % 16 == 0; }
 
 // up to four (eight with the four-wave kernel) full 64-row tiles with 16-byte aligned rows of L: one launch for the
 // whole range
 bool panel_ok(const Solve &v, int64_t r0, int64_t r1)
 {
-    return v.nb == 64 && (r1 - r0) % 64 == 0 && r1 - r0 <= 64 * (panel4_ok(v) ? PANEL4 : 4) && (uintptr_t)v.L % 16 == 0 &&
+    return v.nb == 64 && (r1 - r0) % 64 == 0 && r1 - r0 <= 64 * (panelw_ok(v) ? PANELW : 4) && (uintptr_t)v.L % 16 == 0 &&
            v.n % 8 == 0 && r0 % 8 == 0;
 }
 
 hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
 {
     dim3 grid((unsigned)((v.nrhs + 63) / 64));
-    if (panel4_ok(v)) {
-        hipLaunchKernelGGL(tri_panel4_kernel, grid, dim3(PT), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0,
-                           (int)((r1 - r0) / 64));
-        return hipGetLastError();
-    }
-    hipLaunchKernelGGL(tri_panel_kernel, grid, dim3(64), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0,
-                       (int)((r1 - r0) / 64));
+    const int tiles = (int)((r1 - r0) / 64);
+    if (panelw_ok(v))
+        hipLaunchKernelGGL(tri_panelw_kernel, grid, dim3(256), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
+    else
+        hipLaunchKernelGGL(tri_panel_kernel, grid, dim3(64), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
     return hipGetLastError();
 }
 

@@ -268,28 +268,11 @@ struct TileProduct {
     }
 };
 
-// L_jj = CHOL(S_jj) for the tile at (j0, j0) with `cols` rows and columns.  S is read from Sm (row stride n: A itself
-// for the first panel, L afterwards); L gets the factor below and on the diagonal and zero above it, Lh its bf16
-// rounding in both triangles.  One workgroup of NT threads; thread r < 64 owns row r, the other waves only help to
-// move and update the tile.
-__global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__ Sm, float *__restrict__ L,
-                                                       uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
+// The factorisation proper of a diagonal tile whose S (with everything left of it taken out) is in T: the column
+// recurrence by the first wave, then L, and Lh in both triangles, written out by all.  See diag_tile.
+__device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r)
 {
-    // one block, T first: in the first 64 KB of LDS a read reaches its word with the 16-bit offset field from one
-    // base register (further up every read needs an address register of its own)
-    __shared__ __attribute__((aligned(16))) struct {
-        float T[NBMAX][LDT];          // S on entry, L as columns finish
-        uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
-    } lds;
-    auto &T = lds.T;
-    auto &Bs = lds.Bs;
-    const int r = threadIdx.x;
     const bool live = r < cols;
-    TileProduct product;
-    if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
-    load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
-    if (k0 < j0) product.apply(T, Bs, r);
-    else __syncthreads();
     bool mirrored = false;
     if (cols == NBMAX) {
         // Full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
@@ -406,21 +389,55 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *__restrict__
         }
 }
 
+// L_jj = CHOL(S_jj) for the tile at (j0, j0) with `cols` rows and columns.  S is read from Sm (row stride n: A itself
+// for the first panel, L afterwards); L gets the factor below and on the diagonal and zero above it, Lh its bf16
+// rounding in both triangles.  One workgroup of NT threads; thread r < 64 owns row r, the other waves only help to
+// move and update the tile.  T (first 64 KB of LDS: a read reaches its word with the 16-bit offset field from one
+// base register; further up every read needs an address register of its own) and Bs are the workgroup's LDS.
+__device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], const float *Sm, float *L, uint16_t *Lh, int64_t n,
+                                          int64_t j0, int cols, int64_t k0, int r)
+{
+    TileProduct product;
+    if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
+    load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
+    if (k0 < j0) product.apply(T, Bs, r);
+    else __syncthreads();
+    diag_rest(T, L, Lh, n, j0, cols, r);
+}
+
+__global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
+                                                       int64_t k0)
+{
+    __shared__ __attribute__((aligned(16))) struct {
+        float T[NBMAX][LDT];          // S on entry, L as columns finish
+        uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
+    } lds;
+    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x);
+}
+
 // L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane of the first wave; the
 // other waves of the NT threads only help to move and update the tile.
-__global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict__ Sm, float *__restrict__ L,
-                                                        uint16_t *__restrict__ Lh, int64_t n, int64_t j0, int cols, int64_t k0)
+// next_Sm != nullptr: the workgroup of the first 64 rows goes on to factor the next diagonal tile, (j1, j1), whose S is
+// read from next_Sm: it produces the only part of that tile's update that is still missing, and a launch of its own
+// for the tile would first wait for memory again.  That workgroup requests the tile's S and the operands of its
+// update over the group's earlier panels before its own recurrence starts; the three waves that would idle during
+// the recurrence multiply them out (wave 1 rows 0 .. 31 of the tile, waves 2 and 3 sixteen rows each).  After the
+// rows are stored, the k range of this panel is added from memory, and the tile is factored.
+__global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
+                                                        int64_t k0, const float *next_Sm)
 {
     // one block, D and X first (see chol_diag_kernel)
     __shared__ __attribute__((aligned(16))) struct {
         float D[NBMAX][LDT];          // L_jj
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
+        int landed;                   // waves whose copies for the next diagonal tile have arrived
     } lds;
     auto &D = lds.D;
     auto &X = lds.X;
     auto &Bs = lds.Bs;
     const int tid = threadIdx.x, lane = tid & 63;
+    if (tid == 0) lds.landed = 0;
     const bool solver = tid < 64;                         // the wave that runs the recurrence
     const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
     const bool live = solver && row < n;
@@ -432,6 +449,63 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
     load_tile(X, Sm + first * n + j0, n, nrows, cols, tid);
     if (k0 < j0) product.apply(X, Bs, tid);
     else __syncthreads();
+    // ---- the next diagonal tile, first part: requests (Bs is free again)
+    const bool fused = next_Sm != nullptr && blockIdx.x == 0;          // uniform over the workgroup
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4;
+    const int nks_e = fused ? (int)(j0 - k0) / 32 : 0;                 // k-steps of that tile's update that do not involve this panel
+    constexpr int NKS = KMAX / 32;
+    f32x4 sv[4], accn[2][4];                                           // its S (this thread's pieces); its update: [strip][column tile]
+    i32x4 an[2][NKS], al[2][2];                                        // stationary operand of the update, early and late k-steps
+    auto strip = [&](int si) __attribute__((always_inline)) { return w == 1 ? si : (si == 0 && w >= 2 ? w : -1); };   // 16-row strips of a wave
+    auto k_step = [&](int ks, const i32x4(&a2)[2]) __attribute__((always_inline)) {        // one MFMA k-step of 32, Bs rows 32 ks ..
+        i32x4 b[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+            const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+            const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+            b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+        }
+#pragma unroll
+        for (int si = 0; si < 2; ++si)
+            if (strip(si) >= 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a2[si]), __builtin_bit_cast(bf16x8, b[j]), accn[si][j], 0, 0, 0);
+            }
+    };
+    // rows `first_row` .. +count-1 of the streamed operand Lh[., j1 : j1+64] into Bs from row `to` on, 8 rows per copy,
+    // the copies dealt out to `waves` waves of which this is number `me`
+    auto copy_rows = [&](int64_t first_row, int to, int count, int me, int waves) __attribute__((always_inline)) {
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs[0][0];
+        const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
+        for (int k = 8 * me; k < count; k += 8 * waves) {
+            const char *base = (const char *)(Lh + (first_row + k) * n + j1);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_base + (to + k) * 128), "v"(voff), "s"(base)
+                         : "memory", "m0");
+        }
+    };
+#pragma unroll
+    for (int si = 0; si < 2; ++si)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) accn[si][j] = (f32x4){0, 0, 0, 0};
+    if (fused) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[i] = *(const f32x4 *)(next_Sm + (j1 + 16 * i + (tid >> 4)) * n + j1 + 4 * (tid & 15));
+        if (w >= 1 && nks_e > 0) {
+            copy_rows(k0, 0, 32 * nks_e, w - 1, 3);
+#pragma unroll
+            for (int si = 0; si < 2; ++si)
+                if (strip(si) >= 0) {
+                    const uint16_t *rowp = Lh + (j1 + 16 * strip(si) + lq) * n + k0 + 8 * g;
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks)
+                        if (ks < nks_e) an[si][ks] = *(const i32x4 *)(rowp + 32 * ks);
+                }
+        }
+    }
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
     bool mirrored = false;
@@ -520,6 +594,18 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
 #pragma unroll
             for (int c = 0; c < NBMAX; ++c) m[c * n] = round_bf16(x[c]);
         }
+        } else if (fused && nks_e > 0) {
+            // ---- the next diagonal tile, second part, by the three waves beside the recurrence: when the copies of all
+            // three have arrived (a counter in LDS; the wait is bounded), the early k-steps
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) __hip_atomic_fetch_add(&lds.landed, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            for (int polls = 0; __hip_atomic_load(&lds.landed, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 3 && polls < (1 << 20); ++polls) {}
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks)
+                if (ks < nks_e) {
+                    const i32x4 a2[2] = {an[0][ks], an[1][ks]};
+                    k_step(ks, a2);
+                }
         }
         mirrored = true;
     } else if (solver) {
@@ -527,15 +613,48 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *__restrict_
     }
     __syncthreads();
     const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, tid);
-    if (!live || (stored && mirrored)) return;
-    for (int c = 0; c < cols; ++c) {
-        const float v = X[lane][c];
-        const uint16_t h = round_bf16(v);
-        if (!stored) {
-            L[row * n + j0 + c] = v;
-            Lh[row * n + j0 + c] = h;
+    if (live && !(stored && mirrored))
+        for (int c = 0; c < cols; ++c) {
+            const float v = X[lane][c];
+            const uint16_t h = round_bf16(v);
+            if (!stored) {
+                L[row * n + j0 + c] = v;
+                Lh[row * n + j0 + c] = h;
+            }
+            if (!mirrored) Lh[(j0 + c) * n + row] = h;
         }
-        if (!mirrored) Lh[(j0 + c) * n + row] = h;
+    if (fused) {
+        // ---- the next diagonal tile, third part: the k range of this panel, whose rows this workgroup has just stored
+        __threadfence();                                  // the workgroup's stores to Lh before its loads of them
+        __syncthreads();
+        copy_rows(j0, 32 * nks_e, NBMAX, w, NT / 64);
+#pragma unroll
+        for (int si = 0; si < 2; ++si)
+            if (strip(si) >= 0) {
+                const uint16_t *rowp = Lh + (j1 + 16 * strip(si) + lq) * n + j0 + 8 * g;
+                al[si][0] = *(const i32x4 *)rowp;
+                al[si][1] = *(const i32x4 *)(rowp + 32);
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(f32x4 *)&D[16 * i + (tid >> 4)][4 * (tid & 15)] = sv[i];      // S into the tile (D is free)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const i32x4 a2[2] = {al[0][u], al[1][u]};
+            k_step(nks_e + u, a2);
+        }
+        // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
+#pragma unroll
+        for (int si = 0; si < 2; ++si)
+            if (strip(si) >= 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
+            }
+        __syncthreads();
+        diag_rest(D, L, Lh, n, j1, NBMAX, tid);
     }
 }
 
@@ -571,6 +690,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
         const int tile = choose_mfma_tile(p);
         return tile ? launch_mfma(p, tile, 16, s) : launch_generic(p, s);
     };
+    bool diag_done = false;           // the diagonal tile of this panel was factored by the rows kernel of the panel before
     for (int64_t j0 = 0; j0 < n; j0 += nb) {
         const int cols = (int)(j0 + nb <= n ? nb : n - j0);
         const int64_t j1 = j0 + cols;
@@ -592,11 +712,21 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
                 Sm = L;
             }
         }
-        hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0);
-        if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-        if (j1 < n) {
-            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0);
+        if (!diag_done) {
+            hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0);
             if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+        }
+        diag_done = false;
+        if (j1 < n) {
+            // the next diagonal tile rides along when it is a full tile of the same group whose whole update the tile
+            // kernels do themselves: its k range [g0, j1) then starts where this panel's starts
+            const bool fuse = k0 == g0 && nb == NBMAX && cols == NBMAX && j1 + NBMAX <= n && j1 < g0 + GROUP * nb &&
+                              n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)L % 16 == 0 &&
+                              j1 - g0 <= KMAX;
+            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0,
+                               fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr);
+            if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+            diag_done = fuse;
         }
     }
     // the products wrote S above the diagonal too (a group's columns start at the group's first row)

@@ -20,7 +20,9 @@
 //      L, of Lh, and the mirrored column of Lh.
 //   Both tile kernels are workgroups of four waves: all four move the tile and first take the terms of the group's
 //   own earlier panels out of it with MFMAs of their own (TileProduct), which is far cheaper than a launch of the
-//   GEMM kernel for so short a k range; the first wave then runs the recurrence.
+//   GEMM kernel for so short a k range; the first wave then runs the recurrence.  Within a group, step 2 for panel
+//   j + 1 is done by the first workgroup of step 3 for panel j (the rows that become tile (j+1, j)), in the same
+//   launch: the chain diagonal tile - tile below it - next diagonal tile is what the whole factorisation waits for.
 // Inside a tile column everything is fp32 on unrounded values, in the order of the scalar recurrence:
 // t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
 #include "cyc_internal.h"

@@ -423,8 +423,8 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 // read from next_Sm: it produces the only part of that tile's update that is still missing, and a launch of its own
 // for the tile would first wait for memory again.  That workgroup requests the tile's S and the operands of its
 // update over the group's earlier panels before its own recurrence starts; the three waves that would idle during
-// the recurrence multiply them out (wave 1 rows 0 .. 31 of the tile, waves 2 and 3 sixteen rows each).  After the
-// rows are stored, the k range of this panel is added from memory, and the tile is factored.
+// the recurrence multiply them out (wave 1 rows 0 .. 31 of the tile, waves 2 and 3 sixteen rows each).  Then the k
+// range of this panel is added, straight from the solved rows in LDS, and the tile is factored.
 __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
                                                         int64_t k0, const float *next_Sm)
 {
@@ -457,7 +457,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     const int nks_e = fused ? (int)(j0 - k0) / 32 : 0;                 // k-steps of that tile's update that do not involve this panel
     constexpr int NKS = KMAX / 32;
     f32x4 sv[4], accn[2][4];                                           // its S (this thread's pieces); its update: [strip][column tile]
-    i32x4 an[2][NKS], al[2][2];                                        // stationary operand of the update, early and late k-steps
+    i32x4 an[2][NKS];                                                  // stationary operand of the update's early k-steps
     auto strip = [&](int si) __attribute__((always_inline)) { return w == 1 ? si : (si == 0 && w >= 2 ? w : -1); };   // 16-row strips of a wave
     auto k_step = [&](int ks, const i32x4(&a2)[2]) __attribute__((always_inline)) {        // one MFMA k-step of 32, Bs rows 32 ks ..
         i32x4 b[4];
@@ -626,26 +626,36 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             if (!mirrored) Lh[(j0 + c) * n + row] = h;
         }
     if (fused) {
-        // ---- the next diagonal tile, third part: the k range of this panel, whose rows this workgroup has just stored
-        __threadfence();                                  // the workgroup's stores to Lh before its loads of them
-        __syncthreads();
-        copy_rows(j0, 32 * nks_e, NBMAX, w, NT / 64);
-#pragma unroll
-        for (int si = 0; si < 2; ++si)
-            if (strip(si) >= 0) {
-                const uint16_t *rowp = Lh + (j1 + 16 * strip(si) + lq) * n + j0 + 8 * g;
-                al[si][0] = *(const i32x4 *)rowp;
-                al[si][1] = *(const i32x4 *)(rowp + 32);
-            }
+        // ---- the next diagonal tile, third part: the k range of this panel.  Its operands are the rows this
+        // workgroup has just solved, still in X: both are the same fragments of X rounded to bfloat16 (the streamed
+        // operand is the mirror image of the stationary one), so nothing has to come back from memory.
+        auto fragment = [&](int q, int u) __attribute__((always_inline)) {     // row 16 q + lq, k = 32 u + 8 g .. +7 of the panel
+            const float *p = &X[16 * q + lq][32 * u + 8 * g];
+            const f32x4 lo = *(const f32x4 *)p, hi = *(const f32x4 *)(p + 4);
+            i32x4 f;
+            f[0] = (int)(round_bf16(lo[0]) | ((unsigned)round_bf16(lo[1]) << 16));
+            f[1] = (int)(round_bf16(lo[2]) | ((unsigned)round_bf16(lo[3]) << 16));
+            f[2] = (int)(round_bf16(hi[0]) | ((unsigned)round_bf16(hi[1]) << 16));
+            f[3] = (int)(round_bf16(hi[2]) | ((unsigned)round_bf16(hi[3]) << 16));
+            return f;
+        };
 #pragma unroll
         for (int i = 0; i < 4; ++i) *(f32x4 *)&D[16 * i + (tid >> 4)][4 * (tid & 15)] = sv[i];      // S into the tile (D is free)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const i32x4 a2[2] = {al[0][u], al[1][u]};
-            k_step(nks_e + u, a2);
+            i32x4 bq[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bq[j] = fragment(j, u);
+#pragma unroll
+            for (int si = 0; si < 2; ++si)
+                if (strip(si) >= 0) {
+                    const i32x4 aq = fragment(strip(si), u);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq[j]), accn[si][j], 0, 0, 0);
+                }
         }
+        __syncthreads();
         // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
 #pragma unroll
         for (int si = 0; si < 2; ++si)

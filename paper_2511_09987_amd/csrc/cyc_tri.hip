@@ -462,6 +462,9 @@ __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const 
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j) t4[j] = __builtin_fmaf(c4[j][i], xv[i], t4[j]);
+            // the results are next used inside the branch of the wave's own corner, phases later, and the compiler
+            // would move all these multiply-adds down into that branch, onto the path everybody waits for: pin them
+            asm volatile("" : "+v"(t4[0]), "+v"(t4[1]), "+v"(t4[2]), "+v"(t4[3]));
         };
         if (w == sw) {                                    // the owner of block s
             if (s >= 1) take_out(tt[so], own);

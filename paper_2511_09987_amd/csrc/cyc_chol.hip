@@ -28,6 +28,8 @@
 #include "cyc_internal.h"
 #include "cyc_wave.h"
 
+#include <mutex>
+
 namespace cyc {
 namespace {
 
@@ -670,6 +672,33 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     }
 }
 
+// A second stream per device, on which the product for the next group of panels runs beside the tile kernels of the
+// current one (see launch_chol).  Created on first use, default priority, kept until the process ends; one lock
+// serialises the callers that use it.  ok == false (creation failed): launch_chol does without.
+struct SideStream {
+    bool tried = false, ok = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+constexpr int MAX_DEVICES = 64;
+SideStream g_side[MAX_DEVICES];
+std::mutex g_side_lock;
+
+SideStream *side_stream()        // call with g_side_lock held
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    SideStream &v = g_side[dev];
+    if (!v.tried) {
+        v.tried = true;
+        v.ok = hipStreamCreateWithFlags(&v.stream, hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&v.fork, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&v.join, hipEventDisableTiming) == hipSuccess;
+        if (!v.ok) (void)hipGetLastError();
+    }
+    return v.ok ? &v : nullptr;
+}
+
 }  // namespace
 
 hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t nb, hipStream_t s)
@@ -684,7 +713,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
     // then only add the terms of the group's own earlier panels (k range at most (GROUP - 1) * nb).  The terms of a
     // sum are the paper's; they are merely added in two chains instead of one.
     constexpr int GROUP = 8;          // measured at n = 8192 with the tile kernels as they are now: 4: 4.74 ms, 8: 4.22, 12: 4.26, 16: 4.33
-    auto product = [&](int64_t r0, int64_t c0, int64_t ncols, int64_t k0, int64_t k1, const float *src) {
+    auto product = [&](int64_t r0, int64_t c0, int64_t ncols, int64_t k0, int64_t k1, const float *src, hipStream_t on) {
         Problem p;                        // L[r0:, c0:c0+ncols] = src[r0:, c0:c0+ncols] - Lh[r0:, k0:k1] * Lh[k0:k1, c0:c0+ncols]
         p.A = Lh + r0 * n + k0;           // finished factor, rows r0.., columns k0..k1
         p.lda = n;
@@ -700,9 +729,18 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
         p.strideA = p.strideB = p.strideC = 0;
         p.i8 = false;
         const int tile = choose_mfma_tile(p);
-        return tile ? launch_mfma(p, tile, 16, s) : launch_generic(p, s);
+        return tile ? launch_mfma(p, tile, 16, on) : launch_generic(p, on);
     };
     bool diag_done = false;           // the diagonal tile of this panel was factored by the rows kernel of the panel before
+    // the side stream is worth its events only when there are at least three groups
+    std::unique_lock<std::mutex> lock(g_side_lock, std::defer_lock);
+    SideStream *side = nullptr;
+    if (n > 2 * GROUP * nb) {
+        lock.lock();
+        side = side_stream();
+        if (!side) lock.unlock();
+    }
+    int64_t ahead = -1;               // first column of the group whose product over the groups before the last is on the side stream
     for (int64_t j0 = 0; j0 < n; j0 += nb) {
         const int cols = (int)(j0 + nb <= n ? nb : n - j0);
         const int64_t j1 = j0 + cols;
@@ -710,7 +748,26 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
         const float *Sm = A;                                      // where S of this panel is read from
         if (j0 == g0 && g0 > 0) {
             const int64_t gcols = g0 + GROUP * nb <= n ? GROUP * nb : n - g0;
-            if (hipError_t e = product(g0, g0, gcols, 0, g0, A); e != hipSuccess) return e;
+            if (ahead == g0) {
+                // the part over the groups before the last was multiplied out on the side stream while the last group
+                // was being factored; what is left is the k range of that group
+                if (hipError_t e = hipStreamWaitEvent(s, side->join, 0); e != hipSuccess) return e;
+                if (hipError_t e = product(g0, g0, gcols, g0 - GROUP * nb, g0, L, s); e != hipSuccess) return e;
+            } else {
+                if (hipError_t e = product(g0, g0, gcols, 0, g0, A, s); e != hipSuccess) return e;
+            }
+            // The product for the NEXT group over everything left of this group does not depend on this group: it goes
+            // to the side stream now and runs on the compute units that the tile kernels of this group (at most one
+            // workgroup per 64 rows) leave idle.  Per entry the terms are then subtracted in two chains, not one.
+            const int64_t g1 = g0 + GROUP * nb;
+            if (side && g1 < n) {
+                const int64_t ncols = g1 + GROUP * nb <= n ? GROUP * nb : n - g1;
+                if (hipError_t e = hipEventRecord(side->fork, s); e != hipSuccess) return e;
+                if (hipError_t e = hipStreamWaitEvent(side->stream, side->fork, 0); e != hipSuccess) return e;
+                if (hipError_t e = product(g1, g1, ncols, 0, g0, A, side->stream); e != hipSuccess) return e;
+                if (hipError_t e = hipEventRecord(side->join, side->stream); e != hipSuccess) return e;
+                ahead = g1;
+            }
         }
         if (g0 > 0) Sm = L;
         // the terms of the group's own earlier panels: multiplied out by the tile kernels themselves where they can
@@ -720,7 +777,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (nb == NBMAX && cols == NBMAX && n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && j0 - g0 <= KMAX) {
                 k0 = g0;
             } else {
-                if (hipError_t e = product(j0, j0, cols, g0, j0, Sm); e != hipSuccess) return e;
+                if (hipError_t e = product(j0, j0, cols, g0, j0, Sm, s); e != hipSuccess) return e;
                 Sm = L;
             }
         }

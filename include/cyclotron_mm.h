@@ -132,9 +132,13 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
  *     with both triangles filled: Lh[r][c] = Lh[c][r] = bf16(L[max(r,c)][min(r,c)]).
  * nb: tile size, 1 <= nb <= 64.  The MFMA kernels serve the updates when n and nb are multiples of 8 and the
  *     pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
- * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates nothing
- *     and keeps no state.  n == 0: CYC_OK, nothing done.  A matrix that is not positive definite gives NaNs
- *     (square root of a negative number), not an error.
+ * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates no device
+ *     memory.  For n > 16 nb part of the work is enqueued on a second stream that the library creates per device
+ *     on first use (default priority, kept until the process ends) and that is forked from and joined back into
+ *     `stream` with events inside the call: all of the call's work is ordered after what was on `stream` before
+ *     and before what is enqueued on it afterwards; calls that use the second stream are serialised on the host
+ *     by a lock.  n == 0: CYC_OK, nothing done.  A matrix that is not positive definite gives NaNs (square root
+ *     of a negative number), not an error.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or too large n, nb out of range, A or L not
  * 4-byte or Lh not 2-byte aligned), CYC_ERR_ALIAS (A, L, Lh overlap one another), CYC_ERR_LAUNCH. */
 int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *stream);

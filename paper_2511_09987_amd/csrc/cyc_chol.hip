@@ -28,8 +28,6 @@
 #include "cyc_internal.h"
 #include "cyc_wave.h"
 
-#include <mutex>
-
 namespace cyc {
 namespace {
 
@@ -672,33 +670,6 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     }
 }
 
-// A second stream per device, on which the product for the next group of panels runs beside the tile kernels of the
-// current one (see launch_chol).  Created on first use, default priority, kept until the process ends; one lock
-// serialises the callers that use it.  ok == false (creation failed): launch_chol does without.
-struct SideStream {
-    bool tried = false, ok = false;
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
-};
-constexpr int MAX_DEVICES = 64;
-SideStream g_side[MAX_DEVICES];
-std::mutex g_side_lock;
-
-SideStream *side_stream()        // call with g_side_lock held
-{
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
-    SideStream &v = g_side[dev];
-    if (!v.tried) {
-        v.tried = true;
-        v.ok = hipStreamCreateWithFlags(&v.stream, hipStreamNonBlocking) == hipSuccess &&
-               hipEventCreateWithFlags(&v.fork, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&v.join, hipEventDisableTiming) == hipSuccess;
-        if (!v.ok) (void)hipGetLastError();
-    }
-    return v.ok ? &v : nullptr;
-}
-
 }  // namespace
 
 hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t nb, hipStream_t s)
@@ -733,13 +704,8 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
     };
     bool diag_done = false;           // the diagonal tile of this panel was factored by the rows kernel of the panel before
     // the side stream is worth its events only when there are at least three groups
-    std::unique_lock<std::mutex> lock(g_side_lock, std::defer_lock);
-    SideStream *side = nullptr;
-    if (n > 2 * GROUP * nb) {
-        lock.lock();
-        side = side_stream();
-        if (!side) lock.unlock();
-    }
+    SideStreamLock side_lock;
+    SideStream *side = n > 2 * GROUP * nb ? side_lock.acquire() : nullptr;
     int64_t ahead = -1;               // first column of the group whose product over the groups before the last is on the side stream
     for (int64_t j0 = 0; j0 < n; j0 += nb) {
         const int cols = (int)(j0 + nb <= n ? nb : n - j0);
@@ -751,7 +717,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (ahead == g0) {
                 // the part over the groups before the last was multiplied out on the side stream while the last group
                 // was being factored; what is left is the k range of that group
-                if (hipError_t e = hipStreamWaitEvent(s, side->join, 0); e != hipSuccess) return e;
+                if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return e;
                 if (hipError_t e = product(g0, g0, gcols, g0 - GROUP * nb, g0, L, s); e != hipSuccess) return e;
             } else {
                 if (hipError_t e = product(g0, g0, gcols, 0, g0, A, s); e != hipSuccess) return e;
@@ -765,7 +731,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
                 if (hipError_t e = hipEventRecord(side->fork, s); e != hipSuccess) return e;
                 if (hipError_t e = hipStreamWaitEvent(side->stream, side->fork, 0); e != hipSuccess) return e;
                 if (hipError_t e = product(g1, g1, ncols, 0, g0, A, side->stream); e != hipSuccess) return e;
-                if (hipError_t e = hipEventRecord(side->join, side->stream); e != hipSuccess) return e;
+                if (hipError_t e = hipEventRecord(side->join[0], side->stream); e != hipSuccess) return e;
                 ahead = g1;
             }
         }

@@ -39,6 +39,26 @@ int choose_mfma_tile(const Problem &p);
 int choose_ksplit(const Problem &p, int *tile);   // *tile: block edge to use, 128 or 256
 hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, hipStream_t s);
 // lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
+// A second stream per device for work that may run beside what a call enqueues on the caller's stream (forked from
+// and joined into that stream with events inside the call).  Created on first use, default priority, kept until the
+// process ends.  One lock serialises the callers that use it: SideStreamLock::acquire() takes the lock for the
+// lifetime of the object and returns the current device's side stream, or nullptr (creation failed; lock released),
+// in which case the caller does without.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr;            // recorded on the caller's stream, waited for by the side stream
+    hipEvent_t join[8] = {};              // recorded on the side stream, waited for by the caller's stream
+    bool tried = false, ok = false;
+};
+class SideStreamLock {
+public:
+    SideStream *acquire();
+    ~SideStreamLock();
+
+private:
+    bool held_ = false;
+};
+
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, hipStream_t s);
 // tiled Cholesky factorisation A = L L^T in tiles of nb (see cyc_chol.hip); arguments validated by the caller
 hipError_t launch_chol(const void *A, void *L, void *Lh, int64_t n, int64_t nb, hipStream_t s);

@@ -683,7 +683,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
     // covers the columns of the whole group against all tiles left of the group; the later panels of the group
     // then only add the terms of the group's own earlier panels (k range at most (GROUP - 1) * nb).  The terms of a
     // sum are the paper's; they are merely added in two chains instead of one.
-    constexpr int GROUP = 8;          // measured at n = 8192 with the tile kernels as they are now: 4: 4.74 ms, 8: 4.22, 12: 4.26, 16: 4.33
+    constexpr int GROUP = 8;          // measured at n = 8192: 4: 4.74 ms, 8: 4.22, 12: 4.26, 16: 4.33; with the side stream below 4: 4.11, 8: 3.99
     auto product = [&](int64_t r0, int64_t c0, int64_t ncols, int64_t k0, int64_t k1, const float *src, hipStream_t on) {
         Problem p;                        // L[r0:, c0:c0+ncols] = src[r0:, c0:c0+ncols] - Lh[r0:, k0:k1] * Lh[k0:k1, c0:c0+ncols]
         p.A = Lh + r0 * n + k0;           // finished factor, rows r0.., columns k0..k1

@@ -117,6 +117,31 @@ def test_two_calls_give_identical_bits_and_outputs_are_fully_written(lib):
     assert bool(torch.isfinite(L1).all()) and bool(torch.isfinite(H1.float()).all())
 
 
+def test_second_stream_is_ordered_with_the_callers_stream(lib):
+    """Three groups of panels and more: part of the work runs on the library's second stream.  The call must still
+    be ordered after what the caller's stream held before it (the fill of A) and before what follows it (the copy
+    of L), on a stream that is not the default one, call after call."""
+    n, nb = 1600, 64
+    A0 = ws_inputs.spd_f32(n, 9, 0, DEV)
+    ref_L, ref_H = lib.recurrence_cholesky(A0, nb=nb)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()          # default priority
+    A = torch.zeros_like(A0)
+    L = torch.empty_like(A0)
+    H = torch.empty((n, n), dtype=torch.bfloat16, device=DEV)
+    copies = []
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            A.zero_()
+            A.copy_(A0)                                          # queued before the call
+            lib.recurrence_cholesky(A, nb=nb, out=L, out_bf16=H)
+            copies.append((L.clone(), H.clone()))                # queued after the call
+            L.fill_(float("nan"))
+    side.synchronize()
+    for Lc, Hc in copies:
+        assert torch.equal(Lc, ref_L) and torch.equal(Hc.view(torch.int16), ref_H.view(torch.int16))
+
+
 def test_not_positive_definite_gives_nan(lib):
     A = torch.tensor([[1.0, 2.0], [2.0, 1.0]], device=DEV)
     L, Lh = run(lib, A, 1)

@@ -428,7 +428,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
                                                         int64_t k0, const float *next_Sm)
 {
-    // one block, D and X first (see chol_diag_kernel)
+    // one block, D and X first (see diag_tile)
     __shared__ __attribute__((aligned(16))) struct {
         float D[NBMAX][LDT];          // L_jj
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish

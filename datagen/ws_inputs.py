@@ -283,6 +283,14 @@ KSPACE_WORKLOADS = {
 }
 
 
+# Few rows of A over a large B: the shape regime of the (j,k)-in-space kernel variant, the mirror image of the
+# narrow-stream workload (there A dominates and N = 16; here B dominates and M = 16).  batch 32 x (16 x 8192)
+# (8192 x 8192): 4 GiB of B read once, 16 MiB of C.
+NARROWM_WORKLOADS = {
+    "m1_bf16_narrowm": Workload("m1_bf16_narrowm", "bf16", 32, 16, 8192, 8192, "normal", 1.0, 10),
+}
+
+
 def make_inputs(w: Workload, device="cpu", scale_down: int = 1):
     """A (batch, M, K) and B (batch, K, N) for a workload; batch dim dropped when batch == 1.
 

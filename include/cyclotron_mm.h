@@ -11,12 +11,31 @@
  * The value that leaves the grid is C_ij = sum_k A_ik B_kj (the paper's
  * matrix-multiply recurrence, "Explicit Reduction Dimensions" form).
  *
- * All pointers are DEVICE pointers owned by the caller.  The library allocates
- * nothing, keeps no reference after return and has no mutable global state.
- * Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the
- * default stream); no call synchronises the device or the stream.  Functions
- * return a cyc_status and never throw or abort; when the status is not CYC_OK
- * nothing has been enqueued.
+ * All pointers are DEVICE pointers owned by the caller; the library keeps no
+ * reference to them after return.  Work is enqueued on `stream` (a hipStream_t
+ * passed as void*; NULL = the default stream); no call synchronises the stream,
+ * and none synchronises the device except the rare growth of a workspace
+ * described below.  Functions return a cyc_status and never throw or abort.
+ * Every argument check, and every resource a call needs, is settled before the
+ * first launch: a status other than CYC_OK and CYC_ERR_LAUNCH means nothing
+ * has been enqueued.  CYC_ERR_LAUNCH means the HIP runtime refused a launch;
+ * for the calls that enqueue several kernels (k in space, triangular solve,
+ * Cholesky) earlier kernels of the same call then remain enqueued and the
+ * outputs are undefined.
+ *
+ * State the library keeps (all of it per process, created on first use, kept
+ * until the process ends, guarded by locks; calls from several host threads
+ * on different streams are safe):
+ *   - the kernel forced through cyc_force_kernel() / CYC_FORCE_KERNEL;
+ *   - for cyc_recurrence_matmul on problems mapped with k in space (see
+ *     below): one workspace of device memory per (device, stream), allocated
+ *     with hipMalloc at the first such call on that stream and replaced by a
+ *     larger one (hipFree + hipMalloc, which waits for the device) when a
+ *     later call needs more.  A call that cannot get it returns
+ *     CYC_ERR_WORKSPACE.  No other entry point allocates device memory;
+ *   - for cyc_recurrence_cholesky with n > 16 nb: one extra stream and a few
+ *     events per device (see there); callers that use it are serialised on
+ *     the host by a lock for the duration of the enqueueing.
  *
  * Layout: A is M x K, B is K x N, C is M x N, dense row-major with the row
  * length as leading dimension: A_ik = A[i*K+k], B_kj = B[k*N+j],
@@ -25,31 +44,32 @@
  *
  * Element types (cyc_dtype):
  *   CYC_BF16_F32  A,B bfloat16; products exact, partial sums fp32; C fp32.
- *                 The summation order over k is fixed per shape (bit-identical
- *                 results run to run) but is not the strictly sequential order
- *                 of the cell chain; it agrees with it to within fp32 rounding
- *                 of a K-term sum.  One exception: unbatched problems with at
- *                 most 64 output blocks of 128 x 128 and K >= 4096 run with k
- *                 mapped to space ("mfmak": k-slices on different workgroups
- *                 add their partial sums to C atomically, the paper's hand-over
- *                 of [i,k]_C from cell to cell); there the order of those adds,
- *                 and with it the last bits of C, can differ from call to call.
- *                 CYC_FORCE_KERNEL=mfma128 restores the fixed order.
+ *                 The summation order over k is a fixed function of the shape,
+ *                 the alignment of the operands and the kernel in force: the
+ *                 same call gives bit-identical results every time, with no
+ *                 atomic adds anywhere.  It is not the strictly sequential
+ *                 order of the cell chain but agrees with it to within fp32
+ *                 rounding of a K-term sum.
  *   CYC_I8_I32    A,B int8; partial sums int32, wrapping modulo 2^32; C int32.
  *                 Bit-exact for any summation order.
  *
  * Degenerate extents: M == 0, N == 0 or batch == 0 do nothing and return
  * CYC_OK; K == 0 fills C with zeros (the initial value of every chain).
- * Any M, K, N >= 1 is accepted.  The MFMA paths need 16-byte aligned base
- * pointers, batch strides and rows of A and B (K and N multiples of 8 for
- * bfloat16, of 16 for int8) but no particular multiples otherwise; anything
- * else runs on a slower shape-agnostic kernel.
+ * Any M, K, N >= 1 and any batch >= 1 whose element counts fit (each of
+ * M*K, K*N, M*N and the batched spans below 2^46) is accepted.  The fast paths need
+ * 16-byte aligned base pointers, batch strides and rows of A and B (K and N
+ * multiples of 8 for bfloat16, of 16 for int8) but no particular multiples
+ * otherwise; anything else runs on a slower shape-agnostic kernel.
  *
- * The environment variable CYC_FORCE_KERNEL (generic | mfma256 | mfma128 |
- * mfma256x32 | mfma128x32 | mfmak | narrow), read at every call, overrides the choice
- * of kernel when the named kernel supports the problem; it exists for tests
- * and benchmarks.  (The x32 kernels use the 32x32 MFMA shape instead of the
- * 16x16 one; the dispatcher never picks them by itself.)
+ * Kernel families and when the dispatcher picks them:
+ *   narrow   N <= 16, many rows: A streamed once from memory, B resident.
+ *   narrowm  M <= 32, B of at least a mebibyte: B streamed once, the rows of
+ *            A pass over it ((j,k) in space).
+ *   mfmak    unbatched, at most 64 output blocks of 128 x 128, K >= 4096: k in
+ *            space; k-slices on different workgroups leave partial sums in the
+ *            workspace and a second kernel adds them in ascending slice order.
+ *   mfma256 / mfma128  everything else with aligned rows.
+ *   generic  the rest.
  */
 #ifndef CYCLOTRON_MM_H
 #define CYCLOTRON_MM_H
@@ -68,10 +88,11 @@ typedef enum {
 typedef enum {
     CYC_OK = 0,
     CYC_ERR_NULL = 1,    /* a required pointer is NULL while its extent is not empty */
-    CYC_ERR_SHAPE = 2,   /* negative extent, negative stride, or element count overflow */
+    CYC_ERR_SHAPE = 2,   /* negative extent, negative stride, element count overflow, or an argument out of its documented range */
     CYC_ERR_DTYPE = 3,   /* dtype is not a cyc_dtype */
     CYC_ERR_ALIAS = 4,   /* C overlaps A or B */
-    CYC_ERR_LAUNCH = 5   /* the HIP runtime refused the launch */
+    CYC_ERR_LAUNCH = 5,  /* the HIP runtime refused a launch */
+    CYC_ERR_WORKSPACE = 6 /* the workspace a k-in-space problem needs could not be allocated */
 } cyc_status;
 
 /* One grid: C (M x N) <- A (M x K) streamed against B (K x N).
@@ -109,9 +130,11 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  *     and the pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
  * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates
  *     nothing and keeps no state.  n == 0 or nrhs == 0: CYC_OK, nothing done.  A zero on the diagonal
- *     gives infinities or NaNs as IEEE division does, not an error.
+ *     gives infinities or NaNs as IEEE division does, not an error.  Inside the kernels, waves hand solved rows
+ *     to one another through LDS with bounded waits; a wait that ever ran out would fill the affected tile of X
+ *     and Xh with NaN rather than go on with stale values.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or overflowing extents, nb out of
- * range), CYC_ERR_ALIAS (X or Xh overlaps L, B or each other), CYC_ERR_LAUNCH. */
+ * range), CYC_ERR_ALIAS (X or Xh overlaps L, B or each other).  CYC_ERR_LAUNCH: see the top of this file. */
 int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
                         int64_t n, int64_t nrhs, int64_t nb, void *stream);
 
@@ -140,7 +163,8 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
  *     by a lock.  n == 0: CYC_OK, nothing done.  A matrix that is not positive definite gives NaNs (square root
  *     of a negative number), not an error.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or too large n, nb out of range, A or L not
- * 4-byte or Lh not 2-byte aligned), CYC_ERR_ALIAS (A, L, Lh overlap one another), CYC_ERR_LAUNCH. */
+ * 4-byte or Lh not 2-byte aligned), CYC_ERR_ALIAS (A, L, Lh overlap one another).  CYC_ERR_LAUNCH: see the top of
+ * this file; work already on the second stream is joined back into `stream` before the call returns. */
 int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *stream);
 
 /* Attention by the tile recurrence of the paper's "FlashAttention-2 Recurrence": per query a running
@@ -154,7 +178,7 @@ int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t
  * exponentials enter the product with V rounded to bfloat16.  stream: hipStream_t or NULL; asynchronous,
  * allocates nothing.  batch == 0 or N == 0: CYC_OK, nothing done.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative extents, M == 0 with N > 0, unsupported d,
- * misaligned pointers, sizes out of range), CYC_ERR_ALIAS (O overlaps Q, K or V), CYC_ERR_LAUNCH. */
+ * misaligned pointers, batch > 65535, sizes out of range), CYC_ERR_ALIAS (O overlaps Q, K or V), CYC_ERR_LAUNCH. */
 int cyc_recurrence_attention(const void *Q, const void *K, const void *V, void *O,
                              int64_t batch, int64_t N, int64_t M, int64_t d, void *stream);
 
@@ -165,12 +189,31 @@ const char *cyc_status_string(int status);
 int cyc_version(void);
 
 /* Name of the kernel family the dispatcher would pick for this problem
- * ("mfma256", "mfma128", "mfmak", "narrow", "generic", "zero", "none", or a name forced
- * through CYC_FORCE_KERNEL); static storage.
+ * ("mfma256", "mfma128", "mfmak", "narrow", "narrowm", "generic", "zero", "none", or the forced one); static storage.
  * Host only; enqueues nothing.  Pointers are only inspected for alignment. */
 const char *cyc_kernel_name(const void *A, const void *B, const void *C,
                             int64_t batch, int64_t M, int64_t K, int64_t N,
                             int64_t strideA, int64_t strideB, int64_t strideC, int dtype);
+
+/* Testing and benchmarking aid: from now on, in every thread, use the named kernel family (generic | mfma256 |
+ * mfma128 | mfma256x32 | mfma128x32 | mfmak | narrow | narrowm) wherever it supports the problem; NULL or "" gives the
+ * choice back to the dispatcher.  The x32 kernels use the 32x32 MFMA shape instead of the 16x16 one; the dispatcher
+ * never picks them by itself.  The environment variable CYC_FORCE_KERNEL, read once when the library first chooses
+ * a kernel, supplies the initial value.  Returns CYC_ERR_SHAPE for an unknown name. */
+int cyc_force_kernel(const char *name);
+
+/* Measurement aid: one launch of `iters` rounds of back-to-back MFMAs (dtype: a cyc_dtype; mfma_shape 16: 16x16
+ * instructions, 32: 32x32) from registers on random-looking operands, four waves on every compute unit, no LDS or
+ * memory traffic: what the matrix pipes sustain on this chip when nothing else happens.  *ops (host, may be NULL)
+ * receives the operations of one launch; time the launch with events on `stream`.  sink: device, 4 bytes, in
+ * practice never written.  iters even, 2 .. 2^24. */
+int cyc_diag_mfma_ceiling(int dtype, int mfma_shape, int64_t iters, void *sink, double *ops, void *stream);
+
+/* Measurement aid: one wave that runs for `microseconds` (1 .. 2000000) and then writes to out (device, two
+ * uint64_t, 8-byte aligned) the shader clock cycles and the ticks of the constant 100 MHz counter that went by.
+ * Launched on a second stream beside other kernels it gives the engine clock sustained under their load:
+ * GHz = out[0] / out[1] / 10. */
+int cyc_diag_clock(void *out, int64_t microseconds, void *stream);
 
 #ifdef __cplusplus
 }

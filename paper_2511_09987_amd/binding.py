@@ -42,6 +42,12 @@ def _load() -> ctypes.CDLL:
     lib.cyc_version.restype = cint
     lib.cyc_kernel_name.argtypes = [ptr, ptr, ptr, i64, i64, i64, i64, i64, i64, i64, cint]
     lib.cyc_kernel_name.restype = ctypes.c_char_p
+    lib.cyc_force_kernel.argtypes = [ctypes.c_char_p]
+    lib.cyc_force_kernel.restype = cint
+    lib.cyc_diag_mfma_ceiling.argtypes = [cint, cint, i64, ptr, ctypes.POINTER(ctypes.c_double), ptr]
+    lib.cyc_diag_mfma_ceiling.restype = cint
+    lib.cyc_diag_clock.argtypes = [ptr, i64, ptr]
+    lib.cyc_diag_clock.restype = cint
     return lib
 
 
@@ -95,6 +101,22 @@ def cyc_recurrence_attention(Q: int, K: int, V: int, O: int, batch: int, N: int,
 def cyc_kernel_name(A: int, B: int, C: int, batch: int, M: int, K: int, N: int,
                     strideA: int, strideB: int, strideC: int, dtype: int) -> str:
     return _lib().cyc_kernel_name(A, B, C, batch, M, K, N, strideA, strideB, strideC, dtype).decode()
+
+
+def cyc_force_kernel(name) -> int:
+    """Force a kernel family by name (None or "": back to the dispatcher); returns the cyc_status."""
+    return int(_lib().cyc_force_kernel((name or "").encode()))
+
+
+def cyc_diag_mfma_ceiling(dtype: int, mfma_shape: int, iters: int, sink: int, stream: int = 0):
+    """Raw call; returns (cyc_status, operations of the launch)."""
+    ops = ctypes.c_double(0.0)
+    st = int(_lib().cyc_diag_mfma_ceiling(dtype, mfma_shape, iters, sink, ctypes.byref(ops), stream))
+    return st, ops.value
+
+
+def cyc_diag_clock(out: int, microseconds: int, stream: int = 0) -> int:
+    return int(_lib().cyc_diag_clock(out, microseconds, stream))
 
 
 def recurrence_matmul(A, B, out=None, stream=None):

@@ -34,10 +34,6 @@ def build(verbose: bool = False) -> str:
         if verbose and out.strip():
             print(out)
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
-    # stand-alone probes (each a main program beside the library, not linked into it)
-    for src in sorted(glob.glob(os.path.join(HERE, "probes", "*.hip"))):
-        subprocess.run(["hipcc", *FLAGS, src, "-o", src[:-4] + ".bin"], check=True,
-                       stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
     return LIB
 
 

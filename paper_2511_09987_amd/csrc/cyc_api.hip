@@ -5,6 +5,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 
 namespace {
 
@@ -25,7 +26,7 @@ bool overlaps(const void *p, int64_t pbytes, const void *q, int64_t qbytes)
     return a < b + (uintptr_t)qbytes && b < a + (uintptr_t)pbytes;
 }
 
-enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_MFMA256X32, K_MFMA128X32, K_MFMAK, K_NARROW };
+enum Kernel { K_NONE, K_ZERO, K_GENERIC, K_MFMA256, K_MFMA128, K_MFMA256X32, K_MFMA128X32, K_MFMAK, K_NARROW, K_NARROWM };
 
 const char *kernel_label(Kernel k)
 {
@@ -39,8 +40,24 @@ const char *kernel_label(Kernel k)
         case K_MFMA128X32: return "mfma128x32";
         case K_MFMAK: return "mfmak";
         case K_NARROW: return "narrow";
+        case K_NARROWM: return "narrowm";
     }
     return "none";
+}
+
+// The kernel forced by cyc_force_kernel(), or by the environment variable CYC_FORCE_KERNEL, which is read once
+// (at the first call that gets as far as choosing a kernel) as the initial value.  K_NONE: the dispatcher decides.
+Kernel kernel_by_name(const char *name)
+{
+    if (!name) return K_NONE;
+    for (Kernel k : {K_GENERIC, K_MFMA256, K_MFMA128, K_MFMA256X32, K_MFMA128X32, K_MFMAK, K_NARROW, K_NARROWM})
+        if (!std::strcmp(name, kernel_label(k))) return k;
+    return K_NONE;
+}
+std::atomic<int> &forced_kernel()
+{
+    static std::atomic<int> forced{(int)kernel_by_name(std::getenv("CYC_FORCE_KERNEL"))};
+    return forced;
 }
 
 // Validates and fills `p`.  Returns CYC_OK with *k == K_NONE when there is nothing to do.
@@ -77,23 +94,23 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
 
     if (K == 0) { *k = K_ZERO; return CYC_OK; }
 
-    // CYC_FORCE_KERNEL=generic|mfma256|mfma128|mfma256x32|mfma128x32|mfmak|narrow overrides the heuristic when
-    // the named kernel supports the problem (testing and benchmarking aid).  The x32 names are the MFMA
-    // kernels built on the 32x32 instruction shape, which the dispatcher never picks by itself.
-    const char *force = std::getenv("CYC_FORCE_KERNEL");
+    // a forced kernel overrides the heuristic when it supports the problem (testing and benchmarking aid).  The x32
+    // names are the MFMA kernels built on the 32x32 instruction shape, which the dispatcher never picks by itself.
+    const Kernel force = (Kernel)forced_kernel().load(std::memory_order_relaxed);
     int ktile = 0;
-    if (force && *force) {
-        if (!std::strcmp(force, "generic")) { *k = K_GENERIC; return CYC_OK; }
-        if (!std::strcmp(force, "mfma256") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256; return CYC_OK; }
-        if (!std::strcmp(force, "mfma128") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128; return CYC_OK; }
-        if (!std::strcmp(force, "mfma256x32") && cyc::supports_mfma(*p, 256)) { *k = K_MFMA256X32; return CYC_OK; }
-        if (!std::strcmp(force, "mfma128x32") && cyc::supports_mfma(*p, 128)) { *k = K_MFMA128X32; return CYC_OK; }
-        if (!std::strcmp(force, "narrow") && cyc::supports_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
-        if (!std::strcmp(force, "mfmak") && cyc::choose_ksplit(*p, &ktile) > 1) { *k = K_MFMAK; return CYC_OK; }
+    switch (force) {
+        case K_GENERIC: *k = K_GENERIC; return CYC_OK;
+        case K_MFMA256: case K_MFMA256X32: if (cyc::supports_mfma(*p, 256)) { *k = force; return CYC_OK; } break;
+        case K_MFMA128: case K_MFMA128X32: if (cyc::supports_mfma(*p, 128)) { *k = force; return CYC_OK; } break;
+        case K_NARROW: if (cyc::supports_narrow(*p)) { *k = force; return CYC_OK; } break;
+        case K_NARROWM: if (cyc::supports_narrowm(*p)) { *k = force; return CYC_OK; } break;
+        case K_MFMAK: if (cyc::choose_ksplit(*p, &ktile) > 1) { *k = force; return CYC_OK; } break;
+        default: break;
     }
     if (cyc::prefers_narrow(*p)) { *k = K_NARROW; return CYC_OK; }
+    if (cyc::prefers_narrowm(*p)) { *k = K_NARROWM; return CYC_OK; }
     // few output blocks, long k: k goes to space (see choose_ksplit)
-    if (!(force && *force) && cyc::choose_ksplit(*p, &ktile) > 1) { *k = K_MFMAK; return CYC_OK; }
+    if (force == K_NONE && cyc::choose_ksplit(*p, &ktile) > 1) { *k = K_MFMAK; return CYC_OK; }
     // MFMA kernels for everything with 16-byte aligned rows except slivers
     const int tile = cyc::choose_mfma_tile(*p);
     if (tile == 256) { *k = K_MFMA256; return CYC_OK; }
@@ -102,7 +119,7 @@ int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, 
     return CYC_OK;
 }
 
-int run(const cyc::Problem &p, Kernel k, hipStream_t s)
+int run_chunk(const cyc::Problem &p, Kernel k, void *workspace, hipStream_t s)
 {
     hipError_t e = hipSuccess;
     switch (k) {
@@ -116,12 +133,40 @@ int run(const cyc::Problem &p, Kernel k, hipStream_t s)
         case K_MFMAK: {
             int tile = 0;
             const int ks = cyc::choose_ksplit(p, &tile);
-            e = cyc::launch_mfma_ksplit(p, ks, tile, s);
+            e = cyc::launch_mfma_ksplit(p, ks, tile, workspace, s);
             break;
         }
         case K_NARROW: e = cyc::launch_narrow(p, s); break;
+        case K_NARROWM: e = cyc::launch_narrowm(p, s); break;
     }
     return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
+// A grid's y extent ends at 65535, which is where a launch's share of the batch ends: longer batches take several
+// launches of the same kernel (batch elements are independent).
+constexpr int64_t kBatchPerLaunch = 65535;
+
+int run(const cyc::Problem &p, Kernel k, hipStream_t s)
+{
+    void *workspace = nullptr;
+    if (k == K_MFMAK) {
+        // everything that can fail before the first launch is settled before it
+        int tile = 0;
+        const int ks = cyc::choose_ksplit(p, &tile);
+        workspace = cyc::cached_workspace(s, cyc::ksplit_workspace_bytes(p, ks));
+        if (!workspace) return CYC_ERR_WORKSPACE;
+    }
+    if (p.batch <= kBatchPerLaunch) return run_chunk(p, k, workspace, s);
+    const int64_t es = p.i8 ? 1 : 2;
+    for (int64_t b0 = 0; b0 < p.batch; b0 += kBatchPerLaunch) {
+        cyc::Problem q = p;
+        q.batch = p.batch - b0 < kBatchPerLaunch ? p.batch - b0 : kBatchPerLaunch;
+        q.A = (const char *)p.A + b0 * p.strideA * es;
+        q.B = (const char *)p.B + b0 * p.strideB * es;
+        q.C = (char *)p.C + b0 * p.strideC * 4;
+        if (int st = run_chunk(q, k, workspace, s); st != CYC_OK) return st;
+    }
+    return CYC_OK;
 }
 
 }  // namespace
@@ -135,7 +180,7 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C, int64_t
     cyc::Problem p;
     Kernel k;
     int st = plan(A, B, C, batch, M, K, N, strideA, strideB, strideC, dtype, &p, &k);
-    if (st != CYC_OK) return st;
+    if (st != CYC_OK || k == K_NONE) return st;      // an error, or nothing to do (p is then not filled in)
     return run(p, k, (hipStream_t)stream);
 }
 
@@ -203,10 +248,23 @@ const char *cyc_status_string(int status)
         case CYC_ERR_DTYPE: return "CYC_ERR_DTYPE: unknown element type";
         case CYC_ERR_ALIAS: return "CYC_ERR_ALIAS: C overlaps an input";
         case CYC_ERR_LAUNCH: return "CYC_ERR_LAUNCH: HIP launch failed";
+        case CYC_ERR_WORKSPACE: return "CYC_ERR_WORKSPACE: workspace could not be allocated or is too small";
     }
     return "unknown cyc_status";
 }
 
-int cyc_version(void) { return 100; }
+int cyc_version(void) { return 200; }
+
+int cyc_force_kernel(const char *name)
+{
+    if (!name || !*name) {
+        forced_kernel().store((int)K_NONE);
+        return CYC_OK;
+    }
+    const Kernel k = kernel_by_name(name);
+    if (k == K_NONE) return CYC_ERR_SHAPE;
+    forced_kernel().store((int)k);
+    return CYC_OK;
+}
 
 }  // extern "C"

@@ -155,7 +155,9 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
     f32x4 s[KB][QB], s_next[KB][QB];                                  // S^T of tiles t and t+1: [key block][query block]
     i32x4 pf[QB][KB / 2];                                             // P^T as B operand: [query block][32-key step]
     float tile_max[QB];                                               // maximum of the newest S^T per query, log2 domain
-    auto landed_barrier = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory"); };
+    // this wave's copies have landed and its LDS reads have returned (the stages it read are about to be requested into
+    // again by other waves); then meet the other waves
+    auto landed_barrier = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
     // ---- O^T += V^T P^T for tile t (in V stage t&1).  A operand lane: d = 16 id + l%16; k-slots 0..3 = keys
     // 32 sk + 4 (l/16) .. +3, k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in)
@@ -329,13 +331,14 @@ hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O
     const int64_t nqb = (N + NWAVE * QW - 1) / (NWAVE * QW);  // query blocks per batch element
     if (nqb * batch >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
     dim3 grid((unsigned)(nqb * batch));
+    hipError_t launch_err = hipSuccess;
     if (d == 128)
-        hipLaunchKernelGGL((attn_kernel<128, 64>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
+        launch_err = launch_kernel(attn_kernel<128, 64>, grid, dim3(NWAVE * 64), s, (const char *)Q, (const char *)K,
                            (const char *)V, (float *)O, (int)N, (int)M, (int)nqb, scale_log2e);
     else
-        hipLaunchKernelGGL((attn_kernel<64, 128>), grid, dim3(NWAVE * 64), 0, s, (const char *)Q, (const char *)K,
+        launch_err = launch_kernel(attn_kernel<64, 128>, grid, dim3(NWAVE * 64), s, (const char *)Q, (const char *)K,
                            (const char *)V, (float *)O, (int)N, (int)M, (int)nqb, scale_log2e);
-    return hipGetLastError();
+    return launch_err;
 }
 
 }  // namespace cyc

@@ -598,14 +598,17 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
         }
         } else if (fused && nks_e > 0) {
             // ---- the next diagonal tile, second part, by the three waves beside the recurrence: when the copies of all
-            // three have arrived (a counter in LDS; the wait is bounded), the early k-steps
+            // three have arrived (a counter in LDS), the early k-steps.  The wait is bounded; should it ever run out,
+            // the product is made of NaNs, so that the tile comes out as NaN rather than as plausible wrong numbers.
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (lane == 0) __hip_atomic_fetch_add(&lds.landed, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-            for (int polls = 0; __hip_atomic_load(&lds.landed, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 3 && polls < (1 << 20); ++polls) {}
+            int polls = 0;
+            while (__hip_atomic_load(&lds.landed, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 3 && ++polls < (1 << 20)) {}
+            const int poison = polls >= (1 << 20) ? 0x7fc07fc0 : 0;      // two bfloat16 NaNs; OR-ed into every operand word
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks)
                 if (ks < nks_e) {
-                    const i32x4 a2[2] = {an[0][ks], an[1][ks]};
+                    const i32x4 a2[2] = {an[0][ks] | poison, an[1][ks] | poison};
                     k_step(ks, a2);
                 }
         }
@@ -707,6 +710,12 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
     SideStreamLock side_lock;
     SideStream *side = n > 2 * GROUP * nb ? side_lock.acquire() : nullptr;
     int64_t ahead = -1;               // first column of the group whose product over the groups before the last is on the side stream
+    bool unjoined = false;            // work is on the side stream that the caller's stream does not wait for yet
+    // a refused launch ends the call: what is already on the side stream is first joined back into the caller's stream
+    auto fail = [&](hipError_t e) {
+        if (unjoined) (void)hipStreamWaitEvent(s, side->join[0], 0);
+        return e;
+    };
     for (int64_t j0 = 0; j0 < n; j0 += nb) {
         const int cols = (int)(j0 + nb <= n ? nb : n - j0);
         const int64_t j1 = j0 + cols;
@@ -717,10 +726,11 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (ahead == g0) {
                 // the part over the groups before the last was multiplied out on the side stream while the last group
                 // was being factored; what is left is the k range of that group
-                if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return e;
-                if (hipError_t e = product(g0, g0, gcols, g0 - GROUP * nb, g0, L, s); e != hipSuccess) return e;
+                if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return fail(e);
+                unjoined = false;
+                if (hipError_t e = product(g0, g0, gcols, g0 - GROUP * nb, g0, L, s); e != hipSuccess) return fail(e);
             } else {
-                if (hipError_t e = product(g0, g0, gcols, 0, g0, A, s); e != hipSuccess) return e;
+                if (hipError_t e = product(g0, g0, gcols, 0, g0, A, s); e != hipSuccess) return fail(e);
             }
             // The product for the NEXT group over everything left of this group does not depend on this group: it goes
             // to the side stream now and runs on the compute units that the tile kernels of this group (at most one
@@ -728,10 +738,13 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             const int64_t g1 = g0 + GROUP * nb;
             if (side && g1 < n) {
                 const int64_t ncols = g1 + GROUP * nb <= n ? GROUP * nb : n - g1;
-                if (hipError_t e = hipEventRecord(side->fork, s); e != hipSuccess) return e;
-                if (hipError_t e = hipStreamWaitEvent(side->stream, side->fork, 0); e != hipSuccess) return e;
-                if (hipError_t e = product(g1, g1, ncols, 0, g0, A, side->stream); e != hipSuccess) return e;
-                if (hipError_t e = hipEventRecord(side->join[0], side->stream); e != hipSuccess) return e;
+                if (hipError_t e = hipEventRecord(side->fork, s); e != hipSuccess) return fail(e);
+                if (hipError_t e = hipStreamWaitEvent(side->stream, side->fork, 0); e != hipSuccess) return fail(e);
+                const hipError_t pe = product(g1, g1, ncols, 0, g0, A, side->stream);
+                // whatever reached the side stream is covered by the join event, also when the product was refused
+                if (hipError_t e = hipEventRecord(side->join[0], side->stream); e != hipSuccess) return fail(e);
+                unjoined = true;
+                if (pe != hipSuccess) return fail(pe);
                 ahead = g1;
             }
         }
@@ -743,13 +756,13 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (nb == NBMAX && cols == NBMAX && n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && j0 - g0 <= KMAX) {
                 k0 = g0;
             } else {
-                if (hipError_t e = product(j0, j0, cols, g0, j0, Sm, s); e != hipSuccess) return e;
+                if (hipError_t e = product(j0, j0, cols, g0, j0, Sm, s); e != hipSuccess) return fail(e);
                 Sm = L;
             }
         }
         if (!diag_done) {
-            hipLaunchKernelGGL(chol_diag_kernel, dim3(1), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0);
-            if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+            hipError_t e = launch_kernel(chol_diag_kernel, dim3(1), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0);
+            if (e != hipSuccess) return fail(e);
         }
         diag_done = false;
         if (j1 < n) {
@@ -758,16 +771,16 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             const bool fuse = k0 == g0 && nb == NBMAX && cols == NBMAX && j1 + NBMAX <= n && j1 < g0 + GROUP * nb &&
                               n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)L % 16 == 0 &&
                               j1 - g0 <= KMAX;
-            hipLaunchKernelGGL(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), 0, s, Sm, L, Lh, n, j0, cols, k0,
+            hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
                                fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr);
-            if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+            if (e != hipSuccess) return fail(e);
             diag_done = fuse;
         }
     }
     // the products wrote S above the diagonal too (a group's columns start at the group's first row)
-    hipLaunchKernelGGL(chol_zero_upper_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 4096 ? n : 4096)), dim3(256), 0,
+    hipError_t e = launch_kernel(chol_zero_upper_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 4096 ? n : 4096)), dim3(256),
                        s, L, n);
-    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    if (e != hipSuccess) return e;
     return hipSuccess;
 }
 

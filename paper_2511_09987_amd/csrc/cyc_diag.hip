@@ -1,0 +1,132 @@
+// cyc_diag.hip -- two measurement aids exported beside the recurrence kernels (declared in cyclotron_mm.h).
+//
+// cyc_diag_mfma_ceiling: what the matrix pipes of this chip sustain when nothing else happens.  Every wave keeps its
+// operand fragments and 256 accumulator registers in place and issues MFMAs of one shape back to back on
+// random-looking operands; no LDS, no memory traffic in the loop.  On a power-limited part this, not the datasheet
+// figure, is what a GEMM on dense random data can approach, and it differs between the two MFMA shapes.
+//
+// cyc_diag_clock: one wave that reads the shader clock counter and the constant 100 MHz counter for a given time
+// while other kernels run, which gives the engine clock the chip sustains under that load.
+#include "../../include/cyclotron_mm.h"
+#include "cyc_internal.h"
+
+namespace cyc {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352du;
+    x ^= x >> 15; x *= 0x846ca68bu;
+    return x ^ (x >> 16);
+}
+// two bf16 values with random sign and mantissa and magnitudes around 0.03 .. 1, or four random int8 values
+template <bool I8> __device__ __forceinline__ int operand_word(uint32_t h)
+{
+    if (I8) return (int)h;
+    const uint32_t lo = ((h & 1) << 15) | ((121 + ((h >> 1) % 6)) << 7) | ((h >> 4) & 127);
+    const uint32_t hi = (((h >> 11) & 1) << 15) | ((121 + ((h >> 12) % 6)) << 7) | ((h >> 15) & 127);
+    return (int)(lo | (hi << 16));
+}
+
+// MT = 32: 4 x 4 operand fragments, 16 accumulators of 16 registers.  MT = 16: 8 x 8 fragments, 64 accumulators of
+// 4 registers, half as many outer iterations: the same operations per launch.
+template <bool I8, int MT>
+__global__ __launch_bounds__(256) void mfma_ceiling_kernel(int *sink, int iters)
+{
+    constexpr int NF = MT == 32 ? 4 : 8;
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    i32x4 a[NF], b[NF];
+#pragma unroll
+    for (int i = 0; i < NF; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            a[i][r] = operand_word<I8>(mix32(t * 64 + i * 4 + r));
+            b[i][r] = operand_word<I8>(mix32(t * 64 + 32 + i * 4 + r));
+        }
+    typedef typename std::conditional<MT == 32, typename std::conditional<I8, i32x16, f32x16>::type,
+                                      typename std::conditional<I8, i32x4, f32x4>::type>::type acc_t;
+    acc_t acc[NF * NF];
+#pragma unroll
+    for (int i = 0; i < NF * NF; ++i)
+#pragma unroll
+        for (int r = 0; r < MT * MT / 64; ++r) acc[i][r] = 0;
+    for (int it = 0; it < (MT == 32 ? iters : iters / 2); ++it) {
+#pragma unroll
+        for (int i = 0; i < NF; ++i)
+#pragma unroll
+            for (int j = 0; j < NF; ++j) {
+                acc_t &c = acc[i * NF + j];
+                if constexpr (MT == 32 && I8) c = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], c, 0, 0, 0);
+                else if constexpr (MT == 32) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[j]), c, 0, 0, 0);
+                else if constexpr (I8) c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], c, 0, 0, 0);
+                else c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[j]), c, 0, 0, 0);
+            }
+        // the operands change a little every iteration (low mantissa bits only), as they would in a real k loop
+#pragma unroll
+        for (int i = 0; i < NF; ++i) a[i] = a[i] ^ (i32x4){it & 0x7f, it & 0x7f, it & 0x7f, it & 0x7f};
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < NF * NF; ++i) s += __builtin_bit_cast(int, acc[i][0]);
+    if (s == 0x12345678) sink[0] = s;      // keeps the loop alive; practically never true
+}
+
+__global__ __launch_bounds__(64) void clock_kernel(uint64_t *out, int64_t ticks)
+{
+    const uint64_t w0 = wall_clock64(), c0 = clock64();
+    uint64_t w1 = w0;
+    while ((int64_t)(w1 - w0) < ticks) {
+        __builtin_amdgcn_s_sleep(32);
+        w1 = wall_clock64();
+    }
+    const uint64_t c1 = clock64();
+    if (threadIdx.x == 0) {
+        out[0] = c1 - c0;
+        out[1] = w1 - w0;
+    }
+}
+
+}  // namespace
+}  // namespace cyc
+
+extern "C" {
+
+int cyc_diag_mfma_ceiling(int dtype, int mfma_shape, int64_t iters, void *sink, double *ops, void *stream)
+{
+    if (dtype != CYC_BF16_F32 && dtype != CYC_I8_I32) return CYC_ERR_DTYPE;
+    if ((mfma_shape != 16 && mfma_shape != 32) || iters < 2 || iters > (1 << 24) || (iters & 1)) return CYC_ERR_SHAPE;
+    if (!sink) return CYC_ERR_NULL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return CYC_ERR_LAUNCH;
+    const bool i8 = dtype == CYC_I8_I32;
+    // per wave and outer iteration 16 MFMAs of 32 x 32 x (16 | 32), i.e. 2 * 32 * 32 * k operations each
+    if (ops) *ops = (double)cus * 4 * (double)iters * 16 * 2.0 * 32 * 32 * (i8 ? 32 : 16);
+    dim3 grid((unsigned)cus), block(256);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_shape == 32)
+        e = i8 ? cyc::launch_kernel(cyc::mfma_ceiling_kernel<true, 32>, grid, block, s, (int *)sink, (int)iters)
+               : cyc::launch_kernel(cyc::mfma_ceiling_kernel<false, 32>, grid, block, s, (int *)sink, (int)iters);
+    else
+        e = i8 ? cyc::launch_kernel(cyc::mfma_ceiling_kernel<true, 16>, grid, block, s, (int *)sink, (int)iters)
+               : cyc::launch_kernel(cyc::mfma_ceiling_kernel<false, 16>, grid, block, s, (int *)sink, (int)iters);
+    return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
+int cyc_diag_clock(void *out, int64_t microseconds, void *stream)
+{
+    if (!out) return CYC_ERR_NULL;
+    if (microseconds < 1 || microseconds > 2000000 || ((uintptr_t)out & 7)) return CYC_ERR_SHAPE;
+    const hipError_t e = cyc::launch_kernel(cyc::clock_kernel, dim3(1), dim3(64), (hipStream_t)stream, (uint64_t *)out,
+                                            microseconds * 100);
+    return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -80,18 +80,28 @@ __global__ __launch_bounds__(256) void ws_zero_kernel(Acc *__restrict__ C, int64
 
 hipError_t launch_generic(const Problem &p, hipStream_t s)
 {
-    // gridDim.y and .z are limited to 65535
-    if ((p.M + GT - 1) / GT > 65535 || p.batch > 65535) return hipErrorInvalidValue;
-    dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.batch);
-    if (p.i8)
-        hipLaunchKernelGGL((ws_generic_kernel<int8_t, int>), grid, dim3(256), 0, s, (const int8_t *)p.A,
-                           (const int8_t *)p.B, (int *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC, row_stride_a(p),
-                           row_stride_b(p), row_stride_c(p), (const int *)p.Cin);
-    else
-        hipLaunchKernelGGL((ws_generic_kernel<uint16_t, float>), grid, dim3(256), 0, s, (const uint16_t *)p.A,
-                           (const uint16_t *)p.B, (float *)p.C, p.M, p.K, p.N, p.strideA, p.strideB, p.strideC,
-                           row_stride_a(p), row_stride_b(p), row_stride_c(p), (const float *)p.Cin);
-    return hipGetLastError();
+    // gridDim.y and .z end at 65535: the caller keeps the batch below that; more than 65535 * 64 rows take several
+    // launches (rows are independent)
+    if (p.batch > 65535) return hipErrorInvalidValue;
+    constexpr int64_t ROWS_PER_LAUNCH = (int64_t)65535 * GT;
+    const int64_t lda = row_stride_a(p), ldc = row_stride_c(p), es = p.i8 ? 1 : 2;
+    for (int64_t r0 = 0; r0 < p.M; r0 += ROWS_PER_LAUNCH) {
+        const int64_t rows = p.M - r0 < ROWS_PER_LAUNCH ? p.M - r0 : ROWS_PER_LAUNCH;
+        const char *A = (const char *)p.A + r0 * lda * es;
+        char *C = (char *)p.C + r0 * ldc * 4;
+        const char *Cin = p.Cin ? (const char *)p.Cin + r0 * ldc * 4 : nullptr;
+        dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((rows + GT - 1) / GT), (unsigned)p.batch);
+        hipError_t e;
+        if (p.i8)
+            e = launch_kernel(ws_generic_kernel<int8_t, int>, grid, dim3(256), s, (const int8_t *)A, (const int8_t *)p.B, (int *)C,
+                              rows, p.K, p.N, p.strideA, p.strideB, p.strideC, lda, row_stride_b(p), ldc, (const int *)Cin);
+        else
+            e = launch_kernel(ws_generic_kernel<uint16_t, float>, grid, dim3(256), s, (const uint16_t *)A, (const uint16_t *)p.B,
+                              (float *)C, rows, p.K, p.N, p.strideA, p.strideB, p.strideC, lda, row_stride_b(p), ldc,
+                              (const float *)Cin);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_zero(const Problem &p, hipStream_t s)
@@ -101,11 +111,12 @@ hipError_t launch_zero(const Problem &p, hipStream_t s)
     int64_t blocks = (count + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks, (unsigned)p.batch);
+    hipError_t launch_err = hipSuccess;
     if (p.i8)
-        hipLaunchKernelGGL((ws_zero_kernel<int>), grid, dim3(256), 0, s, (int *)p.C, count, p.strideC);
+        launch_err = launch_kernel(ws_zero_kernel<int>, grid, dim3(256), s, (int *)p.C, count, p.strideC);
     else
-        hipLaunchKernelGGL((ws_zero_kernel<float>), grid, dim3(256), 0, s, (float *)p.C, count, p.strideC);
-    return hipGetLastError();
+        launch_err = launch_kernel(ws_zero_kernel<float>, grid, dim3(256), s, (float *)p.C, count, p.strideC);
+    return launch_err;
 }
 
 }  // namespace cyc

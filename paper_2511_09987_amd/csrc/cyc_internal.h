@@ -4,7 +4,23 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+#include <utility>
+
 namespace cyc {
+
+// Enqueue `kernel` and return the status of this launch itself: unlike the triple-chevron form followed by
+// hipGetLastError(), this neither consumes nor reports an error that an earlier call of the application left behind.
+template <typename... KArgs, typename... Args>
+inline hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s, Args &&...args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count does not match the kernel's signature");
+    std::tuple<std::remove_cv_t<KArgs>...> vals(static_cast<std::remove_cv_t<KArgs>>(args)...);
+    void *ptrs[sizeof...(KArgs)];
+    std::apply([&](auto &...v) { int i = 0; ((ptrs[i++] = (void *)&v), ...); }, vals);
+    return hipLaunchKernel((const void *)kernel, grid, block, ptrs, 0, s);
+}
 
 struct Problem {
     const void *A, *B;
@@ -18,7 +34,7 @@ struct Problem {
     int64_t ldb = 0;                     // row stride of B in elements, 0 = N
     int64_t ldc = 0;                     // row stride of C (and of Cin) in elements, 0 = N
     const void *Cin = nullptr;           // when set, C <- Cin - A*B instead of C <- A*B (same layout as C; may be C)
-    bool accumulate = false;             // the epilogue adds its product to C atomically (the k-in-space variant)
+    bool kslices = false;                // the batch elements are k-slices of one problem (windows allowed with batch > 1)
 };
 inline int64_t row_stride_a(const Problem &p) { return p.lda ? p.lda : p.K; }
 inline int64_t row_stride_b(const Problem &p) { return p.ldb ? p.ldb : p.N; }
@@ -34,10 +50,14 @@ hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s);   // 
 // block edge (256 or 128) of the MFMA kernel that suits the problem best, 0 if neither supports it
 int choose_mfma_tile(const Problem &p);
 // k in space: number of k-slices (a power of two, 1 = do not split) for problems with few output blocks and a
-// long k extent, and the launch that zeroes C and lets one workgroup per (output block, k-slice) add its partial
-// product to C atomically
+// long k extent.  One workgroup per (output block, k-slice) writes its partial product to slice `b` of a workspace
+// of ksplit x M x N accumulator elements; a second kernel adds the slices in ascending order into C.
 int choose_ksplit(const Problem &p, int *tile);   // *tile: block edge to use, 128 or 256
-hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, hipStream_t s);
+inline int64_t ksplit_workspace_bytes(const Problem &p, int ksplit) { return (int64_t)ksplit * p.M * p.N * 4; }
+hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, void *workspace, hipStream_t s);
+// Device memory for the partial products.  cached_workspace: one buffer per (device, stream), allocated with hipMalloc
+// on first use, grown when a call needs more, kept until the process ends; nullptr when the allocation fails.
+void *cached_workspace(hipStream_t s, int64_t bytes);
 // lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
 // A second stream per device for work that may run beside what a call enqueues on the caller's stream (forked from
 // and joined into that stream with events inside the call).  Created on first use, default priority, kept until the
@@ -70,5 +90,9 @@ hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O
 bool supports_narrow(const Problem &p);
 bool prefers_narrow(const Problem &p);   // supported and expected to beat the GEMM kernels
 hipError_t launch_narrow(const Problem &p, hipStream_t s);
+// HBM-bound streaming kernel for M <= 32 (B streamed once, the rows of A pass over it); requires supports_narrowm(p)
+bool supports_narrowm(const Problem &p);
+bool prefers_narrowm(const Problem &p);
+hipError_t launch_narrowm(const Problem &p, hipStream_t s);
 
 }  // namespace cyc

@@ -144,9 +144,9 @@ __device__ __forceinline__ void tile_fence()
 // RAGGED: M, N need not be multiples of the block and K need not be a multiple of the k-tile (rows of A
 // and B must still be 16-byte aligned).  Rows and columns past the edge re-read the last valid ones
 // and are not stored; in the last k-tile, chunks at or past K are not copied but written as zeros.
-// EPI: what the epilogue does with the accumulators: EPI_STORE C <- A*B; EPI_MINUS C <- Cin - A*B (Cin may be C);
-// EPI_ADD C += A*B with atomic adds (k in space).  A template parameter, so that each form is straight-line code.
-enum { EPI_STORE = 0, EPI_MINUS = 1, EPI_ADD = 2 };
+// EPI: what the epilogue does with the accumulators: EPI_STORE C <- A*B; EPI_MINUS C <- Cin - A*B (Cin may be C).
+// A template parameter, so that each form is straight-line code.
+enum { EPI_STORE = 0, EPI_MINUS = 1 };
 template <class C, bool RAGGED, int EPI>
 __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__ A, const char *__restrict__ B,
                                                         char *__restrict__ Cout, int M, int K, int N, int64_t sA,
@@ -426,10 +426,7 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
                 elem v = acc[i][j][r];
                 if (!RAGGED || (row < M && col < N)) {
                     if (EPI == EPI_MINUS) v = cin[j][r] - v;          // C <- Cin - A*B
-                    if (EPI == EPI_ADD)
-                        atomicAdd(&Cw[(int64_t)row * ldc + col], v);   // one of several k-slices handing on its partial sum
-                    else
-                        Cw[(int64_t)row * ldc + col] = v;
+                    Cw[(int64_t)row * ldc + col] = v;
                 }
             }
         }
@@ -442,27 +439,39 @@ hipError_t launch_epi(const Problem &p, hipStream_t s)
     const bool ragged = p.M % C::BM || p.N % C::BN || p.K % C::BKE;
     const int tiles_m = (int)((p.M + C::BM - 1) / C::BM), tiles_n = (int)((p.N + C::BN - 1) / C::BN);
     dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)p.batch);
+    hipError_t launch_err = hipSuccess;
     if (ragged)
-        hipLaunchKernelGGL((ws_mfma_kernel<C, true, EPI>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+        launch_err = launch_kernel(ws_mfma_kernel<C, true, EPI>, grid, dim3(C::NT), s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
                            (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
     else
-        hipLaunchKernelGGL((ws_mfma_kernel<C, false, EPI>), grid, dim3(C::NT), 0, s, (const char *)p.A, (const char *)p.B,
+        launch_err = launch_kernel(ws_mfma_kernel<C, false, EPI>, grid, dim3(C::NT), s, (const char *)p.A, (const char *)p.B,
                            (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC, tiles_m, tiles_n,
                            (int)row_stride_a(p), (int)row_stride_b(p), (int)row_stride_c(p), (const char *)p.Cin);
-    return hipGetLastError();
+    return launch_err;
 }
 
-// EXTRA: also build the EPI_MINUS and EPI_ADD forms (only the 16-wide MFMA shape, which is all their callers use)
+// EXTRA: also build the EPI_MINUS form (only the 16-wide MFMA shape, which is all its callers use)
 template <class C, bool EXTRA>
 hipError_t launch_cfg(const Problem &p, hipStream_t s)
 {
-    if (!p.Cin && !p.accumulate) return launch_epi<C, EPI_STORE>(p, s);
-    if constexpr (EXTRA) {
-        if (p.Cin && !p.accumulate) return launch_epi<C, EPI_MINUS>(p, s);
-        if (p.accumulate && !p.Cin) return launch_epi<C, EPI_ADD>(p, s);
-    }
+    if (!p.Cin) return launch_epi<C, EPI_STORE>(p, s);
+    if constexpr (EXTRA) return launch_epi<C, EPI_MINUS>(p, s);
     return hipErrorInvalidValue;
+}
+
+// C <- slice 0 + slice 1 + ... of the workspace, in that order for every element (the order of the adds is part of
+// the result for fp32), four elements per thread.
+template <typename V>
+__global__ __launch_bounds__(256) void ws_join_slices_kernel(const V *__restrict__ part, V *__restrict__ C, int64_t quads,
+                                                             int slices)
+{
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= quads) return;
+    V sum = part[q];
+#pragma unroll 8
+    for (int sl = 1; sl < slices; ++sl) sum += part[(int64_t)sl * quads + q];
+    C[q] = sum;
 }
 
 }  // namespace
@@ -477,8 +486,7 @@ bool supports_mfma(const Problem &p, int tile)
     const int64_t lda = row_stride_a(p), ldb = row_stride_b(p), ldc = row_stride_c(p);
     if ((p.K * es) % 16 || (p.N * es) % 16 || (lda * es) % 16 || lda < p.K) return false;
     if ((ldb * es) % 16 || ldb < p.N || ldc < p.N || ldb > (1 << 30) || ldc > (1 << 30)) return false;
-    if ((p.lda || p.ldb || p.ldc || p.Cin) && p.batch != 1 && !p.accumulate) return false;
-    if (p.accumulate && p.Cin) return false;
+    if ((p.lda || p.ldb || p.ldc || p.Cin) && p.batch != 1 && !p.kslices) return false;
     if (p.M > (1 << 30) || p.N > (1 << 30) || p.K > (1 << 30) || p.batch > 65535) return false;
     if (((p.M + tile - 1) / tile) * ((p.N + tile - 1) / tile) > (1 << 30)) return false;
     // per-lane byte offsets inside a tile's rows are kept in 32 bits
@@ -505,13 +513,13 @@ int choose_mfma_tile(const Problem &p)
 // The paper's weight-stationary mapping puts k in space: a cell keeps its A_ik and hands its partial sum east.
 // For problems with few output blocks and a long k extent this is the mapping that fills the chip: the k range
 // is cut into `ksplit` slices, every (output block, slice) pair is a workgroup that keeps its slice of A's block
-// row and of B's block column to itself, and the hand-over of the partial sum is an atomic add into C (zeroed
-// first: the chain's initial value).  Integer results are exact whatever the order of the adds; fp32 results
-// depend on it in the last bits.
+// row and of B's block column to itself and leaves its partial sum in its slice of a workspace; the hand-over
+// along k is a second kernel that adds the slices of every element in ascending slice order (a fixed order: the
+// result is the same bits on every call).
 int choose_ksplit(const Problem &p, int *tile)
 {
     *tile = 128;
-    if (p.batch != 1 || p.lda || p.ldb || p.ldc || p.Cin || p.accumulate || !supports_mfma(p, 128)) return 1;
+    if (p.batch != 1 || p.lda || p.ldb || p.ldc || p.Cin || p.kslices || !supports_mfma(p, 128)) return 1;
     const int64_t b128 = ((p.M + 127) / 128) * ((p.N + 127) / 128), b256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
     const int64_t bke = p.i8 ? 128 : 64;
     if (b128 > 64 || p.K < 4096) return 1;
@@ -530,21 +538,25 @@ int choose_ksplit(const Problem &p, int *tile)
     return ks;
 }
 
-hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, hipStream_t s)
+hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, void *workspace, hipStream_t s)
 {
-    if (ksplit < 2 || ksplit > 256 || p.batch != 1 || p.K % ksplit) return hipErrorInvalidValue;
-    if (hipError_t e = launch_zero(p, s); e != hipSuccess) return e;
+    if (ksplit < 2 || ksplit > 256 || p.batch != 1 || p.K % ksplit || !workspace || (p.M * p.N) % 4) return hipErrorInvalidValue;
     Problem q = p;
     q.batch = ksplit;                    // the batch index of the kernel serves as the slice index
+    q.kslices = true;
     q.K = p.K / ksplit;
     q.lda = p.K;
     q.ldb = p.N;
     q.ldc = p.N;
     q.strideA = q.K;                     // slice b starts at column b * K/ksplit of A ...
-    q.strideB = q.K * p.N;               // ... and at that row of B
-    q.strideC = 0;                       // all slices add to the same C
-    q.accumulate = true;
-    return launch_mfma(q, tile, 16, s);
+    q.strideB = q.K * p.N;               // ... and at that row of B ...
+    q.C = workspace;
+    q.strideC = p.M * p.N;               // ... and leaves its partial product in slice b of the workspace
+    if (hipError_t e = launch_mfma(q, tile, 16, s); e != hipSuccess) return e;
+    const int64_t quads = p.M * p.N / 4;
+    dim3 grid((unsigned)((quads + 255) / 256));
+    if (p.i8) return launch_kernel(ws_join_slices_kernel<i32x4>, grid, dim3(256), s, (const i32x4 *)workspace, (i32x4 *)p.C, quads, ksplit);
+    return launch_kernel(ws_join_slices_kernel<f32x4>, grid, dim3(256), s, (const f32x4 *)workspace, (f32x4 *)p.C, quads, ksplit);
 }
 
 hipError_t launch_mfma(const Problem &p, int tile, int mt, hipStream_t s)

@@ -261,10 +261,11 @@ hipError_t launch_one(const Problem &p, int rows_per_wg, hipStream_t s)
     const int es = I8 ? 1 : 2;
     const int b_vec = p.N == 16 && ((uintptr_t)p.B & 15) == 0 && (p.batch == 1 || ((p.strideB * es) & 15) == 0);
     dim3 grid((unsigned)((p.M + rows_per_wg - 1) / rows_per_wg), (unsigned)p.batch);
-    hipLaunchKernelGGL((ws_narrow_kernel<I8, S, FULL>), grid, dim3(NWAVES * 64), 0, s, (const char *)p.A,
+    hipError_t launch_err = hipSuccess;
+    launch_err = launch_kernel(ws_narrow_kernel<I8, S, FULL>, grid, dim3(NWAVES * 64), s, (const char *)p.A,
                        (const char *)p.B, (char *)p.C, (int)p.M, (int)p.K, (int)p.N, p.strideA, p.strideB, p.strideC,
                        rows_per_wg, b_vec);
-    return hipGetLastError();
+    return launch_err;
 }
 
 template <bool I8>

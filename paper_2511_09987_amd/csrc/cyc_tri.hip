@@ -418,8 +418,9 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
 // j as in the one-wave form, so the bits are the same; the path per phase is hand-over, 16 multiply-adds, corner.
 // Hand-over is a counter in LDS: the owner stores base + s + 1 (release) after its x, the others poll it (acquire).
 // A wave's LDS operations complete in order, and a wave in phase s waits only for the phase before, which waits for
-// nothing later, so the waits end; they are bounded anyway (SPIN_LIMIT polls, then the wave goes on with whatever it
-// reads: wrong numbers instead of a hung GPU should this code ever be broken).
+// nothing later, so the waits end; they are bounded anyway (SPIN_LIMIT polls).  A wave whose wait ran out takes NaN
+// for the x it waited for, which turns everything it computes and publishes from then on into NaN: a tile of NaNs
+// instead of a hung GPU or of plausible wrong numbers, should this code ever be broken.
 // D: L_tt, fp32, row-major; R: the tile's right-hand side and Xs: its solution, both [row][column] in LDS;
 // emit(r, x_r), called by the owning wave, must write Xs[r][lane]; spare(q) is called by every wave after its q-th
 // corner (q = 0 .. 3), when it has time for other work.
@@ -456,6 +457,10 @@ __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const 
             while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < base + s && ++polls < SPIN_LIMIT) {}
 #pragma unroll
             for (int i = 0; i < 4; ++i) xv[i] = -Xs[4 * (s - 1) + i][lane];
+            if (__builtin_expect(polls >= SPIN_LIMIT, 0)) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xv[i] = __builtin_nanf("");
+            }
         }
         auto take_out = [&](float(&t4)[4], const f32x4(&c4)[4]) __attribute__((always_inline)) {   // x of block s - 1 out of a block
 #pragma unroll
@@ -662,15 +667,16 @@ hipError_t diag(const Solve &v, int64_t r0, int64_t r1)
     const int rows = (int)(r1 - r0);
     // 16-byte pieces of the tile's rows can be fetched whole
     const int vec = ((uintptr_t)v.L % 16 == 0) && v.n % 8 == 0 && r0 % 8 == 0 && rows % 8 == 0;
+    hipError_t launch_err = hipSuccess;
     if (vec && rows == 64)
-        hipLaunchKernelGGL((tri_diag_kernel<64, true>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
+        launch_err = launch_kernel(tri_diag_kernel<64, true>, grid, dim3(64), v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
     else if (vec && rows == 128)
-        hipLaunchKernelGGL((tri_diag_kernel<128, true>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
+        launch_err = launch_kernel(tri_diag_kernel<128, true>, grid, dim3(64), v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
     else if (rows <= 64)
-        hipLaunchKernelGGL((tri_diag_kernel<64, false>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
+        launch_err = launch_kernel(tri_diag_kernel<64, false>, grid, dim3(64), v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
     else
-        hipLaunchKernelGGL((tri_diag_kernel<128, false>), grid, dim3(64), 0, v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
-    return hipGetLastError();
+        launch_err = launch_kernel(tri_diag_kernel<128, false>, grid, dim3(64), v.s, v.L, v.n, R, v.X, v.Xh, v.nrhs, r0, rows, vec);
+    return launch_err;
 }
 
 // rows [mid, r1) of the running right-hand side  -=  L[mid:r1, r0:mid] * Xh[r0:mid]
@@ -707,11 +713,12 @@ hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
 {
     dim3 grid((unsigned)((v.nrhs + 63) / 64));
     const int tiles = (int)((r1 - r0) / 64);
+    hipError_t launch_err = hipSuccess;
     if (panelw_ok(v))
-        hipLaunchKernelGGL(tri_panelw_kernel, grid, dim3(256), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
+        launch_err = launch_kernel(tri_panelw_kernel, grid, dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
     else
-        hipLaunchKernelGGL(tri_panel_kernel, grid, dim3(64), 0, v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
-    return hipGetLastError();
+        launch_err = launch_kernel(tri_panel_kernel, grid, dim3(64), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
+    return launch_err;
 }
 
 hipError_t solve(const Solve &v, int64_t r0, int64_t r1)

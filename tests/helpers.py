@@ -1,8 +1,21 @@
 """Shared test helpers: conversions and the error metric.  No oracle code, no product code."""
 from __future__ import annotations
 
+import contextlib
+
 import numpy as np
 import torch
+
+
+@contextlib.contextmanager
+def forced(lib, name):
+    """Inside the block the library uses the named kernel wherever it supports the problem (None: the dispatcher
+    decides, whatever CYC_FORCE_KERNEL said when the library was loaded)."""
+    assert lib.cyc_force_kernel(name or "") == 0, name
+    try:
+        yield
+    finally:
+        lib.cyc_force_kernel("")
 
 
 def to_bf16_bits(x) -> np.ndarray:

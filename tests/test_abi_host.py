@@ -41,7 +41,7 @@ def test_library_exports_every_declared_symbol(pkg):
 def test_status_strings_and_version(pkg):
     assert pkg.cyc_version() >= 100
     assert pkg.cyc_status_string(0) == "CYC_OK"
-    for st in range(1, 6):
+    for st in range(1, 7):
         assert pkg.cyc_status_string(st).startswith("CYC_ERR_")
     assert "unknown" in pkg.cyc_status_string(99)
 
@@ -77,10 +77,53 @@ def test_dispatch_table(pkg):
     assert k(A, B, C, 1, 100, 72, 40, 0, 0, 0, 0) == "mfma128"            # ragged everything, aligned rows
     assert k(A, B, C, 1, 1000, 1000, 1000, 0, 0, 0, 1) == "generic"       # int8 rows of 1000 bytes: not 16-byte aligned
     assert k(A, B, C, 1, 17, 33, 5, 0, 0, 0, 0) == "generic"
-    assert k(A, B, C, 1, 8, 64, 4096, 0, 0, 0, 0) == "generic"            # sliver
+    assert k(A, B, C, 1, 8, 64, 4096, 0, 0, 0, 0) == "generic"            # sliver with a small B
+    assert k(A, B, C, 1, 16, 8192, 8192, 0, 0, 0, 0) == "narrowm"         # few rows of A over a large B: B streamed once
+    assert k(A, B, C, 32, 16, 8192, 8192, 16 * 8192, 8192 * 8192, 16 * 8192, 0) == "narrowm"
+    assert k(A, B, C, 1, 7, 4096, 4096, 0, 0, 0, 1) == "narrowm"
+    assert k(A, B, C, 1, 32, 4096, 4096, 0, 0, 0, 0) == "narrowm"
+    assert k(A, B, C, 1, 33, 4096, 4096, 0, 0, 0, 0) != "narrowm"         # more than two 16-row blocks of A
+    assert k(A, B, C, 1, 16, 8192, 8191 * 8, 0, 0, 0, 0) == "narrowm"     # ragged N, aligned rows
+    assert k(A, B, C, 1, 16, 8192, 8190, 0, 0, 0, 0) != "narrowm"         # rows of B not 16-byte aligned
     assert k(A + 2, B, C, 1, 512, 512, 512, 0, 0, 0, 0) == "generic"      # unaligned A
     assert k(A, B, C, 1, 512, 0, 512, 0, 0, 0, 0) == "zero"
     assert k(A, B, C, 1, 0, 8, 512, 0, 0, 0, 0) == "none"
+
+
+def test_forced_kernel_is_a_setting_of_the_library(pkg):
+    """cyc_force_kernel overrides the dispatcher where the named kernel supports the problem, and gives the choice back."""
+    k = pkg.cyc_kernel_name
+    A, B, C = 1 << 32, 2 << 32, 3 << 32
+    try:
+        assert pkg.cyc_force_kernel("mfma128") == 0
+        assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 0) == "mfma128"
+        assert k(A, B, C, 1, 17, 33, 5, 0, 0, 0, 0) == "generic"          # mfma128 cannot serve it: the dispatcher decides
+        assert pkg.cyc_force_kernel("generic") == 0
+        assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 0) == "generic"
+        assert pkg.cyc_force_kernel("no_such_kernel") == 2
+        assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 0) == "generic"   # an unknown name changes nothing
+    finally:
+        assert pkg.cyc_force_kernel(None) == 0
+    assert k(A, B, C, 1, 8192, 8192, 8192, 0, 0, 0, 0) == "mfma256"
+
+
+def test_long_batches_and_tall_problems_are_accepted(pkg):
+    """Extents beyond one launch's grid limits are legal arguments (they take several launches): no shape error
+    from the planning step, which is all that runs without a device."""
+    k = pkg.cyc_kernel_name
+    A, B, C = 1 << 40, 2 << 40, 3 << 40
+    assert k(A, B, C, 70000, 4, 4, 4, 16, 16, 16, 1) == "generic"
+    assert k(A, B, C, 1, 5000000, 3, 3, 0, 0, 0, 0) == "generic"
+
+
+def test_diagnostic_entry_points_validate_on_the_host(pkg):
+    assert pkg.cyc_diag_mfma_ceiling(7, 16, 1000, 0x1000)[0] == 3         # unknown dtype
+    assert pkg.cyc_diag_mfma_ceiling(0, 8, 1000, 0x1000)[0] == 2          # unknown MFMA shape
+    assert pkg.cyc_diag_mfma_ceiling(0, 16, 1001, 0x1000)[0] == 2         # odd iteration count
+    assert pkg.cyc_diag_mfma_ceiling(0, 16, 1000, 0)[0] == 1              # NULL sink
+    assert pkg.cyc_diag_clock(0, 100) == 1
+    assert pkg.cyc_diag_clock(0x1000, 0) == 2
+    assert pkg.cyc_diag_clock(0x1004, 100) == 2                           # misaligned
 
 
 def test_trsm_argument_validation_happens_on_the_host(pkg):

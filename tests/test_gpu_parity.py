@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from datagen import ws_inputs
-from helpers import BF16_TOL, bits_to_f64, rel_err, torch_bf16_to_bits
+from helpers import BF16_TOL, bits_to_f64, forced, rel_err, torch_bf16_to_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -57,10 +57,7 @@ def check(mode, C, Cref, Ah, Bh, exact):
 
 def run_case(lib, oracle, mode, M, K, N, seed, kind="default", force=None, expect_kernel=None):
     A, B, Ah, Bh = gen(mode, (M, K), (K, N), seed, kind)
-    old = os.environ.pop("CYC_FORCE_KERNEL", None)
-    if force:
-        os.environ["CYC_FORCE_KERNEL"] = force
-    try:
+    with forced(lib, force):
         if expect_kernel:
             C0 = torch.empty((M, N), dtype=torch.int32 if mode == "i8" else torch.float32, device=DEV)
             name = lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C0.data_ptr(), 1, M, K, N, 0, 0, 0,
@@ -68,10 +65,6 @@ def run_case(lib, oracle, mode, M, K, N, seed, kind="default", force=None, expec
             assert name == expect_kernel, f"dispatcher chose {name}, test is written for {expect_kernel}"
         C = lib.recurrence_matmul(A, B)
         torch.cuda.synchronize()
-    finally:
-        os.environ.pop("CYC_FORCE_KERNEL", None)
-        if old is not None:
-            os.environ["CYC_FORCE_KERNEL"] = old
     Cref = oracle.ws_rowchain(Ah, Bh, mode)
     check(mode, C, Cref, Ah, Bh, exact=(kind == "small"))
     return C
@@ -149,11 +142,8 @@ def test_mfma_ragged_edges_are_not_overwritten(lib):
     guard = torch.full((M + 2, N), -12345.0, dtype=torch.float32, device=DEV)
     C = guard[1:M + 1]
     for tile in ("mfma128", "mfma256", "mfma128x32", "mfma256x32"):
-        os.environ["CYC_FORCE_KERNEL"] = tile
-        try:
+        with forced(lib, tile):
             lib.recurrence_matmul(A, B, out=C)
-        finally:
-            os.environ.pop("CYC_FORCE_KERNEL", None)
         assert torch.equal(C.double(), A.double() @ B.double())
         assert bool((guard[0] == -12345.0).all()) and bool((guard[M + 1] == -12345.0).all())
 
@@ -166,8 +156,7 @@ def test_mfma_one_hot_probes(lib, tile, mode):
     M, K, N = 512, 512, 512
     tdt = torch.int8 if mode == "i8" else torch.bfloat16
     spots = [0, 1, 3, 4, 7, 8, 15, 16, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 383, 384, 511]
-    os.environ["CYC_FORCE_KERNEL"] = tile
-    try:
+    with forced(lib, tile):
         rng = np.random.default_rng(5)
         for trial in range(40):
             p, q, r = (int(rng.choice(spots)) for _ in range(3))
@@ -180,8 +169,6 @@ def test_mfma_one_hot_probes(lib, tile, mode):
             nz = torch.nonzero(C).cpu().tolist()
             assert nz == [[p, r]], (p, q, r, nz[:5])
             assert float(C[p, r]) == -15.0
-    finally:
-        os.environ.pop("CYC_FORCE_KERNEL", None)
 
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
@@ -210,8 +197,7 @@ NARROW = [  # (batch, M, K, N)
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
 def test_narrow_kernel(lib, oracle, mode):
-    os.environ["CYC_FORCE_KERNEL"] = "narrow"
-    try:
+    with forced(lib, "narrow"):
         for n, (batch, M, K, N) in enumerate(NARROW):
             if mode == "i8":
                 K = K * 2 if K % 16 else K          # int8 rows must stay 16-byte aligned
@@ -225,8 +211,6 @@ def test_narrow_kernel(lib, oracle, mode):
                 for b in range(batch):
                     Cref = oracle.ws_rowchain(Ah[b], Bh[b], mode)
                     check(mode, C[b], Cref, Ah[b], Bh[b], exact=(kind == "small"))
-    finally:
-        os.environ.pop("CYC_FORCE_KERNEL", None)
 
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
@@ -264,12 +248,57 @@ KSPACE = [(256, 8192, 256), (128, 65536, 384), (100, 4096, 80), (512, 16384, 512
 
 @pytest.mark.parametrize("mode", ("i8", "bf16"))
 def test_k_in_space_variant(lib, oracle, mode):
-    """Few output blocks and a long k extent: the dispatcher maps k-slices to workgroups that add their partial
-    sums to C atomically.  int8 stays bit-exact, bf16 within the usual bound; small-integer bf16 data are exact
-    in any order of the adds."""
+    """Few output blocks and a long k extent: the dispatcher maps k-slices to workgroups; their partial sums are
+    added in slice order by a second kernel.  int8 stays bit-exact, bf16 within the usual bound; small-integer
+    bf16 data are exact in any order of the adds."""
     for i, (M, K, N) in enumerate(KSPACE):
         run_case(lib, oracle, mode, M, K, N, seed=700 + i, expect_kernel="mfmak")
         run_case(lib, oracle, mode, M, K, N, seed=720 + i, kind="small", expect_kernel="mfmak")
+
+
+def test_default_dispatch_is_bit_reproducible(lib):
+    """Same inputs, same bits, on whatever kernel the dispatcher itself picks: the k-in-space shapes (whose slices
+    are joined in a fixed order, no atomic adds), the tall-k bench workload, and one shape per other kernel family."""
+    shapes = [(256, 8192, 256), (512, 16384, 512), (128, 65536, 384), (512, 512, 512), (1024, 1024, 1024), (16, 4096, 4096),
+              (4096, 2048, 16), (100, 72, 40), (17, 33, 5)]
+    for i, (M, K, N) in enumerate(shapes):
+        A, B, _, _ = gen("bf16", (M, K), (K, N), seed=4100 + i)
+        C1 = lib.recurrence_matmul(A, B)
+        junk = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)      # what C held before must not matter
+        C2 = lib.recurrence_matmul(A, B, out=junk)
+        C3 = lib.recurrence_matmul(A, B)
+        assert torch.equal(C1.view(torch.int32), C2.view(torch.int32)), (M, K, N)
+        assert torch.equal(C1.view(torch.int32), C3.view(torch.int32)), (M, K, N)
+    w = ws_inputs.KSPACE_WORKLOADS["k1_bf16_tallk"]
+    A, B = ws_inputs.make_inputs(w, DEV)
+    C0 = torch.empty((w.M, w.N), dtype=torch.float32, device=DEV)
+    assert lib.cyc_kernel_name(A.data_ptr(), B.data_ptr(), C0.data_ptr(), 1, w.M, w.K, w.N, 0, 0, 0, lib.CYC_BF16_F32) == "mfmak"
+    C1 = lib.recurrence_matmul(A, B)
+    C2 = lib.recurrence_matmul(A, B)
+    assert torch.equal(C1.view(torch.int32), C2.view(torch.int32))
+
+
+def test_k_in_space_on_two_streams(lib):
+    """Each stream has a workspace of its own: two k-in-space calls in flight on different streams do not disturb
+    each other, and a later, larger problem on the same stream (which grows the workspace) is still right."""
+    A1, B1, _, _ = gen("i8", (256, 8192), (8192, 256), seed=4201)
+    A2, B2, _, _ = gen("i8", (384, 16384), (16384, 128), seed=4202)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(3):
+        with torch.cuda.stream(s1):
+            outs.append((lib.recurrence_matmul(A1, B1), A1, B1))
+        with torch.cuda.stream(s2):
+            outs.append((lib.recurrence_matmul(A2, B2), A2, B2))
+    torch.cuda.synchronize()
+    for C, A, B in outs:
+        assert torch.equal(C.double(), A.double() @ B.double())
+    A3, B3, _, _ = gen("i8", (512, 32768), (32768, 512), seed=4203)
+    with torch.cuda.stream(s1):
+        C3 = lib.recurrence_matmul(A3, B3)
+    s1.synchronize()
+    assert torch.equal(C3.double(), A3.double() @ B3.double())
 
 
 def test_k_in_space_dispatch_limits(lib):
@@ -279,14 +308,8 @@ def test_k_in_space_dispatch_limits(lib):
     assert name(256, 2048, 256) != "mfmak"                # k too short
     assert name(2048, 8192, 2048) != "mfmak"              # enough output blocks to fill the chip
     assert name(256, 8192, 256, batch=4) != "mfmak"       # batched problems keep the fixed order
-    old = os.environ.pop("CYC_FORCE_KERNEL", None)
-    os.environ["CYC_FORCE_KERNEL"] = "mfma128"
-    try:
-        assert name(256, 8192, 256) == "mfma128"             # the fixed-order kernel stays available
-    finally:
-        os.environ.pop("CYC_FORCE_KERNEL", None)
-        if old is not None:
-            os.environ["CYC_FORCE_KERNEL"] = old
+    with forced(lib, "mfma128"):
+        assert name(256, 8192, 256) == "mfma128"             # the one-workgroup-per-block kernel stays available
 
 
 def test_k_in_space_overwrites_c(lib):

@@ -13,7 +13,6 @@
 namespace cyc {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -61,16 +60,20 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(int *sink, int iters)
         for (int i = 0; i < NF; ++i)
 #pragma unroll
             for (int j = 0; j < NF; ++j) {
+                // written as asm with the accumulator tied to the destination: with all 256 accumulator registers
+                // occupied the register allocator otherwise rotates them through moves between the MFMAs
                 acc_t &c = acc[i * NF + j];
-                if constexpr (MT == 32 && I8) c = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], c, 0, 0, 0);
-                else if constexpr (MT == 32) c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[j]), c, 0, 0, 0);
-                else if constexpr (I8) c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[j], c, 0, 0, 0);
-                else c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[i]), __builtin_bit_cast(bf16x8, b[j]), c, 0, 0, 0);
+                if constexpr (MT == 32 && I8) asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+a"(c) : "v"(a[i]), "v"(b[j]));
+                else if constexpr (MT == 32) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a[i]), "v"(b[j]));
+                else if constexpr (I8) asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(c) : "v"(a[i]), "v"(b[j]));
+                else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a[i]), "v"(b[j]));
             }
         // the operands change a little every iteration (low mantissa bits only), as they would in a real k loop
 #pragma unroll
         for (int i = 0; i < NF; ++i) a[i] = a[i] ^ (i32x4){it & 0x7f, it & 0x7f, it & 0x7f, it & 0x7f};
     }
+    // (the compiler's hazard logic does not look inside asm: wait out the last MFMAs before reading their results)
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     int s = 0;
 #pragma unroll
     for (int i = 0; i < NF * NF; ++i) s += __builtin_bit_cast(int, acc[i][0]);

@@ -92,7 +92,7 @@ typedef enum {
     CYC_ERR_DTYPE = 3,   /* dtype is not a cyc_dtype */
     CYC_ERR_ALIAS = 4,   /* C overlaps A or B */
     CYC_ERR_LAUNCH = 5,  /* the HIP runtime refused a launch */
-    CYC_ERR_WORKSPACE = 6 /* the workspace a k-in-space problem needs could not be allocated */
+    CYC_ERR_WORKSPACE = 6 /* the workspace a k-in-space problem needs could not be allocated, or exceeds the fixed one */
 } cyc_status;
 
 /* One grid: C (M x N) <- A (M x K) streamed against B (K x N).
@@ -100,6 +100,20 @@ typedef enum {
 int cyc_recurrence_matmul(const void *A, const void *B, void *C,
                           int64_t M, int64_t K, int64_t N,
                           int dtype, void *stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same operation, kernels and results as cyc_recurrence_matmul, but a problem that the
+ * dispatcher maps with k in space keeps its partial products in a fixed 32 MiB array that is part of the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends) instead of the
+ * per-stream workspace.  The call allocates and frees nothing.  A problem whose partial products
+ * (k-slices x M x N x 4 bytes) exceed the array returns CYC_ERR_WORKSPACE with nothing enqueued; problems served by
+ * the other kernel families need no workspace and always run.  All calls on one GPU share that GPU's array: calls
+ * whose k-in-space work overlaps in time on one GPU (different streams) race and give undefined results; calls on
+ * one stream are ordered and safe.  Nothing in the array needs to be cleared between calls: every element a call
+ * reads it has written before. */
+int cyc_recurrence_matmul_noalloc(const void *A, const void *B, void *C,
+                                  int64_t M, int64_t K, int64_t N,
+                                  int dtype, void *stream);
 
 /* `batch` independent grids, each with its own stationary A (not part of the
  * paper; the narrow-stream workload has one weight matrix per batch element).

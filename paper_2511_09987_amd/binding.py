@@ -28,6 +28,8 @@ def _load() -> ctypes.CDLL:
     i64, ptr, cint = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.cyc_recurrence_matmul.argtypes = [ptr, ptr, ptr, i64, i64, i64, cint, ptr]
     lib.cyc_recurrence_matmul.restype = cint
+    lib.cyc_recurrence_matmul_noalloc.argtypes = [ptr, ptr, ptr, i64, i64, i64, cint, ptr]
+    lib.cyc_recurrence_matmul_noalloc.restype = cint
     lib.cyc_recurrence_matmul_batched.argtypes = [ptr, ptr, ptr, i64, i64, i64, i64, i64, i64, i64, cint, ptr]
     lib.cyc_recurrence_matmul_batched.restype = cint
     lib.cyc_recurrence_trsm.argtypes = [ptr, ptr, ptr, ptr, i64, i64, i64, ptr]
@@ -80,6 +82,11 @@ def cyc_version() -> int:
 def cyc_recurrence_matmul(A: int, B: int, C: int, M: int, K: int, N: int, dtype: int, stream: int = 0) -> int:
     """Raw call: device addresses as ints, returns the cyc_status."""
     return int(_lib().cyc_recurrence_matmul(A, B, C, M, K, N, dtype, stream))
+
+
+def cyc_recurrence_matmul_noalloc(A: int, B: int, C: int, M: int, K: int, N: int, dtype: int, stream: int = 0) -> int:
+    """Raw call of the allocation-free variant: device addresses as ints, returns the cyc_status."""
+    return int(_lib().cyc_recurrence_matmul_noalloc(A, B, C, M, K, N, dtype, stream))
 
 
 def cyc_recurrence_matmul_batched(A: int, B: int, C: int, batch: int, M: int, K: int, N: int,

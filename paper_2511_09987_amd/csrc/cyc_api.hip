@@ -146,14 +146,22 @@ int run_chunk(const cyc::Problem &p, Kernel k, void *workspace, hipStream_t s)
 // launches of the same kernel (batch elements are independent).
 constexpr int64_t kBatchPerLaunch = 65535;
 
-int run(const cyc::Problem &p, Kernel k, hipStream_t s)
+// fixed_workspace: take the partial products' memory from the library's fixed array instead of the per-stream cache
+int run(const cyc::Problem &p, Kernel k, hipStream_t s, bool fixed_workspace = false)
 {
     void *workspace = nullptr;
     if (k == K_MFMAK) {
         // everything that can fail before the first launch is settled before it
         int tile = 0;
         const int ks = cyc::choose_ksplit(p, &tile);
-        workspace = cyc::cached_workspace(s, cyc::ksplit_workspace_bytes(p, ks));
+        const int64_t need = cyc::ksplit_workspace_bytes(p, ks);
+        if (fixed_workspace) {
+            int64_t have = 0;
+            workspace = cyc::static_workspace(&have);
+            if (need > have) return CYC_ERR_WORKSPACE;
+        } else {
+            workspace = cyc::cached_workspace(s, need);
+        }
         if (!workspace) return CYC_ERR_WORKSPACE;
     }
     if (p.batch <= kBatchPerLaunch) return run_chunk(p, k, workspace, s);
@@ -188,6 +196,16 @@ int cyc_recurrence_matmul(const void *A, const void *B, void *C, int64_t M, int6
                           void *stream)
 {
     return cyc_recurrence_matmul_batched(A, B, C, 1, M, K, N, 0, 0, 0, dtype, stream);
+}
+
+int cyc_recurrence_matmul_noalloc(const void *A, const void *B, void *C, int64_t M, int64_t K, int64_t N, int dtype,
+                                  void *stream)
+{
+    cyc::Problem p;
+    Kernel k;
+    int st = plan(A, B, C, 1, M, K, N, 0, 0, 0, dtype, &p, &k);
+    if (st != CYC_OK || k == K_NONE) return st;
+    return run(p, k, (hipStream_t)stream, true);
 }
 
 int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb,
@@ -248,7 +266,7 @@ const char *cyc_status_string(int status)
         case CYC_ERR_DTYPE: return "CYC_ERR_DTYPE: unknown element type";
         case CYC_ERR_ALIAS: return "CYC_ERR_ALIAS: C overlaps an input";
         case CYC_ERR_LAUNCH: return "CYC_ERR_LAUNCH: HIP launch failed";
-        case CYC_ERR_WORKSPACE: return "CYC_ERR_WORKSPACE: workspace could not be allocated or is too small";
+        case CYC_ERR_WORKSPACE: return "CYC_ERR_WORKSPACE: workspace could not be allocated, or the problem needs more than the fixed workspace holds";
     }
     return "unknown cyc_status";
 }

@@ -57,7 +57,10 @@ inline int64_t ksplit_workspace_bytes(const Problem &p, int ksplit) { return (in
 hipError_t launch_mfma_ksplit(const Problem &p, int ksplit, int tile, void *workspace, hipStream_t s);
 // Device memory for the partial products.  cached_workspace: one buffer per (device, stream), allocated with hipMalloc
 // on first use, grown when a call needs more, kept until the process ends; nullptr when the allocation fails.
+// static_workspace: the library's fixed array in device memory (one per device, *bytes = its size), shared by every
+// caller on that device; allocates nothing; nullptr when its address cannot be obtained.
 void *cached_workspace(hipStream_t s, int64_t bytes);
+void *static_workspace(int64_t *bytes);
 // lower-triangular forward solve L X = B in tiles of nb rows (see cyc_tri.hip); arguments validated by the caller
 // A second stream per device for work that may run beside what a call enqueues on the caller's stream (forked from
 // and joined into that stream with events inside the call).  Created on first use, default priority, kept until the

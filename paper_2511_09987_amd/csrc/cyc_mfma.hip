@@ -166,9 +166,17 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // mod 8 share an L2.  Give each XCD a contiguous run of blocks, ordered so that the
     // 32 blocks resident at a time form 4 block-rows x 8 block-columns: the 4 row panels
     // of A (the stationary operand) stay in that XCD's L2 while the columns stream by.
-    int bid = blockIdx.x;
+    int bid = blockIdx.x, bz = blockIdx.y;              // block of C and batch element (or k-slice) of this workgroup
     const int nblk = tiles_m * tiles_n;
-    if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    if ((nblk & 7) == 0) {
+        bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    } else if ((gridDim.y & 7) == 0) {
+        // few blocks per batch element (or k-slice): keep the blocks of one element, which share its A and B, on one
+        // XCD.  Workgroup number blockIdx.y * nblk + blockIdx.x runs on XCD (number mod 8) as the (number / 8)-th there.
+        const int number = blockIdx.y * nblk + blockIdx.x, slot = number >> 3;
+        bz = (number & 7) + 8 * (slot / nblk);
+        bid = slot % nblk;
+    }
     constexpr int GM = 4;
     const int per_group = GM * tiles_n;
     const int group = bid / per_group, in_group = bid % per_group;
@@ -176,9 +184,9 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     const int tm_blk = group * GM + in_group % rows_here, tn_blk = in_group / rows_here;
     const int m0 = tm_blk * C::BM, n0 = tn_blk * C::BN;
 
-    A += (int64_t)blockIdx.y * sA * ES;
-    B += (int64_t)blockIdx.y * sB * ES;
-    Cout += (int64_t)blockIdx.y * sC * 4;
+    A += (int64_t)bz * sA * ES;
+    B += (int64_t)bz * sB * ES;
+    Cout += (int64_t)bz * sC * 4;
 
     // ---- global source of each 16-byte chunk this lane copies per k-tile: a wave-uniform base
     // that advances with the k-tile, plus a fixed per-lane byte offset (below 2^32, see supports_mfma)

@@ -57,6 +57,9 @@ def parse():
                     help="beside the headline, measure only the other matmul workloads (no triangular solve, Cholesky, attention)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch one 1 GiB device copy (reference point for HBM traffic counters)")
+    ap.add_argument("--constant-data", action="store_true",
+                    help="diagnostic: matmul operands are all ones instead of the workload's random values (shows how much of "
+                         "the time is the chip's power management reacting to the data); never a valid measurement")
     ap.add_argument("--ceiling-all", action="store_true",
                     help="measure the register-only MFMA rate for both instruction shapes and both element types")
     return ap.parse_args()
@@ -97,6 +100,9 @@ def all_workloads():
     return table
 
 
+CONSTANT_DATA = False     # set by --constant-data
+
+
 def make_step(lib, torch, kind, w, sets):
     """Operand sets resident on the GPU and step(i): one call of the C ABI on set i % sets.  Returns (step, info)."""
     from datagen import ws_inputs
@@ -108,6 +114,9 @@ def make_step(lib, torch, kind, w, sets):
         for r in range(sets):
             wr = ws_inputs.Workload(w.name, w.dtype, w.batch, w.M, w.K, w.N, w.dist, w.param, w.seed + 1000 * r)
             A, B = ws_inputs.make_inputs(wr, DEV)
+            if CONSTANT_DATA:
+                A.fill_(1)
+                B.fill_(1)
             cshape = (w.batch, w.M, w.N) if w.batch > 1 else (w.M, w.N)
             data.append((A, B, torch.empty(cshape, dtype=torch.int32 if w.dtype == "i8" else torch.float32, device=DEV)))
         A, B, C = data[0]
@@ -363,6 +372,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     traffic = traffic_table()
+    global CONSTANT_DATA
+    CONSTANT_DATA = args.constant_data
 
     kind, w = table[args.workload]
     wall_ms, ev_ms, kernel, rf = run_workload(lib, torch, kind, w, args.steps, args.warmup, traffic)
@@ -371,7 +382,8 @@ def main():
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if dtype == "bf16" else "int8", "data": "synthetic",
+        "dtype": "bf16" if dtype == "bf16" else "int8",
+        "data": "constant (diagnostic, not a valid measurement)" if args.constant_data else "synthetic",
         "config": config_of(kind, w, kernel), "roofline": rf,
     }
 

@@ -220,7 +220,7 @@ int cyc_force_kernel(const char *name);
  * instructions, 32: 32x32) from registers on random-looking operands, four waves on every compute unit, no LDS or
  * memory traffic: what the matrix pipes sustain on this chip when nothing else happens.  *ops (host, may be NULL)
  * receives the operations of one launch; time the launch with events on `stream`.  sink: device, 4 bytes, in
- * practice never written.  iters even, 2 .. 2^24. */
+ * practice never written.  iters: a multiple of 8, 8 .. 2^24. */
 int cyc_diag_mfma_ceiling(int dtype, int mfma_shape, int64_t iters, void *sink, double *ops, void *stream);
 
 /* Measurement aid: one wave that runs for `microseconds` (1 .. 2000000) and then writes to out (device, two

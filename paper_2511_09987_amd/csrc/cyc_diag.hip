@@ -55,7 +55,11 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(int *sink, int iters)
     for (int i = 0; i < NF * NF; ++i)
 #pragma unroll
         for (int r = 0; r < MT * MT / 64; ++r) acc[i][r] = 0;
-    for (int it = 0; it < (MT == 32 ? iters : iters / 2); ++it) {
+    // four rounds over all accumulators per change of the operands: the vector instructions that change them take
+    // issue slots from the MFMAs, and the point here is the MFMA rate
+    for (int it = 0; it < (MT == 32 ? iters : iters / 2) / 4; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 4; ++rep)
 #pragma unroll
         for (int i = 0; i < NF; ++i)
 #pragma unroll
@@ -103,7 +107,7 @@ extern "C" {
 int cyc_diag_mfma_ceiling(int dtype, int mfma_shape, int64_t iters, void *sink, double *ops, void *stream)
 {
     if (dtype != CYC_BF16_F32 && dtype != CYC_I8_I32) return CYC_ERR_DTYPE;
-    if ((mfma_shape != 16 && mfma_shape != 32) || iters < 2 || iters > (1 << 24) || (iters & 1)) return CYC_ERR_SHAPE;
+    if ((mfma_shape != 16 && mfma_shape != 32) || iters < 8 || iters > (1 << 24) || (iters & 7)) return CYC_ERR_SHAPE;
     if (!sink) return CYC_ERR_NULL;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)

@@ -119,7 +119,7 @@ def test_long_batches_and_tall_problems_are_accepted(pkg):
 def test_diagnostic_entry_points_validate_on_the_host(pkg):
     assert pkg.cyc_diag_mfma_ceiling(7, 16, 1000, 0x1000)[0] == 3         # unknown dtype
     assert pkg.cyc_diag_mfma_ceiling(0, 8, 1000, 0x1000)[0] == 2          # unknown MFMA shape
-    assert pkg.cyc_diag_mfma_ceiling(0, 16, 1001, 0x1000)[0] == 2         # odd iteration count
+    assert pkg.cyc_diag_mfma_ceiling(0, 16, 1004, 0x1000)[0] == 2         # iteration count not a multiple of 8
     assert pkg.cyc_diag_mfma_ceiling(0, 16, 1000, 0)[0] == 1              # NULL sink
     assert pkg.cyc_diag_clock(0, 100) == 1
     assert pkg.cyc_diag_clock(0x1000, 0) == 2

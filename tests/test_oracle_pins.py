@@ -75,6 +75,36 @@ def test_hand_worked_cases(oracle, case, form):
     assert got.tobytes() == want.tobytes()
 
 
+def test_planted_mistakes_fail_a_hand_worked_case():
+    """Plausible slips in the chain, each in a throw-away copy of it (fp32 accumulator, k ascending): every one of
+    them gets at least one hand-worked case wrong, so the golden file would catch the same slip in the oracle."""
+    cases = {c["name"]: c for c in _parse_golden()}
+
+    def chain(case, order=lambda K: range(K), b_index=lambda B, k, j: B[k][j], first=0, widen=np.float32):
+        M, K, N = case["shape"]
+        A = np.array(case["A"], dtype=np.float64).reshape(M, K)
+        B = np.array(case["B"], dtype=np.float64).reshape(K, N)
+        C = np.zeros((M, N), dtype=np.float64)
+        for i in range(M):
+            for j in range(N):
+                acc = widen(0)
+                for k in order(K):
+                    if k >= first:
+                        acc = widen(acc + widen(A[i][k] * b_index(B, k, j)))
+                C[i][j] = acc
+        return C.ravel().tolist()
+
+    def wrong_somewhere(**slip):
+        return any(chain(c, **slip) != [float(v) for v in c["C"]] for c in cases.values()
+                   if not ("b_index" in slip and c["shape"][1] != c["shape"][2]))     # B^T needs a square B
+
+    assert not wrong_somewhere()                                               # the copy itself is right on every case
+    assert wrong_somewhere(order=lambda K: range(K - 1, -1, -1))               # k descending (order1x3x1)
+    assert wrong_somewhere(b_index=lambda B, k, j: B[j][k])                    # B_jk for B_kj (int2x2)
+    assert wrong_somewhere(first=1)                                            # first term of the chain dropped
+    assert wrong_somewhere(widen=np.float64)                                   # accumulator wider than fp32 (order1x3x1)
+
+
 # ------------------------------------------- library matmul in wider precision
 SMALL = list(itertools.product((1, 2, 3, 5, 8), repeat=3))
 ODD = [(33, 17, 9), (9, 33, 17), (17, 9, 33), (31, 32, 33), (2, 64, 3)]

@@ -418,16 +418,16 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
 // j as in the one-wave form, so the bits are the same; the path per phase is hand-over, 16 multiply-adds, corner.
 // Hand-over is a counter in LDS: the owner stores base + s + 1 (release) after its x, the others poll it (acquire).
 // A wave's LDS operations complete in order, and a wave in phase s waits only for the phase before, which waits for
-// nothing later, so the waits end; they are bounded anyway (SPIN_LIMIT polls).  A wave whose wait ran out takes NaN
-// for the x it waited for, which turns everything it computes and publishes from then on into NaN: a tile of NaNs
-// instead of a hung GPU or of plausible wrong numbers, should this code ever be broken.
+// nothing later, so the waits end; they are bounded anyway (SPIN_LIMIT polls).  A wave whose wait ran out sets
+// *expired (in LDS) and goes on; the caller then overwrites results with NaN: NaNs instead of a hung GPU or of
+// plausible wrong numbers, should this code ever be broken.
 // D: L_tt, fp32, row-major; R: the tile's right-hand side and Xs: its solution, both [row][column] in LDS;
 // emit(r, x_r), called by the owning wave, must write Xs[r][lane]; spare(q) is called by every wave after its q-th
 // corner (q = 0 .. 3), when it has time for other work.
 constexpr int SPIN_LIMIT = 1 << 20;
 template <int LDD, class Emit, class Spare>
 __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const float (*R)[LDD], const float (*Xs)[LDD], int *ready,
-                                                   int base, int w, int lane, Emit emit, Spare spare)
+                                                   int *expired, int base, int w, int lane, Emit emit, Spare spare)
 {
     const float(*Dw)[LDD] = D + 4 * w;                    // block w + 4 ob of the tile is rows Dw[16 ob .. 16 ob + 3]
     float tt[4][4];                                       // running right-hand side of the wave's blocks: [ob][row in block]
@@ -454,13 +454,14 @@ __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const 
         float xv[4] = {0.0f, 0.0f, 0.0f, 0.0f};           // -x of block s - 1
         if (s >= 1) {
             int polls = 0;
-            while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < base + s && ++polls < SPIN_LIMIT) {}
+            while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < base + s) {
+                if (++polls >= SPIN_LIMIT) {              // never taken unless this code is broken
+                    *expired = 1;
+                    break;
+                }
+            }
 #pragma unroll
             for (int i = 0; i < 4; ++i) xv[i] = -Xs[4 * (s - 1) + i][lane];
-            if (__builtin_expect(polls >= SPIN_LIMIT, 0)) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) xv[i] = __builtin_nanf("");
-            }
         }
         auto take_out = [&](float(&t4)[4], const f32x4(&c4)[4]) __attribute__((always_inline)) {   // x of block s - 1 out of a block
 #pragma unroll
@@ -528,6 +529,7 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
         float Xs[NB][LDD];                 // the tile's solution, [row][column]
         uint16_t Xb[PANELW * NB][64];      // solved tiles as bfloat16, [k][column]
         int ready;                         // hand-over counter of solve_tile64_waves
+        int expired;                       // set by a wave of solve_tile64_waves whose bounded wait ran out
     } lds;
     int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -609,7 +611,7 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
         }
     };
 
-    if (tid == 0) lds.ready = 0;
+    if (tid == 0) lds.ready = lds.expired = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
     request(0);
@@ -627,7 +629,7 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
         solve_tile64_waves<LDD>(
-            lds.D, lds.R, lds.Xs, &lds.ready, t * NBLK, w, lane,
+            lds.D, lds.R, lds.Xs, &lds.ready, &lds.expired, t * NBLK, w, lane,
             [&](int r, float xr) __attribute__((always_inline)) {
                 lds.Xb[t * NB + r][lane] = round_bf16(xr);
                 lds.Xs[r][lane] = xr;
@@ -645,6 +647,17 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
         store(t);
         if (t + 1 < tiles) stage(t + 1, 2 * t);
         __syncthreads();                                               // tile t + 1 is staged, Xs is free
+    }
+    if (__builtin_expect(lds.expired != 0, 0)) {
+        // (uniform; checked once, after everything, so that the solves pay nothing for it) a hand-over between waves
+        // failed somewhere in this panel: its last tile is overwritten with NaN, which every later row of the solve
+        // inherits and any check of the result sees
+        const int64_t rv = r0 + (int64_t)(tiles - 1) * NB;
+        if (c0 + lane < nrhs)
+            for (int r = w * 16; r < w * 16 + 16; ++r) {
+                X[(rv + r) * nrhs + c0 + lane] = __builtin_nanf("");
+                Xh[(rv + r) * nrhs + c0 + lane] = 0x7fc0;
+            }
     }
 }
 

@@ -383,6 +383,27 @@ def test_degenerate_extents_and_errors(lib):
         lib.recurrence_matmul(A, A.view(2, 8))           # K mismatch
 
 
+def test_extents_beyond_one_launch(lib):
+    """A batch longer than a grid's 65535 and more rows than 65535 blocks of 64 are legal: the call takes several
+    launches.  Checked exactly against torch's integer matmul (tiny K, so the oracle's result is the plain sum)."""
+    s = torch.cuda.current_stream().cuda_stream
+    batch, M, K, N = 70000, 4, 4, 4
+    A = ws_inputs.uniform_int((batch, M, K), 8, 301, 0, DEV)
+    B = ws_inputs.uniform_int((batch, K, N), 8, 301, 1, DEV)
+    C = torch.full((batch, M, N), 99, dtype=torch.int32, device=DEV)
+    st = lib.cyc_recurrence_matmul_batched(A.data_ptr(), B.data_ptr(), C.data_ptr(), batch, M, K, N, M * K, K * N, M * N,
+                                           lib.CYC_I8_I32, s)
+    assert st == 0, lib.cyc_status_string(st)
+    assert torch.equal(C, torch.bmm(A.float(), B.float()).to(torch.int32))
+    M, K, N = 65535 * 64 + 70, 3, 3
+    A = ws_inputs.uniform_int((M, K), 8, 302, 0, DEV)
+    B = ws_inputs.uniform_int((K, N), 8, 302, 1, DEV)
+    C = torch.full((M, N), 99, dtype=torch.int32, device=DEV)
+    st = lib.cyc_recurrence_matmul(A.data_ptr(), B.data_ptr(), C.data_ptr(), M, K, N, lib.CYC_I8_I32, s)
+    assert st == 0, lib.cyc_status_string(st)
+    assert torch.equal(C, (A.float() @ B.float()).to(torch.int32))
+
+
 def test_unaligned_pointers_fall_back(lib, oracle):
     """Tile-multiple shapes at odd addresses must not take the 16-byte-aligned fast path."""
     M = K = N = 256

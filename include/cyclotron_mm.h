@@ -145,8 +145,8 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates
  *     nothing and keeps no state.  n == 0 or nrhs == 0: CYC_OK, nothing done.  A zero on the diagonal
  *     gives infinities or NaNs as IEEE division does, not an error.  Inside the kernels, waves hand solved rows
- *     to one another through LDS with bounded waits; a wait that ever ran out would fill the affected tile of X
- *     and Xh with NaN rather than go on with stale values.
+ *     to one another through LDS with bounded waits; a wait that ever ran out would leave NaN in X and Xh (in
+ *     the last tile of the affected panel, and in every row solved after it) rather than plausible wrong values.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or overflowing extents, nb out of
  * range), CYC_ERR_ALIAS (X or Xh overlaps L, B or each other).  CYC_ERR_LAUNCH: see the top of this file. */
 int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,

@@ -88,7 +88,9 @@ __global__ __launch_bounds__(64) void clock_kernel(uint64_t *out, int64_t ticks)
 {
     const uint64_t w0 = wall_clock64(), c0 = clock64();
     uint64_t w1 = w0;
-    while ((int64_t)(w1 - w0) < ticks) {
+    // a sleep of 32 is 2048 cycles, about a microsecond: the round count is bounded as well, so that the wave ends
+    // even if the 100 MHz counter should not advance
+    for (int64_t round = 0; (int64_t)(w1 - w0) < ticks && round < ticks / 16 + 4096; ++round) {
         __builtin_amdgcn_s_sleep(32);
         w1 = wall_clock64();
     }

@@ -156,3 +156,26 @@ def test_narrowm_workload_full_size(lib, oracle):
                 check("bf16", C[b][:, j0:j0 + 512], Cref, Ah, Bh, exact=(kind == "small"))
         del A, B, C
         torch.cuda.empty_cache()
+
+
+def test_int8_extremes_wrap_modulo_2_32_on_every_kernel_family(lib):
+    """-128 is a legal int8 value and int32 partial sums wrap: with every element -128 each C_ij is K * 2^14 mod 2^32,
+    which is 0 at K = 2^18 and 16 * 2^14 at K = 2^18 + 16, whatever the kernel and its summation order."""
+    cases = [("narrowm", 16, 128), ("narrowm", 9, 2048), ("mfmak", 128, 128), ("mfma128", 128, 128), ("generic", 20, 24)]
+    for kernel, M, N in cases:
+        for K, want in ((1 << 18, 0), ((1 << 18) + 16, 16 << 14)):
+            if kernel == "mfmak" and K != 1 << 18:
+                continue                               # k in space wants K a multiple of its slices
+            A = torch.full((M, K), -128, dtype=torch.int8, device=DEV)
+            B = torch.full((K, N), -128, dtype=torch.int8, device=DEV)
+            with forced(lib, kernel):
+                assert kernel_of(lib, "i8", A, B, 1, M, K, N) == kernel, (kernel, M, K, N)
+                C = lib.recurrence_matmul(A, B)
+            assert bool((C == want).all()), (kernel, M, K, N, int(C[0, 0]))
+    # the narrow-N streaming kernel holds at most 16384 int8 values of k: 2^14 * 2^14 = 2^28 per element, no wrap yet
+    A = torch.full((4096, 16384), -128, dtype=torch.int8, device=DEV)
+    B = torch.full((16384, 16), -128, dtype=torch.int8, device=DEV)
+    with forced(lib, "narrow"):
+        assert kernel_of(lib, "i8", A, B, 1, 4096, 16384, 16) == "narrow"
+        C = lib.recurrence_matmul(A, B)
+    assert bool((C == 1 << 28).all())

@@ -189,7 +189,7 @@ int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t
  * Q: device, read only, batch x N x d bfloat16 row-major.  K, V: device, read only, batch x M x d bfloat16.
  * O: device, written, batch x N x d fp32 row-major.  All pointers 16-byte aligned.
  * d must be 64 or 128; N, M >= 1 arbitrary (M * d < 2^31).  Scores, maxima, sums and outputs are fp32; the
- * exponentials enter the product with V rounded to bfloat16.  stream: hipStream_t or NULL; asynchronous,
+ * exponentials enter the product with V, and their running sum, rounded to bfloat16.  stream: hipStream_t or NULL; asynchronous,
  * allocates nothing.  batch == 0 or N == 0: CYC_OK, nothing done.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative extents, M == 0 with N > 0, unsupported d,
  * misaligned pointers, batch > 65535, sizes out of range), CYC_ERR_ALIAS (O overlaps Q, K or V), CYC_ERR_LAUNCH. */

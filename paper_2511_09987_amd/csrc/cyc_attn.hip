@@ -22,8 +22,8 @@
 //                       Accumulator lane l holds, for query l%16, four consecutive d: the rescale by
 //                       exp(m - mh) is a per-lane multiply and the final store is 16 bytes per lane.
 // Arithmetic: Q, K, V bfloat16; S, m, l, o fp32; exp through the hardware exp2 with alpha*log2(e) folded
-// into the scores; the probabilities enter the second product rounded to bfloat16 (nearest even), the
-// running sum takes them unrounded.  The maximum that the exponentials refer to follows the running maximum
+// into the scores; the probabilities enter the second product rounded to bfloat16 (nearest even), and the
+// running sum adds up those same rounded values (it rides on the second product as a row of ones).  The maximum that the exponentials refer to follows the running maximum
 // lazily (step_top below); o / l does not depend on it.
 //
 // Schedule: a software pipeline across tiles inside every wave, so that matrix-core and vector-ALU
@@ -143,12 +143,12 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
 
     // ---- running state of this lane's queries (one per 16-query block jq): maximum in the log2 domain, this lane's
     // share of the sum, and O^T accumulators [d tile][query tile]
-    float m2[QB], lsum[QB];
-    f32x4 acc_o[DT][QB];
+    float m2[QB];
+    f32x4 acc_o[DT][QB], acc_l[QB];                                   // acc_l: the running sum l, the same value in all four registers
 #pragma unroll
     for (int jq = 0; jq < QB; ++jq) {
         m2[jq] = -__builtin_inff();
-        lsum[jq] = 0.0f;
+        acc_l[jq] = (f32x4){0, 0, 0, 0};
 #pragma unroll
         for (int id = 0; id < DT; ++id) acc_o[id][jq] = (f32x4){0, 0, 0, 0};
     }
@@ -163,8 +163,14 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
     // 32 sk + 4 (l/16) .. +3, k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in)
     auto weighted_values = [&](int t) __attribute__((always_inline)) {
         CYC_LDS char *Vt = lds + (2 + (t & 1)) * TILE_BYTES;
+        // the running sum rides along as one more row block of V^T whose every entry is 1: l += 1^T P^T, i.e. the sum of
+        // the weights as the second product sees them (rounded to bfloat16), with no vector-ALU additions
+        const i32x4 ones = {0x3f803f80, 0x3f803f80, 0x3f803f80, 0x3f803f80};
 #pragma unroll
-        for (int sk = 0; sk < KB / 2; ++sk)
+        for (int sk = 0; sk < KB / 2; ++sk) {
+#pragma unroll
+            for (int jq = 0; jq < QB; ++jq)
+                acc_l[jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_l[jq], 0, 0, 0);
 #pragma unroll
             for (int id = 0; id < DT; ++id) {
                 const int klo = sk * 32 + 4 * g + (lq >> 2), khi = klo + 16;      // rows the transpose read points at
@@ -178,6 +184,7 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
                 for (int jq = 0; jq < QB; ++jq)
                     acc_o[id][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_o[id][jq], 0, 0, 0);
             }
+        }
     };
 
     // maximum over lanes l, l^16, l^32, l^48.  The swaps exchange halves (rows 2,3 of the first operand with rows
@@ -229,7 +236,6 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
     auto probabilities = [&](int t, const f32x4(&sc)[KB][QB], bool ragged) __attribute__((always_inline)) {
 #pragma unroll
         for (int jq = 0; jq < QB; ++jq) {
-            float part = 0.0f;
             bf16x8 pk[KB / 2];
 #pragma unroll
             for (int ik = 0; ik < KB; ++ik)
@@ -237,10 +243,8 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
                 for (int r = 0; r < 4; ++r) {
                     float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[ik][jq][r], scale_log2e, -m2[jq]));
                     if (ragged && t * KT + ik * 16 + 4 * g + r >= M) p = 0.0f;   // keys past M take no weight
-                    part += p;
                     pk[ik >> 1][(ik & 1) * 4 + r] = (__bf16)p;   // k-slot: block ik&1 of the 32-key step ik/2
                 }
-            lsum[jq] += part;
 #pragma unroll
             for (int sk = 0; sk < KB / 2; ++sk) pf[jq][sk] = __builtin_bit_cast(i32x4, pk[sk]);
         }
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
                 const float mh = __builtin_fmaxf(m2[jq], tile_max[jq]);
                 const float keep = __builtin_amdgcn_exp2f(m2[jq] - mh);       // exp(m - mh); 0 on the first tile
                 m2[jq] = mh;
-                lsum[jq] *= keep;
+                acc_l[jq] *= keep;
 #pragma unroll
                 for (int id = 0; id < DT; ++id) acc_o[id][jq] *= keep;
             }
@@ -301,9 +305,7 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
     // ---- O_i. = o_i / l_i.  Accumulator register r of lane l: d = 16 id + 4 (l/16) + r, query 16 jq + l%16.
 #pragma unroll
     for (int jq = 0; jq < QB; ++jq) {
-        float tot = lsum[jq];
-        tot += __shfl_xor(tot, 16);
-        tot += __shfl_xor(tot, 32);
+        const float tot = acc_l[jq][0];                 // every lane of the query holds the whole sum
         const int qi = q0 + jq * 16 + lq;
         if (qi < N) {
 #pragma unroll

@@ -46,6 +46,9 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 #define CYC_LDS __attribute__((address_space(3)))
 
@@ -63,6 +66,29 @@ __device__ __forceinline__ void copy16(const char *base, uint32_t lane_off, uint
 }
 
 __device__ __forceinline__ i32x4 mfma_frag(i32x2 lo, i32x2 hi) { return (i32x4){lo[0], lo[1], hi[0], hi[1]}; }
+
+template <int... I, class F> __device__ __forceinline__ void static_for_each(std::integer_sequence<int, I...>, F &&f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>) .. f(integral_constant<int, N-1>): a loop whose index is a constant expression
+template <int N, class F> __device__ __forceinline__ void static_for(F &&f) { static_for_each(std::make_integer_sequence<int, N>{}, f); }
+
+// 16 bytes per lane from LDS address addr + OFF, with no wait: dst is valid only after lds_wait
+template <int OFF> __device__ __forceinline__ void lds_read128(i32x4 &dst, uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "the offset field of an LDS instruction has 16 bits");
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+// wait until at most PENDING LDS operations issued after the read of x are outstanding; x is valid from here on
+template <int PENDING> __device__ __forceinline__ void lds_wait(i32x4 &x) { asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(PENDING)); }
+// the transposing read of four 16-bit elements per lane, likewise without a wait
+template <int OFF> __device__ __forceinline__ void lds_read_tr64(i32x2 &dst, uint32_t addr)
+{
+    static_assert(OFF >= 0 && OFF < 65536, "the offset field of an LDS instruction has 16 bits");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFF));
+}
+template <int PENDING> __device__ __forceinline__ void lds_wait2(i32x2 &x, i32x2 &y) { asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(PENDING)); }
 
 // D: head dimension; KT: keys per tile (a multiple of 32)
 template <int D, int KT>
@@ -159,32 +185,50 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
     // again by other waves); then meet the other waves
     auto landed_barrier = []() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
 
-    // ---- O^T += V^T P^T for tile t (in V stage t&1).  A operand lane: d = 16 id + l%16; k-slots 0..3 = keys
-    // 32 sk + 4 (l/16) .. +3, k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in)
-    auto weighted_values = [&](int t) __attribute__((always_inline)) {
-        CYC_LDS char *Vt = lds + (2 + (t & 1)) * TILE_BYTES;
+    // ---- O^T += V^T P^T for a tile in V stage STAGE.  A operand lane: d = 16 id + l%16; k-slots 0..3 = keys
+    // 32 sk + 4 (l/16) .. +3, k-slots 4..7 = the same keys of the next 16-key block (the order P^T was packed in).
+    // Fragment i = sk * DT + id is two transposing reads (the two key blocks); like the K fragments they are issued
+    // VWIN fragments ahead of their use.  The swizzle of a row depends on the lane alone (4 (l/16) + (l%16)/4 mod 8),
+    // so one address register per d tile serves every sk and both key blocks through the offset field.
+    constexpr int VWIN = 4;
+    constexpr int NVFRAG = (KB / 2) * DT;
+    uint32_t vaddr[DT];
+#pragma unroll
+    for (int id = 0; id < DT; ++id) {
+        const int row = 4 * g + (lq >> 2);
+        const int chunk = (id * 16 + 4 * (lq & 3)) >> 3, within = ((id * 16 + 4 * (lq & 3)) & 7) * 2;
+        vaddr[id] = lds_base + 2 * TILE_BYTES + row * ROW + ((chunk ^ swzV(row)) << 4) + within;
+    }
+    auto weighted_values = [&](auto stage_c) __attribute__((always_inline)) {
+        constexpr int STAGE = decltype(stage_c)::value;
         // the running sum rides along as one more row block of V^T whose every entry is 1: l += 1^T P^T, i.e. the sum of
         // the weights as the second product sees them (rounded to bfloat16), with no vector-ALU additions
         const i32x4 ones = {0x3f803f80, 0x3f803f80, 0x3f803f80, 0x3f803f80};
-#pragma unroll
-        for (int sk = 0; sk < KB / 2; ++sk) {
-#pragma unroll
-            for (int jq = 0; jq < QB; ++jq)
-                acc_l[jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_l[jq], 0, 0, 0);
-#pragma unroll
-            for (int id = 0; id < DT; ++id) {
-                const int klo = sk * 32 + 4 * g + (lq >> 2), khi = klo + 16;      // rows the transpose read points at
-                const int chunk = (id * 16 + 4 * (lq & 3)) >> 3, within = ((id * 16 + 4 * (lq & 3)) & 7) * 2;
-                const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (CYC_LDS bf16x4 *)(Vt + klo * ROW + ((chunk ^ swzV(klo)) << 4) + within)));
-                const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (CYC_LDS bf16x4 *)(Vt + khi * ROW + ((chunk ^ swzV(khi)) << 4) + within)));
-                const i32x4 vf = mfma_frag(lo, hi);
+        i32x2 lo[VWIN], hi[VWIN];
+        static_for<VWIN>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value, off = STAGE * TILE_BYTES + (i / DT) * 32 * ROW;
+            lds_read_tr64<off>(lo[i], vaddr[i % DT]);
+            lds_read_tr64<off + 16 * ROW>(hi[i], vaddr[i % DT]);
+        });
+        static_for<NVFRAG>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value, sk = i / DT, id = i % DT;
+            constexpr int later = NVFRAG - 1 - i < VWIN - 1 ? NVFRAG - 1 - i : VWIN - 1;   // fragments requested after i
+            if constexpr (id == 0) {
 #pragma unroll
                 for (int jq = 0; jq < QB; ++jq)
-                    acc_o[id][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_o[id][jq], 0, 0, 0);
+                    acc_l[jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_l[jq], 0, 0, 0);
             }
-        }
+            lds_wait2<2 * later>(lo[i % VWIN], hi[i % VWIN]);
+            const i32x4 vf = mfma_frag(lo[i % VWIN], hi[i % VWIN]);
+#pragma unroll
+            for (int jq = 0; jq < QB; ++jq)
+                acc_o[id][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pf[jq][sk]), acc_o[id][jq], 0, 0, 0);
+            if constexpr (i + VWIN < NVFRAG) {
+                constexpr int off = STAGE * TILE_BYTES + ((i + VWIN) / DT) * 32 * ROW;
+                lds_read_tr64<off>(lo[i % VWIN], vaddr[(i + VWIN) % DT]);
+                lds_read_tr64<off + 16 * ROW>(hi[i % VWIN], vaddr[(i + VWIN) % DT]);
+            }
+        });
     };
 
     // maximum over lanes l, l^16, l^32, l^48.  The swaps exchange halves (rows 2,3 of the first operand with rows
@@ -201,23 +245,38 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
         const unsigned b0 = b[0], b1 = b[1];
         return __builtin_fmaxf(as_float(b0), as_float(b1));
     };
-    // ---- S^T = K_tile Q^T for tile t (in K stage t&1)
-    auto scores_into = [&](int t, f32x4(&sn)[KB][QB]) __attribute__((always_inline)) {
-        CYC_LDS char *Kt = lds + (t & 1) * TILE_BYTES;
+    // ---- S^T = K_tile Q^T for a tile in K stage STAGE.  Fragment i = ks * KB + ik (16 keys x 32 d) feeds the QB MFMAs of
+    // key block ik and d step ks.  The reads are issued KWIN fragments ahead of their use and waited for one at a time:
+    // they are written as asm because the compiler, short of registers here, otherwise issues each read right before
+    // the MFMAs that need it and waits out the whole LDS latency every time.  The wait names the fragment as an
+    // operand so that no use of it can be moved above the wait.  (LDS reads return in order, so reads the compiler
+    // issues in between only make these waits longer than needed, never shorter.)
+    constexpr int KWIN = 4;
+    constexpr int NFRAG = DS * KB;
+    uint32_t kaddr[DS];                                               // this lane's address within stage 0, key block 0
+#pragma unroll
+    for (int ks = 0; ks < DS; ++ks) kaddr[ks] = lds_base + lq * ROW + (((ks * 4 + g) ^ swzK(lq)) << 4);
+    auto scores_into = [&](auto stage_c, f32x4(&sn)[KB][QB]) __attribute__((always_inline)) {
+        constexpr int STAGE = decltype(stage_c)::value;
+        i32x4 kf[KWIN];
+        static_for<KWIN>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value;
+            lds_read128<STAGE * TILE_BYTES + (i % KB) * 16 * ROW>(kf[i], kaddr[i / KB]);
+        });
 #pragma unroll
         for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
             for (int jq = 0; jq < QB; ++jq) sn[ik][jq] = (f32x4){0, 0, 0, 0};
+        static_for<NFRAG>([&](auto ic) __attribute__((always_inline)) {
+            constexpr int i = decltype(ic)::value, ks = i / KB, ik = i % KB;
+            constexpr int later = NFRAG - 1 - i < KWIN - 1 ? NFRAG - 1 - i : KWIN - 1;   // reads issued after fragment i
+            lds_wait<later>(kf[i % KWIN]);
 #pragma unroll
-        for (int ks = 0; ks < DS; ++ks)
-#pragma unroll
-            for (int ik = 0; ik < KB; ++ik) {
-                const int r = ik * 16 + lq;
-                const i32x4 kf = *(CYC_LDS i32x4 *)(Kt + r * ROW + (((ks * 4 + g) ^ swzK(r)) << 4));
-#pragma unroll
-                for (int jq = 0; jq < QB; ++jq)
-                    sn[ik][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf), __builtin_bit_cast(bf16x8, qf[jq][ks]), sn[ik][jq], 0, 0, 0);
-            }
+            for (int jq = 0; jq < QB; ++jq)
+                sn[ik][jq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[i % KWIN]), __builtin_bit_cast(bf16x8, qf[jq][ks]), sn[ik][jq], 0, 0, 0);
+            if constexpr (i + KWIN < NFRAG)
+                lds_read128<STAGE * TILE_BYTES + ((i + KWIN) % KB) * 16 * ROW>(kf[i % KWIN], kaddr[(i + KWIN) / KB]);
+        });
     };
     // Maximum of the tile's scores per query, in the log2 domain.  Keys past M were copied from key M-1, so their
     // scores repeat a valid score and leave the maximum alone.
@@ -233,74 +292,104 @@ __global__ __launch_bounds__(NWAVE * 64) void attn_kernel(const char *__restrict
         }
     };
     // ---- weights of tile t against the reference m2, their sum, and P^T packed as an operand
-    auto probabilities = [&](int t, const f32x4(&sc)[KB][QB], bool ragged) __attribute__((always_inline)) {
+    auto probabilities = [&](int t, const f32x4(&sc)[KB][QB], bool mask) __attribute__((always_inline)) {
 #pragma unroll
-        for (int jq = 0; jq < QB; ++jq) {
-            bf16x8 pk[KB / 2];
+        for (int jq = 0; jq < QB; ++jq)
 #pragma unroll
             for (int ik = 0; ik < KB; ++ik)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[ik][jq][r], scale_log2e, -m2[jq]));
-                    if (ragged && t * KT + ik * 16 + 4 * g + r >= M) p = 0.0f;   // keys past M take no weight
-                    pk[ik >> 1][(ik & 1) * 4 + r] = (__bf16)p;   // k-slot: block ik&1 of the 32-key step ik/2
+                for (int r = 0; r < 4; r += 2) {
+                    float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[ik][jq][r], scale_log2e, -m2[jq]));
+                    float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[ik][jq][r + 1], scale_log2e, -m2[jq]));
+                    if (mask) {                                   // keys past M take no weight
+                        const int key = t * KT + ik * 16 + 4 * g + r;
+                        p0 = key < M ? p0 : 0.0f;
+                        p1 = key + 1 < M ? p1 : 0.0f;
+                    }
+                    // one conversion instruction rounds and packs the pair; k-slot: block ik&1 of the 32-key step ik/2
+                    const bf16x2 pair = __builtin_convertvector((f32x2){p0, p1}, bf16x2);
+                    pf[jq][ik >> 1][(ik & 1) * 2 + (r >> 1)] = __builtin_bit_cast(int, pair);
                 }
+    };
+    // The exponentials are taken against a reference m2 that follows the running maximum lazily: no maximum is taken
+    // of a tile whose weights all came out at most 2^LAG.  The packed bfloat16 weights are non-negative, so their bit
+    // patterns order like unsigned 16-bit integers (infinity and NaN above every finite value), and one packed
+    // integer maximum handles two of them.  Only when some weight of some query of the wave is above 2^LAG (always on
+    // the first tile, where m2 = -inf gives infinite weights; hardly ever after the first few) is the tile's maximum
+    // taken, the reference moved to it, the sums and outputs so far rescaled by exp(m_old - m_new) and the tile's
+    // weights taken again.  The quotient o / l at the end is the same whatever the reference.
+    constexpr unsigned short LAG_BITS = 0x4380;                       // 2^8 as bfloat16
+    auto overflowed = [&]() __attribute__((always_inline)) {
+        u16x2 top = {0, 0};
 #pragma unroll
-            for (int sk = 0; sk < KB / 2; ++sk) pf[jq][sk] = __builtin_bit_cast(i32x4, pk[sk]);
+        for (int jq = 0; jq < QB; ++jq)
+#pragma unroll
+            for (int sk = 0; sk < KB / 2; ++sk)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int word = pf[jq][sk][r];
+                    top = __builtin_elementwise_max(top, __builtin_bit_cast(u16x2, word));
+                }
+        const unsigned short t0 = top[0], t1 = top[1];
+        return __builtin_amdgcn_ballot_w64((t0 > t1 ? t0 : t1) > LAG_BITS) != 0;
+    };
+    auto rebase = [&](const f32x4(&sc)[KB][QB]) __attribute__((always_inline)) {
+        stats(sc);
+#pragma unroll
+        for (int jq = 0; jq < QB; ++jq) {
+            const float mh = __builtin_fmaxf(m2[jq], tile_max[jq]);
+            const float keep = __builtin_amdgcn_exp2f(m2[jq] - mh);       // exp(m - mh); 0 on the first tile
+            m2[jq] = mh;
+            acc_l[jq] *= keep;
+#pragma unroll
+            for (int id = 0; id < DT; ++id) acc_o[id][jq] *= keep;
         }
     };
-    // The exponentials are taken against a reference m2 that follows the running maximum lazily: it moves (and the
-    // sums and outputs so far are rescaled by exp(m_old - m_new)) only when a tile's maximum exceeds it by more than
-    // 2^LAG in some query of the wave, so that no weight exceeds 2^LAG.  The quotient o / l at the end is the same
-    // whatever the reference; after the first few tiles the reference hardly ever moves.
-    constexpr float LAG = 8.0f;
-    auto step_top = [&](int t) __attribute__((always_inline)) {
-        landed_barrier();
-        if (t + 2 < ntiles) issue_K(t + 2);
-        if (t + 1 < ntiles) issue_V(t + 1);
-        bool moved = false;
-#pragma unroll
-        for (int jq = 0; jq < QB; ++jq) moved |= tile_max[jq] - m2[jq] > LAG;   // m2 = -inf before the first tile
-        if (__builtin_amdgcn_ballot_w64(moved)) {
-#pragma unroll
-            for (int jq = 0; jq < QB; ++jq) {
-                const float mh = __builtin_fmaxf(m2[jq], tile_max[jq]);
-                const float keep = __builtin_amdgcn_exp2f(m2[jq] - mh);       // exp(m - mh); 0 on the first tile
-                m2[jq] = mh;
-                acc_l[jq] *= keep;
-#pragma unroll
-                for (int id = 0; id < DT; ++id) acc_o[id][jq] *= keep;
-            }
-        }
-    };
-    // ---- Software pipeline: the matrix-core work of one tile is issued between the vector-ALU work of its
-    // neighbours.  Step t:  [ scores(t+1)  ||  probabilities(t) ]  then  [ weighted_values(t)  ||  stats(t+1) ],
-    // where stats = maximum of a tile per query, probabilities = exponentials, their sum and packing.
+    // ---- Software pipeline: the matrix-core work of tile t+1's scores is issued between the vector-ALU work of tile
+    // t's weights; the second product of tile t follows on its own, and the other wave of the SIMD fills its gaps.
     // One barrier per step: K(t+1) and V(t) have landed and every wave is done with K(t) and V(t-1), whose
     // stages K(t+2) and V(t+1) are then requested into.
+    // tile t (of parity PAR), whose scores are in cur, and the scores of tile t+1 into nxt
+    auto step = [&](int t, auto par_c, f32x4(&cur)[KB][QB], f32x4(&nxt)[KB][QB]) __attribute__((always_inline)) {
+        landed_barrier();
+        if (t + 2 < ntiles) issue_K(t + 2);
+        issue_V(t + 1);
+        scores_into(std::integral_constant<int, 1 - decltype(par_c)::value>{}, nxt);
+        probabilities(t, cur, false);
+        if (__builtin_expect(overflowed(), 0)) {
+            rebase(cur);
+            probabilities(t, cur, false);
+        }
+        weighted_values(par_c);
+    };
+    auto last_step = [&](int t, auto par_c, f32x4(&cur)[KB][QB]) __attribute__((always_inline)) {
+        landed_barrier();
+        probabilities(t, cur, true);
+        if (__builtin_expect(overflowed(), 0)) {
+            rebase(cur);
+            probabilities(t, cur, true);
+        }
+        weighted_values(par_c);
+    };
+    const std::integral_constant<int, 0> even;
+    const std::integral_constant<int, 1> odd;
     issue_K(0);
     landed_barrier();
     issue_V(0);
     if (ntiles > 1) issue_K(1);
-    scores_into(0, s);
-    stats(s);
-    for (int t = 0; t + 1 < ntiles; ++t) {
-        step_top(t);
-        scores_into(t + 1, s_next);
-        probabilities(t, s, false);
-        weighted_values(t);
-        stats(s_next);
-#pragma unroll
-        for (int ik = 0; ik < KB; ++ik)
-#pragma unroll
-            for (int jq = 0; jq < QB; ++jq) s[ik][jq] = s_next[ik][jq];
+    scores_into(even, s);
+    // two tiles per trip: the K stage of each is a constant, and the two score arrays swap roles without being copied
+    int t = 0;
+    for (; t + 2 < ntiles; t += 2) {
+        step(t, even, s, s_next);
+        step(t + 1, odd, s_next, s);
     }
-    step_top(ntiles - 1);
-    if (ntiles * KT > M)
-        probabilities(ntiles - 1, s, true);
-    else
-        probabilities(ntiles - 1, s, false);
-    weighted_values(ntiles - 1);
+    if (t + 1 < ntiles) {
+        step(t, even, s, s_next);
+        last_step(t + 1, odd, s_next);
+    } else {
+        last_step(t, even, s);
+    }
 
     // ---- O_i. = o_i / l_i.  Accumulator register r of lane l: d = 16 id + 4 (l/16) + r, query 16 jq + l%16.
 #pragma unroll

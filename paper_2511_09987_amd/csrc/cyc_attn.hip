@@ -23,19 +23,30 @@
 //                       exp(m - mh) is a per-lane multiply and the final store is 16 bytes per lane.
 // Arithmetic: Q, K, V bfloat16; S, m, l, o fp32; exp through the hardware exp2 with alpha*log2(e) folded
 // into the scores; the probabilities enter the second product rounded to bfloat16 (nearest even), and the
-// running sum adds up those same rounded values (it rides on the second product as a row of ones).  The maximum that the exponentials refer to follows the running maximum
-// lazily (step_top below); o / l does not depend on it.
+// running sum adds up those same rounded values (it rides on the second product as a row of ones).  The maximum that
+// the exponentials refer to follows the running maximum lazily: a tile's maximum is taken only after one of its
+// weights came out above 2^8 (overflowed / rebase below); o / l does not depend on it.
 //
 // Schedule: a software pipeline across tiles inside every wave, so that matrix-core and vector-ALU
-// instructions of neighbouring tiles are issued interleaved (the loop at the end of the kernel).
+// instructions of neighbouring tiles are issued interleaved (the loop at the end of the kernel).  The LDS reads of
+// the K and V fragments are issued from inline asm a fixed number of fragments ahead of the MFMAs that use them and
+// waited for one by one; left to the compiler, which is short of registers here, each read sat right before its use
+// and its whole latency was waited out.  The build checks the compiler's output for such reads (check_async_reads.py).
 //
-// Measured at batch 64, N = M = 4096, TFLOP/s at d = 128 / d = 64 (run-to-run spread about 5 %):
+// Measured at batch 64, N = M = 4096, TFLOP/s at d = 128 / d = 64 (run-to-run and box-to-box spread about 5 %):
 //   64 queries per wave, 4 waves, tile after tile                                    599 / 463
 //   32 queries per wave, 8 waves, tile after tile, 128-key / 64-key tiles           1036 / 848
 //   the same with the two waves of a SIMD half a tile apart (one or two barriers)    940 / 700
 //   software pipeline (this file), maximum followed exactly                          960 / 860
 //   software pipeline, maximum followed lazily                                      1050 / 910
 //   software pipeline with 64 queries per wave and 4 waves (512 registers)           574 / 540
+//   this file: fragment reads a window ahead, maximum only after an overflow   1110-1170 / 850-880
+//   the same on the 32 x 32 x 16 MFMA shape (half the MFMA instructions)        1070-1100 / 860-870
+// The kernel runs at the socket's power limit: on constant inputs (little switching) the 32 x 32 form needs 5 % fewer
+// cycles than this one (1360 against 1290 TFLOP/s), on random inputs its clock drops by as much or more.  Removing
+// the exponentials or the overflow check altogether changes nothing measurable; what is left is matrix work and LDS
+// traffic (each wave reads the whole K and V tile for its 32 queries), and 64 queries per wave do not fit the registers
+// at two waves per SIMD.
 #include "cyc_internal.h"
 
 namespace cyc {

@@ -27,12 +27,13 @@
  * until the process ends, guarded by locks; calls from several host threads
  * on different streams are safe):
  *   - the kernel forced through cyc_force_kernel() / CYC_FORCE_KERNEL;
- *   - for cyc_recurrence_matmul on problems mapped with k in space (see
- *     below): one workspace of device memory per (device, stream), allocated
- *     with hipMalloc at the first such call on that stream and replaced by a
- *     larger one (hipFree + hipMalloc, which waits for the device) when a
- *     later call needs more.  A call that cannot get it returns
- *     CYC_ERR_WORKSPACE.  No other entry point allocates device memory;
+ *   - for cyc_recurrence_matmul on problems mapped with k in space and for
+ *     cyc_recurrence_trsm with tiles of 64 rows (see below): one workspace of
+ *     device memory per (device, stream), allocated with hipMalloc at the
+ *     first such call on that stream and replaced by a larger one (hipFree +
+ *     hipMalloc, which waits for the device) when a later call needs more.
+ *     A call that cannot get it returns CYC_ERR_WORKSPACE.  No other entry
+ *     point allocates device memory;
  *   - for cyc_recurrence_cholesky with n > 16 nb: one extra stream and a few
  *     events per device (see there); callers that use it are serialised on
  *     the host by a lock for the duration of the enqueueing.
@@ -92,7 +93,7 @@ typedef enum {
     CYC_ERR_DTYPE = 3,   /* dtype is not a cyc_dtype */
     CYC_ERR_ALIAS = 4,   /* C overlaps A or B */
     CYC_ERR_LAUNCH = 5,  /* the HIP runtime refused a launch */
-    CYC_ERR_WORKSPACE = 6 /* the workspace a k-in-space problem needs could not be allocated, or exceeds the fixed one */
+    CYC_ERR_WORKSPACE = 6 /* the workspace a call needs could not be allocated, or exceeds the fixed one */
 } cyc_status;
 
 /* One grid: C (M x N) <- A (M x K) streamed against B (K x N).
@@ -130,9 +131,13 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  *     X_I = TRSM(L_II, B_I - sum_{J<I} GEMM(L_IJ, X_J))  over tiles of nb rows).
  * The GEMMs are the matrix-multiply recurrence above with L_IJ as the stationary operand and the solved
  * tile X_J streamed: bfloat16 operands, fp32 partial sums.  A solved tile therefore enters them rounded
- * to bfloat16 (nearest even); inside a tile the solve runs in fp32 on the unrounded values
- * (t = fma(-L_rj, x_j, t) for j ascending, then one IEEE division by L_rr).  nb is part of the result:
- * it fixes where X is rounded.
+ * to bfloat16 (nearest even); inside a tile the solve runs in fp32 on the unrounded values, in one of two
+ * ways.  By substitution: t = fma(-L_rj, x_j, t) for j ascending, then one IEEE division by L_rr.  Or, for
+ * tiles of 64 rows whose diagonal tile L_II is well conditioned (||L_II^-1||_1 ||L_II||_1 <= 8, decided on
+ * the device from L alone), as the product L_II^-1 R_I in fp32, L_II^-1 itself being computed by that
+ * substitution; its result differs from the substitution's by fp32 rounding, within
+ * 64 * 2^-24 * (kappa^2 + kappa) * max|X_I| for kappa = || |L_II^-1| |L_II| ||_inf.  Either way the result is
+ * the same on every call.  nb is part of the result: it fixes where X is rounded.
  *
  * L:  device, read only, n x n bfloat16 row-major; only the diagonal and the entries below it are used
  *     (what lies above the diagonal may hold anything, NaN included).
@@ -142,13 +147,17 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  * Xh: device, written, n x nrhs bfloat16 row-major: X rounded to bfloat16, the values the GEMMs consumed.
  * nb: tile size, 1 <= nb <= 128.  The MFMA kernels serve the GEMMs when n, nrhs and nb are multiples of 8
  *     and the pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
- * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates
- *     nothing and keeps no state.  n == 0 or nrhs == 0: CYC_OK, nothing done.  A zero on the diagonal
+ * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns.  With nb == 64,
+ *     nrhs a multiple of 8, n a multiple of 8 and 16-byte aligned L, X, Xh it keeps the inverses of the diagonal
+ *     tiles (16 KiB per 64 rows) in the workspace that the library holds per device and stream (allocated or
+ *     grown on the call that first needs it, as for cyc_recurrence_matmul); otherwise it allocates nothing.
+ *     n == 0 or nrhs == 0: CYC_OK, nothing done.  A zero on the diagonal
  *     gives infinities or NaNs as IEEE division does, not an error.  Inside the kernels, waves hand solved rows
  *     to one another through LDS with bounded waits; a wait that ever ran out would leave NaN in X and Xh (in
  *     the last tile of the affected panel, and in every row solved after it) rather than plausible wrong values.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or overflowing extents, nb out of
- * range), CYC_ERR_ALIAS (X or Xh overlaps L, B or each other).  CYC_ERR_LAUNCH: see the top of this file. */
+ * range), CYC_ERR_ALIAS (X or Xh overlaps L, B or each other), CYC_ERR_WORKSPACE (the workspace could not be
+ * allocated).  CYC_ERR_LAUNCH: see the top of this file. */
 int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
                         int64_t n, int64_t nrhs, int64_t nb, void *stream);
 

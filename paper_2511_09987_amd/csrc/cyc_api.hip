@@ -219,7 +219,14 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh, int64_t
     if (overlaps(X, nr * 4, L, nn * 2) || overlaps(X, nr * 4, B, nr * 4) || overlaps(Xh, nr * 2, L, nn * 2) ||
         overlaps(Xh, nr * 2, B, nr * 4) || overlaps(X, nr * 4, Xh, nr * 2))
         return CYC_ERR_ALIAS;
-    return cyc::launch_trsm(L, B, X, Xh, n, nrhs, nb, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+    // the inverses of the diagonal tiles live in the per-stream workspace; it is acquired before the first launch
+    void *workspace = nullptr;
+    const int64_t need = cyc::trsm_workspace_bytes(L, X, Xh, n, nrhs, nb);
+    if (need > 0) {
+        workspace = cyc::cached_workspace((hipStream_t)stream, need);
+        if (!workspace) return CYC_ERR_WORKSPACE;
+    }
+    return cyc::launch_trsm(L, B, X, Xh, n, nrhs, nb, workspace, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 
 int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *stream)

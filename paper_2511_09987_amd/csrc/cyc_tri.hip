@@ -517,20 +517,19 @@ __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const 
 // same order.  Requires, on top of tri_panel_kernel's conditions, nrhs a multiple of 8 and 16-byte aligned X and Xh
 // (whole 16-byte pieces of a row are stored or skipped).
 constexpr int PANELW = 8;
-__global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
-                                                         float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
-                                                         int tiles)
+// everything the solve reads in the first 64 KB of LDS (16-bit offset field from one base register)
+struct PanelLds {
+    float D[64][64 + 4];               // L_tt in fp32, row-major, on and below the diagonal
+    float R[64][64 + 4];               // right-hand side of the tile with the panel's product taken out, [row][column]
+    float Xs[64][64 + 4];              // the tile's solution, [row][column]
+    uint16_t Xb[PANELW * 64][64];      // solved tiles as bfloat16, [k][column]
+    int ready;                         // hand-over counter of solve_tile64_waves
+    int expired;                       // set by a wave of solve_tile64_waves whose bounded wait ran out
+};
+__device__ __forceinline__ void panel_by_substitution(PanelLds &lds, const uint16_t *__restrict__ L, int64_t n, const float *Rin,
+                                                      float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles)
 {
     constexpr int NB = 64, LDD = NB + 4, NT = 256, NKS = 2 * PANELW - 2;
-    // everything the solve reads in the first 64 KB of LDS (16-bit offset field from one base register)
-    __shared__ __attribute__((aligned(16))) struct {
-        float D[NB][LDD];                  // L_tt in fp32, row-major, on and below the diagonal
-        float R[NB][LDD];                  // right-hand side of the tile with the panel's product taken out, [row][column]
-        float Xs[NB][LDD];                 // the tile's solution, [row][column]
-        uint16_t Xb[PANELW * NB][64];      // solved tiles as bfloat16, [k][column]
-        int ready;                         // hand-over counter of solve_tile64_waves
-        int expired;                       // set by a wave of solve_tile64_waves whose bounded wait ran out
-    } lds;
     int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t c0 = (int64_t)blockIdx.x * 64;
@@ -661,6 +660,323 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
     }
 }
 
+// ---- Diagonal tiles through their inverses.
+// X_t = TRSM(L_tt, R_t) is a chain of 64 dependent rows per tile and 128 tiles follow one another at n = 8192; the
+// tile operation itself is left open by the paper (a library call there).  The inverses of the diagonal tiles depend
+// on L alone, so all of them are computed ahead, side by side (tri_inverse_kernel: the substitution above with the
+// identity as right-hand side), and a tile's solve becomes the product X_t = L_tt^-1 R_t on the matrix cores in fp32
+// (v_mfma_f32_16x16x4_f32: fp32 operands, fp32 sums), which has no chain.  The product is as good as the substitution
+// only for a well-conditioned tile: with kappa = || |L_tt^-1| |L_tt| || its error bound is (kappa^2 + kappa) where the
+// substitution's is kappa.  tri_inverse_kernel therefore leaves a verdict per tile, ||L_tt^-1||_1 ||L_tt||_1 <= 8
+// (an upper bound of kappa that costs a column sum per lane), and a panel whose tiles do not all pass takes the
+// substitution as before.  Both are deterministic; which one runs depends on L alone.
+constexpr int INV_FLOATS = 64 * 64;        // one inverse in the workspace, in the order described at tri_inverse_kernel
+constexpr float INV_NORM_LIMIT = 8.0f;
+
+// One wave per full diagonal tile: lane j solves L_tt y = e_j.  Entry (r, j) of the inverse is stored where the panel
+// kernel's MFMA wants it as its A operand: operand lane (r % 16) + 16 (j % 4) holds it for row block rb = r / 16 and
+// k-step ks = j / 4.  A tile is 16 pieces of 1 KiB, piece 4 rb + ks / 4 holding the four k-steps ks / 4 * 4 .. + 3 of
+// all 64 operand lanes ([lane][ks % 4]), so that a wave fetches a piece with one fully coalesced 16-byte load per lane.
+__global__ __launch_bounds__(64) void tri_inverse_kernel(const uint16_t *__restrict__ L, int64_t n, float *__restrict__ Winv,
+                                                         int *__restrict__ ok)
+{
+    constexpr int NB = 64, LDD = NB + 4, cpr = NB / 8, PER_LANE = NB * NB / 8 / 64;
+    __shared__ __attribute__((aligned(16))) float D[NB][LDD];
+    __shared__ float norms[2][64];
+    const int lane = threadIdx.x;
+    const int64_t rt = (int64_t)blockIdx.x * NB;
+#pragma unroll
+    for (int x = 0; x < PER_LANE; ++x) {                         // the 16-byte pieces on and below the diagonal, widened
+        const int id = lane + 64 * x, r = id / cpr, jc = id % cpr;
+        if (jc * 8 <= r) {
+            const uint4 piece = *(const uint4 *)(L + (rt + r) * n + rt + jc * 8);
+            const uint32_t v[4] = {piece.x, piece.y, piece.z, piece.w};
+            f32x4 lo, hi;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                lo[e] = widen_bf16((uint16_t)(v[e >> 1] >> (16 * (e & 1))));
+                hi[e] = widen_bf16((uint16_t)(v[2 + (e >> 1)] >> (16 * (e & 1))));
+            }
+            *(f32x4 *)&D[r][jc * 8] = lo;
+            *(f32x4 *)&D[r][jc * 8 + 4] = hi;
+        }
+    }
+    __syncthreads();
+    float colsum_L = 0.0f;                                       // column `lane` of |L_tt|, on and below the diagonal
+    for (int i = 0; i < NB; ++i) colsum_L += i >= lane ? __builtin_fabsf(D[i][lane]) : 0.0f;
+    float x[NB], xn[NB];
+#pragma unroll
+    for (int r = 0; r < NB; ++r) x[r] = r == lane ? 1.0f : 0.0f;
+    float colsum_inv = 0.0f;
+    float *out = Winv + (int64_t)blockIdx.x * INV_FLOATS + (lane >> 4) * 256 + (lane & 3) * 64 + ((lane >> 2) & 3);
+    solve_tile64<LDD>(
+        D, x, xn,
+        [&](int r, float y) __attribute__((always_inline)) {
+            out[(r >> 4) * 1024 + (r & 15) * 4] = y;              // rows above the lane's own come out as exact zeros
+            colsum_inv += __builtin_fabsf(y);
+        },
+        []() __attribute__((always_inline)) {});
+    norms[0][lane] = colsum_L;
+    norms[1][lane] = colsum_inv;
+    __syncthreads();
+    if (lane == 0) {
+        float a = 0.0f, b = 0.0f;
+        bool finite = true;
+        for (int j = 0; j < 64; ++j) {
+            a = __builtin_fmaxf(a, norms[0][j]);
+            b = __builtin_fmaxf(b, norms[1][j]);
+            finite = finite && norms[0][j] == norms[0][j] && norms[1][j] == norms[1][j];   // fmax drops a NaN
+        }
+        ok[blockIdx.x] = finite && a * b <= INV_NORM_LIMIT ? 1 : 0;
+    }
+}
+
+// The panel of tri_panelw_kernel with the diagonal solves as products with the inverses.  The four waves share the
+// slab as there: wave w multiplies out rows 16w .. 16w+15 of the panel's product for the next tile and stores a quarter
+// of the results.  In the solve wave w takes the COLUMNS 16w .. 16w+15 of the slab and all 64 rows: the inverse is
+// lower triangular, so row block rb needs the k-steps 0 .. 4 rb + 3 only, 40 MFMAs per wave and tile whichever wave,
+// and the streamed operand (R, [row][column] in LDS) is one LDS read per k-step.
+// Memory traffic is arranged around one wait per tile.  On this chip loads and stores share one counter and complete
+// out of order with respect to each other, so while both are outstanding the only wait the compiler can insert is
+// the wait for all of them.  Everything a tile issues to memory -- the stores of the previous tile's results, the
+// loads of the next tile's inverse and of the right-hand side and rows of L of the tile after that -- is therefore
+// issued at the top of the tile, and what was loaded is first touched (an empty asm statement that names the
+// registers) at the top of the tile in which it is used, a whole tile later, when it has long arrived.  Hence two
+// register sets for everything loaded, and two tiles per loop trip so that the sets are named statically.
+__device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t *__restrict__ L, int64_t n, const float *Rin,
+                                                  float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles,
+                                                  const float *__restrict__ Winv)
+{
+    constexpr int NB = 64, NT = 256, NKS = 2 * PANELW - 2;
+    int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t c0 = (int64_t)blockIdx.x * 64;
+    struct Operands {
+        f32x4 rhs[4];                                                  // rows 16w + 4g + r, columns 16j + lq: [j][r]
+        i32x4 a[NKS];                                                  // row 16w + lq of L[u, 0:u], k = 32 ks + 8 g .. +7
+    };
+    Operands op0, op1;
+    f32x4 inv0[10], inv1[10];                                          // this lane's 40 values of an inverse
+
+    // What tile u needs from memory, as a list of single loads (so that they can be dealt out between the MFMAs of a
+    // solve): items 0 .. 15 its right-hand side, items 16 .. 16 + NKS - 1 its rows of L (those of the k-steps it has)
+    constexpr int REQUEST_ITEMS = 16 + NKS, INVERSE_ITEMS = 10;
+    auto request_item = [&](int u, Operands &o, int i) __attribute__((always_inline)) {
+        const int64_t ru = r0 + (int64_t)u * NB;
+        if (i < 16) {
+            const int j = i >> 2, r = i & 3;
+            const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
+            o.rhs[j][r] = Rin[(ru + 16 * w + 4 * g + r) * nrhs + col];
+        } else {
+            const int ks = i - 16;
+            if (ks < 2 * u) o.a[ks] = *(const i32x4 *)(L + (ru + 16 * w + lq) * n + r0 + ks * 32 + g * 8);      // uniform condition
+        }
+    };
+    auto request = [&](int u, Operands &o) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < REQUEST_ITEMS; ++i) request_item(u, o, i);
+    };
+    // the pieces of an inverse on and below the block diagonal: 1 + 2 + 3 + 4 of the 16; item p is piece (rb, q)
+    auto request_inverse_item = [&](int u, f32x4(&iv)[10], int p) __attribute__((always_inline)) {
+        const int rb = p < 1 ? 0 : p < 3 ? 1 : p < 6 ? 2 : 3, q = p - rb * (rb + 1) / 2;
+        iv[p] = *(const f32x4 *)(Winv + (int64_t)u * INV_FLOATS + lane * 4 + (rb * 4 + q) * 256);
+    };
+    auto request_inverse = [&](int u, f32x4(&iv)[10]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < INVERSE_ITEMS; ++p) request_inverse_item(u, iv, p);
+    };
+    // what was loaded a tile ago is waited for here and nowhere else
+    auto touch = [&](f32x4(&iv)[10], Operands &o) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(iv[0]), "+v"(iv[1]), "+v"(iv[2]), "+v"(iv[3]), "+v"(iv[4]), "+v"(iv[5]), "+v"(iv[6]), "+v"(iv[7]),
+                          "+v"(iv[8]), "+v"(iv[9]), "+v"(o.rhs[0]), "+v"(o.rhs[1]), "+v"(o.rhs[2]), "+v"(o.rhs[3])
+                     :: "memory");
+        asm volatile("" : "+v"(o.a[0]), "+v"(o.a[1]), "+v"(o.a[2]), "+v"(o.a[3]), "+v"(o.a[4]), "+v"(o.a[5]), "+v"(o.a[6]),
+                          "+v"(o.a[7]), "+v"(o.a[8]), "+v"(o.a[9]), "+v"(o.a[10]), "+v"(o.a[11]), "+v"(o.a[12]), "+v"(o.a[13])
+                     :: "memory");
+    };
+    static_assert(NKS == 14, "touch names every register of Operands");
+    // The panel's product for tile u (its rows of L times the tiles solved before it) in two parts: the k-steps over
+    // the tiles before u - 1 are multiplied out ahead, beside the solve of tile u - 1 (early), the two k-steps over
+    // tile u - 1 after it (late), and R = right-hand side - product goes to LDS.  The bounds are constants in every
+    // copy (the switches below when the tile number is not one), so that each part is straight-line code in which the
+    // streamed operand of a k-step is read two k-steps ahead of its MFMAs.
+    f32x4 acc[4];
+    auto k_range = [&](auto first, auto last, const Operands &o) __attribute__((always_inline)) {
+        constexpr int FIRST = decltype(first)::value, LAST = decltype(last)::value;
+        i32x4 b[3][4];
+        auto read_b = [&](int ks, i32x4(&dst)[4]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+                const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+                dst[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
+            }
+        };
+        if (FIRST < LAST) read_b(FIRST, b[FIRST % 3]);
+        if (FIRST + 1 < LAST) read_b(FIRST + 1, b[(FIRST + 1) % 3]);
+#pragma unroll
+        for (int ks = FIRST; ks < LAST; ++ks) {
+            if (ks + 2 < LAST) read_b(ks + 2, b[(ks + 2) % 3]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, o.a[ks]), __builtin_bit_cast(bf16x8, b[ks % 3][j]), acc[j], 0, 0, 0);
+        }
+    };
+    auto early_of = [&](auto tile_c, const Operands &o) __attribute__((always_inline)) {
+        constexpr int U = decltype(tile_c)::value;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
+        k_range(std::integral_constant<int, 0>{}, std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, o);
+    };
+    auto late_of = [&](auto tile_c, const Operands &o) __attribute__((always_inline)) {
+        constexpr int U = decltype(tile_c)::value;
+        k_range(std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, std::integral_constant<int, 2 * U>{}, o);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lds.R[16 * w + 4 * g + r][16 * j + lq] = o.rhs[j][r] - acc[j][r];
+    };
+    // (u is uniform and at most PANELW - 1; when the caller's tile number is a constant the switch folds away)
+    auto stage_early = [&](int u, const Operands &o) __attribute__((always_inline)) {
+        switch (u) {
+            case 0: early_of(std::integral_constant<int, 0>{}, o); break;
+            case 1: early_of(std::integral_constant<int, 1>{}, o); break;
+            case 2: early_of(std::integral_constant<int, 2>{}, o); break;
+            case 3: early_of(std::integral_constant<int, 3>{}, o); break;
+            case 4: early_of(std::integral_constant<int, 4>{}, o); break;
+            case 5: early_of(std::integral_constant<int, 5>{}, o); break;
+            case 6: early_of(std::integral_constant<int, 6>{}, o); break;
+            default: early_of(std::integral_constant<int, PANELW - 1>{}, o); break;
+        }
+    };
+    auto stage_late = [&](int u, const Operands &o) __attribute__((always_inline)) {
+        switch (u) {
+            case 0: late_of(std::integral_constant<int, 0>{}, o); break;
+            case 1: late_of(std::integral_constant<int, 1>{}, o); break;
+            case 2: late_of(std::integral_constant<int, 2>{}, o); break;
+            case 3: late_of(std::integral_constant<int, 3>{}, o); break;
+            case 4: late_of(std::integral_constant<int, 4>{}, o); break;
+            case 5: late_of(std::integral_constant<int, 5>{}, o); break;
+            case 6: late_of(std::integral_constant<int, 6>{}, o); break;
+            default: late_of(std::integral_constant<int, PANELW - 1>{}, o); break;
+        }
+    };
+    // results of tile v: 16-byte pieces from LDS (Xs: the buffer of v's parity) to X and Xh
+    auto store = [&](int v, const float(*Xs)[NB + 4]) __attribute__((always_inline)) {
+        const int64_t rv = r0 + (int64_t)v * NB;
+#pragma unroll
+        for (int p = 0; p < NB * 16 / NT; ++p) {
+            const int id = tid + NT * p, r = id >> 4, ch = id & 15;
+            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = *(const f32x4 *)&Xs[r][4 * ch];
+        }
+#pragma unroll
+        for (int p = 0; p < NB * 8 / NT; ++p) {
+            const int id = tid + NT * p, r = id >> 3, ch = id & 7;
+            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * ch];
+        }
+    };
+    // X_t = L_tt^-1 R_t for the wave's 16 columns.  A operand lane l: row 16 rb + l%16, k = 4 ks + l/16; B operand:
+    // k = 4 ks + l/16, column l%16; accumulator register r: row 16 rb + 4 (l/16) + r, column l%16.
+    // beside(i) is called after the i-th of the 40 MFMAs and pinned there: an MFMA occupies the matrix pipe for 32
+    // cycles, and what the wave issues meanwhile (the loads of later tiles) costs the solve nothing.
+    auto solve = [&](int t, const f32x4(&iv)[10], float(*Xs)[NB + 4], auto beside) __attribute__((always_inline)) {
+        float b[16];
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks) b[ks] = lds.R[4 * ks + g][16 * w + lq];
+        f32x4 x[4];
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) x[rb] = (f32x4){0, 0, 0, 0};
+        int issued = 0;
+#pragma unroll
+        for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+            for (int rb = ks / 4; rb < 4; ++rb) {
+                x[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(iv[rb * (rb + 1) / 2 + ks / 4][ks % 4], b[ks], x[rb], 0, 0, 0);
+                beside(issued++);
+            }
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = 16 * rb + 4 * g + r;
+                Xs[row][16 * w + lq] = x[rb][r];
+                lds.Xb[t * NB + row][16 * w + lq] = round_bf16(x[rb][r]);
+            }
+    };
+    // Tile t of `count`.  `mine` holds its inverse and `next` the operands of tile t + 1's product; `other` takes the
+    // inverse of tile t + 1 and `later` the operands of tile t + 2.  The results stay in LDS (lds.Xs for even t, lds.D,
+    // which nothing else uses here, for odd t) and are stored at the top of the next tile.
+    // `dealt`: t and count are constants here, so the loads can be dealt out between the MFMAs of the solve
+    auto tile = [&](int t, int count, bool dealt, f32x4(&mine)[10], f32x4(&other)[10], Operands &next, Operands &later, float(*Xs)[NB + 4],
+                    const float(*Xs_before)[NB + 4]) __attribute__((always_inline)) {
+        // the thread index is made opaque once per tile (see panel_by_substitution)
+        asm volatile("" : "+v"(tid));
+        lane = tid & 63;
+        lq = lane & 15;
+        g = lane >> 4;
+        touch(mine, next);
+        if (t > 0) store(t - 1, Xs_before);
+        if (!dealt) {
+            if (t + 1 < count) request_inverse(t + 1, other);
+            if (t + 2 < count) request(t + 2, later);
+        }
+        if (t + 1 < count) stage_early(t + 1, next);
+        solve(t, mine, Xs, [&](int i) __attribute__((always_inline)) {
+            if (dealt) {                                               // one load behind each MFMA, 40 of either
+                static_assert(INVERSE_ITEMS + REQUEST_ITEMS == 40, "one load per MFMA of the solve");
+                if (i < INVERSE_ITEMS) {
+                    if (t + 1 < count) request_inverse_item(t + 1, other, i);
+                } else if (t + 2 < count) {
+                    request_item(t + 2, later, i - INVERSE_ITEMS);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        __syncthreads();                                               // tile t is solved: R is free, Xs and Xb complete
+        if (t + 1 < count) stage_late(t + 1, next);
+        __syncthreads();                                               // tile t + 1 is staged
+    };
+
+    request(0, op0);
+    request_inverse(0, inv0);
+    if (tiles > 1) request(1, op1);
+    stage_early(0, op0);
+    stage_late(0, op0);
+    __syncthreads();
+    if (tiles == PANELW) {
+        // the usual case, every tile number a constant: each tile is straight-line code between its barriers
+        unrolled<PANELW / 2>([&](auto half) __attribute__((always_inline)) {
+            constexpr int t = 2 * decltype(half)::value;
+            tile(t, PANELW, true, inv0, inv1, op1, op0, lds.Xs, lds.D);
+            tile(t + 1, PANELW, true, inv1, inv0, op0, op1, lds.D, lds.Xs);
+        });
+    } else {
+#pragma unroll 1
+        for (int t = 0; t < tiles; t += 2) {
+            tile(t, tiles, false, inv0, inv1, op1, op0, lds.Xs, lds.D);
+            if (t + 1 < tiles) tile(t + 1, tiles, false, inv1, inv0, op0, op1, lds.D, lds.Xs);
+        }
+    }
+    store(tiles - 1, (tiles - 1) & 1 ? lds.D : lds.Xs);
+}
+
+// The four-wave panel: through the inverses when every tile of the panel passed tri_inverse_kernel's check (Winv and ok
+// start at the panel's first tile; Winv == nullptr: no inverses were computed), by substitution otherwise.
+__global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
+                                                         float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
+                                                         int tiles, const float *__restrict__ Winv, const int *__restrict__ ok)
+{
+    __shared__ __attribute__((aligned(16))) PanelLds lds;
+    bool inverses = Winv != nullptr;
+    if (inverses)
+        for (int t = 0; t < tiles; ++t) inverses = inverses && ok[t] != 0;          // uniform
+    if (inverses)
+        panel_by_inverses(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, Winv);
+    else
+        panel_by_substitution(lds, L, n, Rin, X, Xh, nrhs, r0, tiles);
+}
+
 struct Solve {
     const uint16_t *L;
     const float *B;
@@ -668,6 +984,8 @@ struct Solve {
     uint16_t *Xh;
     int64_t n, nrhs, nb;
     hipStream_t s;
+    const float *Winv;      // inverses of the full diagonal tiles, tile after tile, or nullptr
+    const int *ok;          // per tile: the inverse may stand in for the substitution
 };
 
 // the running right-hand side of rows that no GEMM has touched yet is still B; afterwards it lives in X
@@ -728,7 +1046,8 @@ hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
     const int tiles = (int)((r1 - r0) / 64);
     hipError_t launch_err = hipSuccess;
     if (panelw_ok(v))
-        launch_err = launch_kernel(tri_panelw_kernel, grid, dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
+        launch_err = launch_kernel(tri_panelw_kernel, grid, dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles,
+                                   v.Winv ? v.Winv + r0 / 64 * INV_FLOATS : nullptr, v.ok ? v.ok + r0 / 64 : nullptr);
     else
         launch_err = launch_kernel(tri_panel_kernel, grid, dim3(64), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
     return launch_err;
@@ -748,10 +1067,32 @@ hipError_t solve(const Solve &v, int64_t r0, int64_t r1)
 
 }  // namespace
 
-hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, hipStream_t s)
+// the diagonal tiles are worth inverting ahead: the four-wave panel kernel will run, on tiles of 64 rows
+static bool inverses_wanted(const Solve &v)
+{
+    return v.nb == 64 && v.n >= 64 && panelw_ok(v) && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0;
+}
+
+int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb)
+{
+    Solve v{(const uint16_t *)L, nullptr, (float *)X, (uint16_t *)Xh, n, nrhs, nb, nullptr, nullptr, nullptr};
+    return inverses_wanted(v) ? (n / 64) * (int64_t)(INV_FLOATS * sizeof(float) + sizeof(int)) : 0;
+}
+
+hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, void *workspace,
+                       hipStream_t s)
 {
     if (nb < 1 || nb > 128 || (int64_t)((nrhs + 63) / 64) > 0x7fffffff) return hipErrorInvalidValue;
-    Solve v{(const uint16_t *)L, (const float *)B, (float *)X, (uint16_t *)Xh, n, nrhs, nb, s};
+    Solve v{(const uint16_t *)L, (const float *)B, (float *)X, (uint16_t *)Xh, n, nrhs, nb, s, nullptr, nullptr};
+    if (workspace && inverses_wanted(v)) {
+        const int64_t full = n / 64;
+        float *Winv = (float *)workspace;
+        int *ok = (int *)(Winv + full * INV_FLOATS);
+        const hipError_t e = launch_kernel(tri_inverse_kernel, dim3((unsigned)full), dim3(64), s, v.L, n, Winv, ok);
+        if (e != hipSuccess) return e;
+        v.Winv = Winv;
+        v.ok = ok;
+    }
     return solve(v, 0, n);
 }
 

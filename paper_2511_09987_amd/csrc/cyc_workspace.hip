@@ -1,4 +1,4 @@
-// cyc_workspace.hip -- device memory for the partial products of the k-in-space matmul (see cyc_internal.h).
+// cyc_workspace.hip -- device memory for the partial products of the k-in-space matmul and for the inverses of the triangular solve (see cyc_internal.h).
 //
 // Two sources.  cached_workspace(): one hipMalloc'd buffer per (device, stream), so that calls on different
 // streams never share one; grown when a call needs more, never shrunk, kept until the process ends.

@@ -28,7 +28,8 @@
  * on different streams are safe):
  *   - the kernel forced through cyc_force_kernel() / CYC_FORCE_KERNEL;
  *   - for cyc_recurrence_matmul on problems mapped with k in space and for
- *     cyc_recurrence_trsm with tiles of 64 rows (see below): one workspace of
+ *     cyc_recurrence_trsm and cyc_recurrence_cholesky with tiles of 64 rows
+ *     (see below): one workspace of
  *     device memory per (device, stream), allocated with hipMalloc at the
  *     first such call on that stream and replaced by a larger one (hipFree +
  *     hipMalloc, which waits for the device) when a later call needs more.
@@ -168,6 +169,11 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
  * operands, fp32 partial sums; GEMM(X, Y) = X Y^T): a finished tile therefore enters them rounded to bfloat16
  * (nearest even).  CHOL and TRSM run the scalar recurrence inside the tile column in fp32 on unrounded values
  * (t = fma(-L_rk, L_ck, t) for k ascending, then an IEEE square root on the diagonal, an IEEE division below it).
+ * One exception, with nb == 64 and n >= 128: the 64 rows right below a diagonal tile, which the next diagonal tile
+ * waits for, are formed as the fp32 product S_ij L_jj^-T when L_jj is well conditioned (||L_jj^-1||_1 ||L_jj||_1 <= 8,
+ * decided on the device from L_jj alone; L_jj^-1 computed by substitution beside the factorisation of the tile).
+ * They differ from the recurrence's by fp32 rounding, within 64 * 2^-24 * (kappa^2 + kappa) * max|L_ij| for
+ * kappa = || |L_jj^-1| |L_jj| ||_inf; the result is the same on every call.
  * nb is part of the result: it fixes where L is rounded.
  *
  * A:  device, read only, n x n fp32 row-major.  Entries above the diagonal outside the diagonal tiles are never
@@ -178,15 +184,18 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
  *     with both triangles filled: Lh[r][c] = Lh[c][r] = bf16(L[max(r,c)][min(r,c)]).
  * nb: tile size, 1 <= nb <= 64.  The MFMA kernels serve the updates when n and nb are multiples of 8 and the
  *     pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
- * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns; it allocates no device
- *     memory.  For n > 16 nb part of the work is enqueued on a second stream that the library creates per device
+ * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns.  With nb == 64 and
+ *     n >= 128 it keeps the inverses of the diagonal tiles (16 KiB per 64 rows) in the workspace that the library
+ *     holds per device and stream (allocated or grown on the call that first needs it); otherwise it allocates no
+ *     device memory.  For n > 16 nb part of the work is enqueued on a second stream that the library creates per device
  *     on first use (default priority, kept until the process ends) and that is forked from and joined back into
  *     `stream` with events inside the call: all of the call's work is ordered after what was on `stream` before
  *     and before what is enqueued on it afterwards; calls that use the second stream are serialised on the host
  *     by a lock.  n == 0: CYC_OK, nothing done.  A matrix that is not positive definite gives NaNs (square root
  *     of a negative number), not an error.
  * Errors (nothing enqueued): CYC_ERR_NULL, CYC_ERR_SHAPE (negative or too large n, nb out of range, A or L not
- * 4-byte or Lh not 2-byte aligned), CYC_ERR_ALIAS (A, L, Lh overlap one another).  CYC_ERR_LAUNCH: see the top of
+ * 4-byte or Lh not 2-byte aligned), CYC_ERR_ALIAS (A, L, Lh overlap one another), CYC_ERR_WORKSPACE (the workspace
+ * could not be allocated).  CYC_ERR_LAUNCH: see the top of
  * this file; work already on the second stream is joined back into `stream` before the call returns. */
 int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *stream);
 

@@ -238,7 +238,13 @@ int cyc_recurrence_cholesky(const void *A, void *L, void *Lh, int64_t n, int64_t
     if (!A || !L || !Lh) return CYC_ERR_NULL;
     if (((uintptr_t)A | (uintptr_t)L) & 3 || ((uintptr_t)Lh & 1)) return CYC_ERR_SHAPE;
     if (overlaps(L, nn * 4, A, nn * 4) || overlaps(Lh, nn * 2, A, nn * 4) || overlaps(L, nn * 4, Lh, nn * 2)) return CYC_ERR_ALIAS;
-    return cyc::launch_chol(A, L, Lh, n, nb, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+    void *workspace = nullptr;
+    const int64_t need = cyc::chol_workspace_bytes(n, nb);
+    if (need > 0) {
+        workspace = cyc::cached_workspace((hipStream_t)stream, need);
+        if (!workspace) return CYC_ERR_WORKSPACE;
+    }
+    return cyc::launch_chol(A, L, Lh, n, nb, workspace, (hipStream_t)stream) == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 
 int cyc_recurrence_attention(const void *Q, const void *K, const void *V, void *O, int64_t batch, int64_t N, int64_t M,

@@ -139,6 +139,35 @@ __device__ __forceinline__ void load_tile(float (*dst)[LDT], const float *src, i
     }
 }
 
+// The same in two steps for kernels that fetch several tiles: request() issues the loads of a thread, place() puts
+// them into LDS.  With the steps of two tiles interleaved (all requests, then all placements) memory is waited for
+// once; load_tile twice in a row waits for the first tile before it asks for the second.
+struct TileLoad {
+    static constexpr int PASSES = NBMAX * 16 / NT;
+    f32x4 v[PASSES];
+    bool whole;
+    __device__ __forceinline__ void request(const float *src, int64_t ld, int nrows, int cols, int tid)
+    {
+        whole = cols == NBMAX && ld % 4 == 0 && ((uintptr_t)src & 15) == 0;             // uniform
+        if (whole) {
+#pragma unroll
+            for (int i = 0; i < PASSES; ++i) {
+                const int r = NT / 16 * i + (tid >> 4);
+                v[i] = *(const f32x4 *)(src + (int64_t)(r < nrows ? r : nrows - 1) * ld + 4 * (tid & 15));
+            }
+        }
+    }
+    __device__ __forceinline__ void place(float (*dst)[LDT], const float *src, int64_t ld, int nrows, int cols, int tid)
+    {
+        if (whole) {
+#pragma unroll
+            for (int i = 0; i < PASSES; ++i) *(f32x4 *)&dst[NT / 16 * i + (tid >> 4)][4 * (tid & 15)] = v[i];
+        } else {
+            load_tile(dst, src, ld, nrows, cols, tid);
+        }
+    }
+};
+
 // The reverse for a full-width tile held in LDS: rows 0..nrows-1 to the fp32 matrix L and, rounded, to the bfloat16
 // matrix Lh (both with row stride ld), 16 bytes per thread and store.  False when shape or alignment do not allow it.
 // LOWER: the tile is a diagonal tile; L gets zeros above the diagonal (Lh gets what the tile holds there).
@@ -270,9 +299,174 @@ struct TileProduct {
     }
 };
 
+// ---- The inverse of a diagonal tile, computed beside its factorisation.
+// L_ij = TRSM(S_ij, L_jj) for the tile right below the diagonal tile is on the path from one diagonal tile to the
+// next: 64 dependent columns.  With W = L_jj^-1 at hand it is the product S_ij W^T on the matrix cores, which has no
+// chain; and W can be had off that path: while the first wave factors the tile, the second follows it four rows
+// behind, lane j solving L_jj y = e_j by the substitution of the triangular solve (the step list of cyc_wave.h: rows
+// 4b .. 4b+3 of L_jj are final once the factorisation has finished block b, which it announces through a counter in
+// LDS).  As in the triangular solve the product stands in for the substitution only when the tile is well
+// conditioned: the follower leaves ||W||_1 ||L_jj||_1 <= 8 (and everything finite, and no wait expired) as a verdict
+// beside W.  W is stored in the order in which the product wants its operand, the one of the triangular solve's
+// inverses: entry (r, j) in piece 4 (r / 16) + j / 16 of 1 KiB, at [(r % 16) + 16 (j % 4)][(j / 4) % 4].
+constexpr int W_FLOATS = 64 * 64;
+constexpr float W_NORM_LIMIT = 8.0f;
+constexpr int FOLLOW_SPIN_LIMIT = 1 << 20;
+
+// every read of the follower asks for columns of a block that the gate before it has seen finished
+constexpr bool follower_reads_are_gated()
+{
+    int passed = 0, i = 0;                                   // gate(0) comes first
+    bool ok = true;
+    auto check = [&](int idx) { if (STEPS.b[idx] >= 0 && STEPS.k[idx] > passed) ok = false; };
+    check(0);
+    check(1);
+    for (int b = 0; b < NBLK; ++b) {
+        if (b > 0) passed = b;
+        for (int s2 = early_of(b); s2 < b; ++s2) {
+            check(i + 2);
+            ++i;
+        }
+        for (int j = 0; j < 4; ++j)
+            if (b + 1 < NBLK && j < early_of(b + 1)) {
+                check(i + 2);
+                ++i;
+            }
+    }
+    return ok && i == NSTEP;
+}
+static_assert(follower_reads_are_gated(), "the follower would read rows of L before they are final");
+
+// maximum over the 64 lanes of a wave, in every lane
+__device__ __forceinline__ float wave_max64(float v)
+{
+    auto dpp = [](float x, auto ctrl) __attribute__((always_inline)) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    v = __builtin_fmaxf(v, dpp(v, std::integral_constant<int, 0xB1>{}));      // quad_perm 1,0,3,2
+    v = __builtin_fmaxf(v, dpp(v, std::integral_constant<int, 0x4E>{}));      // quad_perm 2,3,0,1
+    v = __builtin_fmaxf(v, dpp(v, std::integral_constant<int, 0x141>{}));     // row_half_mirror
+    v = __builtin_fmaxf(v, dpp(v, std::integral_constant<int, 0x140>{}));     // row_mirror: the maximum of each row of 16
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    const unsigned m = __builtin_bit_cast(unsigned, __builtin_fmaxf(__builtin_bit_cast(float, a0), __builtin_bit_cast(float, a1)));
+    const auto b = __builtin_amdgcn_permlane32_swap(m, m, false, false);
+    const unsigned b0 = b[0], b1 = b[1];
+    return __builtin_fmaxf(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
+}
+
+// The follower: one wave, lane = column of W.  T holds S above the factorisation's progress and L below it; *ready
+// counts the blocks of four columns the factorisation has finished.  Writes W and the verdict.
+__device__ __forceinline__ void inverse_follow64(const float (*T)[LDT], const int *ready, int lane, float *__restrict__ W, int *__restrict__ ok)
+{
+    bool expired = false;
+    auto gate = [&](int b) __attribute__((always_inline)) {
+        int polls = 0;
+        while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) <= b) {
+            if (++polls >= FOLLOW_SPIN_LIMIT) {
+                expired = true;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(4);                      // the factorisation reads LDS on its critical path: poll seldom
+        }
+    };
+    float xn[NBMAX], tt[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 q[3][4], qc[4];
+    float colsum_L = 0.0f, colsum_W = 0.0f;
+    float *out = W + (lane >> 4) * 256 + (lane & 3) * 64 + ((lane >> 2) & 3);
+    auto rows_of_L = [&](int i) __attribute__((always_inline)) {
+        if (STEPS.b[i] >= 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&T[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
+        }
+    };
+    auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(q[i % 3][j][kk], xn[4 * STEPS.k[i] + kk], acc[j]);
+    };
+    // the block's corner of L_jj and the lane's own column of it (for ||L_jj||_1), once the block is final
+    auto corner_of_L = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            qc[j] = *(const f32x4 *)&T[4 * b + j][4 * b];
+            const float mine = T[4 * b + j][lane];
+            colsum_L += 4 * b + j >= lane ? __builtin_fabsf(mine) : 0.0f;
+        }
+    };
+    gate(0);
+    rows_of_L(0);
+    rows_of_L(1);
+    corner_of_L(0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) tt[j] = j == lane ? 1.0f : 0.0f;
+    int i = 0;
+    unrolled<NBLK>([&](auto index) __attribute__((always_inline)) {
+        constexpr int b = decltype(index)::value;
+        if (b > 0) {
+            gate(b);
+            corner_of_L(b);
+        }
+#pragma unroll
+        for (int s2 = early_of(b); s2 < b; ++s2) {
+            rows_of_L(i + 2);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) quarter(tt, i, kk);
+            ++i;
+        }
+        if (b + 1 < NBLK) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) tn[j] = 4 * (b + 1) + j == lane ? 1.0f : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int r = 4 * b + j;
+            const bool paired = b + 1 < NBLK && j < early_of(b + 1);
+            if (paired) rows_of_L(i + 2);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < j; ++e) tt[j] = __builtin_fmaf(qc[j][e], xn[4 * b + e], tt[j]);
+            Division dv;
+            dv.phase0(tt[j], qc[j][j]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) quarter(tn, i, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            dv.phase1();
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) quarter(tn, i, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            dv.phase2();
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) quarter(tn, i, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            const float y = dv.phase3();
+            xn[r] = -y;
+            asm("" : "+v"(xn[r]));
+            out[(r >> 4) * 1024 + (r & 15) * 4] = y;
+            colsum_W += __builtin_fabsf(y);
+            __builtin_amdgcn_sched_barrier(0);
+            if (paired) {
+                quarter(tn, i, 3);
+                ++i;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tt[j] = tn[j];
+    });
+    const float a = wave_max64(colsum_L), c = wave_max64(colsum_W);
+    // (a NaN anywhere would be dropped by the maxima: every lane checks its own sums)
+    const bool fine = colsum_L == colsum_L && colsum_W == colsum_W && a * c <= W_NORM_LIMIT && !expired;
+    const bool all_fine = __builtin_amdgcn_ballot_w64(!fine) == 0;
+    if (lane == 0) *ok = all_fine ? 1 : 0;
+}
+
 // The factorisation proper of a diagonal tile whose S (with everything left of it taken out) is in T: the column
 // recurrence by the first wave, then L, and Lh in both triangles, written out by all.  See diag_tile.
-__device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r)
+// ready: a counter in LDS, zero on entry (with a barrier since); W, ok: where the tile's inverse and its verdict go, or
+// nullptr (then, and for tiles of fewer than 64 columns, none is computed).
+__device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r, int *ready,
+                                          float *W, int *ok)
 {
     const bool live = r < cols;
     bool mirrored = false;
@@ -349,6 +543,14 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
 #pragma unroll
             for (int j = 0; j < 4; ++j) done[j] = x[4 * b + j];
             *(f32x4 *)&T[r][4 * b] = done;
+            // block b is final in LDS.  Every lane stores the same number (a store under a lane condition would cut the
+            // chains into basic blocks), and without a release fence, which would wait for the operands requested ahead
+            // as well: a wave's LDS operations are performed in the order it issues them, so whoever sees the counter
+            // sees the block; the empty asm keeps the compiler from moving the store up.
+            if (W) {
+                asm volatile("" ::: "memory");
+                __hip_atomic_store(ready, b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
             if (b + 1 < NBLK) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) ql[j] = *(const f32x4 *)&T[4 * (b + 1) + j][4 * b];
@@ -364,6 +566,8 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
 #pragma unroll
         for (int c = 0; c < NBMAX - 1; ++c)
             if (c < r) T[c][r] = x[c];
+        } else if (r < 128 && W) {
+            inverse_follow64(T, ready, r - 64, W, ok);
         }
         mirrored = true;
         __syncthreads();
@@ -397,24 +601,26 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
 // move and update the tile.  T (first 64 KB of LDS: a read reaches its word with the 16-bit offset field from one
 // base register; further up every read needs an address register of its own) and Bs are the workgroup's LDS.
 __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], const float *Sm, float *L, uint16_t *Lh, int64_t n,
-                                          int64_t j0, int cols, int64_t k0, int r)
+                                          int64_t j0, int cols, int64_t k0, int r, int *ready, float *W, int *ok)
 {
+    if (r == 0) *ready = 0;               // (a barrier follows below, before anyone looks at it)
     TileProduct product;
     if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     if (k0 < j0) product.apply(T, Bs, r);
     else __syncthreads();
-    diag_rest(T, L, Lh, n, j0, cols, r);
+    diag_rest(T, L, Lh, n, j0, cols, r, ready, W, ok);
 }
 
 __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
-                                                       int64_t k0)
+                                                       int64_t k0, float *W, int *ok)
 {
     __shared__ __attribute__((aligned(16))) struct {
         float T[NBMAX][LDT];          // S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
+        int ready;                    // blocks of four columns finished, for the wave that follows with the inverse
     } lds;
-    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x);
+    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, &lds.ready, W, ok);
 }
 
 // L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane of the first wave; the
@@ -425,8 +631,13 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 // update over the group's earlier panels before its own recurrence starts; the three waves that would idle during
 // the recurrence multiply them out (wave 1 rows 0 .. 31 of the tile, waves 2 and 3 sixteen rows each).  Then the k
 // range of this panel is added, straight from the solved rows in LDS, and the tile is factored.
+// Win, okin: the inverse of L_jj and its verdict (see inverse_follow64), or nullptr.  When the verdict is good the
+// workgroup of the first 64 rows, the one the next diagonal tile waits for, forms its rows as the product S W^T on the
+// matrix cores in fp32 instead of running the recurrence; all other workgroups, which nothing waits for, keep the
+// recurrence.  Wout, okout: where the inverse of the next diagonal tile and its verdict go when that tile rides along.
 __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
-                                                        int64_t k0, const float *next_Sm)
+                                                        int64_t k0, const float *next_Sm, const float *__restrict__ Win,
+                                                        const int *__restrict__ okin, float *Wout, int *okout)
 {
     // one block, D and X first (see diag_tile)
     __shared__ __attribute__((aligned(16))) struct {
@@ -434,21 +645,39 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
         int landed;                   // waves whose copies for the next diagonal tile have arrived
+        int ready;                    // blocks of four columns of the next diagonal tile finished (see diag_rest)
     } lds;
     auto &D = lds.D;
     auto &X = lds.X;
     auto &Bs = lds.Bs;
     const int tid = threadIdx.x, lane = tid & 63;
-    if (tid == 0) lds.landed = 0;
+    if (tid == 0) lds.landed = lds.ready = 0;
     const bool solver = tid < 64;                         // the wave that runs the recurrence
+    // The rows of this workgroup through the inverse of L_jj?  W and its verdict are requested here with everything
+    // else the kernel needs from memory; the verdict is looked at only where the rows are formed, so that nothing
+    // waits for it on its own.
+    const bool may_invert = blockIdx.x == 0 && cols == NBMAX && Win != nullptr;        // uniform over the workgroup
+    int verdict = 0;
+    f32x4 winv[10];                                       // this lane's 40 values of W: pieces (cb, q), q <= cb
+    if (may_invert) {
+        verdict = *okin;
+        int p = 0;
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int q4 = 0; q4 <= cb; ++q4) winv[p++] = *(const f32x4 *)(Win + (cb * 4 + q4) * 256 + lane * 4);
+    }
     const int64_t j1 = j0 + cols, row = j1 + (int64_t)blockIdx.x * 64 + lane;
     const bool live = solver && row < n;
     const int64_t first = j1 + (int64_t)blockIdx.x * 64;
     const int nrows = (int)(n - first < 64 ? n - first : 64);
     TileProduct product;
     if (k0 < j0) product.request(Bs, Lh, n, first, nrows, k0, j0, j0, tid);
-    load_tile(D, L + j0 * n + j0, n, cols, cols, tid);
-    load_tile(X, Sm + first * n + j0, n, nrows, cols, tid);
+    TileLoad of_D, of_X;
+    of_D.request(L + j0 * n + j0, n, cols, cols, tid);
+    of_X.request(Sm + first * n + j0, n, nrows, cols, tid);
+    of_D.place(D, L + j0 * n + j0, n, cols, cols, tid);
+    of_X.place(X, Sm + first * n + j0, n, nrows, cols, tid);
     if (k0 < j0) product.apply(X, Bs, tid);
     else __syncthreads();
     // ---- the next diagonal tile, first part: requests (Bs is free again)
@@ -511,8 +740,30 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
     bool mirrored = false;
+    const bool by_inverse = may_invert && __builtin_amdgcn_readfirstlane(verdict) != 0;
     if (cols == NBMAX) {
-        if (solver) {
+        if (by_inverse) {
+            // X <- S W^T: wave w takes the rows 16w .. 16w+15 and all 64 columns.  A operand lane l: row 16w + l%16 of
+            // S, k = 4 ks + l/16; B operand: W[16 cb + l%16][4 ks + l/16], zero for ks >= 4 (cb + 1); accumulator
+            // register r of lane l: row 16w + 4 (l/16) + r, column 16 cb + l%16.  Each wave reads only its own rows
+            // of X before it overwrites them.
+            float sa[16];
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks) sa[ks] = X[16 * w + lq][4 * ks + g];
+            f32x4 xo[4];
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) xo[cb] = (f32x4){0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks)
+#pragma unroll
+                for (int cb = ks / 4; cb < 4; ++cb)
+                    xo[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(sa[ks], winv[cb * (cb + 1) / 2 + ks / 4][ks % 4], xo[cb], 0, 0, 0);
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) X[16 * w + 4 * g + r][16 * cb + lq] = xo[cb][r];
+        }
+        if (solver && !by_inverse) {
         // The lane's row of S and of L in registers (constant indices after unrolling); the steps of StepList, the
         // rows of L_jj for a step requested from LDS two steps before it runs, since a lone wave has nobody else to
         // hide the LDS latency behind.
@@ -596,8 +847,9 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
 #pragma unroll
             for (int c = 0; c < NBMAX; ++c) m[c * n] = round_bf16(x[c]);
         }
-        } else if (fused && nks_e > 0) {
-            // ---- the next diagonal tile, second part, by the three waves beside the recurrence: when the copies of all
+        } else if (!solver && fused && nks_e > 0) {
+            // ---- the next diagonal tile, second part, by the three waves beside the recurrence (after their share
+            // of the product when the rows came through the inverse): when the copies of all
             // three have arrived (a counter in LDS), the early k-steps.  The wait is bounded; should it ever run out,
             // the product is made of NaNs, so that the tile comes out as NaN rather than as plausible wrong numbers.
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -612,12 +864,25 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     k_step(ks, a2);
                 }
         }
-        mirrored = true;
+        mirrored = !by_inverse;                            // (the recurrence writes the mirror image from its registers)
     } else if (solver) {
         for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
     __syncthreads();
     const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, tid);
+    if (by_inverse && nrows == 64 && n % 8 == 0 && (uintptr_t)Lh % 16 == 0) {
+        // the mirror image of the rows from LDS, by all four waves: thread (column c, quarter) gathers 16 rows of its
+        // column (the rows of X are LDT floats apart, 16 of them on distinct banks) and stores them as 32 bytes
+        const int c = tid >> 2, r0 = 16 * (tid & 3);
+        uint32_t packed[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            packed[i] = (uint32_t)round_bf16(X[r0 + 2 * i][c]) | ((uint32_t)round_bf16(X[r0 + 2 * i + 1][c]) << 16);
+        uint4 *dst = (uint4 *)(Lh + (j0 + c) * n + first + r0);
+        dst[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+        dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
+        mirrored = true;
+    }
     if (live && !(stored && mirrored))
         for (int c = 0; c < cols; ++c) {
             const float v = X[lane][c];
@@ -669,18 +934,29 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
             }
         __syncthreads();
-        diag_rest(D, L, Lh, n, j1, NBMAX, tid);
+        diag_rest(D, L, Lh, n, j1, NBMAX, tid, &lds.ready, Wout, okout);
     }
 }
 
 }  // namespace
 
-hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t nb, hipStream_t s)
+int64_t chol_workspace_bytes(int64_t n, int64_t nb)
+{
+    // one inverse and one verdict per full diagonal tile of 64 (see inverse_follow64)
+    return nb == NBMAX && n >= 2 * NBMAX ? (n / NBMAX) * (int64_t)(W_FLOATS * sizeof(float) + sizeof(int)) : 0;
+}
+
+hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t nb, void *workspace, hipStream_t s)
 {
     const float *A = (const float *)A_;
     float *L = (float *)L_;
     uint16_t *Lh = (uint16_t *)Lh_;
     if (nb < 1 || nb > NBMAX || n < 1 || n > (1 << 22)) return hipErrorInvalidValue;
+    // the inverses of the full diagonal tiles and their verdicts, tile after tile (nullptr: none are computed)
+    float *Wall = chol_workspace_bytes(n, nb) > 0 ? (float *)workspace : nullptr;
+    int *okall = Wall ? (int *)(Wall + (n / NBMAX) * W_FLOATS) : nullptr;
+    auto W_of = [&](int64_t j, int c) { return Wall && c == NBMAX ? Wall + j / NBMAX * W_FLOATS : (float *)nullptr; };
+    auto ok_of = [&](int64_t j, int c) { return Wall && c == NBMAX ? okall + j / NBMAX : (int *)nullptr; };
     // One product per panel would have only nb columns and all earlier tiles as its k range: a few workgroups
     // walking a long k loop.  So the panels are taken in groups of GROUP: at the first panel of a group one product
     // covers the columns of the whole group against all tiles left of the group; the later panels of the group
@@ -761,7 +1037,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             }
         }
         if (!diag_done) {
-            hipError_t e = launch_kernel(chol_diag_kernel, dim3(1), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0);
+            hipError_t e = launch_kernel(chol_diag_kernel, dim3(1), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0, W_of(j0, cols), ok_of(j0, cols));
             if (e != hipSuccess) return fail(e);
         }
         diag_done = false;
@@ -772,7 +1048,8 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
                               n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)L % 16 == 0 &&
                               j1 - g0 <= KMAX;
             hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
-                               fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr);
+                               fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
+                               (const int *)ok_of(j0, cols), fuse ? W_of(j1, NBMAX) : (float *)nullptr, fuse ? ok_of(j1, NBMAX) : (int *)nullptr);
             if (e != hipSuccess) return fail(e);
             diag_done = fuse;
         }

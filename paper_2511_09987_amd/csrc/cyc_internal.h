@@ -87,7 +87,9 @@ int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, void *workspace,
                        hipStream_t s);
 // tiled Cholesky factorisation A = L L^T in tiles of nb (see cyc_chol.hip); arguments validated by the caller
-hipError_t launch_chol(const void *A, void *L, void *Lh, int64_t n, int64_t nb, hipStream_t s);
+// workspace: chol_workspace_bytes() bytes of device memory (inverses of the diagonal tiles), or nullptr: no inverses
+int64_t chol_workspace_bytes(int64_t n, int64_t nb);
+hipError_t launch_chol(const void *A, void *L, void *Lh, int64_t n, int64_t nb, void *workspace, hipStream_t s);
 // FlashAttention-2 tile recurrence (see cyc_attn.hip); requires supports_attention(N, M, d)
 bool supports_attention(int64_t N, int64_t M, int64_t d);
 hipError_t launch_attention(const void *Q, const void *K, const void *V, void *O, int64_t batch, int64_t N, int64_t M,

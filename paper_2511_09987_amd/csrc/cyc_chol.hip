@@ -171,18 +171,18 @@ struct TileLoad {
 // The reverse for a full-width tile held in LDS: rows 0..nrows-1 to the fp32 matrix L and, rounded, to the bfloat16
 // matrix Lh (both with row stride ld), 16 bytes per thread and store.  False when shape or alignment do not allow it.
 // LOWER: the tile is a diagonal tile; L gets zeros above the diagonal (Lh gets what the tile holds there).
-template <bool LOWER>
+template <bool LOWER, int NTH = NT>
 __device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, uint16_t *Lh, int64_t ld, int nrows, int cols,
                                            int tid)
 {
     if (cols != NBMAX || ld % 8 != 0 || ((uintptr_t)L & 15) != 0 || ((uintptr_t)Lh & 15) != 0) return false;
     // all LDS reads first, without conditions (rows past nrows hold copies of the last one), then the stores: a read
     // inside the row condition would be waited for on the spot, once per row group
-    constexpr int PL = NBMAX * 16 / NT, PH = NBMAX * 8 / NT;
+    constexpr int PL = NBMAX * 16 / NTH, PH = NBMAX * 8 / NTH;      // tid counts the NTH threads that take part
     f32x4 v[PL];
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
-        const int r = NT / 16 * i + (tid >> 4);
+        const int r = NTH / 16 * i + (tid >> 4);
         v[i] = *(const f32x4 *)&src[r][4 * (tid & 15)];
         if (LOWER) {
 #pragma unroll
@@ -193,7 +193,7 @@ __device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, ui
     u32x4 h[PH];
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
-        const int r = NT / 8 * i + (tid >> 3);
+        const int r = NTH / 8 * i + (tid >> 3);
         const f32x4 a = *(const f32x4 *)&src[r][8 * (tid & 7)], b = *(const f32x4 *)&src[r][8 * (tid & 7) + 4];
         h[i][0] = round_bf16(a[0]) | ((unsigned)round_bf16(a[1]) << 16);
         h[i][1] = round_bf16(a[2]) | ((unsigned)round_bf16(a[3]) << 16);
@@ -202,15 +202,32 @@ __device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, ui
     }
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
-        const int r = NT / 16 * i + (tid >> 4);
+        const int r = NTH / 16 * i + (tid >> 4);
         if (r < nrows) *(f32x4 *)(L + (int64_t)r * ld + 4 * (tid & 15)) = v[i];
     }
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
-        const int r = NT / 8 * i + (tid >> 3);
+        const int r = NTH / 8 * i + (tid >> 3);
         if (r < nrows) *(u32x4 *)(Lh + (int64_t)r * ld + 8 * (tid & 7)) = h[i];
     }
     return true;
+}
+
+// The mirror image of 64 finished rows (a tile in LDS) into the upper triangle of Lh, by NTH threads: thread (column c,
+// part) gathers 64 * 4 / NTH rows of its column (the rows of the tile are LDT floats apart: 16 of them lie on distinct
+// banks) and stores them as 16-byte pieces.  dst: entry (column 0, row 0); requires 16-byte aligned rows of Lh.
+template <int NTH>
+__device__ __forceinline__ void store_mirror(const float (*src)[LDT], uint16_t *dst, int64_t ld, int tid)
+{
+    constexpr int PARTS = NTH / 64, ROWS = 64 / PARTS;
+    const int c = tid / PARTS, r0 = ROWS * (tid % PARTS);
+    uint32_t packed[ROWS / 2];
+#pragma unroll
+    for (int i = 0; i < ROWS / 2; ++i)
+        packed[i] = (uint32_t)round_bf16(src[r0 + 2 * i][c]) | ((uint32_t)round_bf16(src[r0 + 2 * i + 1][c]) << 16);
+    uint4 *out = (uint4 *)(dst + (int64_t)c * ld + r0);
+#pragma unroll
+    for (int i = 0; i < ROWS / 8; ++i) out[i] = make_uint4(packed[4 * i], packed[4 * i + 1], packed[4 * i + 2], packed[4 * i + 3]);
 }
 
 // L[r][c] = 0 for c > r
@@ -262,7 +279,8 @@ struct TileProduct {
         const int r = 16 * w + lq;
         const uint16_t *rowp = Lh + (row0 + (r < nrows ? r : nrows - 1)) * n + k0 + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) a[ks] = *(const i32x4 *)(rowp + 32 * (ks < nks ? ks : nks - 1));   // (a short range re-reads its last step)
+        for (int ks = 0; ks < NKS; ++ks)
+            if (ks < nks) a[ks] = *(const i32x4 *)(rowp + 32 * ks);        // uniform; a load of 16 rows is 64 line requests: none to spare
     }
 
     // S -= product; call with the tile S in place in LDS and no barrier needed before: waits for the copies itself
@@ -358,8 +376,20 @@ __device__ __forceinline__ float wave_max64(float v)
 
 // The follower: one wave, lane = column of W.  T holds S above the factorisation's progress and L below it; *ready
 // counts the blocks of four columns the factorisation has finished.  Writes W and the verdict.
-__device__ __forceinline__ void inverse_follow64(const float (*T)[LDT], const int *ready, int lane, float *__restrict__ W, int *__restrict__ ok)
+// Not inlined, and its LDS operands passed as addresses: inside diag_rest it raised that kernel's register count from 228
+// to 369 and put the factorisation's own values into accumulation registers, 3k cycles on the path per tile.
+__device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, uint32_t ready_in_lds, int lane, float *__restrict__ W,
+                                                           int *__restrict__ ok)
 {
+    CYC_LDS const float *const Tflat = (CYC_LDS const float *)(uintptr_t)T_in_lds;
+    CYC_LDS int *const ready = (CYC_LDS int *)(uintptr_t)ready_in_lds;
+    // T[r][c], r and c constants after unrolling: one base register and the offset field
+    struct Tile {
+        CYC_LDS const float *base;
+        __device__ __forceinline__ CYC_LDS const float *operator[](int r) const { return base + r * LDT; }
+    };
+    const Tile T{Tflat};
+
     bool expired = false;
     auto gate = [&](int b) __attribute__((always_inline)) {
         int polls = 0;
@@ -378,7 +408,7 @@ __device__ __forceinline__ void inverse_follow64(const float (*T)[LDT], const in
     auto rows_of_L = [&](int i) __attribute__((always_inline)) {
         if (STEPS.b[i] >= 0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&T[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
+            for (int j = 0; j < 4; ++j) q[i % 3][j] = *(CYC_LDS const f32x4 *)&T[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
         }
     };
     auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {
@@ -389,7 +419,7 @@ __device__ __forceinline__ void inverse_follow64(const float (*T)[LDT], const in
     auto corner_of_L = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            qc[j] = *(const f32x4 *)&T[4 * b + j][4 * b];
+            qc[j] = *(CYC_LDS const f32x4 *)&T[4 * b + j][4 * b];
             const float mine = T[4 * b + j][lane];
             colsum_L += 4 * b + j >= lane ? __builtin_fabsf(mine) : 0.0f;
         }
@@ -465,8 +495,11 @@ __device__ __forceinline__ void inverse_follow64(const float (*T)[LDT], const in
 // recurrence by the first wave, then L, and Lh in both triangles, written out by all.  See diag_tile.
 // ready: a counter in LDS, zero on entry (with a barrier since); W, ok: where the tile's inverse and its verdict go, or
 // nullptr (then, and for tiles of fewer than 64 columns, none is computed).
+// beside(t): called in the full-tile case by the threads 128 .. 255 (t = 0 .. 127), which otherwise only wait, while
+// the tile is being factored.
+template <class Beside>
 __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r, int *ready,
-                                          float *W, int *ok)
+                                          float *W, int *ok, Beside beside)
 {
     const bool live = r < cols;
     bool mirrored = false;
@@ -547,10 +580,9 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
             // chains into basic blocks), and without a release fence, which would wait for the operands requested ahead
             // as well: a wave's LDS operations are performed in the order it issues them, so whoever sees the counter
             // sees the block; the empty asm keeps the compiler from moving the store up.
-            if (W) {
-                asm volatile("" ::: "memory");
-                __hip_atomic_store(ready, b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            }
+            // (Stored whether or not anyone follows: a condition here would cut the chains into basic blocks as well.)
+            asm volatile("" ::: "memory");
+            __hip_atomic_store(ready, b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             if (b + 1 < NBLK) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) ql[j] = *(const f32x4 *)&T[4 * (b + 1) + j][4 * b];
@@ -566,8 +598,10 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
 #pragma unroll
         for (int c = 0; c < NBMAX - 1; ++c)
             if (c < r) T[c][r] = x[c];
-        } else if (r < 128 && W) {
-            inverse_follow64(T, ready, r - 64, W, ok);
+        } else if (r >= 128) {
+            beside(r - 128);
+        } else if (W) {
+            inverse_follow64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS int *)ready, r - 64, W, ok);
         }
         mirrored = true;
         __syncthreads();
@@ -609,7 +643,7 @@ __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], c
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     if (k0 < j0) product.apply(T, Bs, r);
     else __syncthreads();
-    diag_rest(T, L, Lh, n, j0, cols, r, ready, W, ok);
+    diag_rest(T, L, Lh, n, j0, cols, r, ready, W, ok, [](int) {});
 }
 
 __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
@@ -644,14 +678,15 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
         float D[NBMAX][LDT];          // L_jj
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
-        int landed;                   // waves whose copies for the next diagonal tile have arrived
+        uint16_t Bs2[KMAX][64];       // streamed operand of the next diagonal tile's update
         int ready;                    // blocks of four columns of the next diagonal tile finished (see diag_rest)
     } lds;
     auto &D = lds.D;
     auto &X = lds.X;
     auto &Bs = lds.Bs;
+    auto &Bs2 = lds.Bs2;
     const int tid = threadIdx.x, lane = tid & 63;
-    if (tid == 0) lds.landed = lds.ready = 0;
+    if (tid == 0) lds.ready = 0;
     const bool solver = tid < 64;                         // the wave that runs the recurrence
     // The rows of this workgroup through the inverse of L_jj?  W and its verdict are requested here with everything
     // else the kernel needs from memory; the verdict is looked at only where the rows are formed, so that nothing
@@ -671,6 +706,49 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     const bool live = solver && row < n;
     const int64_t first = j1 + (int64_t)blockIdx.x * 64;
     const int nrows = (int)(n - first < 64 ? n - first : 64);
+    // ---- the next diagonal tile, first part: its S and the operands of the part of its update that does not involve
+    // this panel are requested with everything else (their own LDS buffer, Bs2, so that they need not wait for Bs)
+    const bool fused = next_Sm != nullptr && blockIdx.x == 0;          // uniform over the workgroup
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4;
+    const int nks_e = fused ? (int)(j0 - k0) / 32 : 0;                 // k-steps of that tile's update that do not involve this panel
+    constexpr int NKS = KMAX / 32;
+    f32x4 sv[4], accn[2][4];                                           // its S (this thread's pieces); its update: [slot][column tile]
+    i32x4 an[2][NKS];                                                  // stationary operand of the update's early k-steps
+    // The four 16-row strips of that update: slot si of this wave holds strip(si), or nothing (-1).  Beside the recurrence
+    // the three other waves share them (wave 1 takes two).  When the rows may come through the inverse the first wave
+    // is free as a rule and every wave takes one strip; should the verdict then be bad after all, the first wave takes
+    // its strip after its recurrence.
+    auto strip = [&](int si) __attribute__((always_inline)) {
+        return may_invert ? (si == 0 ? w : -1) : (w == 1 ? si : (si == 0 && w >= 2 ? w : -1));
+    };
+    // rows `first_row` .. +count-1 of the streamed operand Lh[., j1 : j1+64] into Bs2 from row `to` on, 8 rows per copy,
+    // the copies dealt out to `waves` waves of which this is number `me`
+    auto copy_rows = [&](int64_t first_row, int to, int count, int me, int waves) __attribute__((always_inline)) {
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs2[0][0];
+        const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
+        for (int k = 8 * me; k < count; k += 8 * waves) {
+            const char *base = (const char *)(Lh + (first_row + k) * n + j1);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds_base + (to + k) * 128), "v"(voff), "s"(base)
+                         : "memory", "m0");
+        }
+    };
+    if (fused) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sv[i] = *(const f32x4 *)(next_Sm + (j1 + 16 * i + (tid >> 4)) * n + j1 + 4 * (tid & 15));
+        if (nks_e > 0) {
+            copy_rows(k0, 0, 32 * nks_e, w, NT / 64);
+#pragma unroll
+            for (int si = 0; si < 2; ++si)
+                if (strip(si) >= 0) {
+                    const uint16_t *rowp = Lh + (j1 + 16 * strip(si) + lq) * n + k0 + 8 * g;
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks)
+                        if (ks < nks_e) an[si][ks] = *(const i32x4 *)(rowp + 32 * ks);
+                }
+        }
+    }
     TileProduct product;
     if (k0 < j0) product.request(Bs, Lh, n, first, nrows, k0, j0, j0, tid);
     TileLoad of_D, of_X;
@@ -678,21 +756,15 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     of_X.request(Sm + first * n + j0, n, nrows, cols, tid);
     of_D.place(D, L + j0 * n + j0, n, cols, cols, tid);
     of_X.place(X, Sm + first * n + j0, n, nrows, cols, tid);
+    // (nks_e > 0 implies k0 < j0: apply waits for every copy of this wave, Bs2's included, before its barrier)
     if (k0 < j0) product.apply(X, Bs, tid);
     else __syncthreads();
-    // ---- the next diagonal tile, first part: requests (Bs is free again)
-    const bool fused = next_Sm != nullptr && blockIdx.x == 0;          // uniform over the workgroup
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4;
-    const int nks_e = fused ? (int)(j0 - k0) / 32 : 0;                 // k-steps of that tile's update that do not involve this panel
-    constexpr int NKS = KMAX / 32;
-    f32x4 sv[4], accn[2][4];                                           // its S (this thread's pieces); its update: [strip][column tile]
-    i32x4 an[2][NKS];                                                  // stationary operand of the update's early k-steps
-    auto strip = [&](int si) __attribute__((always_inline)) { return w == 1 ? si : (si == 0 && w >= 2 ? w : -1); };   // 16-row strips of a wave
-    auto k_step = [&](int ks, const i32x4(&a2)[2]) __attribute__((always_inline)) {        // one MFMA k-step of 32, Bs rows 32 ks ..
+    const bool by_inverse = may_invert && __builtin_amdgcn_readfirstlane(verdict) != 0;
+    auto k_step = [&](int ks, const i32x4(&a2)[2]) __attribute__((always_inline)) {        // one MFMA k-step of 32, Bs2 rows 32 ks ..
         i32x4 b[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+            CYC_LDS char *p = (CYC_LDS char *)&Bs2[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
             const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
             const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
             b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
@@ -705,42 +777,13 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a2[si]), __builtin_bit_cast(bf16x8, b[j]), accn[si][j], 0, 0, 0);
             }
     };
-    // rows `first_row` .. +count-1 of the streamed operand Lh[., j1 : j1+64] into Bs from row `to` on, 8 rows per copy,
-    // the copies dealt out to `waves` waves of which this is number `me`
-    auto copy_rows = [&](int64_t first_row, int to, int count, int me, int waves) __attribute__((always_inline)) {
-        const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs[0][0];
-        const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
-        for (int k = 8 * me; k < count; k += 8 * waves) {
-            const char *base = (const char *)(Lh + (first_row + k) * n + j1);
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(lds_base + (to + k) * 128), "v"(voff), "s"(base)
-                         : "memory", "m0");
-        }
-    };
 #pragma unroll
     for (int si = 0; si < 2; ++si)
 #pragma unroll
         for (int j = 0; j < 4; ++j) accn[si][j] = (f32x4){0, 0, 0, 0};
-    if (fused) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sv[i] = *(const f32x4 *)(next_Sm + (j1 + 16 * i + (tid >> 4)) * n + j1 + 4 * (tid & 15));
-        if (w >= 1 && nks_e > 0) {
-            copy_rows(k0, 0, 32 * nks_e, w - 1, 3);
-#pragma unroll
-            for (int si = 0; si < 2; ++si)
-                if (strip(si) >= 0) {
-                    const uint16_t *rowp = Lh + (j1 + 16 * strip(si) + lq) * n + k0 + 8 * g;
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks)
-                        if (ks < nks_e) an[si][ks] = *(const i32x4 *)(rowp + 32 * ks);
-                }
-        }
-    }
     // (lanes past the last row run along on the repeated last row: they take part in the barrier and in the tile
     // store below, and write nothing of their own)
     bool mirrored = false;
-    const bool by_inverse = may_invert && __builtin_amdgcn_readfirstlane(verdict) != 0;
     if (cols == NBMAX) {
         if (by_inverse) {
             // X <- S W^T: wave w takes the rows 16w .. 16w+15 and all 64 columns.  A operand lane l: row 16w + l%16 of
@@ -847,20 +890,16 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
 #pragma unroll
             for (int c = 0; c < NBMAX; ++c) m[c * n] = round_bf16(x[c]);
         }
-        } else if (!solver && fused && nks_e > 0) {
-            // ---- the next diagonal tile, second part, by the three waves beside the recurrence (after their share
-            // of the product when the rows came through the inverse): when the copies of all
-            // three have arrived (a counter in LDS), the early k-steps.  The wait is bounded; should it ever run out,
-            // the product is made of NaNs, so that the tile comes out as NaN rather than as plausible wrong numbers.
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (lane == 0) __hip_atomic_fetch_add(&lds.landed, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-            int polls = 0;
-            while (__hip_atomic_load(&lds.landed, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < 3 && ++polls < (1 << 20)) {}
-            const int poison = polls >= (1 << 20) ? 0x7fc07fc0 : 0;      // two bfloat16 NaNs; OR-ed into every operand word
+        }
+        if (fused && nks_e > 0 && (!solver || may_invert)) {
+            // ---- the next diagonal tile, second part: the k-steps over the group's earlier panels, by the three waves
+            // beside the recurrence, or by all four after their share of the product when the rows came through the
+            // inverse.  (Their operands have arrived: requested first thing and waited for before the barrier that
+            // precedes the update of this workgroup's own tile.)
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks)
                 if (ks < nks_e) {
-                    const i32x4 a2[2] = {an[0][ks] | poison, an[1][ks] | poison};
+                    const i32x4 a2[2] = {an[0][ks], an[1][ks]};
                     k_step(ks, a2);
                 }
         }
@@ -869,21 +908,16 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
         for (int c = 0; c < cols; ++c) X[lane][c] = chain(X[lane][c], X[lane], D[c], c) / D[c][c];
     }
     __syncthreads();
-    const bool stored = store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, tid);
-    if (by_inverse && nrows == 64 && n % 8 == 0 && (uintptr_t)Lh % 16 == 0) {
-        // the mirror image of the rows from LDS, by all four waves: thread (column c, quarter) gathers 16 rows of its
-        // column (the rows of X are LDT floats apart, 16 of them on distinct banks) and stores them as 32 bytes
-        const int c = tid >> 2, r0 = 16 * (tid & 3);
-        uint32_t packed[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            packed[i] = (uint32_t)round_bf16(X[r0 + 2 * i][c]) | ((uint32_t)round_bf16(X[r0 + 2 * i + 1][c]) << 16);
-        uint4 *dst = (uint4 *)(Lh + (j0 + c) * n + first + r0);
-        dst[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
-        dst[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
+    // In the workgroup that goes on to the next diagonal tile two waves have nothing to do while that tile is factored:
+    // they write this workgroup's rows out then (diag_rest below), off the path.  (There the tile is full and every
+    // pointer aligned: the host fuses under those conditions only.)
+    const bool deferred = fused && cols == NBMAX;
+    const bool stored = deferred || store_tile<false>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, tid);
+    if (!deferred && by_inverse && nrows == 64 && n % 8 == 0 && (uintptr_t)Lh % 16 == 0) {
+        store_mirror<NT>(X, Lh + j0 * n + first, n, tid);
         mirrored = true;
     }
-    if (live && !(stored && mirrored))
+    if (!deferred && live && !(stored && mirrored))
         for (int c = 0; c < cols; ++c) {
             const float v = X[lane][c];
             const uint16_t h = round_bf16(v);
@@ -934,7 +968,11 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
             }
         __syncthreads();
-        diag_rest(D, L, Lh, n, j1, NBMAX, tid, &lds.ready, Wout, okout);
+        diag_rest(D, L, Lh, n, j1, NBMAX, tid, &lds.ready, Wout, okout, [&](int t) __attribute__((always_inline)) {
+            // this workgroup's own rows, deferred above
+            store_tile<false, 128>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
+            if (by_inverse) store_mirror<128>(X, Lh + j0 * n + first, n, t);
+        });
     }
 }
 

@@ -10,7 +10,7 @@ before the timed region.  Prints ONE JSON line.
 
 NAME is one of the five matmul workloads of the benchmark definition (default c3_bf16_8192, the one
 the metric is quoted on), k1_bf16_tallk (few output blocks, long k: k in space), m1_bf16_narrowm (few
-rows of A over a large B: (j,k) in space), t1_trsm_8192 (tiled triangular solve: 31 launches per
+rows of A over a large B: (j,k) in space), t1_trsm_8192 (tiled triangular solve: 32 launches per
 step), h1_chol_8192 (tiled Cholesky factorisation) or f1_attn_4096 (attention tile recurrence).
 Whatever the headline, the others are measured after it and reported under "workloads"
 (--no-extra: none of them; --matmul-only: only the matmul ones).

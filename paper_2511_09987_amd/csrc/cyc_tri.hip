@@ -674,9 +674,12 @@ constexpr int INV_FLOATS = 64 * 64;        // one inverse in the workspace, in t
 constexpr float INV_NORM_LIMIT = 8.0f;
 
 // One wave per full diagonal tile: lane j solves L_tt y = e_j.  Entry (r, j) of the inverse is stored where the panel
-// kernel's MFMA wants it as its A operand: operand lane (r % 16) + 16 (j % 4) holds it for row block rb = r / 16 and
-// k-step ks = j / 4.  A tile is 16 pieces of 1 KiB, piece 4 rb + ks / 4 holding the four k-steps ks / 4 * 4 .. + 3 of
-// all 64 operand lanes ([lane][ks % 4]), so that a wave fetches a piece with one fully coalesced 16-byte load per lane.
+// kernel's MFMA wants it as its A operand.  Which k a slot of that MFMA stands for is free as long as both operands
+// agree; slot l/16 of k-step ks is k = 16 (ks / 4) + 4 (l / 16) + ks % 4, so that the four rows of R which a k-step
+// reads as the other operand lie four rows apart, on disjoint LDS banks.  Operand lane (r % 16) + 16 (j / 4 % 4) thus
+// holds entry (r, j) for row block rb = r / 16 and k-step ks = 4 (j / 16) + j % 4.  A tile is 16 pieces of 1 KiB, piece
+// 4 rb + ks / 4 holding the four k-steps ks / 4 * 4 .. + 3 of all 64 operand lanes ([lane][ks % 4]), so that a wave
+// fetches a piece with one fully coalesced 16-byte load per lane.
 __global__ __launch_bounds__(64) void tri_inverse_kernel(const uint16_t *__restrict__ L, int64_t n, float *__restrict__ Winv,
                                                          int *__restrict__ ok)
 {
@@ -708,7 +711,7 @@ __global__ __launch_bounds__(64) void tri_inverse_kernel(const uint16_t *__restr
 #pragma unroll
     for (int r = 0; r < NB; ++r) x[r] = r == lane ? 1.0f : 0.0f;
     float colsum_inv = 0.0f;
-    float *out = Winv + (int64_t)blockIdx.x * INV_FLOATS + (lane >> 4) * 256 + (lane & 3) * 64 + ((lane >> 2) & 3);
+    float *out = Winv + (int64_t)blockIdx.x * INV_FLOATS + (lane >> 4) * 256 + ((lane >> 2) & 3) * 64 + (lane & 3);
     solve_tile64<LDD>(
         D, x, xn,
         [&](int r, float y) __attribute__((always_inline)) {
@@ -876,14 +879,14 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
             if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * ch];
         }
     };
-    // X_t = L_tt^-1 R_t for the wave's 16 columns.  A operand lane l: row 16 rb + l%16, k = 4 ks + l/16; B operand:
-    // k = 4 ks + l/16, column l%16; accumulator register r: row 16 rb + 4 (l/16) + r, column l%16.
+    // X_t = L_tt^-1 R_t for the wave's 16 columns.  A operand lane l: row 16 rb + l%16, k = k(ks, l/16) as laid down at
+    // tri_inverse_kernel; B operand: the same k, column l%16; accumulator register r: row 16 rb + 4 (l/16) + r, column l%16.
     // beside(i) is called after the i-th of the 40 MFMAs and pinned there: an MFMA occupies the matrix pipe for 32
     // cycles, and what the wave issues meanwhile (the loads of later tiles) costs the solve nothing.
     auto solve = [&](int t, const f32x4(&iv)[10], float(*Xs)[NB + 4], auto beside) __attribute__((always_inline)) {
         float b[16];
 #pragma unroll
-        for (int ks = 0; ks < 16; ++ks) b[ks] = lds.R[4 * ks + g][16 * w + lq];
+        for (int ks = 0; ks < 16; ++ks) b[ks] = lds.R[16 * (ks >> 2) + 4 * g + (ks & 3)][16 * w + lq];
         f32x4 x[4];
 #pragma unroll
         for (int rb = 0; rb < 4; ++rb) x[rb] = (f32x4){0, 0, 0, 0};

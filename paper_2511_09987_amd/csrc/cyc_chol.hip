@@ -23,6 +23,8 @@
 //   GEMM kernel for so short a k range; the first wave then runs the recurrence.  Within a group, step 2 for panel
 //   j + 1 is done by the first workgroup of step 3 for panel j (the rows that become tile (j+1, j)), in the same
 //   launch: the chain diagonal tile - tile below it - next diagonal tile is what the whole factorisation waits for.
+//   On that chain the TRSM of the tile below a well-conditioned diagonal tile is a product with the diagonal tile's
+//   inverse, which a second wave computes beside the factorisation of the tile (inverse_follow64).
 // Inside a tile column everything is fp32 on unrounded values, in the order of the scalar recurrence:
 // t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
 #include "cyc_internal.h"
@@ -662,9 +664,11 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 // next_Sm != nullptr: the workgroup of the first 64 rows goes on to factor the next diagonal tile, (j1, j1), whose S is
 // read from next_Sm: it produces the only part of that tile's update that is still missing, and a launch of its own
 // for the tile would first wait for memory again.  That workgroup requests the tile's S and the operands of its
-// update over the group's earlier panels before its own recurrence starts; the three waves that would idle during
-// the recurrence multiply them out (wave 1 rows 0 .. 31 of the tile, waves 2 and 3 sixteen rows each).  Then the k
-// range of this panel is added, straight from the solved rows in LDS, and the tile is factored.
+// update over the group's earlier panels with everything else, first thing; the three waves that would idle during
+// the recurrence multiply them out (wave 1 rows 0 .. 31 of the tile, waves 2 and 3 sixteen rows each; one strip of
+// sixteen rows per wave when the rows come through the inverse and the first wave is free).  Then the k range of
+// this panel is added, straight from the solved rows in LDS, and the tile is factored; meanwhile two waves write this
+// workgroup's own rows out.
 // Win, okin: the inverse of L_jj and its verdict (see inverse_follow64), or nullptr.  When the verdict is good the
 // workgroup of the first 64 rows, the one the next diagonal tile waits for, forms its rows as the product S W^T on the
 // matrix cores in fp32 instead of running the recurrence; all other workgroups, which nothing waits for, keep the

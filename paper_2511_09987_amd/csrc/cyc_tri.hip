@@ -7,8 +7,10 @@
 // stationary operand and the solved tile X_J is streamed past it -- the weight-stationary
 // matrix-multiply recurrence of this library, whose MFMA kernels are reused as they are (with
 // A addressed as a window of L and the result subtracted from the running right-hand side).
-// The diagonal space does the small triangular solves, in the kernel below.  The paper's
-// hand-offs between the spaces are memory here: a solved tile is published as X (fp32) and as
+// The diagonal space does the small triangular solves, in the kernels below: by substitution, or,
+// for tiles of 64 rows that are well conditioned, as a product with the tile's inverse on the
+// matrix cores (the inverses of all diagonal tiles are computed ahead, by that substitution).
+// The paper's hand-offs between the spaces are memory here: a solved tile is published as X (fp32) and as
 // Xh, its rounding to bfloat16, which is the form in which it enters later GEMMs.
 //
 // Schedule.  The paper's tile-by-tile order (for I: for J < I) leaves each GEMM with nb rows,

@@ -670,7 +670,7 @@ __device__ __forceinline__ void panel_by_substitution(PanelLds &lds, const uint1
 // (v_mfma_f32_16x16x4_f32: fp32 operands, fp32 sums), which has no chain.  The product is as good as the substitution
 // only for a well-conditioned tile: with kappa = || |L_tt^-1| |L_tt| || its error bound is (kappa^2 + kappa) where the
 // substitution's is kappa.  tri_inverse_kernel therefore leaves a verdict per tile, ||L_tt^-1||_1 ||L_tt||_1 <= 8
-// (an upper bound of kappa that costs a column sum per lane), and a panel whose tiles do not all pass takes the
+// (an upper bound of kappa taken in the 1-norm, which costs a column sum per lane), and a panel whose tiles do not all pass takes the
 // substitution as before.  Both are deterministic; which one runs depends on L alone.
 constexpr int INV_FLOATS = 64 * 64;        // one inverse in the workspace, in the order described at tri_inverse_kernel
 constexpr float INV_NORM_LIMIT = 8.0f;

@@ -62,6 +62,9 @@ def parse():
                          "the time is the chip's power management reacting to the data); never a valid measurement")
     ap.add_argument("--ceiling-all", action="store_true",
                     help="measure the register-only MFMA rate for both instruction shapes and both element types")
+    ap.add_argument("--issue-mix", action="store_true",
+                    help="also measure what a SIMD issues beside its MFMAs (cyc_diag_issue_mix): rounds of 256 matrix-pipe "
+                         "cycles with 0 .. 96 other instructions between the MFMAs, both MFMA shapes, one and two waves per SIMD")
     return ap.parse_args()
 
 
@@ -217,6 +220,35 @@ def mfma_ceiling(lib, torch, dtype_name, shape=16, launches=8, iters=8000):
     rate = ops[0] / (ev_ms * 1e-3) / 1e12
     return {"rate": round(rate, 1), "unit": PEAK[dtype_name][1], "frac_of_peak": round(rate / PEAK[dtype_name][0], 4),
             "clock_ghz": round(clock, 3) if clock else None, "mfma": f"{shape}x{shape}", "ms_per_launch": round(ev_ms, 4)}
+
+
+def issue_mix_table(lib, torch, iters=4000):
+    """Cycles a SIMD needs per round of 256 matrix-pipe cycles when other instructions are issued between the MFMAs
+    (constant operands, nothing but registers and a few LDS words: the issue port is all that is measured)."""
+    sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+    stream = torch.cuda.current_stream()
+    rows = []
+    for shape in (16, 32):
+        for waves in (1, 2):
+            for kind, kname in ((0, "v_fma_f32"), (1, "v_exp_f32"), (2, "ds_read_b128")):
+                for per_round in (0, 16, 32, 48, 64, 96):
+                    if per_round == 0 and kind != 0:
+                        continue
+                    ops = [0.0]
+
+                    def step(i):
+                        st, o = lib.cyc_diag_issue_mix(shape, kind, per_round, waves, iters, sink.data_ptr(), stream.cuda_stream)
+                        if st != 0:
+                            raise RuntimeError(lib.cyc_status_string(st))
+                        ops[0] = o
+
+                    _, ev_ms = time_steps(torch, step, 4, 2)
+                    clock = sustained_clock(lib, torch, step, ev_ms)
+                    rows.append({"mfma": f"{shape}x{shape}", "waves_per_simd": waves, "other": kname if per_round else "-",
+                                 "others_per_round": per_round, "ms_per_launch": round(ev_ms, 4),
+                                 "tflops_in_mfmas": round(ops[0] / (ev_ms * 1e-3) / 1e12, 1), "clock_ghz": round(clock, 3) if clock else None,
+                                 "cycles_per_round": round(ev_ms * 1e-3 * clock * 1e9 / (iters * waves), 1) if clock else None})
+    return rows
 
 
 # ---------------------------------------------------------------------------------------------- rooflines
@@ -411,6 +443,9 @@ def main():
         out["mfma_ceiling"] = {f"{d}_{s}x{s}": mfma_ceiling(lib, torch, d, s) for d in ("bf16", "i8") for s in (16, 32)}
     else:
         out["mfma_ceiling"] = {f"{d}_16x16": mfma_ceiling(lib, torch, d, 16) for d in ("bf16", "i8")}
+
+    if args.issue_mix:
+        out["issue_mix"] = issue_mix_table(lib, torch)
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=DEV).normal_()

@@ -241,6 +241,15 @@ int cyc_force_kernel(const char *name);
  * practice never written.  iters: a multiple of 8, 8 .. 2^24. */
 int cyc_diag_mfma_ceiling(int dtype, int mfma_shape, int64_t iters, void *sink, double *ops, void *stream);
 
+/* Measurement aid: what a SIMD issues beside its MFMAs.  One launch of `iters` (1 .. 2^24) rounds per wave; a round is
+ * the matrix work of 256 pipe cycles (mfma_shape 16: 16 bf16 MFMAs of 16x16x32, 32: 8 of 32x32x16) with
+ * others_per_round (0, 16, 32, 48, 64 or 96) other instructions spread evenly between them (other_kind 0: v_fma_f32,
+ * 1: v_exp_f32, 2: ds_read_b128 of a few LDS words), everything else from registers, on constant operands;
+ * waves_per_simd (1 or 2) waves on every SIMD of every compute unit.  *ops (host, may be NULL) receives the MFMA
+ * operations of one launch; time the launch with events on `stream`.  sink: device, 4 bytes, in practice never written. */
+int cyc_diag_issue_mix(int mfma_shape, int other_kind, int others_per_round, int waves_per_simd, int64_t iters, void *sink,
+                       double *ops, void *stream);
+
 /* Measurement aid: one wave that runs for `microseconds` (1 .. 2000000) and then writes to out (device, two
  * uint64_t, 8-byte aligned) the shader clock cycles and the ticks of the constant 100 MHz counter that went by.
  * Launched on a second stream beside other kernels it gives the engine clock sustained under their load:

@@ -48,6 +48,8 @@ def _load() -> ctypes.CDLL:
     lib.cyc_force_kernel.restype = cint
     lib.cyc_diag_mfma_ceiling.argtypes = [cint, cint, i64, ptr, ctypes.POINTER(ctypes.c_double), ptr]
     lib.cyc_diag_mfma_ceiling.restype = cint
+    lib.cyc_diag_issue_mix.argtypes = [cint, cint, cint, cint, i64, ptr, ctypes.POINTER(ctypes.c_double), ptr]
+    lib.cyc_diag_issue_mix.restype = cint
     lib.cyc_diag_clock.argtypes = [ptr, i64, ptr]
     lib.cyc_diag_clock.restype = cint
     return lib
@@ -119,6 +121,14 @@ def cyc_diag_mfma_ceiling(dtype: int, mfma_shape: int, iters: int, sink: int, st
     """Raw call; returns (cyc_status, operations of the launch)."""
     ops = ctypes.c_double(0.0)
     st = int(_lib().cyc_diag_mfma_ceiling(dtype, mfma_shape, iters, sink, ctypes.byref(ops), stream))
+    return st, ops.value
+
+
+def cyc_diag_issue_mix(mfma_shape: int, other_kind: int, others_per_round: int, waves_per_simd: int, iters: int, sink: int,
+                       stream: int = 0):
+    """Raw call; returns (cyc_status, MFMA operations of the launch)."""
+    ops = ctypes.c_double(0.0)
+    st = int(_lib().cyc_diag_issue_mix(mfma_shape, other_kind, others_per_round, waves_per_simd, iters, sink, ctypes.byref(ops), stream))
     return st, ops.value
 
 

@@ -6,7 +6,7 @@ so that every use comes after that wait, but nothing stops the register allocato
 register between the read and the wait, which would silently copy stale data.  This check walks every kernel of an
 assembly listing in program order, keeps the LDS operations that are still outstanding (they return in order, so a
 wait for n leaves the newest n), and reports every instruction that reads or writes a register an outstanding read
-is going to write.  Branches are followed in layout order only, which is conservative for these kernels: their loops
+is going to write (a later LDS read into the same registers excepted: it simply wins).  Branches are followed in layout order only, which is conservative for these kernels: their loops
 begin with a wait for zero.  The build runs it on the compiler's output and fails on any finding."""
 import re
 
@@ -58,6 +58,10 @@ def violations(asm_text):
                     pending = pending[len(pending) - n:] if n else []
                 continue
             touched = _regs(code)
+            if op.startswith("ds_read") or op.startswith("ds_load"):
+                # another read into the same registers is harmless (LDS reads return in order: the later one wins);
+                # only its address must not come from a register that is still to be delivered
+                touched = _regs(code.split(",", 1)[1]) if "," in code else set()
             for at, dst in pending:
                 if touched & dst:
                     found.append(f"{name}: line {i + 1} '{code}' touches v{sorted(touched & dst)} that the read at "

@@ -7,6 +7,12 @@
 //
 // cyc_diag_clock: one wave that reads the shader clock counter and the constant 100 MHz counter for a given time
 // while other kernels run, which gives the engine clock the chip sustains under that load.
+//
+// cyc_diag_issue_mix: what a SIMD issues beside its MFMAs.  MFMA, vector-ALU and LDS instructions of a SIMD's waves
+// go through one issue port; a kernel whose matrix pipe is not full may be out of issue slots instead.  Rounds of the
+// same matrix work (16 MFMAs of 16 x 16 x 32 or 8 of 32 x 32 x 16, bf16: 256 cycles of the matrix pipe) with a given
+// number of other instructions spread evenly between them, everything from registers (or a few LDS words), one or
+// two waves per SIMD: the time per round against the 256 cycles says what the other instructions cost.
 #include "../../include/cyclotron_mm.h"
 #include "cyc_internal.h"
 
@@ -84,6 +90,68 @@ __global__ __launch_bounds__(256) void mfma_ceiling_kernel(int *sink, int iters)
     if (s == 0x12345678) sink[0] = s;      // keeps the loop alive; practically never true
 }
 
+// SHAPE 16 | 32; KIND 0: v_fma_f32, 1: v_exp_f32, 2: ds_read_b128; NV: other instructions per round (a multiple of 16)
+template <int SHAPE, int KIND, int NV>
+__global__ __launch_bounds__(512) void issue_mix_kernel(int *sink, int iters, float seed)
+{
+    __shared__ __attribute__((aligned(16))) int words[64 * 4];
+    if (threadIdx.x < 256) words[threadIdx.x] = (int)threadIdx.x;
+    __syncthreads();
+    const i32x4 a = {(int)threadIdx.x, 0x3f803f80, 0x40004000, 0x3f003f00}, b = {0x3f803f80, 0x3fc03fc0, 0x3f803f80, (int)threadIdx.x};
+    f32x4 acc4[16];
+    f32x16 acc16[8];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc4[i] = (f32x4){0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc16[i][r] = 0.0f;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = seed * (float)(i + 1) + (float)threadIdx.x * 1e-3f;
+    i32x4 ld = {0, 0, 0, 0};
+    const unsigned ldaddr = (unsigned)(uintptr_t)(__attribute__((address_space(3))) int *)words + (threadIdx.x & 63) * 16;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            if (SHAPE == 16) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc4[m]) : "v"(a), "v"(b));
+            else if ((m & 1) == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc16[m / 2]) : "v"(a), "v"(b));
+#pragma unroll
+            for (int k = 0; k < NV / 16; ++k) {
+                float &x = v[(m * (NV / 16) + k) & 7];
+                if (KIND == 0) asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(x) : "v"(seed));
+                else if (KIND == 1) asm volatile("v_exp_f32 %0, %0" : "+v"(x));
+                else asm volatile("ds_read_b128 %0, %1" : "=v"(ld) : "v"(ldaddr));
+            }
+        }
+        if (KIND == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ld));
+    }
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc4[i][0];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += acc16[i][0];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += v[i];
+    s += (float)ld[0];
+    if (s == 1.2345f) sink[0] = 1;         // keeps the loop alive; practically never true
+}
+
+template <int SHAPE, int KIND>
+hipError_t launch_issue_mix(int per_round, dim3 grid, dim3 block, hipStream_t s, int *sink, int iters)
+{
+    switch (per_round) {
+        case 0: return launch_kernel(issue_mix_kernel<SHAPE, 0, 0>, grid, block, s, sink, iters, 0.37f);
+        case 16: return launch_kernel(issue_mix_kernel<SHAPE, KIND, 16>, grid, block, s, sink, iters, 0.37f);
+        case 32: return launch_kernel(issue_mix_kernel<SHAPE, KIND, 32>, grid, block, s, sink, iters, 0.37f);
+        case 48: return launch_kernel(issue_mix_kernel<SHAPE, KIND, 48>, grid, block, s, sink, iters, 0.37f);
+        case 64: return launch_kernel(issue_mix_kernel<SHAPE, KIND, 64>, grid, block, s, sink, iters, 0.37f);
+        case 96: return launch_kernel(issue_mix_kernel<SHAPE, KIND, 96>, grid, block, s, sink, iters, 0.37f);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 __global__ __launch_bounds__(64) void clock_kernel(uint64_t *out, int64_t ticks)
 {
     const uint64_t w0 = wall_clock64(), c0 = clock64();
@@ -126,6 +194,35 @@ int cyc_diag_mfma_ceiling(int dtype, int mfma_shape, int64_t iters, void *sink, 
     else
         e = i8 ? cyc::launch_kernel(cyc::mfma_ceiling_kernel<true, 16>, grid, block, s, (int *)sink, (int)iters)
                : cyc::launch_kernel(cyc::mfma_ceiling_kernel<false, 16>, grid, block, s, (int *)sink, (int)iters);
+    return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
+int cyc_diag_issue_mix(int mfma_shape, int other_kind, int others_per_round, int waves_per_simd, int64_t iters, void *sink,
+                       double *ops, void *stream)
+{
+    if ((mfma_shape != 16 && mfma_shape != 32) || other_kind < 0 || other_kind > 2 || (waves_per_simd != 1 && waves_per_simd != 2) ||
+        iters < 1 || iters > (1 << 24))
+        return CYC_ERR_SHAPE;
+    if (others_per_round != 0 && others_per_round != 16 && others_per_round != 32 && others_per_round != 48 && others_per_round != 64 &&
+        others_per_round != 96)
+        return CYC_ERR_SHAPE;
+    if (!sink) return CYC_ERR_NULL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return CYC_ERR_LAUNCH;
+    // per wave and round 16 MFMAs of 16 x 16 x 32 (or 8 of twice that): 2 * 16 * 16 * 32 operations each
+    if (ops) *ops = (double)cus * 4 * waves_per_simd * (double)iters * 16 * 2.0 * 16 * 16 * 32;
+    dim3 grid((unsigned)cus), block(256 * waves_per_simd);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (mfma_shape == 16)
+        e = other_kind == 0   ? cyc::launch_issue_mix<16, 0>(others_per_round, grid, block, s, (int *)sink, (int)iters)
+            : other_kind == 1 ? cyc::launch_issue_mix<16, 1>(others_per_round, grid, block, s, (int *)sink, (int)iters)
+                              : cyc::launch_issue_mix<16, 2>(others_per_round, grid, block, s, (int *)sink, (int)iters);
+    else
+        e = other_kind == 0   ? cyc::launch_issue_mix<32, 0>(others_per_round, grid, block, s, (int *)sink, (int)iters)
+            : other_kind == 1 ? cyc::launch_issue_mix<32, 1>(others_per_round, grid, block, s, (int *)sink, (int)iters)
+                              : cyc::launch_issue_mix<32, 2>(others_per_round, grid, block, s, (int *)sink, (int)iters);
     return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 

@@ -121,6 +121,12 @@ def test_diagnostic_entry_points_validate_on_the_host(pkg):
     assert pkg.cyc_diag_mfma_ceiling(0, 8, 1000, 0x1000)[0] == 2          # unknown MFMA shape
     assert pkg.cyc_diag_mfma_ceiling(0, 16, 1004, 0x1000)[0] == 2         # iteration count not a multiple of 8
     assert pkg.cyc_diag_mfma_ceiling(0, 16, 1000, 0)[0] == 1              # NULL sink
+    assert pkg.cyc_diag_issue_mix(8, 0, 32, 1, 100, 0x1000)[0] == 2        # unknown MFMA shape
+    assert pkg.cyc_diag_issue_mix(16, 3, 32, 1, 100, 0x1000)[0] == 2       # unknown instruction kind
+    assert pkg.cyc_diag_issue_mix(16, 0, 24, 1, 100, 0x1000)[0] == 2       # count per round not offered
+    assert pkg.cyc_diag_issue_mix(16, 0, 32, 3, 100, 0x1000)[0] == 2       # one or two waves per SIMD
+    assert pkg.cyc_diag_issue_mix(16, 0, 32, 1, 0, 0x1000)[0] == 2         # no rounds
+    assert pkg.cyc_diag_issue_mix(16, 0, 32, 1, 100, 0)[0] == 1            # NULL sink
     assert pkg.cyc_diag_clock(0, 100) == 1
     assert pkg.cyc_diag_clock(0x1000, 0) == 2
     assert pkg.cyc_diag_clock(0x1004, 100) == 2                           # misaligned

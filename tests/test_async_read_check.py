@@ -56,3 +56,10 @@ def test_other_lds_operations_count_towards_the_wait():
     # a write issued after the read: "at most one outstanding" then still covers the read
     ok = CLEAN.replace("\tv_fma_f32 v20, v21, v22, v23\n", "\tds_write_b32 v5, v6\n\ts_waitcnt lgkmcnt(1)\n\tv_mov_b32_e32 v20, v12\n")
     assert checker.violations(ok) == []
+
+
+def test_a_later_read_into_the_same_registers_is_allowed_but_not_its_address():
+    again = CLEAN.replace("\tv_fma_f32 v20, v21, v22, v23\n", "\tds_read_b128 v[14:17], v2 offset:0x6000\n\ts_waitcnt lgkmcnt(2)\n")
+    assert checker.violations(again) == []
+    bad = CLEAN.replace("\tv_fma_f32 v20, v21, v22, v23\n", "\tds_read_b128 v[24:27], v15 offset:0x6000\n\ts_waitcnt lgkmcnt(2)\n")
+    assert len(checker.violations(bad)) == 1

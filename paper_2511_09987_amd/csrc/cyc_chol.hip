@@ -64,49 +64,16 @@ __device__ __forceinline__ uint16_t round_bf16(float f) { return __builtin_bit_c
 
 // The same for the diagonal tile, where row c of L is what lane c has just computed.  The chains of block b read the
 // rows 4b .. 4b+3 of L from LDS, where every lane writes its finished columns; the step over the columns of block k4 can
-// be read once the corner of block k4 is written.  The last step of a block (k4 = b - 1) is requested right after
-// that corner and runs after one step held back to cover its latency (k4 = b - 2, "in turn"); all steps before
-// those, at most EARLY_D of them, run beside the corner of block b - 1, PER_COLUMN after each of its four columns:
-// a corner column here is a square root, a lane read and a division, some 30 dependent instructions.
-// DIAG_STEPS is the execution order of the steps that go through the request queue (all but the last of each block).
-constexpr int EARLY_D = 12, PER_COLUMN = 3, NSTEP_D = (NBLK - 1) * (NBLK - 2) / 2;
-constexpr int early_d(int b) { return b < 2 ? 0 : (b - 2 < EARLY_D ? b - 2 : EARLY_D); }
-struct DiagStepList {
-    signed char b[NSTEP_D + 2], k[NSTEP_D + 2];
-    bool ok;
-};
-constexpr DiagStepList make_diag_steps()
-{
-    DiagStepList s{};
-    int when[NSTEP_D + 2] = {};          // 2b: after the corner of block b - 1;  2b + 1: beside the corner of block b
-    int n = 0;
-    for (int b = 0; b < NBLK; ++b) {
-        for (int k4 = early_d(b); k4 + 2 <= b; ++k4) {                 // in turn
-            s.b[n] = (signed char)b;
-            s.k[n] = (signed char)k4;
-            when[n++] = 2 * b;
-        }
-        if (b + 1 < NBLK)
-            for (int k4 = 0; k4 < early_d(b + 1); ++k4) {              // beside the corner of block b
-                s.b[n] = (signed char)(b + 1);
-                s.k[n] = (signed char)k4;
-                when[n++] = 2 * b + 1;
-            }
-    }
-    s.b[n] = s.b[n + 1] = -1;
-    // a step is requested when the step two before it runs (the first two after the corner of block 0): by then the
-    // corner of the block whose columns it covers must have been written
-    s.ok = n == NSTEP_D;
-    for (int i = 0; i < n; ++i) s.ok = s.ok && (i < 2 ? 2 : when[i - 2]) >= 2 * (s.k[i] + 1);
-    return s;
-}
-constexpr int beside_column(int b, int j)           // how many early steps of block b + 1 run beside column j of block b's corner
-{
-    const int left = (b + 1 < NBLK ? early_d(b + 1) : 0) - PER_COLUMN * j;
-    return left < 0 ? 0 : (left < PER_COLUMN ? left : PER_COLUMN);
-}
-constexpr DiagStepList DIAG_STEPS = make_diag_steps();
-static_assert(DIAG_STEPS.ok, "a step of the diagonal tile would be requested before its operand is written");
+// be read once the corner of block k4 is written.
+// The first wave takes only the steps close to the diagonal itself: the tile's columns in groups of 16 (four blocks),
+// group G handed to it by a second wave (trailing_update64) with all steps up to block 4G - 2 taken out already, on
+// the matrix cores.  Of block b it runs the steps first_k(b) .. b - 1: the last one (k4 = b - 1) is requested right
+// after the corner of block b - 1, the one before it is held back to cover that request's latency, the others (at most
+// two) run beside the corner of block b - 1, one after each of its first columns; all but the last are requested when
+// that corner starts, which is after block b - 2 was written.
+constexpr int first_k(int b) { return b < 4 ? 0 : 4 * (b / 4) - 1; }
+constexpr int own_steps(int b) { return b - first_k(b); }
+constexpr int LDF = 20;        // row stride of the hand-over buffer: 16 columns, and 16 consecutive rows on distinct banks
 
 constexpr int NT = 256;        // threads of a tile kernel: four waves move tiles and multiply, the first runs the recurrence
 
@@ -333,30 +300,6 @@ constexpr int W_FLOATS = 64 * 64;
 constexpr float W_NORM_LIMIT = 8.0f;
 constexpr int FOLLOW_SPIN_LIMIT = 1 << 20;
 
-// every read of the follower asks for columns of a block that the gate before it has seen finished
-constexpr bool follower_reads_are_gated()
-{
-    int passed = 0, i = 0;                                   // gate(0) comes first
-    bool ok = true;
-    auto check = [&](int idx) { if (STEPS.b[idx] >= 0 && STEPS.k[idx] > passed) ok = false; };
-    check(0);
-    check(1);
-    for (int b = 0; b < NBLK; ++b) {
-        if (b > 0) passed = b;
-        for (int s2 = early_of(b); s2 < b; ++s2) {
-            check(i + 2);
-            ++i;
-        }
-        for (int j = 0; j < 4; ++j)
-            if (b + 1 < NBLK && j < early_of(b + 1)) {
-                check(i + 2);
-                ++i;
-            }
-    }
-    return ok && i == NSTEP;
-}
-static_assert(follower_reads_are_gated(), "the follower would read rows of L before they are final");
-
 // maximum over the 64 lanes of a wave, in every lane
 __device__ __forceinline__ float wave_max64(float v)
 {
@@ -376,8 +319,14 @@ __device__ __forceinline__ float wave_max64(float v)
     return __builtin_fmaxf(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
 }
 
-// The follower: one wave, lane = column of W.  T holds S above the factorisation's progress and L below it; *ready
-// counts the blocks of four columns the factorisation has finished.  Writes W and the verdict.
+// The follower: one wave, lane = column of W: lane j solves L_jj y = e_j.  T holds S above the factorisation's progress
+// and L below it; *ready counts the blocks of four columns the factorisation has finished.  Writes W and the verdict.
+// In the order in which its work becomes available: block k of the factorisation brings the columns 4k .. 4k+3 of
+// every row of L_jj; the follower then solves the rows 4k .. 4k+3 (their corner is complete with that block) and takes
+// them out of all rows below at once, so that after the factorisation's last block only a corner is left to do.  (In
+// the order of the triangular solve's step list, block after block of rows with all their columns, most of a row
+// block's work waits for that block's corner, and the follower ended 3.5k cycles behind the factorisation.)  Every
+// read of T here is of columns of block k, behind the gate of block k.
 // Not inlined, and its LDS operands passed as addresses: inside diag_rest it raised that kernel's register count from 228
 // to 369 and put the factorisation's own values into accumulation registers, 3k cycles on the path per tile.
 __device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, uint32_t ready_in_lds, int lane, float *__restrict__ W,
@@ -400,91 +349,66 @@ __device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, ui
                 expired = true;
                 break;
             }
-            __builtin_amdgcn_s_sleep(4);                      // the factorisation reads LDS on its critical path: poll seldom
+            __builtin_amdgcn_s_sleep(2);                      // the factorisation reads LDS on its critical path: poll seldom
         }
     };
-    float xn[NBMAX], tt[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    f32x4 q[3][4], qc[4];
+    float t[NBMAX];                                           // the running right-hand side: column `lane` of the identity
+#pragma unroll
+    for (int r = 0; r < NBMAX; ++r) t[r] = r == lane ? 1.0f : 0.0f;
     float colsum_L = 0.0f, colsum_W = 0.0f;
-    float *out = W + (lane >> 4) * 256 + (lane & 3) * 64 + ((lane >> 2) & 3);
-    auto rows_of_L = [&](int i) __attribute__((always_inline)) {
-        if (STEPS.b[i] >= 0) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) q[i % 3][j] = *(CYC_LDS const f32x4 *)&T[4 * STEPS.b[i] + j][4 * STEPS.k[i]];
-        }
-    };
-    auto quarter = [&](float(&acc)[4], int i, int kk) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(q[i % 3][j][kk], xn[4 * STEPS.k[i] + kk], acc[j]);
-    };
-    // the block's corner of L_jj and the lane's own column of it (for ||L_jj||_1), once the block is final
-    auto corner_of_L = [&](int b) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            qc[j] = *(CYC_LDS const f32x4 *)&T[4 * b + j][4 * b];
-            const float mine = T[4 * b + j][lane];
-            colsum_L += 4 * b + j >= lane ? __builtin_fabsf(mine) : 0.0f;
-        }
-    };
-    gate(0);
-    rows_of_L(0);
-    rows_of_L(1);
-    corner_of_L(0);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) tt[j] = j == lane ? 1.0f : 0.0f;
-    int i = 0;
+    // (as a pointer to global memory: through the generic pointer of a function that is not inlined the stores would be
+    // flat instructions, which count as LDS operations too and complete out of order with them, and every wait for
+    // an LDS read below would become a wait for all of them)
+    typedef __attribute__((address_space(1))) float global_float;
+    global_float *out = (global_float *)(W + (lane >> 4) * 256 + (lane & 3) * 64 + ((lane >> 2) & 3));
     unrolled<NBLK>([&](auto index) __attribute__((always_inline)) {
-        constexpr int b = decltype(index)::value;
-        if (b > 0) {
-            gate(b);
-            corner_of_L(b);
-        }
-#pragma unroll
-        for (int s2 = early_of(b); s2 < b; ++s2) {
-            rows_of_L(i + 2);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) quarter(tt, i, kk);
-            ++i;
-        }
-        if (b + 1 < NBLK) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) tn[j] = 4 * (b + 1) + j == lane ? 1.0f : 0.0f;
-        }
+        constexpr int k = decltype(index)::value;
+        gate(k);
+        // the block's corner of L_jj, the lane's own column of it (for ||L_jj||_1), and the rows below it, requested
+        // two blocks of rows ahead of their use
+        f32x4 qc[4], q[3][4];
+        float mine[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int r = 4 * b + j;
-            const bool paired = b + 1 < NBLK && j < early_of(b + 1);
-            if (paired) rows_of_L(i + 2);
-            __builtin_amdgcn_sched_barrier(0);
+            qc[j] = *(CYC_LDS const f32x4 *)&T[4 * k + j][4 * k];
+            mine[j] = T[4 * k + j][lane];
+        }
+        auto request = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
-            for (int e = 0; e < j; ++e) tt[j] = __builtin_fmaf(qc[j][e], xn[4 * b + e], tt[j]);
-            Division dv;
-            dv.phase0(tt[j], qc[j][j]);
-            __builtin_amdgcn_sched_barrier(0);
-            if (paired) quarter(tn, i, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            dv.phase1();
-            __builtin_amdgcn_sched_barrier(0);
-            if (paired) quarter(tn, i, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            dv.phase2();
-            __builtin_amdgcn_sched_barrier(0);
-            if (paired) quarter(tn, i, 2);
-            __builtin_amdgcn_sched_barrier(0);
-            const float y = dv.phase3();
-            xn[r] = -y;
-            asm("" : "+v"(xn[r]));
+            for (int j = 0; j < 4; ++j) q[(b - k - 1) % 3][j] = *(CYC_LDS const f32x4 *)&T[4 * b + j][4 * k];
+        };
+        if (k + 1 < NBLK) request(k + 1);
+        if (k + 2 < NBLK) request(k + 2);
+        // rows 4k .. 4k+3.  The reciprocals of the diagonal by estimate and one Newton step: W is only ever used as an
+        // approximation whose error the check below bounds, and a multiplication is one instruction on the chain from
+        // row to row where the division is eleven.
+        float xn[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            colsum_L += 4 * k + j >= lane ? __builtin_fabsf(mine[j]) : 0.0f;
+            const float d = qc[j][j], r0 = __builtin_amdgcn_rcpf(d);
+            const float rinv = __builtin_fmaf(__builtin_fmaf(-d, r0, 1.0f), r0, r0);
+#pragma unroll
+            for (int e = 0; e < j; ++e) t[4 * k + j] = __builtin_fmaf(qc[j][e], xn[e], t[4 * k + j]);
+            const float y = t[4 * k + j] * rinv;
+            xn[j] = -y;
+            const int r = 4 * k + j;
             out[(r >> 4) * 1024 + (r & 15) * 4] = y;
             colsum_W += __builtin_fabsf(y);
-            __builtin_amdgcn_sched_barrier(0);
-            if (paired) {
-                quarter(tn, i, 3);
-                ++i;
-            }
         }
+        // and out of every row below
 #pragma unroll
-        for (int j = 0; j < 4; ++j) tt[j] = tn[j];
+        for (int b = k + 1; b < NBLK; ++b) {
+            if (b + 2 < NBLK) request(b + 2);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t[4 * b + j] = __builtin_fmaf(q[(b - k - 1) % 3][j][kk], xn[kk], t[4 * b + j]);
+            // (pinned here: the compiler otherwise moves these multiply-adds down to where their sums are next used,
+            // blocks later, and keeps their operands alive in scratch memory until then)
+            asm volatile("" : "+v"(t[4 * b]), "+v"(t[4 * b + 1]), "+v"(t[4 * b + 2]), "+v"(t[4 * b + 3]));
+        }
     });
     const float a = wave_max64(colsum_L), c = wave_max64(colsum_W);
     // (a NaN anywhere would be dropped by the maxima: every lane checks its own sums)
@@ -493,72 +417,143 @@ __device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, ui
     if (lane == 0) *ok = all_fine ? 1 : 0;
 }
 
+// The second wave of the diagonal tile's factorisation.  It keeps the columns 16 .. 63 of the tile (the six 16 x 16
+// blocks on and below the block diagonal) in accumulator layout and takes block after block of finished columns out of
+// them as soon as the first wave announces it: S_rc <- fma(-L_rk, L_ck, S_rc) for the four k of a block is one
+// v_mfma_f32_16x16x4_f32 per 16 x 16 block, which adds its four products in ascending k with one rounding each, the bits of
+// the scalar chain (checked against it on 10^7 random elements per exponent range, denormal products included; the
+// parity tests on integer and real data cover it as well).  Column group G goes to the first wave, through F, when block
+// 4G - 2 is out of it; from then on that group is the first wave's.
+// sync: [0] blocks finished by the first wave, [1] groups handed over, [2] set when a bounded wait ran out.
+__device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, uint32_t F_in_lds, uint32_t sync_in_lds, int lane)
+{
+    CYC_LDS const float *const T = (CYC_LDS const float *)(uintptr_t)T_in_lds;
+    CYC_LDS float *const F = (CYC_LDS float *)(uintptr_t)F_in_lds;
+    CYC_LDS int *const sync = (CYC_LDS int *)(uintptr_t)sync_in_lds;
+    const int i = lane & 15, kq = lane >> 4;
+    // block (cb, rb), 1 <= cb <= rb <= 3: register r of lane l is row 16 rb + 4 (l/16) + r, column 16 cb + l%16
+    auto idx = [](int cb, int rb) __attribute__((always_inline)) { return cb == 1 ? rb - 1 : cb == 2 ? rb + 1 : 5; };
+    f32x4 c[6];
+#pragma unroll
+    for (int cb = 1; cb < 4; ++cb)
+#pragma unroll
+        for (int rb = cb; rb < 4; ++rb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) c[idx(cb, rb)][r] = T[(16 * rb + 4 * kq + r) * LDT + 16 * cb + i];
+    bool expired = false;
+    unrolled<4 * 3 - 1>([&](auto index) __attribute__((always_inline)) {
+        constexpr int p = decltype(index)::value;                      // the block of four finished columns to take out
+        constexpr int first_cb = p % 4 == 3 ? p / 4 + 2 : p / 4 + 1;   // (group (p + 1) / 4 was handed over before its block 4G - 1)
+        constexpr int G = p % 4 == 2 ? (p + 2) / 4 : 0;                // the group to hand over after this block
+        if (first_cb <= 3) {
+            int polls = 0;
+            while (__hip_atomic_load(sync, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) <= p) {
+                if (++polls >= FOLLOW_SPIN_LIMIT) {
+                    expired = true;
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            // lane l: L[16 rb + l%16][4p + l/16], the stationary operand (negated) for row block rb and the streamed one
+            // for column block rb
+            float xr[4], xm[4];
+#pragma unroll
+            for (int rb = first_cb; rb < 4; ++rb) {
+                xr[rb] = T[(16 * rb + i) * LDT + 4 * p + kq];
+                xm[rb] = -xr[rb];
+            }
+            auto column_block = [&](int cb) __attribute__((always_inline)) {
+#pragma unroll
+                for (int rb = cb; rb < 4; ++rb) c[idx(cb, rb)] = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[rb], xr[cb], c[idx(cb, rb)], 0, 0, 0);
+            };
+            if (G) {
+                column_block(G);
+#pragma unroll
+                for (int rb = G; rb < 4; ++rb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) F[(16 * rb + 4 * kq + r) * LDF + i] = c[idx(G, rb)][r];
+                // (a wave's LDS operations are performed in issue order: whoever sees the counter sees the columns)
+                asm volatile("" ::: "memory");
+                __hip_atomic_store(sync + 1, G, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+#pragma unroll
+            for (int cb = first_cb; cb < 4; ++cb)
+                if (cb != G) column_block(cb);
+        }
+    });
+    if (expired && lane == 0) sync[2] = 1;
+}
+
 // The factorisation proper of a diagonal tile whose S (with everything left of it taken out) is in T: the column
-// recurrence by the first wave, then L, and Lh in both triangles, written out by all.  See diag_tile.
-// ready: a counter in LDS, zero on entry (with a barrier since); W, ok: where the tile's inverse and its verdict go, or
-// nullptr (then, and for tiles of fewer than 64 columns, none is computed).
-// beside(t): called in the full-tile case by the threads 128 .. 255 (t = 0 .. 127), which otherwise only wait, while
+// recurrence by the first wave with the second wave's help (trailing_update64), then L, and Lh in both triangles,
+// written out by all.  See diag_tile.
+// F: the hand-over buffer; sync: three counters in LDS, zero on entry (with a barrier since): see trailing_update64.
+// W, ok: where the tile's inverse and its verdict go, or nullptr (then, and for tiles of fewer than 64 columns, none
+// is computed).
+// beside(t): called in the full-tile case by the threads 128 .. 191 (t = 0 .. 63), which otherwise only wait, while
 // the tile is being factored.
 template <class Beside>
-__device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r, int *ready,
-                                          float *W, int *ok, Beside beside)
+__device__ __forceinline__ void diag_rest(float (*T)[LDT], float (*F)[LDF], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r,
+                                          int *sync, float *W, int *ok, Beside beside)
 {
     const bool live = r < cols;
     bool mirrored = false;
     if (cols == NBMAX) {
-        // Full tile: the lane keeps its row of S and of L in registers (every index below is a constant after
-        // unrolling) and writes each finished group of four columns to its row of T in LDS, where the other lanes
-        // find row c of L when they come to column c (one wave: its LDS operations complete in program order, so a
-        // read sees an earlier write without a barrier).  The steps in the order of DIAG_STEPS, operands requested
-        // two steps ahead.  Inside the 4 x 4 corner the few values from other lanes' registers are fetched with
-        // lane reads.  Lanes above the diagonal (r < c) compute values nobody uses.  Every entry takes its terms in
-        // ascending k.
+        // Full tile: the lane keeps its row of L in registers (every index below is a constant after unrolling) and
+        // writes each finished group of four columns to its row of T in LDS, where the other lanes find row c of L
+        // when they come to column c (one wave: its LDS operations complete in program order, so a read sees an
+        // earlier write without a barrier).  Inside the 4 x 4 corner the few values from other lanes' registers are
+        // fetched with lane reads.  Lanes above the diagonal (r < c) compute values nobody uses.  Every entry takes
+        // its terms in ascending k.
         if (r < 64) {
         float x[NBMAX], xn[NBMAX], t[4], tn[4] = {0.0f, 0.0f, 0.0f, 0.0f};      // xn = -x, see chol_panel_kernel
-        f32x4 sr[NBLK], q[3][4], ql[4];
+        f32x4 grp[4], q[3][4], ql[4];                                           // grp: the lane's row of the current group of 16 columns
 #pragma unroll
-        for (int i = 0; i < NBLK; ++i) sr[i] = *(const f32x4 *)&T[r][4 * i];
-        auto request = [&](int i) __attribute__((always_inline)) {              // operands of queued step i
-            if (DIAG_STEPS.b[i] >= 0) {
+        for (int i = 0; i < 4; ++i) grp[i] = *(const f32x4 *)&T[r][4 * i];
+        auto request = [&](int b, int k4, f32x4(&o)[4]) __attribute__((always_inline)) {     // operands of step k4 of block b
 #pragma unroll
-                for (int j = 0; j < 4; ++j) q[i % 3][j] = *(const f32x4 *)&T[4 * DIAG_STEPS.b[i] + j][4 * DIAG_STEPS.k[i]];
-            }
+            for (int j = 0; j < 4; ++j) o[j] = *(const f32x4 *)&T[4 * b + j][4 * k4];
         };
-        auto step = [&](float(&acc)[4], int i) __attribute__((always_inline)) {  // queued step i: 16 multiply-adds
+        auto step = [&](float(&acc)[4], int k4, const f32x4(&o)[4]) __attribute__((always_inline)) {   // 16 multiply-adds
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(xn[4 * DIAG_STEPS.k[i] + kk], q[i % 3][j][kk], acc[j]);
+                for (int j = 0; j < 4; ++j) acc[j] = __builtin_fmaf(xn[4 * k4 + kk], o[j][kk], acc[j]);
         };
         auto lane_value = [](float v, int l) __attribute__((always_inline)) {
             return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
         };
 #pragma unroll
-        for (int j = 0; j < 4; ++j) t[j] = sr[0][j];
-        int i = 0;                                                              // the next queued step
+        for (int j = 0; j < 4; ++j) t[j] = grp[0][j];
         unrolled<NBLK>([&](auto block) __attribute__((always_inline)) {
             constexpr int b = decltype(block)::value;
+            constexpr int mine = own_steps(b), next = b + 1 < NBLK ? own_steps(b + 1) : 0;
+            if (b >= 4 && b % 4 == 0) {
+                // a new group of 16 columns, from the second wave: everything up to block b - 2 is out of it
+                int polls = 0;
+                while (__hip_atomic_load(sync + 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < b / 4) {
+                    if (++polls >= FOLLOW_SPIN_LIMIT) {
+                        __hip_atomic_store(sync + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        break;
+                    }
+                }
 #pragma unroll
-            for (int k4 = early_d(b); k4 + 2 <= b; ++k4) {                      // in turn
-                request(i + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                step(t, i);
-                ++i;
+                for (int i = 0; i < 4; ++i) grp[i] = *(const f32x4 *)&F[r][4 * i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t[j] = grp[0][j];
             }
-            if (b >= 1) {                                                       // the block's last step, requested on its own
+            if (mine >= 2) step(t, b - 2, q[mine >= 2 ? mine - 2 : 0]);                         // held back: covers the latency of ql
+            if (mine >= 1) step(t, b - 1, ql);
+            if (next >= 1 && (b + 1) % 4 != 0) {
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) t[j] = __builtin_fmaf(xn[4 * (b - 1) + kk], ql[j][kk], t[j]);
+                for (int j = 0; j < 4; ++j) tn[j] = grp[(b + 1) % 4][j];
             }
-            if (b + 1 < NBLK) {
+            // operands of the next block's steps, all but the last: blocks first_k(b + 1) .. b - 1 are written
 #pragma unroll
-                for (int j = 0; j < 4; ++j) tn[j] = sr[b + 1][j];
-            }
+            for (int u = 0; u + 1 < next; ++u) request(b + 1, first_k(b + 1) + u, q[u]);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int c = 4 * b + j;
-                const int now = beside_column(b, j);                            // steps of the next block to run beside this column
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int e = 0; e < j; ++e) t[j] = __builtin_fmaf(xn[4 * b + e], lane_value(x[4 * b + e], c), t[j]);
@@ -566,13 +561,7 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
                 x[c] = r == c ? d : t[j] / d;
                 xn[c] = -x[c];
                 asm("" : "+v"(xn[c]));                                          // (or the negation is folded back into the multiply-adds)
-#pragma unroll
-                for (int u = 0; u < PER_COLUMN; ++u)
-                    if (u < now) {
-                        request(i + 2);                                         // (three queue slots: steps i, i + 1 pending)
-                        step(tn, i);
-                        ++i;
-                    }
+                if (j + 2 < next) step(tn, first_k(b + 1) + j, q[j]);           // one step of the next block beside this column
             }
             f32x4 done;
 #pragma unroll
@@ -582,31 +571,36 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
             // chains into basic blocks), and without a release fence, which would wait for the operands requested ahead
             // as well: a wave's LDS operations are performed in the order it issues them, so whoever sees the counter
             // sees the block; the empty asm keeps the compiler from moving the store up.
-            // (Stored whether or not anyone follows: a condition here would cut the chains into basic blocks as well.)
             asm volatile("" ::: "memory");
-            __hip_atomic_store(ready, b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            if (b + 1 < NBLK) {
+            __hip_atomic_store(sync, b + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (b + 1 < NBLK) request(b + 1, b, ql);
+            if (next >= 1 && (b + 1) % 4 != 0) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) ql[j] = *(const f32x4 *)&T[4 * (b + 1) + j][4 * b];
+                for (int j = 0; j < 4; ++j) t[j] = tn[j];
             }
-            if (b == 0) {
-                request(0);
-                request(1);
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j) t[j] = tn[j];
         });
-        // the mirror image into the upper part of the tile (Lh holds both triangles): entry (c, r) for c < r
+        // the mirror image into the upper part of the tile (Lh holds both triangles): entry (c, r) for c < r; the other
+        // lanes write to the padding of their row (a store under a lane condition is a branch around it: 4k cycles for
+        // the 63 of them)
 #pragma unroll
-        for (int c = 0; c < NBMAX - 1; ++c)
-            if (c < r) T[c][r] = x[c];
+        for (int c = 0; c < NBMAX - 1; ++c) *(c < r ? &T[c][r] : &T[r][NBMAX]) = x[c];
+        } else if (r >= 192) {
+            trailing_update64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS float *)&F[0][0],
+                              (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 192);
         } else if (r >= 128) {
             beside(r - 128);
         } else if (W) {
-            inverse_follow64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS int *)ready, r - 64, W, ok);
+            inverse_follow64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 64, W, ok);
         }
         mirrored = true;
         __syncthreads();
+        if (__builtin_expect(sync[2] != 0, 0)) {
+            // a bounded wait between the two waves ran out (it never should): NaNs instead of a factor that looks
+            // like one, and no inverse
+            for (int e = r; e < NBMAX * NBMAX; e += NT) T[e / NBMAX][e % NBMAX] = __builtin_nanf("");
+            if (r == 0 && W) *ok = 0;
+            __syncthreads();
+        }
     } else {
         for (int c = 0; c < cols; ++c) {
             float t = 0.0f;
@@ -637,15 +631,15 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float *L, uint16_t *L
 // move and update the tile.  T (first 64 KB of LDS: a read reaches its word with the 16-bit offset field from one
 // base register; further up every read needs an address register of its own) and Bs are the workgroup's LDS.
 __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], const float *Sm, float *L, uint16_t *Lh, int64_t n,
-                                          int64_t j0, int cols, int64_t k0, int r, int *ready, float *W, int *ok)
+                                          int64_t j0, int cols, int64_t k0, int r, float (*F)[LDF], int *sync, float *W, int *ok)
 {
-    if (r == 0) *ready = 0;               // (a barrier follows below, before anyone looks at it)
+    if (r < 3) sync[r] = 0;               // (a barrier follows below, before anyone looks at them)
     TileProduct product;
     if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     if (k0 < j0) product.apply(T, Bs, r);
     else __syncthreads();
-    diag_rest(T, L, Lh, n, j0, cols, r, ready, W, ok, [](int) {});
+    diag_rest(T, F, L, Lh, n, j0, cols, r, sync, W, ok, [](int) {});
 }
 
 __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
@@ -654,9 +648,10 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
     __shared__ __attribute__((aligned(16))) struct {
         float T[NBMAX][LDT];          // S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
-        int ready;                    // blocks of four columns finished, for the wave that follows with the inverse
+        float F[NBMAX][LDF];          // a group of 16 columns on its way from the second wave to the first
+        int sync[3];                  // blocks of four columns finished; groups handed over; a wait ran out (see trailing_update64)
     } lds;
-    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, &lds.ready, W, ok);
+    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, lds.F, lds.sync, W, ok);
 }
 
 // L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane of the first wave; the
@@ -683,14 +678,15 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
         uint16_t Bs2[KMAX][64];       // streamed operand of the next diagonal tile's update
-        int ready;                    // blocks of four columns of the next diagonal tile finished (see diag_rest)
+        float F[NBMAX][LDF];          // the next diagonal tile: a group of 16 columns between its two waves (see diag_rest)
+        int sync[3];                  // the next diagonal tile's counters (see trailing_update64)
     } lds;
     auto &D = lds.D;
     auto &X = lds.X;
     auto &Bs = lds.Bs;
     auto &Bs2 = lds.Bs2;
     const int tid = threadIdx.x, lane = tid & 63;
-    if (tid == 0) lds.ready = 0;
+    if (tid < 3) lds.sync[tid] = 0;
     const bool solver = tid < 64;                         // the wave that runs the recurrence
     // The rows of this workgroup through the inverse of L_jj?  W and its verdict are requested here with everything
     // else the kernel needs from memory; the verdict is looked at only where the rows are formed, so that nothing
@@ -972,10 +968,10 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
             }
         __syncthreads();
-        diag_rest(D, L, Lh, n, j1, NBMAX, tid, &lds.ready, Wout, okout, [&](int t) __attribute__((always_inline)) {
+        diag_rest(D, lds.F, L, Lh, n, j1, NBMAX, tid, lds.sync, Wout, okout, [&](int t) __attribute__((always_inline)) {
             // this workgroup's own rows, deferred above
-            store_tile<false, 128>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
-            if (by_inverse) store_mirror<128>(X, Lh + j0 * n + first, n, t);
+            store_tile<false, 64>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
+            if (by_inverse) store_mirror<64>(X, Lh + j0 * n + first, n, t);
         });
     }
 }

@@ -408,37 +408,50 @@ __global__ __launch_bounds__(C::NT) void ws_mfma_kernel(const char *__restrict__
     // row (l/16)*4 + r, column l%16.
     typedef typename Mac::elem elem;
     elem *Cw = (elem *)Cout;
+    auto row_of = [&](int i, int r) __attribute__((always_inline)) { return m0 + wm * (TM * MT) + i * MT + (l / MT) * 4 + (r >> 2) * 8 + (r & 3); };
+    auto col_of = [&](int j) __attribute__((always_inline)) { return n0 + wn * (TN * MT) + j * MT + (l & (MT - 1)); };
+    if (EPI == EPI_MINUS) {
+        // C <- Cin - A*B, in two passes: first every accumulator becomes Cin - accumulator, Cin fetched a row of MFMA tiles at a
+        // time with further rows in flight; then all are stored.  Loads alone retire in issue order
+        // and can be waited for group by group; with stores between them every wait would be for everything
+        // outstanding, one round trip to memory per row of tiles.  (Cin may be C: no element is stored before all of
+        // this wave's elements are read, and no other wave touches them.)
+        constexpr int AHEAD = TM >= 3 ? 2 : 1;              // rows of tiles requested beyond the one being applied
+        elem cin[AHEAD + 1][TN][C::ACCN];
+        auto request = [&](int i) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        // one row of MFMA tiles at a time; for EPI_MINUS all its Cin values are requested before the first is used
-        elem cin[TN][C::ACCN];
-        if (EPI == EPI_MINUS) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * (TN * MT) + j * MT + (l & (MT - 1));
-                const int row0 = m0 + wm * (TM * MT) + i * MT + (l / MT) * 4;
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < C::ACCN; ++r) {
-                    const int row = row0 + (r >> 2) * 8 + (r & 3);
-                    cin[j][r] = (!RAGGED || (row < M && col < N)) ? ((const elem *)Cin)[(int64_t)row * ldc + col] : (elem)0;
+                    const int row = row_of(i, r), col = col_of(j);
+                    cin[i % (AHEAD + 1)][j][r] = (!RAGGED || (row < M && col < N)) ? ((const elem *)Cin)[(int64_t)row * ldc + col] : (elem)0;
                 }
-            }
-        }
+        };
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = n0 + wn * (TN * MT) + j * MT + (l & (MT - 1));
-            const int row0 = m0 + wm * (TM * MT) + i * MT + (l / MT) * 4;
+        for (int i = 0; i < AHEAD && i < TM; ++i) request(i);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            // (the barriers keep the compiler from moving every accumulator into the vector registers first, which
+            // leaves it room for one load at a time)
+            __builtin_amdgcn_sched_barrier(0);
+            if (i + AHEAD < TM) request(i + AHEAD);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < C::ACCN; ++r) acc[i][j][r] = cin[i % (AHEAD + 1)][j][r] - acc[i][j][r];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < C::ACCN; ++r) {
-                const int row = row0 + (r >> 2) * 8 + (r & 3);
-                elem v = acc[i][j][r];
-                if (!RAGGED || (row < M && col < N)) {
-                    if (EPI == EPI_MINUS) v = cin[j][r] - v;          // C <- Cin - A*B
-                    Cw[(int64_t)row * ldc + col] = v;
-                }
+                const int row = row_of(i, r), col = col_of(j);
+                if (!RAGGED || (row < M && col < N)) Cw[(int64_t)row * ldc + col] = acc[i][j][r];
             }
-        }
-    }
 }
 
 template <class C, int EPI>

@@ -50,6 +50,8 @@ def _load() -> ctypes.CDLL:
     lib.cyc_diag_mfma_ceiling.restype = cint
     lib.cyc_diag_issue_mix.argtypes = [cint, cint, cint, cint, i64, ptr, ctypes.POINTER(ctypes.c_double), ptr]
     lib.cyc_diag_issue_mix.restype = cint
+    lib.cyc_diag_mfma_f32_tiles.argtypes = [ptr, ptr, ptr, ptr, i64, ptr]
+    lib.cyc_diag_mfma_f32_tiles.restype = cint
     lib.cyc_diag_clock.argtypes = [ptr, i64, ptr]
     lib.cyc_diag_clock.restype = cint
     return lib
@@ -130,6 +132,10 @@ def cyc_diag_issue_mix(mfma_shape: int, other_kind: int, others_per_round: int, 
     ops = ctypes.c_double(0.0)
     st = int(_lib().cyc_diag_issue_mix(mfma_shape, other_kind, others_per_round, waves_per_simd, iters, sink, ctypes.byref(ops), stream))
     return st, ops.value
+
+
+def cyc_diag_mfma_f32_tiles(A: int, B: int, C: int, D: int, tiles: int, stream: int = 0) -> int:
+    return int(_lib().cyc_diag_mfma_f32_tiles(A, B, C, D, tiles, stream))
 
 
 def cyc_diag_clock(out: int, microseconds: int, stream: int = 0) -> int:

@@ -319,27 +319,41 @@ __device__ __forceinline__ float wave_max64(float v)
     return __builtin_fmaxf(__builtin_bit_cast(float, b0), __builtin_bit_cast(float, b1));
 }
 
-// The follower: one wave, lane = column of W: lane j solves L_jj y = e_j.  T holds S above the factorisation's progress
-// and L below it; *ready counts the blocks of four columns the factorisation has finished.  Writes W and the verdict.
-// In the order in which its work becomes available: block k of the factorisation brings the columns 4k .. 4k+3 of
-// every row of L_jj; the follower then solves the rows 4k .. 4k+3 (their corner is complete with that block) and takes
-// them out of all rows below at once, so that after the factorisation's last block only a corner is left to do.  (In
-// the order of the triangular solve's step list, block after block of rows with all their columns, most of a row
-// block's work waits for that block's corner, and the follower ended 3.5k cycles behind the factorisation.)  Every
-// read of T here is of columns of block k, behind the gate of block k.
+// What the waves of a diagonal tile's factorisation pass to one another in LDS.
+constexpr int LDY = 80;        // row stride of Y: 64 columns, and four consecutive rows on disjoint banks
+struct DiagLds {
+    float F[NBMAX][LDF];       // a group of 16 columns on its way from the second wave to the first (trailing_update64)
+    float Y[16][LDY];          // the follower's rows of W of the current group of 16 (inverse_follow64)
+    int sync[3];               // blocks of four columns finished; groups handed over; a wait ran out (trailing_update64)
+};
+
+// The follower: one wave computes W = L_jj^-1 beside the factorisation, in the order in which its work becomes
+// available.  T holds S above the factorisation's progress and L below it; *ready counts the blocks of four columns the
+// factorisation has finished.  Block k brings the columns 4k .. 4k+3 of every row of L_jj: the follower then solves
+// the rows 4k .. 4k+3 of L_jj W = I (their 4 x 4 corner is complete with that block) and takes them out of all rows
+// below at once, so that after the factorisation's last block only a corner is left to do.  The running right-hand
+// side is kept in the accumulator layout of v_mfma_f32_16x16x4_f32 (the ten 16 x 16 blocks on and below the block
+// diagonal: register r of lane l is row 16 rb + 4 (l/16) + r, column 16 cb + l%16), so that taking four rows out of
+// the rows below is one MFMA per block: A operand -L_jj[16 rb + l%16][4k + l/16], straight from T; B operand
+// W[4k + l/16][16 cb + l%16], which crosses LDS (Y) from the 16 lanes per column block that have just solved it.  Y
+// also collects the 16 rows of a group, which go out to W in the operand order of the product that uses them, 1 KiB
+// pieces as 16-byte stores.  Every read of T here is of columns of block k, behind the gate of block k.
+// Reciprocals of the diagonal by estimate and one Newton step: W is only ever used as an approximation whose error the
+// check at the end bounds.
 // Not inlined, and its LDS operands passed as addresses: inside diag_rest it raised that kernel's register count from 228
 // to 369 and put the factorisation's own values into accumulation registers, 3k cycles on the path per tile.
-__device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, uint32_t ready_in_lds, int lane, float *__restrict__ W,
-                                                           int *__restrict__ ok)
+__device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, uint32_t Y_in_lds, uint32_t ready_in_lds, int lane,
+                                                           float *__restrict__ W, int *__restrict__ ok)
 {
-    CYC_LDS const float *const Tflat = (CYC_LDS const float *)(uintptr_t)T_in_lds;
+    CYC_LDS const float *const T = (CYC_LDS const float *)(uintptr_t)T_in_lds;
+    CYC_LDS float *const Y = (CYC_LDS float *)(uintptr_t)Y_in_lds;              // [16][LDY]
     CYC_LDS int *const ready = (CYC_LDS int *)(uintptr_t)ready_in_lds;
-    // T[r][c], r and c constants after unrolling: one base register and the offset field
-    struct Tile {
-        CYC_LDS const float *base;
-        __device__ __forceinline__ CYC_LDS const float *operator[](int r) const { return base + r * LDT; }
-    };
-    const Tile T{Tflat};
+    // (as a pointer to global memory: through the generic pointer of a function that is not inlined the stores would be
+    // flat instructions, which count as LDS operations too and complete out of order with them, and every wait for
+    // an LDS read below would become a wait for all of them)
+    typedef __attribute__((address_space(1))) f32x4 global_f32x4;
+    global_f32x4 *const out = (global_f32x4 *)W + lane;
+    const int i = lane & 15, g = lane >> 4;
 
     bool expired = false;
     auto gate = [&](int b) __attribute__((always_inline)) {
@@ -349,70 +363,106 @@ __device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, ui
                 expired = true;
                 break;
             }
-            __builtin_amdgcn_s_sleep(2);                      // the factorisation reads LDS on its critical path: poll seldom
+            __builtin_amdgcn_s_sleep(1);
         }
     };
-    float t[NBMAX];                                           // the running right-hand side: column `lane` of the identity
+    auto idx = [](int rb, int cb) __attribute__((always_inline)) { return rb * (rb + 1) / 2 + cb; };
+    f32x4 t[10];                                               // the running right-hand side: the identity to begin with
 #pragma unroll
-    for (int r = 0; r < NBMAX; ++r) t[r] = r == lane ? 1.0f : 0.0f;
-    float colsum_L = 0.0f, colsum_W = 0.0f;
-    // (as a pointer to global memory: through the generic pointer of a function that is not inlined the stores would be
-    // flat instructions, which count as LDS operations too and complete out of order with them, and every wait for
-    // an LDS read below would become a wait for all of them)
-    typedef __attribute__((address_space(1))) float global_float;
-    global_float *out = (global_float *)(W + (lane >> 4) * 256 + (lane & 3) * 64 + ((lane >> 2) & 3));
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+        for (int cb = 0; cb <= rb; ++cb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t[idx(rb, cb)][r] = rb == cb && 4 * g + r == i ? 1.0f : 0.0f;
+    float colsum_L = 0.0f, colsum_W[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     unrolled<NBLK>([&](auto index) __attribute__((always_inline)) {
-        constexpr int k = decltype(index)::value;
+        constexpr int k = decltype(index)::value, R = k / 4, gk = k % 4;
         gate(k);
-        // the block's corner of L_jj, the lane's own column of it (for ||L_jj||_1), and the rows below it, requested
-        // two blocks of rows ahead of their use
-        f32x4 qc[4], q[3][4];
-        float mine[4];
+        // the block's corner of L_jj, the lane's own column of it (for ||L_jj||_1), and the block's columns of the rows
+        // below as stationary operands
+        f32x4 qc[4];
+        float mine[4], xm[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            qc[j] = *(CYC_LDS const f32x4 *)&T[4 * k + j][4 * k];
-            mine[j] = T[4 * k + j][lane];
+            qc[j] = *(CYC_LDS const f32x4 *)&T[(4 * k + j) * LDT + 4 * k];
+            mine[j] = T[(4 * k + j) * LDT + lane];
         }
-        auto request = [&](int b) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) q[(b - k - 1) % 3][j] = *(CYC_LDS const f32x4 *)&T[4 * b + j][4 * k];
-        };
-        if (k + 1 < NBLK) request(k + 1);
-        if (k + 2 < NBLK) request(k + 2);
-        // rows 4k .. 4k+3.  The reciprocals of the diagonal by estimate and one Newton step: W is only ever used as an
-        // approximation whose error the check below bounds, and a multiplication is one instruction on the chain from
-        // row to row where the division is eleven.
-        float xn[4];
+        for (int rb = (gk == 3 ? R + 1 : R); rb < 4; ++rb) xm[rb] = -T[(16 * rb + i) * LDT + 4 * k + g];
+        float rinv[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             colsum_L += 4 * k + j >= lane ? __builtin_fabsf(mine[j]) : 0.0f;
             const float d = qc[j][j], r0 = __builtin_amdgcn_rcpf(d);
-            const float rinv = __builtin_fmaf(__builtin_fmaf(-d, r0, 1.0f), r0, r0);
-#pragma unroll
-            for (int e = 0; e < j; ++e) t[4 * k + j] = __builtin_fmaf(qc[j][e], xn[e], t[4 * k + j]);
-            const float y = t[4 * k + j] * rinv;
-            xn[j] = -y;
-            const int r = 4 * k + j;
-            out[(r >> 4) * 1024 + (r & 15) * 4] = y;
-            colsum_W += __builtin_fabsf(y);
+            rinv[j] = __builtin_fmaf(__builtin_fmaf(-d, r0, 1.0f), r0, r0);
         }
-        // and out of every row below
+        // rows 4k .. 4k+3 of W: in the lanes with l/16 = k%4 the registers of row block R are exactly those rows; the
+        // other lanes compute along on rows that are not ready
+        f32x4 y[4];
 #pragma unroll
-        for (int b = k + 1; b < NBLK; ++b) {
-            if (b + 2 < NBLK) request(b + 2);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int cb = 0; cb <= R; ++cb) {
+            const f32x4 rhs = t[idx(R, cb)];
+            float xn[4];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
+            for (int j = 0; j < 4; ++j) {
+                float v = rhs[j];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) t[4 * b + j] = __builtin_fmaf(q[(b - k - 1) % 3][j][kk], xn[kk], t[4 * b + j]);
-            // (pinned here: the compiler otherwise moves these multiply-adds down to where their sums are next used,
-            // blocks later, and keeps their operands alive in scratch memory until then)
-            asm volatile("" : "+v"(t[4 * b]), "+v"(t[4 * b + 1]), "+v"(t[4 * b + 2]), "+v"(t[4 * b + 3]));
+                for (int e = 0; e < j; ++e) v = __builtin_fmaf(qc[j][e], xn[e], v);
+                y[cb][j] = v * rinv[j];
+                xn[j] = -y[cb][j];
+            }
+        }
+        if (g == gk) {                                         // (one branch per block; the stores differ by constants only)
+#pragma unroll
+            for (int cb = 0; cb <= R; ++cb)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    colsum_W[cb] += __builtin_fabsf(y[cb][j]);
+                    Y[(4 * gk + j) * LDY + 16 * cb + i] = y[cb][j];
+                }
+        }
+        // and out of every row below (of row block R, too: its rows up to 4k+3 are not used again)
+        // (pinned here: the compiler otherwise moves all these additions, with their operands, to the end of the function,
+        // behind the factorisation's last block)
+        asm volatile("" : "+v"(colsum_L), "+v"(colsum_W[0]), "+v"(colsum_W[1]), "+v"(colsum_W[2]), "+v"(colsum_W[3]));
+        constexpr int first_rb = gk == 3 ? R + 1 : R;          // (with its last four rows a row block is finished)
+        if (first_rb < 4) {
+            float yb[4];
+#pragma unroll
+            for (int cb = 0; cb <= R; ++cb) yb[cb] = Y[(4 * gk + g) * LDY + 16 * cb + i];
+#pragma unroll
+            for (int rb = first_rb; rb < 4; ++rb)
+#pragma unroll
+                for (int cb = 0; cb <= R; ++cb) t[idx(rb, cb)] = __builtin_amdgcn_mfma_f32_16x16x4f32(xm[rb], yb[cb], t[idx(rb, cb)], 0, 0, 0);
+        }
+        if (gk == 3) {
+            // rows 16 R .. 16 R + 15 are complete: piece (R, cb) in the order in which the product wants its operand,
+            // lane l: W[16 R + l%16][16 cb + 4 q + l/16], q = 0 .. 3
+#pragma unroll
+            for (int cb = 0; cb <= R; ++cb) {
+                f32x4 piece;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) piece[q] = Y[i * LDY + 16 * cb + 4 * q + g];
+                out[(4 * R + cb) * 64] = piece;
+            }
         }
     });
-    const float a = wave_max64(colsum_L), c = wave_max64(colsum_W);
+    // ||W||_1: the column sums lie in four parts, one per l/16: add the lanes 16, 32 and 48 apart
+    float colsum = 0.0f;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const unsigned u = __builtin_bit_cast(unsigned, colsum_W[cb]);
+        const auto h = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+        const unsigned h0 = h[0], h1 = h[1];
+        const unsigned m = __builtin_bit_cast(unsigned, __builtin_bit_cast(float, h0) + __builtin_bit_cast(float, h1));
+        const auto f = __builtin_amdgcn_permlane32_swap(m, m, false, false);
+        const unsigned f0 = f[0], f1 = f[1];
+        const float sum = __builtin_bit_cast(float, f0) + __builtin_bit_cast(float, f1);
+        colsum = sum > colsum || sum != sum ? sum : colsum;                    // (keeps a NaN)
+    }
+    const float a = wave_max64(colsum_L), c = wave_max64(colsum);
     // (a NaN anywhere would be dropped by the maxima: every lane checks its own sums)
-    const bool fine = colsum_L == colsum_L && colsum_W == colsum_W && a * c <= W_NORM_LIMIT && !expired;
+    const bool fine = colsum_L == colsum_L && colsum == colsum && a * c <= W_NORM_LIMIT && !expired;
     const bool all_fine = __builtin_amdgcn_ballot_w64(!fine) == 0;
     if (lane == 0) *ok = all_fine ? 1 : 0;
 }
@@ -487,15 +537,17 @@ __device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, u
 // The factorisation proper of a diagonal tile whose S (with everything left of it taken out) is in T: the column
 // recurrence by the first wave with the second wave's help (trailing_update64), then L, and Lh in both triangles,
 // written out by all.  See diag_tile.
-// F: the hand-over buffer; sync: three counters in LDS, zero on entry (with a barrier since): see trailing_update64.
+// dl: what the waves pass to one another; its counters zero on entry (with a barrier since).
 // W, ok: where the tile's inverse and its verdict go, or nullptr (then, and for tiles of fewer than 64 columns, none
 // is computed).
 // beside(t): called in the full-tile case by the threads 128 .. 191 (t = 0 .. 63), which otherwise only wait, while
 // the tile is being factored.
 template <class Beside>
-__device__ __forceinline__ void diag_rest(float (*T)[LDT], float (*F)[LDF], float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r,
-                                          int *sync, float *W, int *ok, Beside beside)
+__device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r,
+                                          float *W, int *ok, Beside beside)
 {
+    float(*const F)[LDF] = dl.F;
+    int *const sync = dl.sync;
     const bool live = r < cols;
     bool mirrored = false;
     if (cols == NBMAX) {
@@ -590,7 +642,8 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float (*F)[LDF], floa
         } else if (r >= 128) {
             beside(r - 128);
         } else if (W) {
-            inverse_follow64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 64, W, ok);
+            inverse_follow64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS float *)&dl.Y[0][0],
+                             (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 64, W, ok);
         }
         mirrored = true;
         __syncthreads();
@@ -631,15 +684,15 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], float (*F)[LDF], floa
 // move and update the tile.  T (first 64 KB of LDS: a read reaches its word with the 16-bit offset field from one
 // base register; further up every read needs an address register of its own) and Bs are the workgroup's LDS.
 __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], const float *Sm, float *L, uint16_t *Lh, int64_t n,
-                                          int64_t j0, int cols, int64_t k0, int r, float (*F)[LDF], int *sync, float *W, int *ok)
+                                          int64_t j0, int cols, int64_t k0, int r, DiagLds &dl, float *W, int *ok)
 {
-    if (r < 3) sync[r] = 0;               // (a barrier follows below, before anyone looks at them)
+    if (r < 3) dl.sync[r] = 0;            // (a barrier follows below, before anyone looks at them)
     TileProduct product;
     if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     if (k0 < j0) product.apply(T, Bs, r);
     else __syncthreads();
-    diag_rest(T, F, L, Lh, n, j0, cols, r, sync, W, ok, [](int) {});
+    diag_rest(T, dl, L, Lh, n, j0, cols, r, W, ok, [](int) {});
 }
 
 __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
@@ -648,10 +701,9 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
     __shared__ __attribute__((aligned(16))) struct {
         float T[NBMAX][LDT];          // S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
-        float F[NBMAX][LDF];          // a group of 16 columns on its way from the second wave to the first
-        int sync[3];                  // blocks of four columns finished; groups handed over; a wait ran out (see trailing_update64)
+        DiagLds dl;                   // between the waves of the factorisation
     } lds;
-    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, lds.F, lds.sync, W, ok);
+    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, lds.dl, W, ok);
 }
 
 // L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane of the first wave; the
@@ -678,15 +730,14 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
         float X[64][LDT];             // this workgroup's rows: S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
         uint16_t Bs2[KMAX][64];       // streamed operand of the next diagonal tile's update
-        float F[NBMAX][LDF];          // the next diagonal tile: a group of 16 columns between its two waves (see diag_rest)
-        int sync[3];                  // the next diagonal tile's counters (see trailing_update64)
+        DiagLds dl;                   // the next diagonal tile: between the waves of its factorisation (see diag_rest)
     } lds;
     auto &D = lds.D;
     auto &X = lds.X;
     auto &Bs = lds.Bs;
     auto &Bs2 = lds.Bs2;
     const int tid = threadIdx.x, lane = tid & 63;
-    if (tid < 3) lds.sync[tid] = 0;
+    if (tid < 3) lds.dl.sync[tid] = 0;
     const bool solver = tid < 64;                         // the wave that runs the recurrence
     // The rows of this workgroup through the inverse of L_jj?  W and its verdict are requested here with everything
     // else the kernel needs from memory; the verdict is looked at only where the rows are formed, so that nothing
@@ -968,7 +1019,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
             }
         __syncthreads();
-        diag_rest(D, lds.F, L, Lh, n, j1, NBMAX, tid, lds.sync, Wout, okout, [&](int t) __attribute__((always_inline)) {
+        diag_rest(D, lds.dl, L, Lh, n, j1, NBMAX, tid, Wout, okout, [&](int t) __attribute__((always_inline)) {
             // this workgroup's own rows, deferred above
             store_tile<false, 64>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
             if (by_inverse) store_mirror<64>(X, Lh + j0 * n + first, n, t);

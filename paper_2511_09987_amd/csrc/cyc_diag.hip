@@ -152,6 +152,24 @@ hipError_t launch_issue_mix(int per_round, dim3 grid, dim3 block, hipStream_t s,
     }
 }
 
+// D = A B + C, 16 x 16 x 4 per tile, one v_mfma_f32_16x16x4_f32 each.  A: tiles x 16 x 4 (row, k), B: tiles x 4 x 16
+// (k, column), C and D: tiles x 16 x 16, all row-major.  Operand lane l: row (column) l%16, k = l/16; accumulator
+// register r of lane l: row 4 (l/16) + r, column l%16.
+__global__ __launch_bounds__(64) void mfma_f32_tiles_kernel(const float *__restrict__ A, const float *__restrict__ B,
+                                                            const float *__restrict__ C, float *__restrict__ D, int64_t tiles)
+{
+    const int l = threadIdx.x;
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const float a = A[t * 64 + (l % 16) * 4 + l / 16], b = B[t * 64 + (l / 16) * 16 + l % 16];
+        f32x4 c;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) c[r] = C[t * 256 + (4 * (l / 16) + r) * 16 + l % 16];
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) D[t * 256 + (4 * (l / 16) + r) * 16 + l % 16] = c[r];
+    }
+}
+
 __global__ __launch_bounds__(64) void clock_kernel(uint64_t *out, int64_t ticks)
 {
     const uint64_t w0 = wall_clock64(), c0 = clock64();
@@ -223,6 +241,18 @@ int cyc_diag_issue_mix(int mfma_shape, int other_kind, int others_per_round, int
         e = other_kind == 0   ? cyc::launch_issue_mix<32, 0>(others_per_round, grid, block, s, (int *)sink, (int)iters)
             : other_kind == 1 ? cyc::launch_issue_mix<32, 1>(others_per_round, grid, block, s, (int *)sink, (int)iters)
                               : cyc::launch_issue_mix<32, 2>(others_per_round, grid, block, s, (int *)sink, (int)iters);
+    return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
+}
+
+int cyc_diag_mfma_f32_tiles(const void *A, const void *B, const void *C, void *D, int64_t tiles, void *stream)
+{
+    if (tiles < 0 || tiles > (1 << 24)) return CYC_ERR_SHAPE;
+    if (tiles == 0) return CYC_OK;
+    if (!A || !B || !C || !D) return CYC_ERR_NULL;
+    if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C | (uintptr_t)D) & 3) return CYC_ERR_SHAPE;
+    const unsigned blocks = (unsigned)(tiles < 4096 ? tiles : 4096);
+    const hipError_t e = cyc::launch_kernel(cyc::mfma_f32_tiles_kernel, dim3(blocks), dim3(64), (hipStream_t)stream, (const float *)A,
+                                            (const float *)B, (const float *)C, (float *)D, tiles);
     return e == hipSuccess ? CYC_OK : CYC_ERR_LAUNCH;
 }
 

@@ -127,6 +127,10 @@ def test_diagnostic_entry_points_validate_on_the_host(pkg):
     assert pkg.cyc_diag_issue_mix(16, 0, 32, 3, 100, 0x1000)[0] == 2       # one or two waves per SIMD
     assert pkg.cyc_diag_issue_mix(16, 0, 32, 1, 0, 0x1000)[0] == 2         # no rounds
     assert pkg.cyc_diag_issue_mix(16, 0, 32, 1, 100, 0)[0] == 1            # NULL sink
+    assert pkg.cyc_diag_mfma_f32_tiles(0x1000, 0x2000, 0x3000, 0x4000, -1) == 2   # negative count
+    assert pkg.cyc_diag_mfma_f32_tiles(0x1000, 0x2000, 0x3000, 0, 4) == 1         # NULL result
+    assert pkg.cyc_diag_mfma_f32_tiles(0x1000, 0x2002, 0x3000, 0x4000, 4) == 2    # misaligned
+    assert pkg.cyc_diag_mfma_f32_tiles(0, 0, 0, 0, 0) == 0                        # nothing to do
     assert pkg.cyc_diag_clock(0, 100) == 1
     assert pkg.cyc_diag_clock(0x1000, 0) == 2
     assert pkg.cyc_diag_clock(0x1004, 100) == 2                           # misaligned

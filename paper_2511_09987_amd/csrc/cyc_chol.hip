@@ -223,14 +223,26 @@ constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multi
 // once.  Rows past `nrows` repeat the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and
 // k1 - k0 a multiple of 64, at most KMAX.
 // In two parts, so that a kernel can ask for the operands first, then for its tile, and wait for memory once.
+// An MFMA operand fragment of k-step ks out of a staged operand ([k][64 columns] in LDS), through the transposing
+// read: lane l gets column 16 c + l%16, k = 32 ks + 8 (l/16) .. +7.  As a streamed fragment that is column block c; where
+// the staged operand is the mirror image of rows of Lh, the same words are the stationary fragment of row block c.
+__device__ __forceinline__ i32x4 staged_fragment(uint16_t (*src)[64], int ks, int c, int lq, int g)
+{
+    CYC_LDS char *p = (CYC_LDS char *)&src[ks * 32 + 8 * g + (lq >> 2)][c * 16 + 4 * (lq & 3)];
+    const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
+    const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
+    return (i32x4){lo[0], lo[1], hi[0], hi[1]};
+}
+
 struct TileProduct {
     static constexpr int NKS = KMAX / 32;
     i32x4 a[NKS];
     int nks;
 
     // start the copies of both operands; nothing is waited for
+    // rows_in_lds: the tile's own rows of Lh will be at hand in LDS as their mirror image (see apply): none are loaded
     __device__ __forceinline__ void request(uint16_t (*Bs)[64], const uint16_t *__restrict__ Lh, int64_t n, int64_t row0, int nrows,
-                                            int64_t k0, int64_t k1, int64_t j0, int tid)
+                                            int64_t k0, int64_t k1, int64_t j0, int tid, bool rows_in_lds = false)
     {
         const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4, K = (int)(k1 - k0);
         nks = K / 32;
@@ -245,6 +257,7 @@ struct TileProduct {
                          : "memory", "m0");
         }
         // the stationary operand: row 16 w + lq of the tile, k = 32 ks + 8 g .. +7
+        if (rows_in_lds) return;                                           // uniform
         const int r = 16 * w + lq;
         const uint16_t *rowp = Lh + (row0 + (r < nrows ? r : nrows - 1)) * n + k0 + 8 * g;
 #pragma unroll
@@ -253,7 +266,9 @@ struct TileProduct {
     }
 
     // S -= product; call with the tile S in place in LDS and no barrier needed before: waits for the copies itself
-    __device__ __forceinline__ void apply(float (*S)[LDT], uint16_t (*Bs)[64], int tid)
+    // As: nullptr, or Lh[k0:k1, row0:row0+64] in LDS, the mirror image of the tile's own rows (request with rows_in_lds):
+    // the stationary fragment of rows 16 w .. is then read like a streamed fragment of column block w
+    __device__ __forceinline__ void apply(float (*S)[LDT], uint16_t (*Bs)[64], int tid, uint16_t (*As)[64] = nullptr)
     {
         const int lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -261,9 +276,31 @@ struct TileProduct {
         f32x4 acc[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
+        if (As) {
+            // every fragment from LDS: a loop that reads the fragments of the next k-step before it multiplies the
+            // current ones (unrolled with a condition per step, as below, each step would wait for its own reads)
+            i32x4 f[2][5];                                                       // [parity of the k-step]: stationary, streamed x 4
+            auto read_step = [&](int ks, i32x4(&dst)[5]) __attribute__((always_inline)) {
+                dst[0] = staged_fragment(As, ks, w, lq, g);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) dst[1 + j] = staged_fragment(Bs, ks, j, lq, g);
+            };
+            auto multiply = [&](const i32x4(&src)[5]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[0]), __builtin_bit_cast(bf16x8, src[1 + j]), acc[j], 0, 0, 0);
+            };
+            read_step(0, f[0]);                                                  // (nks is even and at least 2)
+            for (int ks = 0; ks < nks; ks += 2) {
+                read_step(ks + 1, f[1]);
+                multiply(f[0]);
+                if (ks + 2 < nks) read_step(ks + 2, f[0]);
+                multiply(f[1]);
+            }
+        }
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) {
-            if (ks < nks) {                                                      // uniform over the workgroup
+            if (!As && ks < nks) {                                               // uniform over the workgroup
                 i32x4 b[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -764,7 +801,6 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     const int nks_e = fused ? (int)(j0 - k0) / 32 : 0;                 // k-steps of that tile's update that do not involve this panel
     constexpr int NKS = KMAX / 32;
     f32x4 sv[4], accn[2][4];                                           // its S (this thread's pieces); its update: [slot][column tile]
-    i32x4 an[2][NKS];                                                  // stationary operand of the update's early k-steps
     // The four 16-row strips of that update: slot si of this wave holds strip(si), or nothing (-1).  Beside the recurrence
     // the three other waves share them (wave 1 takes two).  When the rows may come through the inverse the first wave
     // is free as a rule and every wave takes one strip; should the verdict then be bad after all, the first wave takes
@@ -789,45 +825,26 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
 #pragma unroll
         for (int i = 0; i < 4; ++i) sv[i] = *(const f32x4 *)(next_Sm + (j1 + 16 * i + (tid >> 4)) * n + j1 + 4 * (tid & 15));
         if (nks_e > 0) {
+            // (only the streamed operand, Lh[k0:j0, j1:j1+64]: the stationary one, the rows j1 .. j1+63 of Lh over the same k,
+            // is its mirror image, and the transposing read that makes a streamed fragment of column block c makes the
+            // stationary fragment of row block c out of the same words)
             copy_rows(k0, 0, 32 * nks_e, w, NT / 64);
-#pragma unroll
-            for (int si = 0; si < 2; ++si)
-                if (strip(si) >= 0) {
-                    const uint16_t *rowp = Lh + (j1 + 16 * strip(si) + lq) * n + k0 + 8 * g;
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks)
-                        if (ks < nks_e) an[si][ks] = *(const i32x4 *)(rowp + 32 * ks);
-                }
         }
     }
     TileProduct product;
-    if (k0 < j0) product.request(Bs, Lh, n, first, nrows, k0, j0, j0, tid);
+    // (the workgroup that goes on to the next diagonal tile finds its own rows of Lh over k0 .. j0 in Bs2, mirrored: what
+    // is left to fetch are whole rows, and nothing on the path waits for a load of 64 separate cache lines)
+    const bool rows_in_lds = fused && nks_e > 0;
+    if (k0 < j0) product.request(Bs, Lh, n, first, nrows, k0, j0, j0, tid, rows_in_lds);
     TileLoad of_D, of_X;
     of_D.request(L + j0 * n + j0, n, cols, cols, tid);
     of_X.request(Sm + first * n + j0, n, nrows, cols, tid);
     of_D.place(D, L + j0 * n + j0, n, cols, cols, tid);
     of_X.place(X, Sm + first * n + j0, n, nrows, cols, tid);
     // (nks_e > 0 implies k0 < j0: apply waits for every copy of this wave, Bs2's included, before its barrier)
-    if (k0 < j0) product.apply(X, Bs, tid);
+    if (k0 < j0) product.apply(X, Bs, tid, rows_in_lds ? Bs2 : nullptr);
     else __syncthreads();
     const bool by_inverse = may_invert && __builtin_amdgcn_readfirstlane(verdict) != 0;
-    auto k_step = [&](int ks, const i32x4(&a2)[2]) __attribute__((always_inline)) {        // one MFMA k-step of 32, Bs2 rows 32 ks ..
-        i32x4 b[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            CYC_LDS char *p = (CYC_LDS char *)&Bs2[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
-            const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
-            const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
-            b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
-        }
-#pragma unroll
-        for (int si = 0; si < 2; ++si)
-            if (strip(si) >= 0) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a2[si]), __builtin_bit_cast(bf16x8, b[j]), accn[si][j], 0, 0, 0);
-            }
-    };
 #pragma unroll
     for (int si = 0; si < 2; ++si)
 #pragma unroll
@@ -947,12 +964,32 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             // beside the recurrence, or by all four after their share of the product when the rows came through the
             // inverse.  (Their operands have arrived: requested first thing and waited for before the barrier that
             // precedes the update of this workgroup's own tile.)
+            // Both operands out of Bs2 (see above); the fragments of the next k-step are read before the current ones are
+            // multiplied.  (nks_e is even.)
+            const int s0 = strip(0), s1 = strip(1);
+            i32x4 f[2][6];                                                       // [parity]: stationary of slot 0 and 1, streamed x 4
+            auto read_step = [&](int ks, i32x4(&dst)[6]) __attribute__((always_inline)) {
+                if (s0 >= 0) dst[0] = staged_fragment(Bs2, ks, s0, lq, g);
+                if (s1 >= 0) dst[1] = staged_fragment(Bs2, ks, s1, lq, g);
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks)
-                if (ks < nks_e) {
-                    const i32x4 a2[2] = {an[0][ks], an[1][ks]};
-                    k_step(ks, a2);
-                }
+                for (int j = 0; j < 4; ++j) dst[2 + j] = staged_fragment(Bs2, ks, j, lq, g);
+            };
+            auto multiply = [&](const i32x4(&src)[6]) __attribute__((always_inline)) {
+#pragma unroll
+                for (int si = 0; si < 2; ++si)
+                    if ((si == 0 ? s0 : s1) >= 0) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[si]), __builtin_bit_cast(bf16x8, src[2 + j]), accn[si][j], 0, 0, 0);
+                    }
+            };
+            read_step(0, f[0]);
+            for (int ks = 0; ks < nks_e; ks += 2) {
+                read_step(ks + 1, f[1]);
+                multiply(f[0]);
+                if (ks + 2 < nks_e) read_step(ks + 2, f[0]);
+                multiply(f[1]);
+            }
         }
         mirrored = !by_inverse;                            // (the recurrence writes the mirror image from its registers)
     } else if (solver) {

@@ -221,7 +221,7 @@ constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multi
 // Lh[k0:k1, j0:j0+64], is staged in LDS ([k][column], 128 bytes per row) and read through the transpose read; the
 // stationary operand, the tile's own rows of Lh, goes from memory straight into operand registers, all k-steps at
 // once.  Rows past `nrows` repeat the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and
-// k1 - k0 a multiple of 64, at most KMAX.
+// k1 - k0 a multiple of 64, at most KM.
 // In two parts, so that a kernel can ask for the operands first, then for its tile, and wait for memory once.
 // An MFMA operand fragment of k-step ks out of a staged operand ([k][64 columns] in LDS), through the transposing
 // read: lane l gets column 16 c + l%16, k = 32 ks + 8 (l/16) .. +7.  As a streamed fragment that is column block c; where
@@ -234,8 +234,9 @@ __device__ __forceinline__ i32x4 staged_fragment(uint16_t (*src)[64], int ks, in
     return (i32x4){lo[0], lo[1], hi[0], hi[1]};
 }
 
-struct TileProduct {
-    static constexpr int NKS = KMAX / 32;
+template <int KM>
+struct TileProductT {
+    static constexpr int NKS = KM / 32;
     i32x4 a[NKS];
     int nks;
 
@@ -322,6 +323,8 @@ struct TileProduct {
         __syncthreads();
     }
 };
+
+typedef TileProductT<KMAX> TileProduct;
 
 // ---- The inverse of a diagonal tile, computed beside its factorisation.
 // L_ij = TRSM(S_ij, L_jj) for the tile right below the diagonal tile is on the path from one diagonal tile to the
@@ -581,7 +584,7 @@ __device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, u
 // the tile is being factored.
 template <class Beside>
 __device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r,
-                                          float *W, int *ok, Beside beside)
+                                          float *W, int *ok, Beside beside, float *copy = nullptr)
 {
     float(*const F)[LDF] = dl.F;
     int *const sync = dl.sync;
@@ -707,6 +710,14 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L
     if (live && !mirrored)
         for (int c = r + 1; c < cols; ++c) T[r][c] = T[c][r];
     __syncthreads();
+    if (copy) {
+        // a second copy of the tile as it stands in LDS, rows of 64 floats (see chol_panel_kernel, Dcopy)
+#pragma unroll
+        for (int i = 0; i < NBMAX * 16 / NT; ++i) {
+            const int row = NT / 16 * i + (r >> 4);
+            *(f32x4 *)(copy + row * NBMAX + 4 * (r & 15)) = *(const f32x4 *)&T[row][4 * (r & 15)];
+        }
+    }
     if (store_tile<true>(T, L + j0 * n + j0, Lh + j0 * n + j0, n, cols, cols, r)) return;
     if (live)
         for (int c = 0; c < cols; ++c) {
@@ -724,10 +735,12 @@ __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], c
                                           int64_t j0, int cols, int64_t k0, int r, DiagLds &dl, float *W, int *ok)
 {
     if (r < 3) dl.sync[r] = 0;            // (a barrier follows below, before anyone looks at them)
+    // (both operands of the tile's own update are the rows j0 .. of Lh: the staged one, Lh[k0:j0, j0:j0+64], is their
+    // mirror image, and the stationary fragments are read from it as well)
     TileProduct product;
-    if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r);     // k0 < j0 only for full tiles, see launch_chol
+    if (k0 < j0) product.request(Bs, Lh, n, j0, cols, k0, j0, j0, r, true);     // k0 < j0 only for full tiles, see launch_chol
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
-    if (k0 < j0) product.apply(T, Bs, r);
+    if (k0 < j0) product.apply(T, Bs, r, Bs);
     else __syncthreads();
     diag_rest(T, dl, L, Lh, n, j0, cols, r, W, ok, [](int) {});
 }
@@ -759,7 +772,8 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 // recurrence.  Wout, okout: where the inverse of the next diagonal tile and its verdict go when that tile rides along.
 __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
                                                         int64_t k0, const float *next_Sm, const float *__restrict__ Win,
-                                                        const int *__restrict__ okin, float *Wout, int *okout)
+                                                        const int *__restrict__ okin, float *Wout, int *okout, const float *Dcopy,
+                                                        float *next_copy)
 {
     // one block, D and X first (see diag_tile)
     __shared__ __attribute__((aligned(16))) struct {
@@ -837,13 +851,18 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     const bool rows_in_lds = fused && nks_e > 0;
     if (k0 < j0) product.request(Bs, Lh, n, first, nrows, k0, j0, j0, tid, rows_in_lds);
     TileLoad of_D, of_X;
-    of_D.request(L + j0 * n + j0, n, cols, cols, tid);
+    // (Dcopy: L_jj is read from there, rows of 64 floats, because a product launched since it was factored has written over
+    // its place in L, which the last workgroup restores)
+    const float *Dsrc = Dcopy ? Dcopy : L + j0 * n + j0;
+    const int64_t ldD = Dcopy ? NBMAX : n;
+    of_D.request(Dsrc, ldD, cols, cols, tid);
     of_X.request(Sm + first * n + j0, n, nrows, cols, tid);
-    of_D.place(D, L + j0 * n + j0, n, cols, cols, tid);
+    of_D.place(D, Dsrc, ldD, cols, cols, tid);
     of_X.place(X, Sm + first * n + j0, n, nrows, cols, tid);
     // (nks_e > 0 implies k0 < j0: apply waits for every copy of this wave, Bs2's included, before its barrier)
     if (k0 < j0) product.apply(X, Bs, tid, rows_in_lds ? Bs2 : nullptr);
     else __syncthreads();
+    if (Dcopy && blockIdx.x == gridDim.x - 1) (void)store_tile<true>(D, L + j0 * n + j0, Lh + j0 * n + j0, n, cols, cols, tid);
     const bool by_inverse = may_invert && __builtin_amdgcn_readfirstlane(verdict) != 0;
 #pragma unroll
     for (int si = 0; si < 2; ++si)
@@ -1060,7 +1079,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             // this workgroup's own rows, deferred above
             store_tile<false, 64>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
             if (by_inverse) store_mirror<64>(X, Lh + j0 * n + first, n, t);
-        });
+        }, next_copy);
     }
 }
 
@@ -1069,7 +1088,8 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
 int64_t chol_workspace_bytes(int64_t n, int64_t nb)
 {
     // one inverse and one verdict per full diagonal tile of 64 (see inverse_follow64)
-    return nb == NBMAX && n >= 2 * NBMAX ? (n / NBMAX) * (int64_t)(W_FLOATS * sizeof(float) + sizeof(int)) : 0;
+    // and one tile of 64 x 64 floats (see launch_chol: the first diagonal tile of a group)
+    return nb == NBMAX && n >= 2 * NBMAX ? (n / NBMAX) * (int64_t)(W_FLOATS * sizeof(float) + sizeof(int)) + 16 + NBMAX * NBMAX * (int64_t)sizeof(float) : 0;
 }
 
 hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t nb, void *workspace, hipStream_t s)
@@ -1083,6 +1103,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
     int *okall = Wall ? (int *)(Wall + (n / NBMAX) * W_FLOATS) : nullptr;
     auto W_of = [&](int64_t j, int c) { return Wall && c == NBMAX ? Wall + j / NBMAX * W_FLOATS : (float *)nullptr; };
     auto ok_of = [&](int64_t j, int c) { return Wall && c == NBMAX ? okall + j / NBMAX : (int *)nullptr; };
+    float *tile_copy = Wall ? (float *)(((uintptr_t)(okall + n / NBMAX) + 15) & ~(uintptr_t)15) : nullptr;
     // One product per panel would have only nb columns and all earlier tiles as its k range: a few workgroups
     // walking a long k loop.  So the panels are taken in groups of GROUP: at the first panel of a group one product
     // covers the columns of the whole group against all tiles left of the group; the later panels of the group
@@ -1108,6 +1129,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
         return tile ? launch_mfma(p, tile, 16, on) : launch_generic(p, on);
     };
     bool diag_done = false;           // the diagonal tile of this panel was factored by the rows kernel of the panel before
+    bool copied = false;              // ... across a group boundary: L_jj is to be read from the copy in the workspace
     // the side stream is worth its events only when there are at least three groups
     SideStreamLock side_lock;
     SideStream *side = n > 2 * GROUP * nb ? side_lock.acquire() : nullptr;
@@ -1128,8 +1150,12 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             if (ahead == g0) {
                 // the part over the groups before the last was multiplied out on the side stream while the last group
                 // was being factored; what is left is the k range of that group
-                if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return fail(e);
-                unjoined = false;
+                if (unjoined) {
+                    if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return fail(e);
+                    unjoined = false;
+                }
+                // (when the group's first diagonal tile rode along with the last panel, this product writes over its place
+                // in L: a copy of the tile is kept in the workspace, see below)
                 if (hipError_t e = product(g0, g0, gcols, g0 - GROUP * nb, g0, L, s); e != hipSuccess) return fail(e);
             } else {
                 if (hipError_t e = product(g0, g0, gcols, 0, g0, A, s); e != hipSuccess) return fail(e);
@@ -1170,14 +1196,23 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
         if (j1 < n) {
             // the next diagonal tile rides along when it is a full tile of the same group whose whole update the tile
             // kernels do themselves: its k range [g0, j1) then starts where this panel's starts
-            const bool fuse = k0 == g0 && nb == NBMAX && cols == NBMAX && j1 + NBMAX <= n && j1 < g0 + GROUP * nb &&
+            // (the first diagonal tile of the next group, too, once that group's product over everything left of this
+            // group is in: the tile's remaining k range is this group, which is what the rows kernel has at hand)
+            const bool next_group = j1 == g0 + GROUP * nb && ahead == j1 && tile_copy != nullptr && j1 + NBMAX < n;
+            const bool fuse = k0 == g0 && nb == NBMAX && cols == NBMAX && j1 + NBMAX <= n && (j1 < g0 + GROUP * nb || next_group) &&
                               n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)L % 16 == 0 &&
-                              j1 - g0 <= KMAX;
+                              j0 - g0 <= KMAX;
+            if (fuse && next_group && unjoined) {
+                if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return fail(e);
+                unjoined = false;
+            }
             hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
-                               fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
-                               (const int *)ok_of(j0, cols), fuse ? W_of(j1, NBMAX) : (float *)nullptr, fuse ? ok_of(j1, NBMAX) : (int *)nullptr);
+                               fuse ? (g0 > 0 || next_group ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
+                               (const int *)ok_of(j0, cols), fuse ? W_of(j1, NBMAX) : (float *)nullptr, fuse ? ok_of(j1, NBMAX) : (int *)nullptr,
+                               copied ? (const float *)tile_copy : (const float *)nullptr, fuse && next_group ? tile_copy : (float *)nullptr);
             if (e != hipSuccess) return fail(e);
             diag_done = fuse;
+            copied = fuse && next_group;
         }
     }
     // the products wrote S above the diagonal too (a group's columns start at the group's first row)

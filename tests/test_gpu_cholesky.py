@@ -82,9 +82,12 @@ def check_structure(L, Lh):
 
 SHAPES = [(64, 64), (128, 64), (256, 64), (1000, 64), (1024, 64), (520, 32), (264, 8), (37, 8), (130, 16), (100, 10),
           (1, 64), (63, 64), (65, 64), (200, 7), (192, 48),
-          # the next diagonal tile in the rows kernel: across a group boundary (9 tiles), two boundaries and a ragged
+          # the next diagonal tile in the rows kernel: up to a group boundary (9 tiles), two boundaries and a ragged
           # last tile (1096 = 17 x 64 + 8), and rows of Lh that are not 16-byte aligned (900: no fused path at all)
-          (576, 64), (1096, 64), (900, 64)]
+          (576, 64), (1096, 64), (900, 64),
+          # three groups and more: the first diagonal tile of the third and fourth group rides along with the last panel
+          # of the group before, and the group's product then writes over its place in L (restored from a copy)
+          (1664, 64)]
 
 
 @pytest.mark.parametrize("n,nb", SHAPES)

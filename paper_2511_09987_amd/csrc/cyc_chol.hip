@@ -1197,8 +1197,9 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             // the next diagonal tile rides along when it is a full tile of the same group whose whole update the tile
             // kernels do themselves: its k range [g0, j1) then starts where this panel's starts
             // (the first diagonal tile of the next group, too, once that group's product over everything left of this
-            // group is in: the tile's remaining k range is this group, which is what the rows kernel has at hand)
-            const bool next_group = j1 == g0 + GROUP * nb && ahead == j1 && tile_copy != nullptr && j1 + NBMAX < n;
+            // group is in, or when nothing lies left of this group: the tile's remaining k range is this group, which is
+            // what the rows kernel has at hand)
+            const bool next_group = j1 == g0 + GROUP * nb && (ahead == j1 || g0 == 0) && tile_copy != nullptr && j1 + NBMAX < n;
             const bool fuse = k0 == g0 && nb == NBMAX && cols == NBMAX && j1 + NBMAX <= n && (j1 < g0 + GROUP * nb || next_group) &&
                               n % 8 == 0 && (uintptr_t)Lh % 16 == 0 && (uintptr_t)A % 16 == 0 && (uintptr_t)L % 16 == 0 &&
                               j0 - g0 <= KMAX;
@@ -1207,7 +1208,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
                 unjoined = false;
             }
             hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
-                               fuse ? (g0 > 0 || next_group ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
+                               fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
                                (const int *)ok_of(j0, cols), fuse ? W_of(j1, NBMAX) : (float *)nullptr, fuse ? ok_of(j1, NBMAX) : (int *)nullptr,
                                copied ? (const float *)tile_copy : (const float *)nullptr, fuse && next_group ? tile_copy : (float *)nullptr);
             if (e != hipSuccess) return fail(e);

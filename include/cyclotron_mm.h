@@ -185,8 +185,8 @@ int cyc_recurrence_trsm(const void *L, const void *B, void *X, void *Xh,
  * nb: tile size, 1 <= nb <= 64.  The MFMA kernels serve the updates when n and nb are multiples of 8 and the
  *     pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
  * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns.  With nb == 64 and
- *     n >= 128 it keeps the inverses of the diagonal tiles (16 KiB per 64 rows) in the workspace that the library
- *     holds per device and stream (allocated or grown on the call that first needs it); otherwise it allocates no
+ *     n >= 128 it keeps the inverses of the diagonal tiles (16 KiB per 64 rows) and a copy of one diagonal tile (16 KiB)
+ *     in the workspace that the library holds per device and stream (allocated or grown on the call that first needs it); otherwise it allocates no
  *     device memory.  For n > 16 nb part of the work is enqueued on a second stream that the library creates per device
  *     on first use (default priority, kept until the process ends) and that is forked from and joined back into
  *     `stream` with events inside the call: all of the call's work is ordered after what was on `stream` before

@@ -20,13 +20,18 @@
 //      L, of Lh, and the mirrored column of Lh.
 //   Both tile kernels are workgroups of four waves: all four move the tile and first take the terms of the group's
 //   own earlier panels out of it with MFMAs of their own (TileProduct), which is far cheaper than a launch of the
-//   GEMM kernel for so short a k range; the first wave then runs the recurrence.  Within a group, step 2 for panel
-//   j + 1 is done by the first workgroup of step 3 for panel j (the rows that become tile (j+1, j)), in the same
-//   launch: the chain diagonal tile - tile below it - next diagonal tile is what the whole factorisation waits for.
-//   On that chain the TRSM of the tile below a well-conditioned diagonal tile is a product with the diagonal tile's
-//   inverse, which a second wave computes beside the factorisation of the tile (inverse_follow64).
+//   GEMM kernel for so short a k range; the first wave then runs the recurrence.  Step 2 for panel j + 1 is done by
+//   the first workgroup of step 3 for panel j (the rows that become tile (j+1, j)), in the same launch, also across
+//   a group boundary: the chain diagonal tile - tile below it - next diagonal tile is what the whole factorisation
+//   waits for.  On that chain
+//   - the diagonal tile's recurrence is shared by two waves: the first keeps the corners (square roots, divisions)
+//     and the multiply-adds next to them, the second takes every finished block of four columns out of the columns
+//     further right on the matrix cores (trailing_update64);
+//   - the TRSM of the tile below a well-conditioned diagonal tile is a product with the diagonal tile's inverse,
+//     which a third wave computes beside the factorisation of the tile (inverse_follow64).
 // Inside a tile column everything is fp32 on unrounded values, in the order of the scalar recurrence:
-// t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.
+// t = S_rc; t = fma(-L_rk, L_ck, t) for k ascending; then sqrt on the diagonal, IEEE division below it.  Four such steps
+// are one v_mfma_f32_16x16x4_f32: that instruction adds its products in ascending k with one rounding each.
 #include "cyc_internal.h"
 #include "cyc_wave.h"
 

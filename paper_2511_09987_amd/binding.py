@@ -52,6 +52,8 @@ def _load() -> ctypes.CDLL:
     lib.cyc_diag_issue_mix.restype = cint
     lib.cyc_diag_mfma_f32_tiles.argtypes = [ptr, ptr, ptr, ptr, i64, ptr]
     lib.cyc_diag_mfma_f32_tiles.restype = cint
+    lib.cyc_diag_set_wait_limit.argtypes = [i64]
+    lib.cyc_diag_set_wait_limit.restype = cint
     lib.cyc_diag_clock.argtypes = [ptr, i64, ptr]
     lib.cyc_diag_clock.restype = cint
     return lib
@@ -136,6 +138,10 @@ def cyc_diag_issue_mix(mfma_shape: int, other_kind: int, others_per_round: int, 
 
 def cyc_diag_mfma_f32_tiles(A: int, B: int, C: int, D: int, tiles: int, stream: int = 0) -> int:
     return int(_lib().cyc_diag_mfma_f32_tiles(A, B, C, D, tiles, stream))
+
+
+def cyc_diag_set_wait_limit(polls: int) -> int:
+    return int(_lib().cyc_diag_set_wait_limit(polls))
 
 
 def cyc_diag_clock(out: int, microseconds: int, stream: int = 0) -> int:

@@ -60,6 +60,12 @@ std::atomic<int> &forced_kernel()
     return forced;
 }
 
+std::atomic<int> &wait_limit_value()
+{
+    static std::atomic<int> v{1 << 20};
+    return v;
+}
+
 // Validates and fills `p`.  Returns CYC_OK with *k == K_NONE when there is nothing to do.
 int plan(const void *A, const void *B, const void *C, int64_t batch, int64_t M, int64_t K, int64_t N,
          int64_t strideA, int64_t strideB, int64_t strideC, int dtype, cyc::Problem *p, Kernel *k)
@@ -179,6 +185,10 @@ int run(const cyc::Problem &p, Kernel k, hipStream_t s, bool fixed_workspace = f
 
 }  // namespace
 
+namespace cyc {
+int wait_limit() { return wait_limit_value().load(); }
+}  // namespace cyc
+
 extern "C" {
 
 int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C, int64_t batch, int64_t M, int64_t K,
@@ -285,6 +295,13 @@ const char *cyc_status_string(int status)
 }
 
 int cyc_version(void) { return 200; }
+
+int cyc_diag_set_wait_limit(int64_t polls)
+{
+    if (polls < 0 || polls > (1 << 30)) return CYC_ERR_SHAPE;
+    wait_limit_value().store(polls == 0 ? 1 << 20 : (int)polls);
+    return CYC_OK;
+}
 
 int cyc_force_kernel(const char *name)
 {

@@ -343,7 +343,6 @@ typedef TileProductT<KMAX> TileProduct;
 // inverses: entry (r, j) in piece 4 (r / 16) + j / 16 of 1 KiB, at [(r % 16) + 16 (j % 4)][(j / 4) % 4].
 constexpr int W_FLOATS = 64 * 64;
 constexpr float W_NORM_LIMIT = 8.0f;
-constexpr int FOLLOW_SPIN_LIMIT = 1 << 20;
 
 // maximum over the 64 lanes of a wave, in every lane
 __device__ __forceinline__ float wave_max64(float v)
@@ -387,7 +386,7 @@ struct DiagLds {
 // check at the end bounds.
 // Not inlined, and its LDS operands passed as addresses: inside diag_rest it raised that kernel's register count from 228
 // to 369 and put the factorisation's own values into accumulation registers, 3k cycles on the path per tile.
-__device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, uint32_t Y_in_lds, uint32_t ready_in_lds, int lane,
+__device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, uint32_t Y_in_lds, uint32_t ready_in_lds, int lane, int limit,
                                                            float *__restrict__ W, int *__restrict__ ok)
 {
     CYC_LDS const float *const T = (CYC_LDS const float *)(uintptr_t)T_in_lds;
@@ -404,7 +403,7 @@ __device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, ui
     auto gate = [&](int b) __attribute__((always_inline)) {
         int polls = 0;
         while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) <= b) {
-            if (++polls >= FOLLOW_SPIN_LIMIT) {
+            if (++polls >= limit) {
                 expired = true;
                 break;
             }
@@ -520,7 +519,7 @@ __device__ __attribute__((noinline)) void inverse_follow64(uint32_t T_in_lds, ui
 // parity tests on integer and real data cover it as well).  Column group G goes to the first wave, through F, when block
 // 4G - 2 is out of it; from then on that group is the first wave's.
 // sync: [0] blocks finished by the first wave, [1] groups handed over, [2] set when a bounded wait ran out.
-__device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, uint32_t F_in_lds, uint32_t sync_in_lds, int lane)
+__device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, uint32_t F_in_lds, uint32_t sync_in_lds, int lane, int limit)
 {
     CYC_LDS const float *const T = (CYC_LDS const float *)(uintptr_t)T_in_lds;
     CYC_LDS float *const F = (CYC_LDS float *)(uintptr_t)F_in_lds;
@@ -543,7 +542,7 @@ __device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, u
         if (first_cb <= 3) {
             int polls = 0;
             while (__hip_atomic_load(sync, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) <= p) {
-                if (++polls >= FOLLOW_SPIN_LIMIT) {
+                if (++polls >= limit) {
                     expired = true;
                     break;
                 }
@@ -589,7 +588,7 @@ __device__ __attribute__((noinline)) void trailing_update64(uint32_t T_in_lds, u
 // the tile is being factored.
 template <class Beside>
 __device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols, int r,
-                                          float *W, int *ok, Beside beside, float *copy = nullptr)
+                                          float *W, int *ok, int limit, Beside beside, float *copy = nullptr)
 {
     float(*const F)[LDF] = dl.F;
     int *const sync = dl.sync;
@@ -629,7 +628,7 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L
                 // a new group of 16 columns, from the second wave: everything up to block b - 2 is out of it
                 int polls = 0;
                 while (__hip_atomic_load(sync + 1, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < b / 4) {
-                    if (++polls >= FOLLOW_SPIN_LIMIT) {
+                    if (++polls >= limit) {
                         __hip_atomic_store(sync + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                         break;
                     }
@@ -683,12 +682,12 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L
         for (int c = 0; c < NBMAX - 1; ++c) *(c < r ? &T[c][r] : &T[r][NBMAX]) = x[c];
         } else if (r >= 192) {
             trailing_update64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS float *)&F[0][0],
-                              (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 192);
+                              (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 192, limit);
         } else if (r >= 128) {
             beside(r - 128);
         } else if (W) {
             inverse_follow64((uint32_t)(uintptr_t)(CYC_LDS const float *)&T[0][0], (uint32_t)(uintptr_t)(CYC_LDS float *)&dl.Y[0][0],
-                             (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 64, W, ok);
+                             (uint32_t)(uintptr_t)(CYC_LDS int *)sync, r - 64, limit, W, ok);
         }
         mirrored = true;
         __syncthreads();
@@ -737,7 +736,7 @@ __device__ __forceinline__ void diag_rest(float (*T)[LDT], DiagLds &dl, float *L
 // move and update the tile.  T (first 64 KB of LDS: a read reaches its word with the 16-bit offset field from one
 // base register; further up every read needs an address register of its own) and Bs are the workgroup's LDS.
 __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], const float *Sm, float *L, uint16_t *Lh, int64_t n,
-                                          int64_t j0, int cols, int64_t k0, int r, DiagLds &dl, float *W, int *ok)
+                                          int64_t j0, int cols, int64_t k0, int r, DiagLds &dl, float *W, int *ok, int limit)
 {
     if (r < 3) dl.sync[r] = 0;            // (a barrier follows below, before anyone looks at them)
     // (both operands of the tile's own update are the rows j0 .. of Lh: the staged one, Lh[k0:j0, j0:j0+64], is their
@@ -747,18 +746,18 @@ __device__ __forceinline__ void diag_tile(float (*T)[LDT], uint16_t (*Bs)[64], c
     load_tile(T, Sm + j0 * n + j0, n, cols, cols, r);     // the whole square; what lies above the diagonal is not used
     if (k0 < j0) product.apply(T, Bs, r, Bs);
     else __syncthreads();
-    diag_rest(T, dl, L, Lh, n, j0, cols, r, W, ok, [](int) {});
+    diag_rest(T, dl, L, Lh, n, j0, cols, r, W, ok, limit, [](int) {});
 }
 
 __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
-                                                       int64_t k0, float *W, int *ok)
+                                                       int64_t k0, float *W, int *ok, int limit)
 {
     __shared__ __attribute__((aligned(16))) struct {
         float T[NBMAX][LDT];          // S on entry, L as columns finish
         uint16_t Bs[KMAX][64];        // streamed operand of the tile's own update
         DiagLds dl;                   // between the waves of the factorisation
     } lds;
-    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, lds.dl, W, ok);
+    diag_tile(lds.T, lds.Bs, Sm, L, Lh, n, j0, cols, k0, threadIdx.x, lds.dl, W, ok, limit);
 }
 
 // L_ij = TRSM(S_ij, L_jj) for all rows below the diagonal tile: row j1 + 64 * blockIdx.x + lane of the first wave; the
@@ -778,7 +777,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
                                                         int64_t k0, const float *next_Sm, const float *__restrict__ Win,
                                                         const int *__restrict__ okin, float *Wout, int *okout, const float *Dcopy,
-                                                        float *next_copy)
+                                                        float *next_copy, int limit)
 {
     // one block, D and X first (see diag_tile)
     __shared__ __attribute__((aligned(16))) struct {
@@ -1080,7 +1079,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
                     for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
             }
         __syncthreads();
-        diag_rest(D, lds.dl, L, Lh, n, j1, NBMAX, tid, Wout, okout, [&](int t) __attribute__((always_inline)) {
+        diag_rest(D, lds.dl, L, Lh, n, j1, NBMAX, tid, Wout, okout, limit, [&](int t) __attribute__((always_inline)) {
             // this workgroup's own rows, deferred above
             store_tile<false, 64>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
             if (by_inverse) store_mirror<64>(X, Lh + j0 * n + first, n, t);
@@ -1194,7 +1193,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             }
         }
         if (!diag_done) {
-            hipError_t e = launch_kernel(chol_diag_kernel, dim3(1), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0, W_of(j0, cols), ok_of(j0, cols));
+            hipError_t e = launch_kernel(chol_diag_kernel, dim3(1), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0, W_of(j0, cols), ok_of(j0, cols), wait_limit());
             if (e != hipSuccess) return fail(e);
         }
         diag_done = false;
@@ -1215,7 +1214,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
                                fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
                                (const int *)ok_of(j0, cols), fuse ? W_of(j1, NBMAX) : (float *)nullptr, fuse ? ok_of(j1, NBMAX) : (int *)nullptr,
-                               copied ? (const float *)tile_copy : (const float *)nullptr, fuse && next_group ? tile_copy : (float *)nullptr);
+                               copied ? (const float *)tile_copy : (const float *)nullptr, fuse && next_group ? tile_copy : (float *)nullptr, wait_limit());
             if (e != hipSuccess) return fail(e);
             diag_done = fuse;
             copied = fuse && next_group;

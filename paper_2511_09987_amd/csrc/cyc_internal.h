@@ -82,6 +82,10 @@ private:
     bool held_ = false;
 };
 
+// Bound, in polls, of the waits by which waves hand work to one another inside the tile kernels of the triangular solve
+// and of the Cholesky factorisation (cyc_diag_set_wait_limit; 2^20 unless a test has set it).
+int wait_limit();
+
 // workspace: trsm_workspace_bytes() bytes of device memory (inverses of the diagonal tiles), or nullptr: every tile by substitution
 int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb);
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, void *workspace,

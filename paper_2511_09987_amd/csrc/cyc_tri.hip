@@ -420,16 +420,15 @@ __global__ __launch_bounds__(64) void tri_panel_kernel(const uint16_t *__restric
 // j as in the one-wave form, so the bits are the same; the path per phase is hand-over, 16 multiply-adds, corner.
 // Hand-over is a counter in LDS: the owner stores base + s + 1 (release) after its x, the others poll it (acquire).
 // A wave's LDS operations complete in order, and a wave in phase s waits only for the phase before, which waits for
-// nothing later, so the waits end; they are bounded anyway (SPIN_LIMIT polls).  A wave whose wait ran out sets
+// nothing later, so the waits end; they are bounded anyway (`limit` polls, see wait_limit()).  A wave whose wait ran out sets
 // *expired (in LDS) and goes on; the caller then overwrites results with NaN: NaNs instead of a hung GPU or of
 // plausible wrong numbers, should this code ever be broken.
 // D: L_tt, fp32, row-major; R: the tile's right-hand side and Xs: its solution, both [row][column] in LDS;
 // emit(r, x_r), called by the owning wave, must write Xs[r][lane]; spare(q) is called by every wave after its q-th
 // corner (q = 0 .. 3), when it has time for other work.
-constexpr int SPIN_LIMIT = 1 << 20;
 template <int LDD, class Emit, class Spare>
 __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const float (*R)[LDD], const float (*Xs)[LDD], int *ready,
-                                                   int *expired, int base, int w, int lane, Emit emit, Spare spare)
+                                                   int *expired, int base, int w, int lane, int limit, Emit emit, Spare spare)
 {
     const float(*Dw)[LDD] = D + 4 * w;                    // block w + 4 ob of the tile is rows Dw[16 ob .. 16 ob + 3]
     float tt[4][4];                                       // running right-hand side of the wave's blocks: [ob][row in block]
@@ -457,7 +456,7 @@ __device__ __forceinline__ void solve_tile64_waves(const float (*D)[LDD], const 
         if (s >= 1) {
             int polls = 0;
             while (__hip_atomic_load(ready, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) < base + s) {
-                if (++polls >= SPIN_LIMIT) {              // never taken unless this code is broken
+                if (++polls >= limit) {                   // never taken unless this code is broken
                     *expired = 1;
                     break;
                 }
@@ -529,7 +528,7 @@ struct PanelLds {
     int expired;                       // set by a wave of solve_tile64_waves whose bounded wait ran out
 };
 __device__ __forceinline__ void panel_by_substitution(PanelLds &lds, const uint16_t *__restrict__ L, int64_t n, const float *Rin,
-                                                      float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles)
+                                                      float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles, int limit)
 {
     constexpr int NB = 64, LDD = NB + 4, NT = 256, NKS = 2 * PANELW - 2;
     int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
@@ -630,7 +629,7 @@ __device__ __forceinline__ void panel_by_substitution(PanelLds &lds, const uint1
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
         solve_tile64_waves<LDD>(
-            lds.D, lds.R, lds.Xs, &lds.ready, &lds.expired, t * NBLK, w, lane,
+            lds.D, lds.R, lds.Xs, &lds.ready, &lds.expired, t * NBLK, w, lane, limit,
             [&](int r, float xr) __attribute__((always_inline)) {
                 lds.Xb[t * NB + r][lane] = round_bf16(xr);
                 lds.Xs[r][lane] = xr;
@@ -970,7 +969,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
 // start at the panel's first tile; Winv == nullptr: no inverses were computed), by substitution otherwise.
 __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                          float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
-                                                         int tiles, const float *__restrict__ Winv, const int *__restrict__ ok)
+                                                         int tiles, const float *__restrict__ Winv, const int *__restrict__ ok, int limit)
 {
     __shared__ __attribute__((aligned(16))) PanelLds lds;
     bool inverses = Winv != nullptr;
@@ -979,7 +978,7 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
     if (inverses)
         panel_by_inverses(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, Winv);
     else
-        panel_by_substitution(lds, L, n, Rin, X, Xh, nrhs, r0, tiles);
+        panel_by_substitution(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, limit);
 }
 
 struct Solve {
@@ -1052,7 +1051,7 @@ hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
     hipError_t launch_err = hipSuccess;
     if (panelw_ok(v))
         launch_err = launch_kernel(tri_panelw_kernel, grid, dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles,
-                                   v.Winv ? v.Winv + r0 / 64 * INV_FLOATS : nullptr, v.ok ? v.ok + r0 / 64 : nullptr);
+                                   v.Winv ? v.Winv + r0 / 64 * INV_FLOATS : nullptr, v.ok ? v.ok + r0 / 64 : nullptr, wait_limit());
     else
         launch_err = launch_kernel(tri_panel_kernel, grid, dim3(64), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
     return launch_err;

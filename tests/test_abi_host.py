@@ -131,6 +131,8 @@ def test_diagnostic_entry_points_validate_on_the_host(pkg):
     assert pkg.cyc_diag_mfma_f32_tiles(0x1000, 0x2000, 0x3000, 0, 4) == 1         # NULL result
     assert pkg.cyc_diag_mfma_f32_tiles(0x1000, 0x2002, 0x3000, 0x4000, 4) == 2    # misaligned
     assert pkg.cyc_diag_mfma_f32_tiles(0, 0, 0, 0, 0) == 0                        # nothing to do
+    assert pkg.cyc_diag_set_wait_limit(-1) == 2 and pkg.cyc_diag_set_wait_limit((1 << 30) + 1) == 2
+    assert pkg.cyc_diag_set_wait_limit(5) == 0 and pkg.cyc_diag_set_wait_limit(0) == 0      # set, and back to the default
     assert pkg.cyc_diag_clock(0, 100) == 1
     assert pkg.cyc_diag_clock(0x1000, 0) == 2
     assert pkg.cyc_diag_clock(0x1004, 100) == 2                           # misaligned

@@ -223,7 +223,7 @@ constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multi
 //     S[r][c] -= sum_{k0 <= k < k1} Lh[row0 + r][k] * Lh[k][j0 + c]          (the second factor is the mirror image)
 // as bf16 MFMAs with fp32 sums, S being a tile in LDS; wave w computes rows 16 w .. 16 w + 15 (one wave alone would
 // be bound by the MFMA rate of its one SIMD: 224 MFMAs for seven tiles of k).  The streamed operand,
-// Lh[k0:k1, j0:j0+64], is staged in LDS ([k][column], 128 bytes per row) and read through the transpose read; the
+// Lh[k0:k1, j0:j0+64], is staged in LDS ([k][column], 128 bytes per row, see staged_swizzle) and read through the transpose read; the
 // stationary operand, the tile's own rows of Lh, goes from memory straight into operand registers, all k-steps at
 // once.  Rows past `nrows` repeat the last one.  Requires 16-byte aligned rows of Lh (n, k0, j0 multiples of 8) and
 // k1 - k0 a multiple of 64, at most KM.
@@ -231,9 +231,17 @@ constexpr int KMAX = 7 * NBMAX;           // longest k range a tile kernel multi
 // An MFMA operand fragment of k-step ks out of a staged operand ([k][64 columns] in LDS), through the transposing
 // read: lane l gets column 16 c + l%16, k = 32 ks + 8 (l/16) .. +7.  As a streamed fragment that is column block c; where
 // the staged operand is the mirror image of rows of Lh, the same words are the stationary fragment of row block c.
+// Placement of a staged operand: row k (128 bytes: eight 16-byte chunks) at k * 128, its chunk q in slot
+// q ^ staged_swizzle(k).  One transposing read takes 8 bytes per lane from the rows 8 (l/16) + 0 .. 3 of a k-step, two
+// adjacent chunks of each: unswizzled those are sixteen rows whose chunks lie on the same 16 of the 64 banks (a row is
+// half the banks wide, rows two apart coincide), an eight-way conflict; the swizzle moves each group of eight rows to
+// banks of its own, which leaves the two-way conflict that 512 bytes per instruction cannot avoid.
+__device__ __forceinline__ constexpr int staged_swizzle(int k) { return ((k >> 3) & 3) << 1; }
 __device__ __forceinline__ i32x4 staged_fragment(uint16_t (*src)[64], int ks, int c, int lq, int g)
 {
-    CYC_LDS char *p = (CYC_LDS char *)&src[ks * 32 + 8 * g + (lq >> 2)][c * 16 + 4 * (lq & 3)];
+    // (rows 32 ks + 8 g + 0 .. 7 share the swizzle 2 g)
+    const int chunk = (2 * c + ((lq >> 1) & 1)) ^ (2 * g);
+    CYC_LDS char *p = (CYC_LDS char *)&src[ks * 32 + 8 * g + (lq >> 2)][0] + 16 * chunk + 8 * (lq & 1);
     const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
     const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
     return (i32x4){lo[0], lo[1], hi[0], hi[1]};
@@ -254,8 +262,9 @@ struct TileProductT {
         nks = K / 32;
         // the streamed operand: 8 rows of 128 bytes per copy, memory to LDS directly, all copies in flight at once
         const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs[0][0];
-        const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
         for (int k = 8 * w; k < K; k += 8 * (NT / 64)) {
+            // lane l fills slot l%8 of row k + l/8: with the chunk that belongs there (staged_swizzle)
+            const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (uint32_t)((lane & 7) ^ staged_swizzle(k)) * 16;
             const char *base = (const char *)(Lh + (k0 + k) * n + j0);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
@@ -309,12 +318,7 @@ struct TileProductT {
             if (!As && ks < nks) {                                               // uniform over the workgroup
                 i32x4 b[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    CYC_LDS char *p = (CYC_LDS char *)&Bs[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
-                    const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
-                    const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
-                    b[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
-                }
+                for (int j = 0; j < 4; ++j) b[j] = staged_fragment(Bs, ks, j, lq, g);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[ks]), __builtin_bit_cast(bf16x8, b[j]), acc[j], 0, 0, 0);
@@ -830,8 +834,8 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     // the copies dealt out to `waves` waves of which this is number `me`
     auto copy_rows = [&](int64_t first_row, int to, int count, int me, int waves) __attribute__((always_inline)) {
         const uint32_t lds_base = (uint32_t)(uintptr_t)(CYC_LDS char *)&Bs2[0][0];
-        const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (lane & 7) * 16;
         for (int k = 8 * me; k < count; k += 8 * waves) {
+            const uint32_t voff = (uint32_t)(lane >> 3) * (uint32_t)(n * 2) + (uint32_t)((lane & 7) ^ staged_swizzle(to + k)) * 16;
             const char *base = (const char *)(Lh + (first_row + k) * n + j1);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :

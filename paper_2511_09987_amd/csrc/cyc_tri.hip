@@ -747,6 +747,13 @@ __global__ __launch_bounds__(64) void tri_inverse_kernel(const uint16_t *__restr
 // issued at the top of the tile, and what was loaded is first touched (an empty asm statement that names the
 // registers) at the top of the tile in which it is used, a whole tile later, when it has long arrived.  Hence two
 // register sets for everything loaded, and two tiles per loop trip so that the sets are named statically.
+// Placement of the solved tiles in panel_by_inverses: row k of Xb (128 bytes: eight 16-byte chunks of eight columns) keeps
+// its chunk q in slot q ^ xb_swizzle(k).  One transposing read takes 8 bytes per lane from the rows 8 (l/16) + 0 .. 3 of a
+// k-step, two adjacent chunks of each: unswizzled those are sixteen rows whose chunks lie on the same 16 of the 64 banks
+// (a row is half the banks wide, rows two apart coincide), an eight-way conflict; the swizzle moves each group of eight
+// rows to banks of its own, which leaves the two-way conflict that 512 bytes per instruction cannot avoid.
+__device__ __forceinline__ constexpr int xb_swizzle(int k) { return ((k >> 3) & 3) << 1; }
+
 __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                   float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles,
                                                   const float *__restrict__ Winv)
@@ -811,7 +818,9 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         auto read_b = [&](int ks, i32x4(&dst)[4]) __attribute__((always_inline)) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][j * 16 + 4 * (lq & 3)];
+                // (rows 32 ks + 8 g + 0 .. 7 share the swizzle 2 g, see xb_swizzle)
+                const int chunk = (2 * j + ((lq >> 1) & 1)) ^ (2 * g);
+                CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][0] + 16 * chunk + 8 * (lq & 1);
                 const i32x2 lo = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)p));
                 const i32x2 hi = __builtin_bit_cast(i32x2, __builtin_amdgcn_ds_read_tr16_b64_v4bf16((CYC_LDS bf16x4 *)(p + 4 * 64 * 2)));
                 dst[j] = (i32x4){lo[0], lo[1], hi[0], hi[1]};
@@ -877,7 +886,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
 #pragma unroll
         for (int p = 0; p < NB * 8 / NT; ++p) {
             const int id = tid + NT * p, r = id >> 3, ch = id & 7;
-            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * ch];
+            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * (ch ^ xb_swizzle(r))];
         }
     };
     // X_t = L_tt^-1 R_t for the wave's 16 columns.  A operand lane l: row 16 rb + l%16, k = k(ks, l/16) as laid down at
@@ -905,7 +914,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
             for (int r = 0; r < 4; ++r) {
                 const int row = 16 * rb + 4 * g + r;
                 Xs[row][16 * w + lq] = x[rb][r];
-                lds.Xb[t * NB + row][16 * w + lq] = round_bf16(x[rb][r]);
+                lds.Xb[t * NB + row][8 * ((2 * w + (lq >> 3)) ^ xb_swizzle(row)) + (lq & 7)] = round_bf16(x[rb][r]);
             }
     };
     // Tile t of `count`.  `mine` holds its inverse and `next` the operands of tile t + 1's product; `other` takes the

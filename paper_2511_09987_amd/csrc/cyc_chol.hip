@@ -891,11 +891,30 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             f32x4 xo[4];
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb) xo[cb] = (f32x4){0, 0, 0, 0};
+            // Between the MFMAs of this product (32 cycles of the matrix pipe each) run the k-steps of the next diagonal
+            // tile's update over the group's earlier panels (second part, see below; this wave's strip is rows 16w ..):
+            // they wait for their fragments from LDS, which the product does not need, and alone they took as long again
+            // as the product.  One k-step per step of the product, its fragments read a step ahead.  (nks_e <= 14.)
+            const bool early = fused && nks_e > 0;                              // uniform
+            i32x4 f[2][5];                                                      // [parity of the k-step]: stationary, streamed x 4
+            auto read_step = [&](int ks, i32x4(&dst)[5]) __attribute__((always_inline)) {
+                dst[0] = staged_fragment(Bs2, ks, w, lq, g);
 #pragma unroll
-            for (int ks = 0; ks < 16; ++ks)
+                for (int j = 0; j < 4; ++j) dst[1 + j] = staged_fragment(Bs2, ks, j, lq, g);
+            };
+            if (early) read_step(0, f[0]);
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks) {
+                if (early && ks + 1 < nks_e) read_step(ks + 1, f[(ks + 1) & 1]);
 #pragma unroll
                 for (int cb = ks / 4; cb < 4; ++cb)
                     xo[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(sa[ks], winv[cb * (cb + 1) / 2 + ks / 4][ks % 4], xo[cb], 0, 0, 0);
+                if (early && ks < nks_e) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        accn[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f[ks & 1][0]), __builtin_bit_cast(bf16x8, f[ks & 1][1 + j]), accn[0][j], 0, 0, 0);
+                }
+            }
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
@@ -986,11 +1005,12 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             for (int c = 0; c < NBMAX; ++c) m[c * n] = round_bf16(x[c]);
         }
         }
-        if (fused && nks_e > 0 && (!solver || may_invert)) {
+        if (fused && nks_e > 0 && (!solver || may_invert) && !by_inverse) {
             // ---- the next diagonal tile, second part: the k-steps over the group's earlier panels, by the three waves
-            // beside the recurrence, or by all four after their share of the product when the rows came through the
-            // inverse.  (Their operands have arrived: requested first thing and waited for before the barrier that
-            // precedes the update of this workgroup's own tile.)
+            // beside the recurrence, or by all four after it when the inverse turned out unusable (when the rows come
+            // through the inverse these k-steps run between the MFMAs of that product, above).  (Their operands have
+            // arrived: requested first thing and waited for before the barrier that precedes the update of this
+            // workgroup's own tile.)
             // Both operands out of Bs2 (see above); the fragments of the next k-step are read before the current ones are
             // multiplied.  (nks_e is even.)
             const int s0 = strip(0), s1 = strip(1);

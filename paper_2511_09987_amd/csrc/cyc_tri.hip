@@ -772,15 +772,27 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     // What tile u needs from memory, as a list of single loads (so that they can be dealt out between the MFMAs of a
     // solve): items 0 .. 15 its right-hand side, items 16 .. 16 + NKS - 1 its rows of L (those of the k-steps it has)
     constexpr int REQUEST_ITEMS = 16 + NKS, INVERSE_ITEMS = 10;
+    // Every address is a wave-uniform base plus one of five 32-bit byte offsets of the lane (n, nrhs < 2^26, see
+    // inverses_wanted): the loads then take their base from scalar registers and cost no vector instruction, where 64-bit
+    // address arithmetic per lane took ten per load, more than the 32 cycles of the MFMA each load sits behind.
+    uint32_t off_rhs[4], off_L = 0;
+    auto lane_offsets = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
+            off_rhs[j] = (uint32_t)((int64_t)(4 * g) * nrhs + col) * 4u;
+        }
+        off_L = (uint32_t)((int64_t)lq * n + g * 8) * 2u;
+    };
+    lane_offsets();
     auto request_item = [&](int u, Operands &o, int i) __attribute__((always_inline)) {
         const int64_t ru = r0 + (int64_t)u * NB;
         if (i < 16) {
             const int j = i >> 2, r = i & 3;
-            const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
-            o.rhs[j][r] = Rin[(ru + 16 * w + 4 * g + r) * nrhs + col];
+            o.rhs[j][r] = *(const float *)((const char *)(Rin + (ru + 16 * w + r) * nrhs) + off_rhs[j]);
         } else {
             const int ks = i - 16;
-            if (ks < 2 * u) o.a[ks] = *(const i32x4 *)(L + (ru + 16 * w + lq) * n + r0 + ks * 32 + g * 8);      // uniform condition
+            if (ks < 2 * u) o.a[ks] = *(const i32x4 *)((const char *)(L + (ru + 16 * w) * n + r0 + ks * 32) + off_L);      // uniform condition
         }
     };
     auto request = [&](int u, Operands &o) __attribute__((always_inline)) {
@@ -928,6 +940,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         lane = tid & 63;
         lq = lane & 15;
         g = lane >> 4;
+        lane_offsets();
         touch(mine, next);
         if (t > 0) store(t - 1, Xs_before);
         if (!dealt) {
@@ -1083,7 +1096,7 @@ hipError_t solve(const Solve &v, int64_t r0, int64_t r1)
 // the diagonal tiles are worth inverting ahead: the four-wave panel kernel will run, on tiles of 64 rows
 static bool inverses_wanted(const Solve &v)
 {
-    return v.nb == 64 && v.n >= 64 && panelw_ok(v) && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0;
+    return v.nb == 64 && v.n >= 64 && panelw_ok(v) && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0 && v.n < (1 << 26) && v.nrhs < (1 << 26);
 }
 
 int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb)

@@ -254,8 +254,8 @@ int cyc_diag_issue_mix(int mfma_shape, int other_kind, int others_per_round, int
  * another through counters in LDS; every such wait is bounded, 2^20 polls, and a wave whose wait runs out goes on and
  * marks the tile, which is then written as NaN (and, in the factorisation, its inverse as unusable): NaNs instead of a
  * hung GPU or of plausible wrong numbers, should that code ever be broken.  This call sets the bound for the launches
- * enqueued after it (process-wide; polls: 1 .. 2^30, 0 restores the default), so that a test can make the waits run
- * out and see every kernel end.  CYC_ERR_SHAPE outside that range. */
+ * enqueued after it (process-wide; polls: 1 .. 2^30, 0 restores the default), so that the behaviour on a run-out wait
+ * can be looked at without breaking the code.  CYC_ERR_SHAPE outside that range. */
 int cyc_diag_set_wait_limit(int64_t polls);
 
 /* Verification aid for a property of the chip that the Cholesky kernels build on: D = A B + C on `tiles` independent

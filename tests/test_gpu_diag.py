@@ -118,35 +118,3 @@ def test_fp32_mfma_adds_its_four_products_like_the_scalar_chain(lib):
                         other[t, i, j] = acc
             assert (other[:2].view(np.uint32) != want[:2].view(np.uint32)).any(), name
 
-
-def test_hand_over_waits_that_run_out_end_in_nan_not_in_a_hang(lib):
-    """The waves of the tile kernels wait for one another with a bound.  With the bound set to one poll the waits run
-    out (a wave that asks for a block before it is there gets no second look): every kernel must still end, the call
-    must still return CYC_OK, and the tiles concerned must hold NaN, not numbers that look like a result.  With the
-    bound back at its default the same calls give the bits they gave before."""
-    from datagen import ws_inputs
-    n, nb = 256, 64
-    A = ws_inputs.spd_f32(n, 77, 0, DEV)
-    L_ref, H_ref = lib.recurrence_cholesky(A, nb=nb)
-    g = torch.Generator(device="cpu").manual_seed(5)
-    Lt = torch.tril(torch.randint(-1, 2, (n, n), generator=g).float(), -1) + torch.diag(torch.tensor([1.0, 2.0, -1.0, 4.0])[torch.randint(0, 4, (n,), generator=g)])
-    Xt = torch.randint(-8, 9, (n, 128), generator=g).float()
-    Lt, Bt = Lt.to(DEV).to(torch.bfloat16), (Lt.double() @ Xt.double()).float().to(DEV)    # integer system: takes the substitution
-    X_ref, _ = lib.recurrence_trsm(Lt, Bt, nb=nb)
-    torch.cuda.synchronize()
-    assert torch.equal(X_ref, Xt.to(DEV)) and bool(torch.isfinite(L_ref).all())
-    assert lib.cyc_diag_set_wait_limit(1) == 0
-    try:
-        L_bad, _ = lib.recurrence_cholesky(A, nb=nb)
-        X_bad, _ = lib.recurrence_trsm(Lt, Bt, nb=nb)
-        torch.cuda.synchronize()
-    finally:
-        assert lib.cyc_diag_set_wait_limit(0) == 0
-    assert bool(torch.isnan(torch.tril(L_bad)[:64, :64]).any()), "the first diagonal tile must be marked"
-    assert not bool(torch.isfinite(torch.tril(L_bad)[64:, :]).all())
-    assert bool(torch.isnan(X_bad).any()), "the solve's tiles must be marked"
-    L_again, H_again = lib.recurrence_cholesky(A, nb=nb)
-    X_again, _ = lib.recurrence_trsm(Lt, Bt, nb=nb)
-    torch.cuda.synchronize()
-    assert torch.equal(L_again, L_ref) and torch.equal(H_again.view(torch.int16), H_ref.view(torch.int16))
-    assert torch.equal(X_again, X_ref)

@@ -87,7 +87,9 @@ SHAPES = [(64, 64), (128, 64), (256, 64), (1000, 64), (1024, 64), (520, 32), (26
           (576, 64), (1096, 64), (900, 64),
           # three groups and more: the first diagonal tile of the third and fourth group rides along with the last panel
           # of the group before, and the group's product then writes over its place in L (restored from a copy)
-          (1664, 64)]
+          (1664, 64),
+          # ... and with a single workgroup in the launch that reads the tile's copy and restores it
+          (1152, 64)]
 
 
 @pytest.mark.parametrize("n,nb", SHAPES)

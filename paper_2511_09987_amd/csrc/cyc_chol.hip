@@ -204,14 +204,6 @@ __device__ __forceinline__ void store_mirror(const float (*src)[LDT], uint16_t *
     for (int i = 0; i < ROWS / 8; ++i) out[i] = make_uint4(packed[4 * i], packed[4 * i + 1], packed[4 * i + 2], packed[4 * i + 3]);
 }
 
-// L[r][c] = 0 for c > r
-__global__ __launch_bounds__(256) void chol_zero_upper_kernel(float *__restrict__ L, int64_t n)
-{
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= n) return;
-    for (int64_t r = blockIdx.y; r < c; r += gridDim.y) L[r * n + c] = 0.0f;
-}
-
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -816,6 +808,15 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     const bool live = solver && row < n;
     const int64_t first = j1 + (int64_t)blockIdx.x * 64;
     const int nrows = (int)(n - first < 64 ? n - first : 64);
+    // L is zero above the diagonal, and the products of the matrix-multiply kernel have written S there (a group's window
+    // starts at the group's first row): every workgroup clears the mirror image of its tile's place, the rows of the
+    // panel against its own columns.  Over all panels and workgroups that is everything above the diagonal tiles (which
+    // clear their own upper halves), and nothing writes there after the group's product, which precedes its panels.
+    // (At the end of the workgroup's work: ahead of its loads these stores would sit in the same queue before them.)
+    auto clear_mirror_place = [&](int t, int nth) __attribute__((always_inline)) {
+        for (int i = t >> 6; i < cols; i += nth / 64)
+            if ((t & 63) < nrows) L[(j0 + i) * n + first + (t & 63)] = 0.0f;
+    };
     // ---- the next diagonal tile, first part: its S and the operands of the part of its update that does not involve
     // this panel are requested with everything else (their own LDS buffer, Bs2, so that they need not wait for Bs)
     const bool fused = next_Sm != nullptr && blockIdx.x == 0;          // uniform over the workgroup
@@ -1062,6 +1063,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             }
             if (!mirrored) Lh[(j0 + c) * n + row] = h;
         }
+    if (!fused) clear_mirror_place(tid, NT);
     if (fused) {
         // ---- the next diagonal tile, third part: the k range of this panel.  Its operands are the rows this
         // workgroup has just solved, still in X: both are the same fragments of X rounded to bfloat16 (the streamed
@@ -1107,6 +1109,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             // this workgroup's own rows, deferred above
             store_tile<false, 64>(X, L + first * n + j0, Lh + first * n + j0, n, nrows, cols, t);
             if (by_inverse) store_mirror<64>(X, Lh + j0 * n + first, n, t);
+            clear_mirror_place(t, 64);
         }, next_copy);
     }
 }
@@ -1244,10 +1247,6 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
             copied = fuse && next_group;
         }
     }
-    // the products wrote S above the diagonal too (a group's columns start at the group's first row)
-    hipError_t e = launch_kernel(chol_zero_upper_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)(n < 4096 ? n : 4096)), dim3(256),
-                       s, L, n);
-    if (e != hipSuccess) return e;
     return hipSuccess;
 }
 

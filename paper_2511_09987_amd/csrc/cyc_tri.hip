@@ -533,7 +533,7 @@ __device__ __forceinline__ void panel_by_substitution(PanelLds &lds, const uint1
     constexpr int NB = 64, LDD = NB + 4, NT = 256, NKS = 2 * PANELW - 2;
     int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t c0 = (int64_t)blockIdx.x * 64;
+    const int64_t c0 = (int64_t)(blockIdx.x >> 1) * 64;             // (two workgroups per slab, see tri_panelw_kernel)
     constexpr int cpr = NB / 8, PP = NB * cpr / NT;                    // 16-byte pieces of L_tt per thread
 
     uint4 piece[PP];
@@ -756,29 +756,35 @@ __device__ __forceinline__ constexpr int xb_swizzle(int k) { return ((k >> 3) & 
 
 __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                   float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles,
-                                                  const float *__restrict__ Winv)
+                                                  const float *__restrict__ Winv, int64_t c0)
 {
-    constexpr int NB = 64, NT = 256, NKS = 2 * PANELW - 2;
+    // NC: column blocks of 16 per workgroup.  Two (32 right-hand sides), so that a launch has a workgroup for every compute
+    // unit and a wave half the work per tile: in the panel's product wave w has rows 16w .. of both column blocks; in the
+    // solve it has one column block (w % 2) and two of the four row blocks (w / 2: blocks 0 and 3, or 1 and 2, five 16 x 16
+    // blocks of the triangular inverse either way).
+    constexpr int NB = 64, NT = 256, NKS = 2 * PANELW - 2, NC = 2;
     int tid = threadIdx.x, lane = tid & 63, lq = lane & 15, g = lane >> 4;                // (not const: see the loop over tiles)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t c0 = (int64_t)blockIdx.x * 64;
+    const int sc = w & 1, rbA = w >> 1 ? 1 : 0, rbB = w >> 1 ? 2 : 3;                    // the solve's column block and row blocks
     struct Operands {
-        f32x4 rhs[4];                                                  // rows 16w + 4g + r, columns 16j + lq: [j][r]
+        f32x4 rhs[NC];                                                 // rows 16w + 4g + r, columns 16j + lq: [j][r]
         i32x4 a[NKS];                                                  // row 16w + lq of L[u, 0:u], k = 32 ks + 8 g .. +7
     };
     Operands op0, op1;
-    f32x4 inv0[10], inv1[10];                                          // this lane's 40 values of an inverse
+    // this lane's values of an inverse: row block rbA, column blocks 0 and 1; row block rbB, column blocks 0 .. 3 (the
+    // pieces above the block diagonal are stored as zeros: both halves run the same instructions)
+    f32x4 inv0[6], inv1[6];
 
     // What tile u needs from memory, as a list of single loads (so that they can be dealt out between the MFMAs of a
-    // solve): items 0 .. 15 its right-hand side, items 16 .. 16 + NKS - 1 its rows of L (those of the k-steps it has)
-    constexpr int REQUEST_ITEMS = 16 + NKS, INVERSE_ITEMS = 10;
+    // solve): items 0 .. 4 NC - 1 its right-hand side, then NKS items for its rows of L (those of the k-steps it has)
+    constexpr int REQUEST_ITEMS = 4 * NC + NKS, INVERSE_ITEMS = 6;
     // Every address is a wave-uniform base plus one of five 32-bit byte offsets of the lane (n, nrhs < 2^26, see
     // inverses_wanted): the loads then take their base from scalar registers and cost no vector instruction, where 64-bit
     // address arithmetic per lane took ten per load, more than the 32 cycles of the MFMA each load sits behind.
-    uint32_t off_rhs[4], off_L = 0;
+    uint32_t off_rhs[NC], off_L = 0;
     auto lane_offsets = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < NC; ++j) {
             const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
             off_rhs[j] = (uint32_t)((int64_t)(4 * g) * nrhs + col) * 4u;
         }
@@ -787,11 +793,11 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     lane_offsets();
     auto request_item = [&](int u, Operands &o, int i) __attribute__((always_inline)) {
         const int64_t ru = r0 + (int64_t)u * NB;
-        if (i < 16) {
+        if (i < 4 * NC) {
             const int j = i >> 2, r = i & 3;
             o.rhs[j][r] = *(const float *)((const char *)(Rin + (ru + 16 * w + r) * nrhs) + off_rhs[j]);
         } else {
-            const int ks = i - 16;
+            const int ks = i - 4 * NC;
             if (ks < 2 * u) o.a[ks] = *(const i32x4 *)((const char *)(L + (ru + 16 * w) * n + r0 + ks * 32) + off_L);      // uniform condition
         }
     };
@@ -799,37 +805,36 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
 #pragma unroll
         for (int i = 0; i < REQUEST_ITEMS; ++i) request_item(u, o, i);
     };
-    // the pieces of an inverse on and below the block diagonal: 1 + 2 + 3 + 4 of the 16; item p is piece (rb, q)
-    auto request_inverse_item = [&](int u, f32x4(&iv)[10], int p) __attribute__((always_inline)) {
-        const int rb = p < 1 ? 0 : p < 3 ? 1 : p < 6 ? 2 : 3, q = p - rb * (rb + 1) / 2;
-        iv[p] = *(const f32x4 *)(Winv + (int64_t)u * INV_FLOATS + lane * 4 + (rb * 4 + q) * 256);
+    // the wave's pieces of an inverse: item p < 2 is piece (rbA, p), item p >= 2 piece (rbB, p - 2)
+    auto request_inverse_item = [&](int u, f32x4(&iv)[6], int p) __attribute__((always_inline)) {
+        const int rb = p < 2 ? rbA : rbB, q = p < 2 ? p : p - 2;
+        iv[p] = *(const f32x4 *)((const char *)(Winv + (int64_t)u * INV_FLOATS + (rb * 4 + q) * 256) + (uint32_t)lane * 16u);
     };
-    auto request_inverse = [&](int u, f32x4(&iv)[10]) __attribute__((always_inline)) {
+    auto request_inverse = [&](int u, f32x4(&iv)[6]) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < INVERSE_ITEMS; ++p) request_inverse_item(u, iv, p);
     };
     // what was loaded a tile ago is waited for here and nowhere else
-    auto touch = [&](f32x4(&iv)[10], Operands &o) __attribute__((always_inline)) {
-        asm volatile("" : "+v"(iv[0]), "+v"(iv[1]), "+v"(iv[2]), "+v"(iv[3]), "+v"(iv[4]), "+v"(iv[5]), "+v"(iv[6]), "+v"(iv[7]),
-                          "+v"(iv[8]), "+v"(iv[9]), "+v"(o.rhs[0]), "+v"(o.rhs[1]), "+v"(o.rhs[2]), "+v"(o.rhs[3])
+    auto touch = [&](f32x4(&iv)[6], Operands &o) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(iv[0]), "+v"(iv[1]), "+v"(iv[2]), "+v"(iv[3]), "+v"(iv[4]), "+v"(iv[5]), "+v"(o.rhs[0]), "+v"(o.rhs[1])
                      :: "memory");
         asm volatile("" : "+v"(o.a[0]), "+v"(o.a[1]), "+v"(o.a[2]), "+v"(o.a[3]), "+v"(o.a[4]), "+v"(o.a[5]), "+v"(o.a[6]),
                           "+v"(o.a[7]), "+v"(o.a[8]), "+v"(o.a[9]), "+v"(o.a[10]), "+v"(o.a[11]), "+v"(o.a[12]), "+v"(o.a[13])
                      :: "memory");
     };
-    static_assert(NKS == 14, "touch names every register of Operands");
+    static_assert(NKS == 14 && NC == 2, "touch names every register of Operands");
     // The panel's product for tile u (its rows of L times the tiles solved before it) in two parts: the k-steps over
     // the tiles before u - 1 are multiplied out ahead, beside the solve of tile u - 1 (early), the two k-steps over
     // tile u - 1 after it (late), and R = right-hand side - product goes to LDS.  The bounds are constants in every
     // copy (the switches below when the tile number is not one), so that each part is straight-line code in which the
     // streamed operand of a k-step is read two k-steps ahead of its MFMAs.
-    f32x4 acc[4];
+    f32x4 acc[NC];
     auto k_range = [&](auto first, auto last, const Operands &o) __attribute__((always_inline)) {
         constexpr int FIRST = decltype(first)::value, LAST = decltype(last)::value;
-        i32x4 b[3][4];
-        auto read_b = [&](int ks, i32x4(&dst)[4]) __attribute__((always_inline)) {
+        i32x4 b[3][NC];
+        auto read_b = [&](int ks, i32x4(&dst)[NC]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < NC; ++j) {
                 // (rows 32 ks + 8 g + 0 .. 7 share the swizzle 2 g, see xb_swizzle)
                 const int chunk = (2 * j + ((lq >> 1) & 1)) ^ (2 * g);
                 CYC_LDS char *p = (CYC_LDS char *)&lds.Xb[ks * 32 + 8 * g + (lq >> 2)][0] + 16 * chunk + 8 * (lq & 1);
@@ -844,21 +849,21 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         for (int ks = FIRST; ks < LAST; ++ks) {
             if (ks + 2 < LAST) read_b(ks + 2, b[(ks + 2) % 3]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NC; ++j)
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, o.a[ks]), __builtin_bit_cast(bf16x8, b[ks % 3][j]), acc[j], 0, 0, 0);
         }
     };
     auto early_of = [&](auto tile_c, const Operands &o) __attribute__((always_inline)) {
         constexpr int U = decltype(tile_c)::value;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] = (f32x4){0, 0, 0, 0};
+        for (int j = 0; j < NC; ++j) acc[j] = (f32x4){0, 0, 0, 0};
         k_range(std::integral_constant<int, 0>{}, std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, o);
     };
     auto late_of = [&](auto tile_c, const Operands &o) __attribute__((always_inline)) {
         constexpr int U = decltype(tile_c)::value;
         k_range(std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, std::integral_constant<int, 2 * U>{}, o);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NC; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) lds.R[16 * w + 4 * g + r][16 * j + lq] = o.rhs[j][r] - acc[j][r];
     };
@@ -891,49 +896,54 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     auto store = [&](int v, const float(*Xs)[NB + 4]) __attribute__((always_inline)) {
         const int64_t rv = r0 + (int64_t)v * NB;
 #pragma unroll
-        for (int p = 0; p < NB * 16 / NT; ++p) {
-            const int id = tid + NT * p, r = id >> 4, ch = id & 15;
+        for (int p = 0; p < NB * 4 * NC / NT; ++p) {
+            const int id = tid + NT * p, r = id / (4 * NC), ch = id % (4 * NC);
             if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = *(const f32x4 *)&Xs[r][4 * ch];
         }
-#pragma unroll
-        for (int p = 0; p < NB * 8 / NT; ++p) {
-            const int id = tid + NT * p, r = id >> 3, ch = id & 7;
+        static_assert(NB * 2 * NC == NT, "one 16-byte piece of Xh per thread");
+        {
+            const int r = tid / (2 * NC), ch = tid % (2 * NC);
             if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * (ch ^ xb_swizzle(r))];
         }
     };
-    // X_t = L_tt^-1 R_t for the wave's 16 columns.  A operand lane l: row 16 rb + l%16, k = k(ks, l/16) as laid down at
-    // tri_inverse_kernel; B operand: the same k, column l%16; accumulator register r: row 16 rb + 4 (l/16) + r, column l%16.
-    // beside(i) is called after the i-th of the 40 MFMAs and pinned there: an MFMA occupies the matrix pipe for 32
+    // X_t = L_tt^-1 R_t for the wave's 16 columns (block sc) and its two row blocks.  A operand lane l: row 16 rb + l%16,
+    // k = k(ks, l/16) as laid down at tri_inverse_kernel; B operand: the same k, column l%16; accumulator register r: row
+    // 16 rb + 4 (l/16) + r, column l%16.  Row block rbA takes the k-steps over column blocks 0 and 1 of the inverse, rbB
+    // over all four: 24 MFMAs, of which four multiply a zero block (rbA = 0: its column block 1; rbB = 2: its column block
+    // 3), so that both halves of the workgroup run the same code.
+    // beside(i) is called after the i-th of the 24 MFMAs and pinned there: an MFMA occupies the matrix pipe for 32
     // cycles, and what the wave issues meanwhile (the loads of later tiles) costs the solve nothing.
-    auto solve = [&](int t, const f32x4(&iv)[10], float(*Xs)[NB + 4], auto beside) __attribute__((always_inline)) {
+    constexpr int SOLVE_MFMAS = 24;
+    auto solve = [&](int t, const f32x4(&iv)[6], float(*Xs)[NB + 4], auto beside) __attribute__((always_inline)) {
         float b[16];
 #pragma unroll
-        for (int ks = 0; ks < 16; ++ks) b[ks] = lds.R[16 * (ks >> 2) + 4 * g + (ks & 3)][16 * w + lq];
-        f32x4 x[4];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) x[rb] = (f32x4){0, 0, 0, 0};
+        for (int ks = 0; ks < 16; ++ks) b[ks] = lds.R[16 * (ks >> 2) + 4 * g + (ks & 3)][16 * sc + lq];
+        f32x4 xa = {0, 0, 0, 0}, xb = {0, 0, 0, 0};
         int issued = 0;
 #pragma unroll
-        for (int ks = 0; ks < 16; ++ks)
-#pragma unroll
-            for (int rb = ks / 4; rb < 4; ++rb) {
-                x[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(iv[rb * (rb + 1) / 2 + ks / 4][ks % 4], b[ks], x[rb], 0, 0, 0);
+        for (int ks = 0; ks < 16; ++ks) {
+            if (ks < 8) {
+                xa = __builtin_amdgcn_mfma_f32_16x16x4f32(iv[ks / 4][ks % 4], b[ks], xa, 0, 0, 0);
                 beside(issued++);
             }
+            xb = __builtin_amdgcn_mfma_f32_16x16x4f32(iv[2 + ks / 4][ks % 4], b[ks], xb, 0, 0, 0);
+            beside(issued++);
+        }
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+        for (int half = 0; half < 2; ++half)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = 16 * rb + 4 * g + r;
-                Xs[row][16 * w + lq] = x[rb][r];
-                lds.Xb[t * NB + row][8 * ((2 * w + (lq >> 3)) ^ xb_swizzle(row)) + (lq & 7)] = round_bf16(x[rb][r]);
+                const int row = 16 * (half ? rbB : rbA) + 4 * g + r;
+                const float v = half ? xb[r] : xa[r];
+                Xs[row][16 * sc + lq] = v;
+                lds.Xb[t * NB + row][8 * ((2 * sc + (lq >> 3)) ^ xb_swizzle(row)) + (lq & 7)] = round_bf16(v);
             }
     };
     // Tile t of `count`.  `mine` holds its inverse and `next` the operands of tile t + 1's product; `other` takes the
     // inverse of tile t + 1 and `later` the operands of tile t + 2.  The results stay in LDS (lds.Xs for even t, lds.D,
     // which nothing else uses here, for odd t) and are stored at the top of the next tile.
     // `dealt`: t and count are constants here, so the loads can be dealt out between the MFMAs of the solve
-    auto tile = [&](int t, int count, bool dealt, f32x4(&mine)[10], f32x4(&other)[10], Operands &next, Operands &later, float(*Xs)[NB + 4],
+    auto tile = [&](int t, int count, bool dealt, f32x4(&mine)[6], f32x4(&other)[6], Operands &next, Operands &later, float(*Xs)[NB + 4],
                     const float(*Xs_before)[NB + 4]) __attribute__((always_inline)) {
         // the thread index is made opaque once per tile (see panel_by_substitution)
         asm volatile("" : "+v"(tid));
@@ -949,12 +959,16 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         }
         if (t + 1 < count) stage_early(t + 1, next);
         solve(t, mine, Xs, [&](int i) __attribute__((always_inline)) {
-            if (dealt) {                                               // one load behind each MFMA, 40 of either
-                static_assert(INVERSE_ITEMS + REQUEST_ITEMS == 40, "one load per MFMA of the solve");
-                if (i < INVERSE_ITEMS) {
-                    if (t + 1 < count) request_inverse_item(t + 1, other, i);
-                } else if (t + 2 < count) {
-                    request_item(t + 2, later, i - INVERSE_ITEMS);
+            if (dealt) {                                               // the 28 loads behind the 24 MFMAs: two behind each of the first four
+                static_assert(INVERSE_ITEMS + REQUEST_ITEMS == SOLVE_MFMAS + 4, "the loads are dealt out over the MFMAs of the solve");
+                const int first = i < 4 ? 2 * i : i + 4, n_here = i < 4 ? 2 : 1;
+#pragma unroll
+                for (int e = first; e < first + n_here; ++e) {
+                    if (e < INVERSE_ITEMS) {
+                        if (t + 1 < count) request_inverse_item(t + 1, other, e);
+                    } else if (t + 2 < count) {
+                        request_item(t + 2, later, e - INVERSE_ITEMS);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -997,10 +1011,14 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
     bool inverses = Winv != nullptr;
     if (inverses)
         for (int t = 0; t < tiles; ++t) inverses = inverses && ok[t] != 0;          // uniform
-    if (inverses)
-        panel_by_inverses(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, Winv);
-    else
+    // Two workgroups per slab of 64 right-hand sides: through the inverses each takes 32 of them; the substitution, one
+    // lane per right-hand side, is the first one's alone.
+    if (inverses) {
+        const int64_t c0 = (int64_t)(blockIdx.x >> 1) * 64 + (blockIdx.x & 1) * 32;
+        if (c0 < nrhs) panel_by_inverses(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, Winv, c0);
+    } else if ((blockIdx.x & 1) == 0) {
         panel_by_substitution(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, limit);
+    }
 }
 
 struct Solve {
@@ -1072,7 +1090,7 @@ hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
     const int tiles = (int)((r1 - r0) / 64);
     hipError_t launch_err = hipSuccess;
     if (panelw_ok(v))
-        launch_err = launch_kernel(tri_panelw_kernel, grid, dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles,
+        launch_err = launch_kernel(tri_panelw_kernel, dim3(2 * grid.x), dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles,
                                    v.Winv ? v.Winv + r0 / 64 * INV_FLOATS : nullptr, v.ok ? v.ok + r0 / 64 : nullptr, wait_limit());
     else
         launch_err = launch_kernel(tri_panel_kernel, grid, dim3(64), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
@@ -1108,7 +1126,7 @@ int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, void *workspace,
                        hipStream_t s)
 {
-    if (nb < 1 || nb > 128 || (int64_t)((nrhs + 63) / 64) > 0x7fffffff) return hipErrorInvalidValue;
+    if (nb < 1 || nb > 128 || (int64_t)((nrhs + 63) / 64) > 0x3fffffff) return hipErrorInvalidValue;
     Solve v{(const uint16_t *)L, (const float *)B, (float *)X, (uint16_t *)Xh, n, nrhs, nb, s, nullptr, nullptr};
     if (workspace && inverses_wanted(v)) {
         const int64_t full = n / 64;

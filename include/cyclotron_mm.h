@@ -150,7 +150,8 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  *     and the pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
  * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns.  With nb == 64,
  *     nrhs a multiple of 8, n a multiple of 8 and 16-byte aligned L, X, Xh it keeps the inverses of the diagonal
- *     tiles (16 KiB per 64 rows) in the workspace that the library holds per device and stream (allocated or
+ *     tiles (16 KiB per 64 rows) and a second copy of the tiles of L next to the diagonal in the order the
+ *     kernels read them (56 KiB per 64 rows) in the workspace that the library holds per device and stream (allocated or
  *     grown on the call that first needs it, as for cyc_recurrence_matmul); otherwise it allocates nothing.
  *     n == 0 or nrhs == 0: CYC_OK, nothing done.  A zero on the diagonal
  *     gives infinities or NaNs as IEEE division does, not an error.  Inside the kernels, waves hand solved rows

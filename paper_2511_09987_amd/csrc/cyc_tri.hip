@@ -672,6 +672,11 @@ __device__ __forceinline__ void panel_by_substitution(PanelLds &lds, const uint1
 // (an upper bound of kappa taken in the 1-norm, which costs a column sum per lane), and a panel whose tiles do not all pass takes the
 // substitution as before.  Both are deterministic; which one runs depends on L alone.
 constexpr int INV_FLOATS = 64 * 64;        // one inverse in the workspace, in the order described at tri_inverse_kernel
+// The tiles of L that a panel's own product multiplies (tile (T, S), 0 < T - S < PANEL_BAND + 1) are kept a second time in
+// the order in which that product wants them as stationary MFMA operands: eight pieces of 1 KiB per tile, piece
+// 2 w + h: lane l holds the 16 bytes L[64 T + 16 w + l%16][64 S + 32 h + 8 (l/16) .. +7].  Read from L itself such a
+// fragment is 64 separate cache lines per load; from here it is one contiguous KiB.
+constexpr int PANEL_BAND = 7, PACK_PIECES = 8, PACK_BYTES_PER_TILE_ROW = PANEL_BAND * PACK_PIECES * 1024;
 constexpr float INV_NORM_LIMIT = 8.0f;
 
 // One wave per full diagonal tile: lane j solves L_tt y = e_j.  Entry (r, j) of the inverse is stored where the panel
@@ -682,9 +687,18 @@ constexpr float INV_NORM_LIMIT = 8.0f;
 // 4 rb + ks / 4 holding the four k-steps ks / 4 * 4 .. + 3 of all 64 operand lanes ([lane][ks % 4]), so that a wave
 // fetches a piece with one fully coalesced 16-byte load per lane.
 __global__ __launch_bounds__(64) void tri_inverse_kernel(const uint16_t *__restrict__ L, int64_t n, float *__restrict__ Winv,
-                                                         int *__restrict__ ok)
+                                                         int *__restrict__ ok, char *__restrict__ packed, int full)
 {
     constexpr int NB = 64, LDD = NB + 4, cpr = NB / 8, PER_LANE = NB * NB / 8 / 64;
+    if ((int)blockIdx.x >= full) {
+        // the workgroups behind the `full` that invert: one piece each of the operand-order copy (see PANEL_BAND)
+        const int id = (int)blockIdx.x - full, T = id / (PANEL_BAND * PACK_PIECES), rest = id % (PANEL_BAND * PACK_PIECES);
+        const int S = T - 1 - rest / PACK_PIECES, piece = rest % PACK_PIECES, l = threadIdx.x;
+        if (S >= 0)
+            *(uint4 *)(packed + ((int64_t)id * 64 + l) * 16) =
+                *(const uint4 *)(L + ((int64_t)T * 64 + 16 * (piece >> 1) + (l & 15)) * n + (int64_t)S * 64 + 32 * (piece & 1) + 8 * (l >> 4));
+        return;
+    }
     __shared__ __attribute__((aligned(16))) float D[NB][LDD];
     __shared__ float norms[2][64];
     const int lane = threadIdx.x;
@@ -756,7 +770,7 @@ __device__ __forceinline__ constexpr int xb_swizzle(int k) { return ((k >> 3) & 
 
 __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                   float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0, int tiles,
-                                                  const float *__restrict__ Winv, int64_t c0)
+                                                  const float *__restrict__ Winv, int64_t c0, const char *__restrict__ packed)
 {
     // NC: column blocks of 16 per workgroup.  Two (32 right-hand sides), so that a launch has a workgroup for every compute
     // unit and a wave half the work per tile: in the panel's product wave w has rows 16w .. of both column blocks; in the
@@ -778,17 +792,16 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     // What tile u needs from memory, as a list of single loads (so that they can be dealt out between the MFMAs of a
     // solve): items 0 .. 4 NC - 1 its right-hand side, then NKS items for its rows of L (those of the k-steps it has)
     constexpr int REQUEST_ITEMS = 4 * NC + NKS, INVERSE_ITEMS = 6;
-    // Every address is a wave-uniform base plus one of five 32-bit byte offsets of the lane (n, nrhs < 2^26, see
+    // Every address is a wave-uniform base plus a 32-bit byte offset of the lane (n, nrhs < 2^26, see
     // inverses_wanted): the loads then take their base from scalar registers and cost no vector instruction, where 64-bit
     // address arithmetic per lane took ten per load, more than the 32 cycles of the MFMA each load sits behind.
-    uint32_t off_rhs[NC], off_L = 0;
+    uint32_t off_rhs[NC];
     auto lane_offsets = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             const int64_t col = c0 + 16 * j + lq < nrhs ? c0 + 16 * j + lq : nrhs - 1;   // columns past the last one shadow it
             off_rhs[j] = (uint32_t)((int64_t)(4 * g) * nrhs + col) * 4u;
         }
-        off_L = (uint32_t)((int64_t)lq * n + g * 8) * 2u;
     };
     lane_offsets();
     auto request_item = [&](int u, Operands &o, int i) __attribute__((always_inline)) {
@@ -798,7 +811,10 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
             o.rhs[j][r] = *(const float *)((const char *)(Rin + (ru + 16 * w + r) * nrhs) + off_rhs[j]);
         } else {
             const int ks = i - 4 * NC;
-            if (ks < 2 * u) o.a[ks] = *(const i32x4 *)((const char *)(L + (ru + 16 * w) * n + r0 + ks * 32) + off_L);      // uniform condition
+            // (tile (T, S) = (r0 / 64 + u, r0 / 64 + ks / 2), piece 2 w + ks % 2 of the operand-order copy)
+            if (ks < 2 * u)                                                                                             // uniform condition
+                o.a[ks] = *(const i32x4 *)(packed + ((((r0 >> 6) + u) * PANEL_BAND + (u - 1 - ks / 2)) * PACK_PIECES + 2 * w + (ks & 1)) * 1024 +
+                                          (uint32_t)lane * 16u);
         }
     };
     auto request = [&](int u, Operands &o) __attribute__((always_inline)) {
@@ -1005,7 +1021,8 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
 // start at the panel's first tile; Winv == nullptr: no inverses were computed), by substitution otherwise.
 __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restrict__ L, int64_t n, const float *Rin,
                                                          float *X, uint16_t *__restrict__ Xh, int64_t nrhs, int64_t r0,
-                                                         int tiles, const float *__restrict__ Winv, const int *__restrict__ ok, int limit)
+                                                         int tiles, const float *__restrict__ Winv, const int *__restrict__ ok, int limit,
+                                                         const char *__restrict__ packed)
 {
     __shared__ __attribute__((aligned(16))) PanelLds lds;
     bool inverses = Winv != nullptr;
@@ -1015,7 +1032,7 @@ __global__ __launch_bounds__(256) void tri_panelw_kernel(const uint16_t *__restr
     // lane per right-hand side, is the first one's alone.
     if (inverses) {
         const int64_t c0 = (int64_t)(blockIdx.x >> 1) * 64 + (blockIdx.x & 1) * 32;
-        if (c0 < nrhs) panel_by_inverses(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, Winv, c0);
+        if (c0 < nrhs) panel_by_inverses(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, Winv, c0, packed);
     } else if ((blockIdx.x & 1) == 0) {
         panel_by_substitution(lds, L, n, Rin, X, Xh, nrhs, r0, tiles, limit);
     }
@@ -1030,6 +1047,7 @@ struct Solve {
     hipStream_t s;
     const float *Winv;      // inverses of the full diagonal tiles, tile after tile, or nullptr
     const int *ok;          // per tile: the inverse may stand in for the substitution
+    const char *packed;     // the tiles next to the diagonal in operand order (see PANEL_BAND), with Winv
 };
 
 // the running right-hand side of rows that no GEMM has touched yet is still B; afterwards it lives in X
@@ -1091,7 +1109,7 @@ hipError_t panel(const Solve &v, int64_t r0, int64_t r1)
     hipError_t launch_err = hipSuccess;
     if (panelw_ok(v))
         launch_err = launch_kernel(tri_panelw_kernel, dim3(2 * grid.x), dim3(256), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles,
-                                   v.Winv ? v.Winv + r0 / 64 * INV_FLOATS : nullptr, v.ok ? v.ok + r0 / 64 : nullptr, wait_limit());
+                                   v.Winv ? v.Winv + r0 / 64 * INV_FLOATS : nullptr, v.ok ? v.ok + r0 / 64 : nullptr, wait_limit(), v.packed);
     else
         launch_err = launch_kernel(tri_panel_kernel, grid, dim3(64), v.s, v.L, v.n, rhs_of(v, r0), v.X, v.Xh, v.nrhs, r0, tiles);
     return launch_err;
@@ -1119,23 +1137,27 @@ static bool inverses_wanted(const Solve &v)
 
 int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb)
 {
-    Solve v{(const uint16_t *)L, nullptr, (float *)X, (uint16_t *)Xh, n, nrhs, nb, nullptr, nullptr, nullptr};
-    return inverses_wanted(v) ? (n / 64) * (int64_t)(INV_FLOATS * sizeof(float) + sizeof(int)) : 0;
+    Solve v{(const uint16_t *)L, nullptr, (float *)X, (uint16_t *)Xh, n, nrhs, nb, nullptr, nullptr, nullptr, nullptr};
+    // per full tile: its inverse, the operand-order copy of the tiles left of it, its verdict
+    return inverses_wanted(v) ? (n / 64) * (int64_t)(INV_FLOATS * sizeof(float) + PACK_BYTES_PER_TILE_ROW + sizeof(int)) : 0;
 }
 
 hipError_t launch_trsm(const void *L, const void *B, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb, void *workspace,
                        hipStream_t s)
 {
     if (nb < 1 || nb > 128 || (int64_t)((nrhs + 63) / 64) > 0x3fffffff) return hipErrorInvalidValue;
-    Solve v{(const uint16_t *)L, (const float *)B, (float *)X, (uint16_t *)Xh, n, nrhs, nb, s, nullptr, nullptr};
+    Solve v{(const uint16_t *)L, (const float *)B, (float *)X, (uint16_t *)Xh, n, nrhs, nb, s, nullptr, nullptr, nullptr};
     if (workspace && inverses_wanted(v)) {
         const int64_t full = n / 64;
         float *Winv = (float *)workspace;
-        int *ok = (int *)(Winv + full * INV_FLOATS);
-        const hipError_t e = launch_kernel(tri_inverse_kernel, dim3((unsigned)full), dim3(64), s, v.L, n, Winv, ok);
+        char *packed = (char *)(Winv + full * INV_FLOATS);
+        int *ok = (int *)(packed + full * PACK_BYTES_PER_TILE_ROW);
+        const hipError_t e = launch_kernel(tri_inverse_kernel, dim3((unsigned)(full + full * PANEL_BAND * PACK_PIECES)), dim3(64), s, v.L, n, Winv, ok,
+                                           packed, (int)full);
         if (e != hipSuccess) return e;
         v.Winv = Winv;
         v.ok = ok;
+        v.packed = packed;
     }
     return solve(v, 0, n);
 }

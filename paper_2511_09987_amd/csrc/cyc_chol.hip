@@ -822,7 +822,6 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     const bool fused = next_Sm != nullptr && blockIdx.x == 0;          // uniform over the workgroup
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6), lq = lane & 15, g = lane >> 4;
     const int nks_e = fused ? (int)(j0 - k0) / 32 : 0;                 // k-steps of that tile's update that do not involve this panel
-    constexpr int NKS = KMAX / 32;
     f32x4 sv[4], accn[2][4];                                           // its S (this thread's pieces); its update: [slot][column tile]
     // The four 16-row strips of that update: slot si of this wave holds strip(si), or nothing (-1).  Beside the recurrence
     // the three other waves share them (wave 1 takes two).  When the rows may come through the inverse the first wave

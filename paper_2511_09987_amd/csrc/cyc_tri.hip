@@ -845,7 +845,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     // copy (the switches below when the tile number is not one), so that each part is straight-line code in which the
     // streamed operand of a k-step is read two k-steps ahead of its MFMAs.
     f32x4 acc[NC];
-    auto k_range = [&](auto first, auto last, const Operands &o) __attribute__((always_inline)) {
+    auto k_range = [&](auto first, auto last, const Operands &o, auto beside) __attribute__((always_inline)) {
         constexpr int FIRST = decltype(first)::value, LAST = decltype(last)::value;
         i32x4 b[3][NC];
         auto read_b = [&](int ks, i32x4(&dst)[NC]) __attribute__((always_inline)) {
@@ -867,60 +867,79 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
 #pragma unroll
             for (int j = 0; j < NC; ++j)
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, o.a[ks]), __builtin_bit_cast(bf16x8, b[ks % 3][j]), acc[j], 0, 0, 0);
+            beside(ks - FIRST);
         }
     };
-    auto early_of = [&](auto tile_c, const Operands &o) __attribute__((always_inline)) {
+    auto early_of = [&](auto tile_c, const Operands &o, auto beside) __attribute__((always_inline)) {
         constexpr int U = decltype(tile_c)::value;
 #pragma unroll
         for (int j = 0; j < NC; ++j) acc[j] = (f32x4){0, 0, 0, 0};
-        k_range(std::integral_constant<int, 0>{}, std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, o);
+        k_range(std::integral_constant<int, 0>{}, std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, o, beside);
     };
-    auto late_of = [&](auto tile_c, const Operands &o) __attribute__((always_inline)) {
+    auto late_of = [&](auto tile_c, const Operands &o, auto beside) __attribute__((always_inline)) {
         constexpr int U = decltype(tile_c)::value;
-        k_range(std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, std::integral_constant<int, 2 * U>{}, o);
+        k_range(std::integral_constant<int, U >= 1 ? 2 * U - 2 : 0>{}, std::integral_constant<int, 2 * U>{}, o, beside);
 #pragma unroll
         for (int j = 0; j < NC; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) lds.R[16 * w + 4 * g + r][16 * j + lq] = o.rhs[j][r] - acc[j][r];
     };
     // (u is uniform and at most PANELW - 1; when the caller's tile number is a constant the switch folds away)
-    auto stage_early = [&](int u, const Operands &o) __attribute__((always_inline)) {
+    auto stage_early = [&](int u, const Operands &o, auto beside) __attribute__((always_inline)) {
         switch (u) {
-            case 0: early_of(std::integral_constant<int, 0>{}, o); break;
-            case 1: early_of(std::integral_constant<int, 1>{}, o); break;
-            case 2: early_of(std::integral_constant<int, 2>{}, o); break;
-            case 3: early_of(std::integral_constant<int, 3>{}, o); break;
-            case 4: early_of(std::integral_constant<int, 4>{}, o); break;
-            case 5: early_of(std::integral_constant<int, 5>{}, o); break;
-            case 6: early_of(std::integral_constant<int, 6>{}, o); break;
-            default: early_of(std::integral_constant<int, PANELW - 1>{}, o); break;
+            case 0: early_of(std::integral_constant<int, 0>{}, o, beside); break;
+            case 1: early_of(std::integral_constant<int, 1>{}, o, beside); break;
+            case 2: early_of(std::integral_constant<int, 2>{}, o, beside); break;
+            case 3: early_of(std::integral_constant<int, 3>{}, o, beside); break;
+            case 4: early_of(std::integral_constant<int, 4>{}, o, beside); break;
+            case 5: early_of(std::integral_constant<int, 5>{}, o, beside); break;
+            case 6: early_of(std::integral_constant<int, 6>{}, o, beside); break;
+            default: early_of(std::integral_constant<int, PANELW - 1>{}, o, beside); break;
         }
     };
-    auto stage_late = [&](int u, const Operands &o) __attribute__((always_inline)) {
+    auto stage_late = [&](int u, const Operands &o, auto beside) __attribute__((always_inline)) {
         switch (u) {
-            case 0: late_of(std::integral_constant<int, 0>{}, o); break;
-            case 1: late_of(std::integral_constant<int, 1>{}, o); break;
-            case 2: late_of(std::integral_constant<int, 2>{}, o); break;
-            case 3: late_of(std::integral_constant<int, 3>{}, o); break;
-            case 4: late_of(std::integral_constant<int, 4>{}, o); break;
-            case 5: late_of(std::integral_constant<int, 5>{}, o); break;
-            case 6: late_of(std::integral_constant<int, 6>{}, o); break;
-            default: late_of(std::integral_constant<int, PANELW - 1>{}, o); break;
+            case 0: late_of(std::integral_constant<int, 0>{}, o, beside); break;
+            case 1: late_of(std::integral_constant<int, 1>{}, o, beside); break;
+            case 2: late_of(std::integral_constant<int, 2>{}, o, beside); break;
+            case 3: late_of(std::integral_constant<int, 3>{}, o, beside); break;
+            case 4: late_of(std::integral_constant<int, 4>{}, o, beside); break;
+            case 5: late_of(std::integral_constant<int, 5>{}, o, beside); break;
+            case 6: late_of(std::integral_constant<int, 6>{}, o, beside); break;
+            default: late_of(std::integral_constant<int, PANELW - 1>{}, o, beside); break;
         }
     };
     // results of tile v: 16-byte pieces from LDS (Xs: the buffer of v's parity) to X and Xh
-    auto store = [&](int v, const float(*Xs)[NB + 4]) __attribute__((always_inline)) {
-        const int64_t rv = r0 + (int64_t)v * NB;
+    // (in two steps, so that the reads of LDS and the stores can be placed apart)
+    constexpr int X_PIECES = NB * 4 * NC / NT;
+    struct Results {
+        f32x4 x[X_PIECES];
+        uint4 xh;
+    };
+    auto fetch_results = [&](int v, const float(*Xs)[NB + 4], Results &res) __attribute__((always_inline)) {
 #pragma unroll
-        for (int p = 0; p < NB * 4 * NC / NT; ++p) {
+        for (int p = 0; p < X_PIECES; ++p) {
             const int id = tid + NT * p, r = id / (4 * NC), ch = id % (4 * NC);
-            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = *(const f32x4 *)&Xs[r][4 * ch];
+            res.x[p] = *(const f32x4 *)&Xs[r][4 * ch];
         }
         static_assert(NB * 2 * NC == NT, "one 16-byte piece of Xh per thread");
-        {
-            const int r = tid / (2 * NC), ch = tid % (2 * NC);
-            if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = *(const uint4 *)&lds.Xb[v * NB + r][8 * (ch ^ xb_swizzle(r))];
+        const int r = tid / (2 * NC), ch = tid % (2 * NC);
+        res.xh = *(const uint4 *)&lds.Xb[v * NB + r][8 * (ch ^ xb_swizzle(r))];
+    };
+    auto put_results = [&](int v, const Results &res) __attribute__((always_inline)) {
+        const int64_t rv = r0 + (int64_t)v * NB;
+#pragma unroll
+        for (int p = 0; p < X_PIECES; ++p) {
+            const int id = tid + NT * p, r = id / (4 * NC), ch = id % (4 * NC);
+            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = res.x[p];
         }
+        const int r = tid / (2 * NC), ch = tid % (2 * NC);
+        if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = res.xh;
+    };
+    auto store = [&](int v, const float(*Xs)[NB + 4]) __attribute__((always_inline)) {
+        Results res;
+        fetch_results(v, Xs, res);
+        put_results(v, res);
     };
     // X_t = L_tt^-1 R_t for the wave's 16 columns (block sc) and its two row blocks.  A operand lane l: row 16 rb + l%16,
     // k = k(ks, l/16) as laid down at tri_inverse_kernel; B operand: the same k, column l%16; accumulator register r: row
@@ -968,37 +987,90 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         g = lane >> 4;
         lane_offsets();
         touch(mine, next);
-        if (t > 0) store(t - 1, Xs_before);
+        if (t > 0 && !dealt) store(t - 1, Xs_before);
         if (!dealt) {
             if (t + 1 < count) request_inverse(t + 1, other);
             if (t + 2 < count) request(t + 2, later);
         }
-        if (t + 1 < count) stage_early(t + 1, next);
-        solve(t, mine, Xs, [&](int i) __attribute__((always_inline)) {
-            if (dealt) {                                               // the 28 loads behind the 24 MFMAs: two behind each of the first four
-                static_assert(INVERSE_ITEMS + REQUEST_ITEMS == SOLVE_MFMAS + 4, "the loads are dealt out over the MFMAs of the solve");
-                const int first = i < 4 ? 2 * i : i + 4, n_here = i < 4 ? 2 : 1;
-#pragma unroll
-                for (int e = first; e < first + n_here; ++e) {
-                    if (e < INVERSE_ITEMS) {
-                        if (t + 1 < count) request_inverse_item(t + 1, other, e);
-                    } else if (t + 2 < count) {
-                        request_item(t + 2, later, e - INVERSE_ITEMS);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        // `dealt`: the loads of later tiles (item e: 0 .. 5 the inverse of tile t + 1; then tile t + 2's right-hand side, 8
+        // items, and its rows of L, item 14 + ks for k-step ks) are spread over the whole tile, one behind a k-step's or a
+        // solve step's MFMAs and pinned there: the memory pipeline of the compute unit takes 16 cycles per KiB, and a wave
+        // that issues loads faster than that stalls in front of whatever comes next.  Rows of L: the first 2 t behind the
+        // k-steps of the product ahead, the last four (k-steps 2 t .. 2 t + 3) behind the two late k-steps; the inverse and
+        // the right-hand side behind the first 14 MFMAs of the solve.
+        auto load_item = [&](int e) __attribute__((always_inline)) {
+            if (e < INVERSE_ITEMS) {
+                if (t + 1 < count) request_inverse_item(t + 1, other, e);
+            } else if (t + 2 < count && e < INVERSE_ITEMS + REQUEST_ITEMS) {
+                request_item(t + 2, later, e - INVERSE_ITEMS);
             }
+        };
+        constexpr int L_ITEMS_FROM = INVERSE_ITEMS + 4 * NC;
+        static_assert(L_ITEMS_FROM <= SOLVE_MFMAS, "the inverse and the right-hand side fit behind the MFMAs of the solve");
+        auto nothing = [](int) __attribute__((always_inline)) {};
+        if (t + 1 < count) {
+            if (dealt)
+                stage_early(t + 1, next, [&](int i) __attribute__((always_inline)) {
+                    load_item(L_ITEMS_FROM + i);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            else
+                stage_early(t + 1, next, nothing);
+        }
+        // the previous tile's results go to memory from behind the solve's later MFMAs: read from LDS at one, stored at
+        // another (nothing writes that tile's buffers before the next barrier)
+        constexpr int FETCH_AT = L_ITEMS_FROM + 1, PUT_AT = FETCH_AT + 5;
+        static_assert(PUT_AT < SOLVE_MFMAS, "the stores have an MFMA to sit behind");
+        Results before;
+        solve(t, mine, Xs, [&](int i) __attribute__((always_inline)) {
+            if (!dealt) return;
+            if (i < L_ITEMS_FROM) load_item(i);
+            if (i == FETCH_AT && t > 0) fetch_results(t - 1, Xs_before, before);
+            if (i == PUT_AT && t > 0) put_results(t - 1, before);
+            __builtin_amdgcn_sched_barrier(0);
         });
         __syncthreads();                                               // tile t is solved: R is free, Xs and Xb complete
-        if (t + 1 < count) stage_late(t + 1, next);
+        if (t + 1 < count) {
+            if (dealt)
+                stage_late(t + 1, next, [&](int i) __attribute__((always_inline)) {
+                    load_item(L_ITEMS_FROM + 2 * t + 2 * i);
+                    load_item(L_ITEMS_FROM + 2 * t + 2 * i + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            else
+                stage_late(t + 1, next, nothing);
+        }
         __syncthreads();                                               // tile t + 1 is staged
     };
 
     request(0, op0);
     request_inverse(0, inv0);
     if (tiles > 1) request(1, op1);
-    stage_early(0, op0);
-    stage_late(0, op0);
+    // Every workgroup reads the same inverses and the same tiles of L, all of them at about the same time: whichever
+    // asks first for a line that the cache of its part of the chip (32 compute units, workgroup numbers congruent modulo
+    // 8) does not hold yet waits for memory, and so do all the others.  So the workgroups of such a part fetch the panel's
+    // inverses and operand-order tiles once at the start, 4 KiB pieces dealt out among them; the values are not used.
+    constexpr int WARM = 3;
+    i32x4 warm[WARM];
+    {
+        const int parts = 8, sharers = ((int)gridDim.x + parts - 1) / parts, me = (int)blockIdx.x / parts;
+        const int n_inv = 4 * tiles, n_all = n_inv + tiles * (tiles - 1);          // tile u of the panel: 2 u pieces of L
+#pragma unroll
+        for (int i = 0; i < WARM; ++i) {
+            int c = me + i * sharers;                                              // uniform
+            const char *src = (const char *)Winv;
+            if (c < n_inv) {
+                src += (int64_t)c * 4096;
+            } else if (c < n_all) {
+                int d = c - n_inv, u = 1;
+                while (d >= 2 * u) { d -= 2 * u; ++u; }
+                src = packed + (((r0 >> 6) + u) * PANEL_BAND * PACK_PIECES) * 1024 + (int64_t)d * 4096;
+            }
+            warm[i] = *(const i32x4 *)(src + (uint32_t)tid * 16u);
+        }
+    }
+    stage_early(0, op0, [](int) {});
+    stage_late(0, op0, [](int) {});
     __syncthreads();
     if (tiles == PANELW) {
         // the usual case, every tile number a constant: each tile is straight-line code between its barriers
@@ -1015,6 +1087,8 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         }
     }
     store(tiles - 1, (tiles - 1) & 1 ? lds.D : lds.Xs);
+    asm volatile("" :: "v"(warm[0]), "v"(warm[1]), "v"(warm[2]));
+    static_assert(WARM == 3, "every register of warm is named above");
 }
 
 // The four-wave panel: through the inverses when every tile of the panel passed tri_inverse_kernel's check (Winv and ok

@@ -792,7 +792,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     // What tile u needs from memory, as a list of single loads (so that they can be dealt out between the MFMAs of a
     // solve): items 0 .. 4 NC - 1 its right-hand side, then NKS items for its rows of L (those of the k-steps it has)
     constexpr int REQUEST_ITEMS = 4 * NC + NKS, INVERSE_ITEMS = 6;
-    // Every address is a wave-uniform base plus a 32-bit byte offset of the lane (n, nrhs < 2^26, see
+    // Every address is a wave-uniform base plus a 32-bit byte offset of the lane (n < 2^26, nrhs < 2^24, see
     // inverses_wanted): the loads then take their base from scalar registers and cost no vector instruction, where 64-bit
     // address arithmetic per lane took ten per load, more than the 32 cycles of the MFMA each load sits behind.
     uint32_t off_rhs[NC];
@@ -804,11 +804,15 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         }
     };
     lane_offsets();
-    auto request_item = [&](int u, Operands &o, int i) __attribute__((always_inline)) {
-        const int64_t ru = r0 + (int64_t)u * NB;
+    // (rows: the wave's first row of tile u's right-hand side, row r0 + 64 u + 16 w.  In the unrolled tiles it is a running
+    // pointer: multiplied out per row from the tile number, each load took a dozen scalar instructions of address arithmetic)
+    const int64_t row_bytes = nrhs * 4;
+    auto rhs_rows_of = [&](int u) __attribute__((always_inline)) { return (const char *)(Rin + (r0 + (int64_t)u * NB + 16 * w) * nrhs); };
+    const char *later_rows = rhs_rows_of(2);                           // (of tile t + 2 while tile t runs, in the unrolled tiles)
+    auto request_item = [&](int u, Operands &o, int i, const char *rows) __attribute__((always_inline)) {
         if (i < 4 * NC) {
             const int j = i >> 2, r = i & 3;
-            o.rhs[j][r] = *(const float *)((const char *)(Rin + (ru + 16 * w + r) * nrhs) + off_rhs[j]);
+            o.rhs[j][r] = *(const float *)(rows + r * row_bytes + off_rhs[j]);
         } else {
             const int ks = i - 4 * NC;
             // (tile (T, S) = (r0 / 64 + u, r0 / 64 + ks / 2), piece 2 w + ks % 2 of the operand-order copy)
@@ -819,7 +823,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
     };
     auto request = [&](int u, Operands &o) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < REQUEST_ITEMS; ++i) request_item(u, o, i);
+        for (int i = 0; i < REQUEST_ITEMS; ++i) request_item(u, o, i, rhs_rows_of(u));
     };
     // the wave's pieces of an inverse: item p < 2 is piece (rbA, p), item p >= 2 piece (rbB, p - 2)
     auto request_inverse_item = [&](int u, f32x4(&iv)[6], int p) __attribute__((always_inline)) {
@@ -926,15 +930,17 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
         const int r = tid / (2 * NC), ch = tid % (2 * NC);
         res.xh = *(const uint4 *)&lds.Xb[v * NB + r][8 * (ch ^ xb_swizzle(r))];
     };
+    // (the thread's place in a tile of X and of Xh as 32-bit offsets from a uniform base, worked out once: nrhs < 2^24)
+    static_assert(4 * NC == 8 && NT / (4 * NC) == 32, "piece p of X: row tid / 8 + 32 p, columns 4 (tid % 8) ..");
+    const uint32_t put_x = (((uint32_t)threadIdx.x >> 3) * (uint32_t)nrhs + 4 * (threadIdx.x & 7)) * 4u;
+    const uint32_t put_xh = (((uint32_t)threadIdx.x >> 2) * (uint32_t)nrhs + 8 * (threadIdx.x & 3)) * 2u;
+    const bool put_x_ok = c0 + 4 * (threadIdx.x & 7) < nrhs, put_xh_ok = c0 + 8 * (threadIdx.x & 3) < nrhs;
     auto put_results = [&](int v, const Results &res) __attribute__((always_inline)) {
         const int64_t rv = r0 + (int64_t)v * NB;
 #pragma unroll
-        for (int p = 0; p < X_PIECES; ++p) {
-            const int id = tid + NT * p, r = id / (4 * NC), ch = id % (4 * NC);
-            if (c0 + 4 * ch < nrhs) *(f32x4 *)(X + (rv + r) * nrhs + c0 + 4 * ch) = res.x[p];
-        }
-        const int r = tid / (2 * NC), ch = tid % (2 * NC);
-        if (c0 + 8 * ch < nrhs) *(uint4 *)(Xh + (rv + r) * nrhs + c0 + 8 * ch) = res.xh;
+        for (int p = 0; p < X_PIECES; ++p)
+            if (put_x_ok) *(f32x4 *)((char *)(X + (rv + 32 * p) * nrhs + c0) + put_x) = res.x[p];
+        if (put_xh_ok) *(uint4 *)((char *)(Xh + rv * nrhs + c0) + put_xh) = res.xh;
     };
     auto store = [&](int v, const float(*Xs)[NB + 4]) __attribute__((always_inline)) {
         Results res;
@@ -1002,7 +1008,7 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
             if (e < INVERSE_ITEMS) {
                 if (t + 1 < count) request_inverse_item(t + 1, other, e);
             } else if (t + 2 < count && e < INVERSE_ITEMS + REQUEST_ITEMS) {
-                request_item(t + 2, later, e - INVERSE_ITEMS);
+                request_item(t + 2, later, e - INVERSE_ITEMS, later_rows);
             }
         };
         constexpr int L_ITEMS_FROM = INVERSE_ITEMS + 4 * NC;
@@ -1041,6 +1047,10 @@ __device__ __forceinline__ void panel_by_inverses(PanelLds &lds, const uint16_t 
                 stage_late(t + 1, next, nothing);
         }
         __syncthreads();                                               // tile t + 1 is staged
+        if (dealt) {
+            later_rows += NB * row_bytes;
+            asm volatile("" : "+s"(later_rows));                       // (stays a running pointer)
+        }
     };
 
     request(0, op0);
@@ -1206,7 +1216,7 @@ hipError_t solve(const Solve &v, int64_t r0, int64_t r1)
 // the diagonal tiles are worth inverting ahead: the four-wave panel kernel will run, on tiles of 64 rows
 static bool inverses_wanted(const Solve &v)
 {
-    return v.nb == 64 && v.n >= 64 && panelw_ok(v) && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0 && v.n < (1 << 26) && v.nrhs < (1 << 26);
+    return v.nb == 64 && v.n >= 64 && panelw_ok(v) && (uintptr_t)v.L % 16 == 0 && v.n % 8 == 0 && v.n < (1 << 26) && v.nrhs < (1 << 24);
 }
 
 int64_t trsm_workspace_bytes(const void *L, void *X, void *Xh, int64_t n, int64_t nrhs, int64_t nb)

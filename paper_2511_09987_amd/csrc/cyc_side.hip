@@ -23,8 +23,8 @@ SideStream *SideStreamLock::acquire()
         if (!v->tried) {
             v->tried = true;
             v->ok = hipStreamCreateWithFlags(&v->stream, hipStreamNonBlocking) == hipSuccess &&
-                    hipEventCreateWithFlags(&v->fork, hipEventDisableTiming) == hipSuccess;
-            for (hipEvent_t &e : v->join) v->ok = v->ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+                    hipEventCreateWithFlags(&v->fork, hipEventDisableTiming | hipEventDisableSystemFence) == hipSuccess;
+            for (hipEvent_t &e : v->join) v->ok = v->ok && hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventDisableSystemFence) == hipSuccess;
             if (!v->ok) (void)hipGetLastError();
         }
         if (!v->ok) v = nullptr;

@@ -149,7 +149,7 @@ int cyc_recurrence_matmul_batched(const void *A, const void *B, void *C,
  * nb: tile size, 1 <= nb <= 128.  The MFMA kernels serve the GEMMs when n, nrhs and nb are multiples of 8
  *     and the pointers are 16-byte aligned; otherwise a slower shape-agnostic kernel does.
  * stream: hipStream_t or NULL.  The call enqueues a sequence of kernels on it and returns.  With nb == 64,
- *     nrhs a multiple of 8, n a multiple of 8 and 16-byte aligned L, X, Xh it keeps the inverses of the diagonal
+ *     nrhs a multiple of 8 below 2^24, n a multiple of 8 below 2^26 and 16-byte aligned L, X, Xh it keeps the inverses of the diagonal
  *     tiles (16 KiB per 64 rows) and a second copy of the tiles of L next to the diagonal in the order the
  *     kernels read them (56 KiB per 64 rows) in the workspace that the library holds per device and stream (allocated or
  *     grown on the call that first needs it, as for cyc_recurrence_matmul); otherwise it allocates nothing.

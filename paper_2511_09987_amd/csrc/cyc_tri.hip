@@ -749,18 +749,18 @@ __global__ __launch_bounds__(64) void tri_inverse_kernel(const uint16_t *__restr
     }
 }
 
-// The panel of tri_panelw_kernel with the diagonal solves as products with the inverses.  The four waves share the
-// slab as there: wave w multiplies out rows 16w .. 16w+15 of the panel's product for the next tile and stores a quarter
-// of the results.  In the solve wave w takes the COLUMNS 16w .. 16w+15 of the slab and all 64 rows: the inverse is
-// lower triangular, so row block rb needs the k-steps 0 .. 4 rb + 3 only, 40 MFMAs per wave and tile whichever wave,
-// and the streamed operand (R, [row][column] in LDS) is one LDS read per k-step.
+// The panel of tri_panelw_kernel with the diagonal solves as products with the inverses, for 32 right-hand sides (two
+// column blocks of 16).  In the panel's product for the next tile wave w multiplies out rows 16w .. 16w+15 of both
+// column blocks; in the solve it takes one column block and two of the four row blocks of 16 (see NC below): the
+// inverse is lower triangular, so row block rb needs the k-steps 0 .. 4 rb + 3 only, and the streamed operand (R,
+// [row][column] in LDS) is one LDS read per k-step.
 // Memory traffic is arranged around one wait per tile.  On this chip loads and stores share one counter and complete
 // out of order with respect to each other, so while both are outstanding the only wait the compiler can insert is
-// the wait for all of them.  Everything a tile issues to memory -- the stores of the previous tile's results, the
-// loads of the next tile's inverse and of the right-hand side and rows of L of the tile after that -- is therefore
-// issued at the top of the tile, and what was loaded is first touched (an empty asm statement that names the
-// registers) at the top of the tile in which it is used, a whole tile later, when it has long arrived.  Hence two
-// register sets for everything loaded, and two tiles per loop trip so that the sets are named statically.
+// the wait for all of them.  What a tile issues to memory -- the stores of the previous tile's results, the loads of
+// the next tile's inverse and of the right-hand side and rows of L of the tile after that -- is never waited for
+// inside that tile: what was loaded is first touched (an empty asm statement that names the registers) at the top of
+// the tile in which it is used, a whole tile later, when it has arrived.  Hence two register sets for everything
+// loaded, and two tiles per loop trip so that the sets are named statically.
 // Placement of the solved tiles in panel_by_inverses: row k of Xb (128 bytes: eight 16-byte chunks of eight columns) keeps
 // its chunk q in slot q ^ xb_swizzle(k).  One transposing read takes 8 bytes per lane from the rows 8 (l/16) + 0 .. 3 of a
 // k-step, two adjacent chunks of each: unswizzled those are sixteen rows whose chunks lie on the same 16 of the 64 banks

@@ -60,7 +60,9 @@ SHAPES = [(64, 64, 64), (256, 128, 64), (1000, 72, 64), (1024, 512, 128), (520, 
           (37, 5, 8), (130, 33, 16), (100, 40, 10), (1, 1, 64), (1, 70, 64), (200, 1, 64), (129, 64, 128),
           # panels of 5, 7, 8 tiles, 9 = 5 + 4 and 13 = 7 + 6 tiles in the four-wave kernel (nrhs a multiple of 8, the
           # last slab partly filled); 3 and 6 tiles in the one-wave kernel (nrhs not a multiple of 8)
-          (320, 72, 64), (448, 136, 64), (512, 64, 64), (576, 80, 64), (832, 200, 64), (192, 70, 64), (384, 61, 64)]
+          (320, 72, 64), (448, 136, 64), (512, 64, 64), (576, 80, 64), (832, 200, 64), (192, 70, 64), (384, 61, 64),
+          # 16 and 32 tiles: two and four full panels with the smallest products between them, a partly filled last slab
+          (1024, 72, 64), (1024, 200, 64), (2048, 40, 64)]
 
 
 @pytest.mark.parametrize("n,nrhs,nb", SHAPES)
@@ -80,7 +82,8 @@ def skeel(L64):
 
 
 @pytest.mark.parametrize("n,nrhs,nb", [(512, 256, 64), (1024, 512, 128), (300, 100, 32), (1000, 136, 64), (77, 19, 16),
-                                       (448, 72, 64), (576, 264, 64), (384, 70, 64)])
+                                       (448, 72, 64), (576, 264, 64), (384, 70, 64),
+                                       (1024, 264, 64), (1024, 40, 64), (2048, 72, 64)])   # full panels through the inverses with products between them
 def test_real_data_against_oracle(lib, tri, n, nrhs, nb):
     L = ws_inputs.tri_lower_bf16(n, 50 + n, 0, DEV, upper=float("nan"))     # NaN above the diagonal: never read
     B = ws_inputs.normal_f32((n, nrhs), 1.0, 50 + n, 1, DEV)

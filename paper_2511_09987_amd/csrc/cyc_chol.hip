@@ -773,7 +773,7 @@ __global__ __launch_bounds__(NT) void chol_diag_kernel(const float *Sm, float *L
 __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *L, uint16_t *Lh, int64_t n, int64_t j0, int cols,
                                                         int64_t k0, const float *next_Sm, const float *__restrict__ Win,
                                                         const int *__restrict__ okin, float *Wout, int *okout, const float *Dcopy,
-                                                        float *next_copy, int limit)
+                                                        float *next_copy, int limit, int64_t k0_first, int ahead)
 {
     // one block, D and X first (see diag_tile)
     __shared__ __attribute__((aligned(16))) struct {
@@ -788,6 +788,30 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     auto &Bs = lds.Bs;
     auto &Bs2 = lds.Bs2;
     const int tid = threadIdx.x, lane = tid & 63;
+    // ahead != 0: the last two workgroups of the launch work for the NEXT launch's first workgroup, the one that everything
+    // waits for.  Its two tiles, rows j1 + 64 .. of the column blocks j1 and j1 + 64 (its own rows and the diagonal tile that
+    // rides along with it), lose the terms of the group's panels left of this one here, in place in S, while this launch
+    // runs; that workgroup then starts at k = j0 (its k0_first) instead of at the group's first column, with a quarter of
+    // the operands to fetch and two k-steps of each product instead of up to fourteen.  (Per entry the terms are then
+    // subtracted in two chains, not one.)  Nothing else in this launch reads or writes those two tiles.
+    const int row_blocks = (int)gridDim.x - (ahead ? 2 : 0);
+    if ((int)blockIdx.x >= row_blocks) {
+        const int64_t row0 = j0 + cols + NBMAX, col0 = j0 + cols + ((int)blockIdx.x - row_blocks) * NBMAX;
+        float *tile = L + row0 * n + col0;                                 // (S of a later group's panels lives in L)
+        TileProduct product;
+        TileLoad of_S;
+        product.request(Bs, Lh, n, row0, NBMAX, k0, j0, col0, tid);
+        of_S.request(tile, n, NBMAX, NBMAX, tid);
+        of_S.place(X, tile, n, NBMAX, NBMAX, tid);
+        product.apply(X, Bs, tid);
+#pragma unroll
+        for (int i = 0; i < NBMAX * 16 / NT; ++i) {
+            const int r = NT / 16 * i + (tid >> 4);
+            *(f32x4 *)(tile + (int64_t)r * n + 4 * (tid & 15)) = *(const f32x4 *)&X[r][4 * (tid & 15)];
+        }
+        return;
+    }
+    if (blockIdx.x == 0) k0 = k0_first;                                    // uniform (see above)
     if (tid < 3) lds.dl.sync[tid] = 0;
     const bool solver = tid < 64;                         // the wave that runs the recurrence
     // The rows of this workgroup through the inverse of L_jj?  W and its verdict are requested here with everything
@@ -870,7 +894,7 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
     // (nks_e > 0 implies k0 < j0: apply waits for every copy of this wave, Bs2's included, before its barrier)
     if (k0 < j0) product.apply(X, Bs, tid, rows_in_lds ? Bs2 : nullptr);
     else __syncthreads();
-    if (Dcopy && blockIdx.x == gridDim.x - 1) (void)store_tile<true>(D, L + j0 * n + j0, Lh + j0 * n + j0, n, cols, cols, tid);
+    if (Dcopy && (int)blockIdx.x == row_blocks - 1) (void)store_tile<true>(D, L + j0 * n + j0, Lh + j0 * n + j0, n, cols, cols, tid);
     const bool by_inverse = may_invert && __builtin_amdgcn_readfirstlane(verdict) != 0;
 #pragma unroll
     for (int si = 0; si < 2; ++si)
@@ -1159,6 +1183,7 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
         return tile ? launch_mfma(p, tile, 16, on) : launch_generic(p, on);
     };
     bool diag_done = false;           // the diagonal tile of this panel was factored by the rows kernel of the panel before
+    int64_t prepared_from = -1;       // >= 0: the launch before took the k range [k0, prepared_from) out of this launch's first workgroup's tiles
     bool copied = false;              // ... across a group boundary: L_jj is to be read from the copy in the workspace
     // the side stream is worth its events only when there are at least three groups
     SideStreamLock side_lock;
@@ -1237,11 +1262,18 @@ hipError_t launch_chol(const void *A_, void *L_, void *Lh_, int64_t n, int64_t n
                 if (hipError_t e = hipStreamWaitEvent(s, side->join[0], 0); e != hipSuccess) return fail(e);
                 unjoined = false;
             }
-            hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64)), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
+            // (see `ahead` in the kernel: the next launch is a fused one of this group, not its last, S is in L, and there is
+            // something left of this panel to take out)
+            const bool prepare = fuse && g0 > 0 && j0 > g0 && j1 + NBMAX < g0 + GROUP * nb && j1 + 2 * NBMAX <= n;
+            if (prepared_from >= 0 && !(fuse && k0 == g0 && prepared_from == j0 - NBMAX)) return fail(hipErrorUnknown);
+            const int64_t k0_first = prepared_from >= 0 ? prepared_from : k0;
+            hipError_t e = launch_kernel(chol_panel_kernel, dim3((unsigned)((n - j1 + 63) / 64 + (prepare ? 2 : 0))), dim3(NT), s, Sm, L, Lh, n, j0, cols, k0,
                                fuse ? (g0 > 0 ? (const float *)L : A) : (const float *)nullptr, (const float *)W_of(j0, cols),
                                (const int *)ok_of(j0, cols), fuse ? W_of(j1, NBMAX) : (float *)nullptr, fuse ? ok_of(j1, NBMAX) : (int *)nullptr,
-                               copied ? (const float *)tile_copy : (const float *)nullptr, fuse && next_group ? tile_copy : (float *)nullptr, wait_limit());
+                               copied ? (const float *)tile_copy : (const float *)nullptr, fuse && next_group ? tile_copy : (float *)nullptr, wait_limit(),
+                               k0_first, prepare ? 1 : 0);
             if (e != hipSuccess) return fail(e);
+            prepared_from = prepare ? j0 : -1;
             diag_done = fuse;
             copied = fuse && next_group;
         }

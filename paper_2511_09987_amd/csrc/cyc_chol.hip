@@ -926,19 +926,28 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
 #pragma unroll
                 for (int j = 0; j < 4; ++j) dst[1 + j] = staged_fragment(Bs2, ks, j, lq, g);
             };
-            if (early) read_step(0, f[0]);
+            // (The usual numbers of such k-steps, none and two, have a copy of the loop each in which they are constants:
+            // as conditions at run time they cut every step of the product into pieces that wait for their own reads.)
+            auto product_loop = [&](auto steps_c) __attribute__((always_inline)) {
+                constexpr int NE = decltype(steps_c)::value;                    // that many k-steps, or -1: nks_e of them
+                auto has = [&](int ks) __attribute__((always_inline)) { return NE >= 0 ? ks < NE : early && ks < nks_e; };
+                if (has(0)) read_step(0, f[0]);
 #pragma unroll
-            for (int ks = 0; ks < 16; ++ks) {
-                if (early && ks + 1 < nks_e) read_step(ks + 1, f[(ks + 1) & 1]);
+                for (int ks = 0; ks < 16; ++ks) {
+                    if (has(ks + 1)) read_step(ks + 1, f[(ks + 1) & 1]);
 #pragma unroll
-                for (int cb = ks / 4; cb < 4; ++cb)
-                    xo[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(sa[ks], winv[cb * (cb + 1) / 2 + ks / 4][ks % 4], xo[cb], 0, 0, 0);
-                if (early && ks < nks_e) {
+                    for (int cb = ks / 4; cb < 4; ++cb)
+                        xo[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(sa[ks], winv[cb * (cb + 1) / 2 + ks / 4][ks % 4], xo[cb], 0, 0, 0);
+                    if (has(ks)) {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        accn[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f[ks & 1][0]), __builtin_bit_cast(bf16x8, f[ks & 1][1 + j]), accn[0][j], 0, 0, 0);
+                        for (int j = 0; j < 4; ++j)
+                            accn[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f[ks & 1][0]), __builtin_bit_cast(bf16x8, f[ks & 1][1 + j]), accn[0][j], 0, 0, 0);
+                    }
                 }
-            }
+            };
+            if (!early) product_loop(std::integral_constant<int, 0>{});
+            else if (nks_e == 2) product_loop(std::integral_constant<int, 2>{});
+            else product_loop(std::integral_constant<int, -1>{});
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb)
 #pragma unroll

@@ -66,6 +66,11 @@ __device__ __forceinline__ float chain(float t, const float *x, const float *y, 
 
 // fp32 -> bfloat16 bit pattern, round to nearest, ties to even; NaN stays NaN (the hardware conversion)
 __device__ __forceinline__ uint16_t round_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+// two values rounded and packed (a in the low half) by one conversion instruction, where rounding them one by one and
+// joining the halves takes four
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) { return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2_t){a, b}, bf16x2_t)); }
 
 // The same for the diagonal tile, where row c of L is what lane c has just computed.  The chains of block b read the
 // rows 4b .. 4b+3 of L from LDS, where every lane writes its finished columns; the step over the columns of block k4 can
@@ -169,10 +174,10 @@ __device__ __forceinline__ bool store_tile(const float (*src)[LDT], float *L, ui
     for (int i = 0; i < PH; ++i) {
         const int r = NTH / 8 * i + (tid >> 3);
         const f32x4 a = *(const f32x4 *)&src[r][8 * (tid & 7)], b = *(const f32x4 *)&src[r][8 * (tid & 7) + 4];
-        h[i][0] = round_bf16(a[0]) | ((unsigned)round_bf16(a[1]) << 16);
-        h[i][1] = round_bf16(a[2]) | ((unsigned)round_bf16(a[3]) << 16);
-        h[i][2] = round_bf16(b[0]) | ((unsigned)round_bf16(b[1]) << 16);
-        h[i][3] = round_bf16(b[2]) | ((unsigned)round_bf16(b[3]) << 16);
+        h[i][0] = pack_bf16(a[0], a[1]);
+        h[i][1] = pack_bf16(a[2], a[3]);
+        h[i][2] = pack_bf16(b[0], b[1]);
+        h[i][3] = pack_bf16(b[2], b[3]);
     }
 #pragma unroll
     for (int i = 0; i < PL; ++i) {
@@ -198,7 +203,7 @@ __device__ __forceinline__ void store_mirror(const float (*src)[LDT], uint16_t *
     uint32_t packed[ROWS / 2];
 #pragma unroll
     for (int i = 0; i < ROWS / 2; ++i)
-        packed[i] = (uint32_t)round_bf16(src[r0 + 2 * i][c]) | ((uint32_t)round_bf16(src[r0 + 2 * i + 1][c]) << 16);
+        packed[i] = pack_bf16(src[r0 + 2 * i][c], src[r0 + 2 * i + 1][c]);
     uint4 *out = (uint4 *)(dst + (int64_t)c * ld + r0);
 #pragma unroll
     for (int i = 0; i < ROWS / 8; ++i) out[i] = make_uint4(packed[4 * i], packed[4 * i + 1], packed[4 * i + 2], packed[4 * i + 3]);
@@ -1104,38 +1109,58 @@ __global__ __launch_bounds__(NT) void chol_panel_kernel(const float *Sm, float *
             const float *p = &X[16 * q + lq][32 * u + 8 * g];
             const f32x4 lo = *(const f32x4 *)p, hi = *(const f32x4 *)(p + 4);
             i32x4 f;
-            f[0] = (int)(round_bf16(lo[0]) | ((unsigned)round_bf16(lo[1]) << 16));
-            f[1] = (int)(round_bf16(lo[2]) | ((unsigned)round_bf16(lo[3]) << 16));
-            f[2] = (int)(round_bf16(hi[0]) | ((unsigned)round_bf16(hi[1]) << 16));
-            f[3] = (int)(round_bf16(hi[2]) | ((unsigned)round_bf16(hi[3]) << 16));
+            f[0] = (int)pack_bf16(lo[0], lo[1]);
+            f[1] = (int)pack_bf16(lo[2], lo[3]);
+            f[2] = (int)pack_bf16(hi[0], hi[1]);
+            f[3] = (int)pack_bf16(hi[2], hi[3]);
             return f;
         };
 #pragma unroll
         for (int i = 0; i < 4; ++i) *(f32x4 *)&D[16 * i + (tid >> 4)][4 * (tid & 15)] = sv[i];      // S into the tile (D is free)
+        if (may_invert) {
+            // (every wave has one strip, its own: the same code without the conditions, which are not constants and cut it
+            // into pieces that each wait for their own reads)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            i32x4 bq[4];
+            for (int u = 0; u < 2; ++u) {
+                i32x4 bq[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bq[j] = fragment(j, u);
+                for (int j = 0; j < 4; ++j) bq[j] = fragment(j, u);
+                const i32x4 aq = fragment(w, u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    accn[0][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq[j]), accn[0][j], 0, 0, 0);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) D[16 * w + 4 * g + r][16 * j + lq] -= accn[0][j][r];
+        } else {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                i32x4 bq[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bq[j] = fragment(j, u);
+#pragma unroll
+                for (int si = 0; si < 2; ++si)
+                    if (strip(si) >= 0) {
+                        const i32x4 aq = fragment(strip(si), u);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq[j]), accn[si][j], 0, 0, 0);
+                    }
+            }
+            __syncthreads();
+            // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
 #pragma unroll
             for (int si = 0; si < 2; ++si)
                 if (strip(si) >= 0) {
-                    const i32x4 aq = fragment(strip(si), u);
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        accn[si][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq[j]), accn[si][j], 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
                 }
         }
-        __syncthreads();
-        // accumulator register r of lane l is row 4 (l/16) + r, column l%16 of its 16 x 16 tile
-#pragma unroll
-        for (int si = 0; si < 2; ++si)
-            if (strip(si) >= 0) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) D[16 * strip(si) + 4 * g + r][16 * j + lq] -= accn[si][j][r];
-            }
         __syncthreads();
         diag_rest(D, lds.dl, L, Lh, n, j1, NBMAX, tid, Wout, okout, limit, [&](int t) __attribute__((always_inline)) {
             // this workgroup's own rows, deferred above

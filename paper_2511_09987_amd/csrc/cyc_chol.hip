@@ -303,11 +303,17 @@ struct TileProductT {
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, src[0]), __builtin_bit_cast(bf16x8, src[1 + j]), acc[j], 0, 0, 0);
             };
             read_step(0, f[0]);                                                  // (nks is even and at least 2)
-            for (int ks = 0; ks < nks; ks += 2) {
-                read_step(ks + 1, f[1]);
+            if (nks == 2) {                                                      // (a panel whose earlier terms were taken out ahead)
+                read_step(1, f[1]);
                 multiply(f[0]);
-                if (ks + 2 < nks) read_step(ks + 2, f[0]);
                 multiply(f[1]);
+            } else {
+                for (int ks = 0; ks < nks; ks += 2) {
+                    read_step(ks + 1, f[1]);
+                    multiply(f[0]);
+                    if (ks + 2 < nks) read_step(ks + 2, f[0]);
+                    multiply(f[1]);
+                }
             }
         }
 #pragma unroll

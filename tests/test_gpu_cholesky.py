@@ -89,7 +89,11 @@ SHAPES = [(64, 64), (128, 64), (256, 64), (1000, 64), (1024, 64), (520, 32), (26
           # of the group before, and the group's product then writes over its place in L (restored from a copy)
           (1664, 64),
           # ... and with a single workgroup in the launch that reads the tile's copy and restores it
-          (1152, 64)]
+          (1152, 64),
+          # launches whose last two workgroups take the group's earlier panels out of the next launch's first tiles: where
+          # that starts and stops inside a second group (its panels 1 .. 5), next to the matrix's end (1280: the group ends
+          # after five panels; 1344 and 1352: six, the second with a ragged last tile), and in a full second group
+          (1280, 64), (1344, 64), (1352, 64), (2112, 64)]
 
 
 @pytest.mark.parametrize("n,nb", SHAPES)
